@@ -1,0 +1,186 @@
+"""ctypes front end of the CPU oracle (oracle/cdl_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+CPU-baseline leg of the benchmark.  The GPU package never imports it and it
+never imports the GPU package.
+
+The shared object is compiled with gcc next to this file; `build()` does it
+explicitly and `lib()` does it on first use when the object is missing or
+older than its source.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "cdl_oracle.c")
+_SO = os.path.join(_HERE, "libcdl_oracle.so")
+_LIB = None
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP over elements/rows only)."""
+    if force or (not os.path.exists(_SO)) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        tmp = _SO + ".tmp.%d" % os.getpid()
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-ffp-contract=off",
+               "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, _SO)
+    return _SO
+
+
+_f32p = ctypes.POINTER(ctypes.c_float)
+_f64p = ctypes.POINTER(ctypes.c_double)
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_i8p = ctypes.POINTER(ctypes.c_int8)
+
+
+def lib():
+    global _LIB
+    if _LIB is None:
+        build(force=False)
+        L = ctypes.CDLL(_SO)
+        L.cdl_oracle_num_threads.restype = ctypes.c_int
+        L.cdl_oracle_cpmf.restype = ctypes.c_int
+        L.cdl_oracle_cpmf.argtypes = [ctypes.c_double, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                      ctypes.c_double, _f64p, _f64p]
+        L.cdl_oracle_element.restype = None
+        L.cdl_oracle_element.argtypes = [ctypes.c_double, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                         ctypes.c_double, _i32p, _f64p, _f64p, _f64p, _f64p, _f64p]
+        L.cdl_oracle_lemma1_raw.restype = None
+        L.cdl_oracle_lemma1_raw.argtypes = [ctypes.c_double, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                            ctypes.c_double, _f64p, _f64p]
+        L.cdl_oracle_quantize_fwd.restype = None
+        L.cdl_oracle_quantize_fwd.argtypes = [_f32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                              ctypes.c_float, ctypes.c_float, _i32p, _f64p, _f64p]
+        L.cdl_oracle_marginal_entropy.restype = None
+        L.cdl_oracle_marginal_entropy.argtypes = [_f32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                                  ctypes.c_float, ctypes.c_float, _f64p, _f64p]
+        L.cdl_oracle_quantize_bwd.restype = None
+        L.cdl_oracle_quantize_bwd.argtypes = [_f32p, _f32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                              ctypes.c_float, ctypes.c_float, _f64p, _f64p, _f64p, _f64p, _f64p]
+        L.cdl_oracle_qgemm_fwd.restype = None
+        L.cdl_oracle_qgemm_fwd.argtypes = [_i8p, _i8p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                           ctypes.c_float, ctypes.c_float, _i32p, _f64p]
+        L.cdl_oracle_qgemm_bwd.restype = None
+        L.cdl_oracle_qgemm_bwd.argtypes = [_f32p, _i8p, _i8p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                           ctypes.c_float, ctypes.c_float, _f64p, _f64p]
+        _LIB = L
+    return _LIB
+
+
+def num_threads() -> int:
+    return int(lib().cdl_oracle_num_threads())
+
+
+def _c(a: np.ndarray, dtype) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def _ptr(a: Optional[np.ndarray], ptype):
+    return a.ctypes.data_as(ptype) if a is not None else ptype()
+
+
+# ----------------------------------------------------------------- one element (double in, double out)
+
+def cpmf(theta: float, lo: int, n_levels: int, delta: float, alpha: float) -> Tuple[np.ndarray, int, float]:
+    """CPMF over the levels for one element; returns (P, mode index, top-two score gap)."""
+    P = np.empty(n_levels, dtype=np.float64)
+    gap = ctypes.c_double()
+    mode = lib().cdl_oracle_cpmf(float(theta), lo, n_levels, float(delta), float(alpha),
+                                 _ptr(P, _f64p), ctypes.byref(gap))
+    return P, int(mode), gap.value
+
+
+def element(theta: float, lo: int, n_levels: int, delta: float, alpha: float) -> dict:
+    """idx, soft value, score gap and the three partial derivatives of Q_d for one element."""
+    idx = ctypes.c_int32()
+    v = [ctypes.c_double() for _ in range(5)]
+    lib().cdl_oracle_element(float(theta), lo, n_levels, float(delta), float(alpha), ctypes.byref(idx),
+                             *[ctypes.byref(x) for x in v])
+    return dict(idx=idx.value, soft=v[0].value, gap=v[1].value,
+                dtheta=v[2].value, ddelta=v[3].value, dalpha=v[4].value)
+
+
+def lemma1_raw(theta: float, lo: int, n_levels: int, delta: float, alpha: float) -> Tuple[float, float]:
+    a, b = ctypes.c_double(), ctypes.c_double()
+    lib().cdl_oracle_lemma1_raw(float(theta), lo, n_levels, float(delta), float(alpha),
+                                ctypes.byref(a), ctypes.byref(b))
+    return a.value, b.value
+
+
+# ----------------------------------------------------------------- tensors (fp32 in, double out)
+
+def quantize_fwd(theta: np.ndarray, lo: int, n_levels: int, delta: float, alpha: float,
+                 want_soft: bool = True, want_gap: bool = True):
+    """Returns (idx int32[n], soft float64[n] | None, score_gap float64[n] | None)."""
+    th = _c(theta, np.float32).reshape(-1)
+    n = th.size
+    idx = np.empty(n, dtype=np.int32)
+    soft = np.empty(n, dtype=np.float64) if want_soft else None
+    gap = np.empty(n, dtype=np.float64) if want_gap else None
+    lib().cdl_oracle_quantize_fwd(_ptr(th, _f32p), n, lo, n_levels, float(delta), float(alpha),
+                                  _ptr(idx, _i32p), _ptr(soft, _f64p), _ptr(gap, _f64p))
+    return idx, soft, gap
+
+
+def marginal_entropy(theta: np.ndarray, lo: int, n_levels: int, delta: float, alpha: float):
+    """Returns (marg float64[n_levels], entropy in bits)."""
+    th = _c(theta, np.float32).reshape(-1)
+    marg = np.empty(n_levels, dtype=np.float64)
+    H = ctypes.c_double()
+    lib().cdl_oracle_marginal_entropy(_ptr(th, _f32p), th.size, lo, n_levels, float(delta), float(alpha),
+                                      _ptr(marg, _f64p), ctypes.byref(H))
+    return marg, H.value
+
+
+def quantize_bwd(theta: np.ndarray, g: np.ndarray, lo: int, n_levels: int, delta: float, alpha: float,
+                 want_dtheta: bool = True) -> dict:
+    """dtheta float64[n], d_delta, d_alpha and the sums of |term| behind the two scalars."""
+    th = _c(theta, np.float32).reshape(-1)
+    gg = _c(g, np.float32).reshape(-1)
+    assert th.size == gg.size
+    dth = np.empty(th.size, dtype=np.float64) if want_dtheta else None
+    s = [ctypes.c_double() for _ in range(4)]
+    lib().cdl_oracle_quantize_bwd(_ptr(th, _f32p), _ptr(gg, _f32p), th.size, lo, n_levels,
+                                  float(delta), float(alpha), _ptr(dth, _f64p),
+                                  *[ctypes.byref(x) for x in s])
+    return dict(dtheta=dth, d_delta=s[0].value, d_alpha=s[1].value,
+                abs_sum_delta=s[2].value, abs_sum_alpha=s[3].value)
+
+
+def qgemm_fwd(a_idx: np.ndarray, b_idx: np.ndarray, delta_a: float, delta_b: float,
+              want_y: bool = True):
+    """a_idx int8[M,K], b_idx int8[N,K] -> (acc int32[M,N], y float64[M,N] | None)."""
+    a = _c(a_idx, np.int8)
+    b = _c(b_idx, np.int8)
+    M, K = a.shape
+    N, K2 = b.shape
+    assert K == K2
+    acc = np.empty((M, N), dtype=np.int32)
+    y = np.empty((M, N), dtype=np.float64) if want_y else None
+    lib().cdl_oracle_qgemm_fwd(_ptr(a, _i8p), _ptr(b, _i8p), M, N, K, float(delta_a), float(delta_b),
+                               _ptr(acc, _i32p), _ptr(y, _f64p))
+    return acc, y
+
+
+def qgemm_bwd(g: np.ndarray, a_idx: np.ndarray, b_idx: np.ndarray, delta_a: float, delta_b: float,
+              want_da: bool = True, want_db: bool = True):
+    """g fp32[M,N] -> (d_a_hat float64[M,K] | None, d_b_hat float64[N,K] | None)."""
+    gg = _c(g, np.float32)
+    a = _c(a_idx, np.int8)
+    b = _c(b_idx, np.int8)
+    M, K = a.shape
+    N, K2 = b.shape
+    assert K == K2 and gg.shape == (M, N)
+    da = np.empty((M, K), dtype=np.float64) if want_da else None
+    db = np.empty((N, K), dtype=np.float64) if want_db else None
+    lib().cdl_oracle_qgemm_bwd(_ptr(gg, _f32p), _ptr(a, _i8p), _ptr(b, _i8p), M, N, K,
+                               float(delta_a), float(delta_b), _ptr(da, _f64p), _ptr(db, _f64p))
+    return da, db

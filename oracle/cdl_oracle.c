@@ -1,0 +1,328 @@
+/*
+ * CPU oracle for the quantized layer step of Coded Deep Learning (CDL).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what
+ * the method computes, written from the paper's definitions in double
+ * precision.  Only the test-suite, the smoke check and the CPU-baseline leg of
+ * the benchmark may call it; the GPU library never does, and the two share no
+ * code, tables or helpers.
+ *
+ * Every routine evaluates the definition directly: each element visits every
+ * level of the index set, there is no windowing, blocking, recurrence or
+ * reordering.  OpenMP is used only to spread independent elements / output
+ * rows over the host cores.
+ *
+ * Notation (Section III-A): theta is one weight or activation, q (here
+ * `delta`) the step size, alpha the sharpness, the index set is
+ * {lo, ..., lo+n_levels-1}, level i reproduces the value i*delta.
+ *
+ * Readings where the paper is silent are listed next to the code that takes
+ * them; all are repeated in the design notes of the repository.
+ *
+ * Parity pins: every function below is pinned by a CPU test against a closed
+ * form, an invariant, a finite difference or a brute-force / library result;
+ * none is "parity unpinned".  The paper's trained-network results (Table I
+ * and the figures of Section V) are not reproduced by anything here.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int cdl_oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------------
+ * One element: conditional PMF over the levels (eq. CPMF / eq. PMF, Sec. III-A)
+ *
+ *   P(i*delta | theta) = exp(-alpha (theta - i delta)^2) / sum_j exp(-alpha (theta - j delta)^2)
+ *
+ * evaluated as a softmax with the largest score subtracted (the same
+ * quotient, safe against underflow of every term).
+ * Returns the mode (lowest index on an exact tie of scores: the paper does not
+ * say) and the gap between the two largest scores.
+ * ---------------------------------------------------------------------- */
+int cdl_oracle_cpmf(double theta, int lo, int n_levels, double delta, double alpha,
+                    double *P /* n_levels */, double *score_gap /* nullable */)
+{
+    double s_best = -INFINITY, s_second = -INFINITY;
+    int i_best = lo;
+    for (int k = 0; k < n_levels; ++k) {
+        double d = theta - (double)(lo + k) * delta;
+        double s = -alpha * d * d;
+        P[k] = s;
+        if (s > s_best) { s_second = s_best; s_best = s; i_best = lo + k; }
+        else if (s > s_second) { s_second = s; }
+    }
+    double Z = 0.0;
+    for (int k = 0; k < n_levels; ++k) { P[k] = exp(P[k] - s_best); Z += P[k]; }
+    for (int k = 0; k < n_levels; ++k) P[k] /= Z;
+    if (score_gap) *score_gap = s_best - s_second;
+    return i_best;
+}
+
+/* Soft deterministic quantizer Q_d(theta) = sum_i P(i delta | theta) * i delta  (eq. softQ, Sec. III-B) */
+static double soft_value(const double *P, int lo, int n_levels, double delta)
+{
+    double e = 0.0;
+    for (int k = 0; k < n_levels; ++k) e += P[k] * ((double)(lo + k) * delta);
+    return e;
+}
+
+typedef struct {
+    double mean;      /* E{Q_p}  = Q_d                                    */
+    double var;       /* Var{Q_p}                                         */
+    double skew_u;    /* Skew_u{Q_p} = E X^3 - E X * E X^2  (Lemma 1)      */
+    double cov_x_d2;  /* Cov(X, (theta - X)^2)                             */
+} moments_t;
+
+/*
+ * Moments of the quantized value X = Q_p(theta) under the CPMF.
+ * Var and Skew_u are taken about the mean: Var = E(X-EX)^2 by definition and
+ * Skew_u = E(X-EX)^3 + 2 EX Var (expand X = EX + Y with EY = 0 in Lemma 1's
+ * definition).  The raw-power form printed in Lemma 1 is the same number but
+ * cancels to nothing in double once |i| ~ 100 and the distribution is
+ * concentrated; cdl_oracle_lemma1_raw below evaluates it literally so a test
+ * can check the two agree where the raw form is still well conditioned.
+ */
+static moments_t moments(const double *P, double theta, int lo, int n_levels, double delta)
+{
+    moments_t m;
+    m.mean = soft_value(P, lo, n_levels, delta);
+    double c2 = 0.0, c3 = 0.0, cov = 0.0;
+    for (int k = 0; k < n_levels; ++k) {
+        double v = (double)(lo + k) * delta;
+        double y = v - m.mean;
+        double d = theta - v;
+        c2 += P[k] * y * y;
+        c3 += P[k] * y * y * y;
+        cov += P[k] * y * d * d;
+    }
+    m.var = c2;
+    m.skew_u = c3 + 2.0 * m.mean * c2;
+    m.cov_x_d2 = cov;
+    return m;
+}
+
+/*
+ * Partial derivatives of Q_d for one element.
+ *   dQd/dtheta = 2 alpha Var                                   (Lemma 1, eq. partialW)
+ *   dQd/dq     = (E + 2 alpha theta Var - 2 alpha Skew_u) / q  (Lemma 1, eq. partialQ)
+ *   dQd/dalpha = -Cov(X, (theta - X)^2)
+ * The paper only says the last one "can be computed analytically"
+ * (Sec. IV-B, after eq. Jgrad_alpha_q).  Differentiating eq. CPMF gives
+ * dP_i/dalpha = -P_i (d_i^2 - sum_j P_j d_j^2) with d_i = theta - i q, and
+ * summing i q dP_i/dalpha gives the covariance above.
+ */
+void cdl_oracle_element(double theta, int lo, int n_levels, double delta, double alpha,
+                        int *idx, double *soft, double *score_gap,
+                        double *dsoft_dtheta, double *dsoft_ddelta, double *dsoft_dalpha)
+{
+    double *P = (double *)malloc(sizeof(double) * (size_t)n_levels);
+    double gap;
+    int mode = cdl_oracle_cpmf(theta, lo, n_levels, delta, alpha, P, &gap);
+    moments_t m = moments(P, theta, lo, n_levels, delta);
+    if (idx) *idx = mode;
+    if (soft) *soft = m.mean;
+    if (score_gap) *score_gap = gap;
+    if (dsoft_dtheta) *dsoft_dtheta = 2.0 * alpha * m.var;
+    if (dsoft_ddelta) *dsoft_ddelta = (m.mean + 2.0 * alpha * theta * m.var - 2.0 * alpha * m.skew_u) / delta;
+    if (dsoft_dalpha) *dsoft_dalpha = -m.cov_x_d2;
+    free(P);
+}
+
+/* Lemma 1 with Var and Skew_u from raw powers of X exactly as printed. */
+void cdl_oracle_lemma1_raw(double theta, int lo, int n_levels, double delta, double alpha,
+                           double *dsoft_dtheta, double *dsoft_ddelta)
+{
+    double *P = (double *)malloc(sizeof(double) * (size_t)n_levels);
+    cdl_oracle_cpmf(theta, lo, n_levels, delta, alpha, P, NULL);
+    double e1 = 0.0, e2 = 0.0, e3 = 0.0;
+    for (int k = 0; k < n_levels; ++k) {
+        double v = (double)(lo + k) * delta;
+        e1 += P[k] * v; e2 += P[k] * v * v; e3 += P[k] * v * v * v;
+    }
+    double var = e2 - e1 * e1;
+    double skew_u = e3 - e1 * e2;
+    *dsoft_dtheta = 2.0 * alpha * var;
+    *dsoft_ddelta = (e1 + 2.0 * alpha * theta * var - 2.0 * alpha * skew_u) / delta;
+    free(P);
+}
+
+/* ------------------------------------------------------------------------
+ * Tensor forward: hard index (mode of the CPMF = the value Q_p takes with
+ * probability -> 1 as alpha grows, Remark after eq. Qprob) and soft value
+ * Q_d (eq. softboth, Sec. IV-B) for every entry.
+ * ---------------------------------------------------------------------- */
+void cdl_oracle_quantize_fwd(const float *theta, int64_t n, int lo, int n_levels,
+                             float delta_f, float alpha_f,
+                             int32_t *idx /* n, nullable */, double *soft /* n, nullable */,
+                             double *score_gap /* n, nullable */)
+{
+    const double delta = (double)delta_f, alpha = (double)alpha_f;
+#pragma omp parallel
+    {
+        double *P = (double *)malloc(sizeof(double) * (size_t)n_levels);
+#pragma omp for schedule(static)
+        for (int64_t e = 0; e < n; ++e) {
+            double gap;
+            int mode = cdl_oracle_cpmf((double)theta[e], lo, n_levels, delta, alpha, P, &gap);
+            if (idx) idx[e] = mode;
+            if (soft) soft[e] = soft_value(P, lo, n_levels, delta);
+            if (score_gap) score_gap[e] = gap;
+        }
+        free(P);
+    }
+}
+
+/* ------------------------------------------------------------------------
+ * Marginal PMF of the quantized tensor (eq. approx1/n, Sec. IV-C):
+ *   marg[k] = (1/n) sum_e P(level k | theta_e)
+ * and its Shannon entropy H = -sum_k marg[k] log2 marg[k] in bits (the paper
+ * writes "log" and measures the result in bits per weight; terms with
+ * marg[k] = 0 contribute 0).  The total for the layer is n*H.
+ * One call = one PMF over the whole tensor handed in.
+ * ---------------------------------------------------------------------- */
+void cdl_oracle_marginal_entropy(const float *theta, int64_t n, int lo, int n_levels,
+                                 float delta_f, float alpha_f,
+                                 double *marg /* n_levels */, double *entropy_bits /* 1 */)
+{
+    const double delta = (double)delta_f, alpha = (double)alpha_f;
+    int nthreads = cdl_oracle_num_threads();
+    double *partial = (double *)calloc((size_t)nthreads * (size_t)n_levels, sizeof(double));
+#pragma omp parallel
+    {
+#ifdef _OPENMP
+        int t = omp_get_thread_num();
+#else
+        int t = 0;
+#endif
+        double *mine = partial + (size_t)t * (size_t)n_levels;
+        double *P = (double *)malloc(sizeof(double) * (size_t)n_levels);
+#pragma omp for schedule(static)
+        for (int64_t e = 0; e < n; ++e) {
+            cdl_oracle_cpmf((double)theta[e], lo, n_levels, delta, alpha, P, NULL);
+            for (int k = 0; k < n_levels; ++k) mine[k] += P[k];
+        }
+        free(P);
+    }
+    double H = 0.0;
+    for (int k = 0; k < n_levels; ++k) {
+        double s = 0.0;
+        for (int t = 0; t < nthreads; ++t) s += partial[(size_t)t * (size_t)n_levels + k];
+        marg[k] = (n > 0) ? s / (double)n : 0.0;
+        if (marg[k] > 0.0) H -= marg[k] * log2(marg[k]);
+    }
+    *entropy_bits = H;
+    free(partial);
+}
+
+/* ------------------------------------------------------------------------
+ * Tensor backward (Sec. IV-B): with g[e] = dL/dQ_p(theta_e) from the layer,
+ *   dtheta[e] = g[e] * dQd/dtheta                    (eq. partialX3 / partialW3)
+ *   d_delta   = sum_e g[e] * dQd/dq                  (eq. Jgradqw / Jgradqx)
+ *   d_alpha   = sum_e g[e] * dQd/dalpha              (eq. Jgradq_alpha_w / Jgrad_alpha_q)
+ * Also returns sum_e |term| for the two scalar sums so a caller can judge a
+ * difference against the size of what was added up.
+ * ---------------------------------------------------------------------- */
+void cdl_oracle_quantize_bwd(const float *theta, const float *g, int64_t n, int lo, int n_levels,
+                             float delta_f, float alpha_f,
+                             double *dtheta /* n, nullable */,
+                             double *d_delta, double *d_alpha,
+                             double *abs_sum_delta /* nullable */, double *abs_sum_alpha /* nullable */)
+{
+    const double delta = (double)delta_f, alpha = (double)alpha_f;
+    double sd = 0.0, sa = 0.0, ad = 0.0, aa = 0.0;
+#pragma omp parallel reduction(+ : sd, sa, ad, aa)
+    {
+        double *P = (double *)malloc(sizeof(double) * (size_t)n_levels);
+#pragma omp for schedule(static)
+        for (int64_t e = 0; e < n; ++e) {
+            double th = (double)theta[e], ge = (double)g[e];
+            cdl_oracle_cpmf(th, lo, n_levels, delta, alpha, P, NULL);
+            moments_t m = moments(P, th, lo, n_levels, delta);
+            double d_th = 2.0 * alpha * m.var;
+            double d_q = (m.mean + 2.0 * alpha * th * m.var - 2.0 * alpha * m.skew_u) / delta;
+            double d_al = -m.cov_x_d2;
+            if (dtheta) dtheta[e] = ge * d_th;
+            sd += ge * d_q;  ad += fabs(ge * d_q);
+            sa += ge * d_al; aa += fabs(ge * d_al);
+        }
+        free(P);
+    }
+    *d_delta = sd;
+    *d_alpha = sa;
+    if (abs_sum_delta) *abs_sum_delta = ad;
+    if (abs_sum_alpha) *abs_sum_alpha = aa;
+}
+
+/* ------------------------------------------------------------------------
+ * Layer compute over quantized operands (Sec. IV-A: forward and backward
+ * passes run on the quantized weights and activations; Algorithm 1, the
+ * forward and backward steps).  Operands are level indices; the quantized
+ * values are a_idx*delta_a and b_idx*delta_b, so
+ *   acc[m,n] = sum_k a_idx[m,k] * b_idx[n,k]          (exact integers)
+ *   y[m,n]   = delta_a * delta_b * acc[m,n]
+ * Both index matrices are row-major with the contraction index contiguous.
+ * ---------------------------------------------------------------------- */
+void cdl_oracle_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int M, int N, int K,
+                          float delta_a, float delta_b,
+                          int32_t *acc /* M*N, nullable */, double *y /* M*N, nullable */)
+{
+    const double scale = (double)delta_a * (double)delta_b;
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m) {
+        for (int n = 0; n < N; ++n) {
+            int64_t s = 0;
+            for (int k = 0; k < K; ++k)
+                s += (int64_t)a_idx[(size_t)m * K + k] * (int64_t)b_idx[(size_t)n * K + k];
+            if (acc) acc[(size_t)m * N + n] = (int32_t)s;
+            if (y) y[(size_t)m * N + n] = scale * (double)s;
+        }
+    }
+}
+
+/*
+ * Backward of the same product with respect to the two quantized operands.
+ * With Yhat = Ahat . Bhat^T, Ahat = delta_a*a_idx, Bhat = delta_b*b_idx and
+ * g = dL/dYhat (kept in fp32: the paper quantizes weights and activations,
+ * never the gradient signal):
+ *   d_a_hat[m,k] = sum_n g[m,n] * Bhat[n,k] = delta_b * sum_n g[m,n] b_idx[n,k]
+ *   d_b_hat[n,k] = sum_m g[m,n] * Ahat[m,k] = delta_a * sum_m g[m,n] a_idx[m,k]
+ * These are dL/dQ_p(x) and dL/dQ_p(w) of Sec. IV-B, the factors that the
+ * quantizer backward multiplies by dQd/dtheta.
+ */
+void cdl_oracle_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
+                          int M, int N, int K, float delta_a, float delta_b,
+                          double *d_a_hat /* M*K, nullable */, double *d_b_hat /* N*K, nullable */)
+{
+    if (d_a_hat) {
+#pragma omp parallel for schedule(static)
+        for (int m = 0; m < M; ++m)
+            for (int k = 0; k < K; ++k) {
+                double s = 0.0;
+                for (int n = 0; n < N; ++n)
+                    s += (double)g[(size_t)m * N + n] * (double)b_idx[(size_t)n * K + k];
+                d_a_hat[(size_t)m * K + k] = (double)delta_b * s;
+            }
+    }
+    if (d_b_hat) {
+#pragma omp parallel for schedule(static)
+        for (int n = 0; n < N; ++n)
+            for (int k = 0; k < K; ++k) {
+                double s = 0.0;
+                for (int m = 0; m < M; ++m)
+                    s += (double)g[(size_t)m * N + n] * (double)a_idx[(size_t)m * K + k];
+                d_b_hat[(size_t)n * K + k] = (double)delta_a * s;
+            }
+    }
+}
