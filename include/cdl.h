@@ -1,0 +1,149 @@
+/*
+ * libcdl - the quantized layer step of Coded Deep Learning (CDL) on AMD MI355X (gfx950).
+ *
+ * One layer, one minibatch, in the order of Algorithm 1 of the paper:
+ *
+ *   quantize weights        cdl_quantize_fwd(W)            -> level indices, soft values, marginal PMF / entropy
+ *   quantize activations    cdl_quantize_fwd(X)
+ *   forward over indices    cdl_qgemm_fwd(Xi, Wi)          -> Y = dx*dw * (Xi . Wi^T)
+ *   backward over indices   cdl_qgemm_bwd(G, Xi, Wi)       -> dL/dQ(X), dL/dQ(W)
+ *   quantizer backward      cdl_quantize_bwd(X, dL/dQ(X))  -> dL/dX, dL/d(step), dL/d(sharpness); same for W
+ *
+ * Conventions for every entry point
+ *   - All tensor and scalar-output pointers are DEVICE pointers owned by the caller; tensors are
+ *     contiguous, row-major.  fp32 tensors must be 16-byte aligned, int8 index tensors 4-byte
+ *     aligned (16-byte for the GEMMs), else CDL_ERR_ALIGN.
+ *   - Step size and sharpness are HOST scalars.
+ *   - `ws` is caller-owned device scratch of at least the size the matching *_workspace_bytes()
+ *     query returns (256-byte aligned); the library allocates and frees nothing and keeps no state
+ *     between calls except the last HIP error code.  Two calls may share `ws` only if they are
+ *     ordered on one stream.
+ *   - `hip_stream` is a hipStream_t (NULL = the default stream).  Calls enqueue kernels and return
+ *     without synchronising.  Outputs are overwritten, never accumulated into.
+ *   - Return value: CDL_OK or a negative cdl_status.  Arguments are validated on the host before
+ *     any GPU call; on error nothing is launched.  Inputs must be finite; the result for NaN or
+ *     infinite tensor entries is unspecified.
+ *   - n == 0 (or an empty GEMM dimension of an output) is CDL_OK: scalar outputs and the marginal
+ *     PMF are set to 0.
+ */
+#ifndef CDL_H
+#define CDL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * A uniform quantizer of the paper (Sec. III-A, Sec. IV-A): index set {lo, ..., lo+n_levels-1},
+ * reproduction value of index i is i*delta (the paper's q_l for weights, s_l for activations),
+ * sharpness alpha (the paper's alpha_l / beta_l).  The paper's signed b-bit set is
+ * lo = -2^(b-1), n_levels = 2^b; its unsigned set is lo = 0, n_levels = 2^b; any contiguous set
+ * inside [-128, 127] is accepted, so indices always fit an int8.
+ */
+typedef struct cdl_qparams {
+    int32_t lo;
+    int32_t n_levels;
+    float   delta;
+    float   alpha;
+} cdl_qparams;
+
+typedef enum cdl_status {
+    CDL_OK            =  0,
+    CDL_ERR_NULL      = -1,   /* a required pointer is NULL */
+    CDL_ERR_PARAM     = -2,   /* negative size, n_levels < 2, delta/alpha not finite and positive, ... */
+    CDL_ERR_RANGE     = -3,   /* level set leaves [-128,127], or an int32 accumulator could overflow */
+    CDL_ERR_ALIGN     = -4,   /* pointer alignment, see above */
+    CDL_ERR_WORKSPACE = -5,   /* ws is NULL or smaller than the query says */
+    CDL_ERR_HIP       = -6    /* a HIP call failed; see cdl_last_hip_error() */
+} cdl_status;
+
+/* Scratch needed by cdl_quantize_fwd / cdl_quantize_bwd / cdl_marginal_entropy for n elements. */
+size_t cdl_quantize_workspace_bytes(int64_t n, int32_t n_levels);
+
+/* Scratch needed by cdl_qgemm_fwd (staging copies when K is not a multiple of 16). */
+size_t cdl_qgemm_fwd_workspace_bytes(int32_t M, int32_t N, int32_t K);
+
+/* Scratch needed by cdl_qgemm_bwd (integer limb planes of g, transposed index copies). */
+size_t cdl_qgemm_bwd_workspace_bytes(int32_t M, int32_t N, int32_t K);
+
+/*
+ * Forward quantizer over a flat tensor (eq. CPMF, eq. softQ; per-layer forms eq. PMFw / PMFa and
+ * eq. softboth).  For each entry theta[e] the conditional PMF over the levels is
+ * softmax_i(-alpha (theta[e] - i delta)^2).  Outputs:
+ *   idx[e]   the level index at the mode of that PMF, i.e. the nearest level, clamped to the set;
+ *            an exact tie between two levels goes to the lower index          (int8[n], required)
+ *   soft[e]  Q_d(theta[e]) = sum_i P_i * i * delta                            (fp32[n], nullable)
+ *   marg[k]  (1/n) sum_e P(level lo+k | theta[e]), the marginal PMF of eq. approx1/n
+ *                                                                      (fp32[n_levels], nullable)
+ *   entropy_bits   -sum_k marg[k] log2 marg[k], bits per entry (Sec. IV-C) (fp32[1], nullable)
+ * marg may be NULL while entropy_bits is not.
+ */
+int cdl_quantize_fwd(const float *theta, int64_t n, const cdl_qparams *p,
+                     int8_t *idx, float *soft, float *marg, float *entropy_bits,
+                     void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Backward of the quantizer through its soft proxy Q_d (Lemma 1; chain rule of Sec. IV-B,
+ * eq. partialX3, partialW3, Jgradqw, Jgradqx, Jgradq_alpha_w, Jgrad_alpha_q).
+ * g[e] is dL/dQ_p(theta[e]) as produced by cdl_qgemm_bwd.  Outputs:
+ *   dtheta[e] = g[e] * 2 alpha Var{Q_p | theta[e]}                              (fp32[n], nullable)
+ *   d_delta   = sum_e g[e] * (E + 2 alpha theta Var - 2 alpha Skew_u) / delta  (fp32[1], nullable)
+ *   d_alpha   = sum_e g[e] * (2 theta Var - Skew_u)                           (fp32[1], nullable)
+ * The last formula is the derivative the paper says "can be computed analytically" without
+ * printing it: dQ_d/dalpha = -Cov(Q_p, (theta - Q_p)^2).  At least one output must be non-NULL.
+ * The two sums are reproducible: same inputs, same bits.
+ */
+int cdl_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl_qparams *p,
+                     float *dtheta, float *d_delta, float *d_alpha,
+                     void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Marginal PMF of the quantized tensor and its entropy (Sec. IV-C, eq. approx1/n and the
+ * definition of H(W^)), without the per-entry outputs.  marg: fp32[n_levels] (nullable),
+ * entropy_bits: fp32[1] (nullable); at least one non-NULL.  Total bits of the tensor = n * entropy.
+ */
+int cdl_marginal_entropy(const float *theta, int64_t n, const cdl_qparams *p,
+                         float *marg, float *entropy_bits,
+                         void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Forward layer product over quantized operands (Sec. IV-A; Algorithm 1, forward step):
+ *   acc[m,n] = sum_k a_idx[m,k] * b_idx[n,k]        exact int32             (int32[M,N], nullable)
+ *   y[m,n]   = (delta_a * delta_b) * acc[m,n]       one fp32 multiply       (fp32[M,N],  nullable)
+ * a_idx: int8[M,K] (activations), b_idx: int8[N,K] (weights, one row per output feature); the
+ * contraction index is contiguous in both.  At least one of acc / y must be non-NULL.
+ * CDL_ERR_RANGE if K * 128 * 128 could overflow int32 (K > 131071).
+ */
+int cdl_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
+                  float delta_a, float delta_b, int32_t *acc, float *y,
+                  void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Backward of that product with respect to the two quantized operands (Algorithm 1, backward
+ * step; these are the dL/dQ_p factors of eq. partialX3 / partialW3).  g: fp32[M,N] = dL/dy.
+ *   d_a_hat[m,k] = delta_b * sum_n g[m,n] * b_idx[n,k]                       (fp32[M,K], nullable)
+ *   d_b_hat[n,k] = delta_a * sum_m g[m,n] * a_idx[m,k]                       (fp32[N,K], nullable)
+ * The gradient stays fp32 (the paper quantizes weights and activations only); the sums are
+ * evaluated exactly on integer limbs of g, see the design notes.  At least one output non-NULL.
+ */
+int cdl_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
+                  int32_t M, int32_t N, int32_t K, float delta_a, float delta_b,
+                  float *d_a_hat, float *d_b_hat,
+                  void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Text for a cdl_status. */
+const char *cdl_status_string(int status);
+
+/* hipError_t of the most recent failed HIP call made by this library in this process (0 = none). */
+int cdl_last_hip_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int cdl_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CDL_H */

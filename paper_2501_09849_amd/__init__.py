@@ -1,0 +1,10 @@
+"""MI355X-native quantized layer step of Coded Deep Learning (arxiv 2501.09849).
+
+The work is done by hand-written HIP kernels for gfx950 behind the C library
+declared in include/cdl.h; `binding` marshals arguments to it, nothing more.
+"""
+from .binding import (  # noqa: F401
+    CdlError, QParams, lib_path, load,
+    quantize_workspace_bytes, qgemm_fwd_workspace_bytes, qgemm_bwd_workspace_bytes,
+    cdl_quantize_fwd, cdl_quantize_bwd, cdl_marginal_entropy, cdl_qgemm_fwd, cdl_qgemm_bwd,
+)

@@ -1,0 +1,156 @@
+"""Thin ctypes binding of libcdl.so: same names and arguments as include/cdl.h.
+
+Tensors are torch CUDA (ROCm) tensors used only as device memory; every step
+of the computation runs in the library's kernels.  There is no fallback: if
+the shared library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libcdl.so")
+_LIB = None
+
+EXPORTS = (
+    "cdl_quantize_workspace_bytes", "cdl_qgemm_fwd_workspace_bytes", "cdl_qgemm_bwd_workspace_bytes",
+    "cdl_quantize_fwd", "cdl_quantize_bwd", "cdl_marginal_entropy", "cdl_qgemm_fwd", "cdl_qgemm_bwd",
+    "cdl_status_string", "cdl_last_hip_error", "cdl_version",
+)
+
+
+class CdlError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = load().cdl_status_string(status).decode()
+        if status == -6:
+            msg += " [hipError %d]" % load().cdl_last_hip_error()
+        super().__init__("%s: %s (status %d)" % (where, msg, status))
+
+
+class QParams(ctypes.Structure):
+    """struct cdl_qparams"""
+    _fields_ = [("lo", ctypes.c_int32), ("n_levels", ctypes.c_int32),
+                ("delta", ctypes.c_float), ("alpha", ctypes.c_float)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Load libcdl.so (built beforehand by paper_2501_09849_amd.build / __graft_entry__.build)."""
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError("libcdl.so is not built: run `python -m paper_2501_09849_amd.build` "
+                               "(or __graft_entry__.build()) first; there is no fallback path")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i64, i32, f32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+        qp = ctypes.POINTER(QParams)
+        L.cdl_quantize_workspace_bytes.restype = sz
+        L.cdl_quantize_workspace_bytes.argtypes = [i64, i32]
+        L.cdl_qgemm_fwd_workspace_bytes.restype = sz
+        L.cdl_qgemm_fwd_workspace_bytes.argtypes = [i32, i32, i32]
+        L.cdl_qgemm_bwd_workspace_bytes.restype = sz
+        L.cdl_qgemm_bwd_workspace_bytes.argtypes = [i32, i32, i32]
+        L.cdl_quantize_fwd.restype = ctypes.c_int
+        L.cdl_quantize_fwd.argtypes = [vp, i64, qp, vp, vp, vp, vp, vp, sz, vp]
+        L.cdl_quantize_bwd.restype = ctypes.c_int
+        L.cdl_quantize_bwd.argtypes = [vp, vp, i64, qp, vp, vp, vp, vp, sz, vp]
+        L.cdl_marginal_entropy.restype = ctypes.c_int
+        L.cdl_marginal_entropy.argtypes = [vp, i64, qp, vp, vp, vp, sz, vp]
+        L.cdl_qgemm_fwd.restype = ctypes.c_int
+        L.cdl_qgemm_fwd.argtypes = [vp, vp, i32, i32, i32, f32, f32, vp, vp, vp, sz, vp]
+        L.cdl_qgemm_bwd.restype = ctypes.c_int
+        L.cdl_qgemm_bwd.argtypes = [vp, vp, vp, i32, i32, i32, f32, f32, vp, vp, vp, sz, vp]
+        L.cdl_status_string.restype = ctypes.c_char_p
+        L.cdl_status_string.argtypes = [ctypes.c_int]
+        L.cdl_last_hip_error.restype = ctypes.c_int
+        L.cdl_version.restype = ctypes.c_int
+        _LIB = L
+    return _LIB
+
+
+def _ptr(t) -> Optional[int]:
+    """Device address of a torch tensor (None -> NULL); a bare int passes through."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _ws(ws):
+    if ws is None:
+        return None, 0
+    return ws.data_ptr(), ws.numel() * ws.element_size()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _qp(lo: int, n_levels: int, delta: float, alpha: float) -> QParams:
+    return QParams(int(lo), int(n_levels), float(delta), float(alpha))
+
+
+def quantize_workspace_bytes(n: int, n_levels: int) -> int:
+    return int(load().cdl_quantize_workspace_bytes(n, n_levels))
+
+
+def qgemm_fwd_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(load().cdl_qgemm_fwd_workspace_bytes(M, N, K))
+
+
+def qgemm_bwd_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(load().cdl_qgemm_bwd_workspace_bytes(M, N, K))
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise CdlError(rc, where)
+
+
+def cdl_quantize_fwd(theta, n, lo, n_levels, delta, alpha, idx, soft=None, marg=None, entropy_bits=None,
+                     ws=None, stream=None):
+    wp, wb = _ws(ws)
+    q = _qp(lo, n_levels, delta, alpha)
+    _check(load().cdl_quantize_fwd(_ptr(theta), n, ctypes.byref(q), _ptr(idx), _ptr(soft), _ptr(marg),
+                                   _ptr(entropy_bits), wp, wb, _stream(stream)), "cdl_quantize_fwd")
+
+
+def cdl_quantize_bwd(theta, g, n, lo, n_levels, delta, alpha, dtheta=None, d_delta=None, d_alpha=None,
+                     ws=None, stream=None):
+    wp, wb = _ws(ws)
+    q = _qp(lo, n_levels, delta, alpha)
+    _check(load().cdl_quantize_bwd(_ptr(theta), _ptr(g), n, ctypes.byref(q), _ptr(dtheta), _ptr(d_delta),
+                                   _ptr(d_alpha), wp, wb, _stream(stream)), "cdl_quantize_bwd")
+
+
+def cdl_marginal_entropy(theta, n, lo, n_levels, delta, alpha, marg=None, entropy_bits=None, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    q = _qp(lo, n_levels, delta, alpha)
+    _check(load().cdl_marginal_entropy(_ptr(theta), n, ctypes.byref(q), _ptr(marg), _ptr(entropy_bits),
+                                       wp, wb, _stream(stream)), "cdl_marginal_entropy")
+
+
+def cdl_qgemm_fwd(a_idx, b_idx, M, N, K, delta_a, delta_b, acc=None, y=None, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(load().cdl_qgemm_fwd(_ptr(a_idx), _ptr(b_idx), M, N, K, delta_a, delta_b, _ptr(acc), _ptr(y),
+                                wp, wb, _stream(stream)), "cdl_qgemm_fwd")
+
+
+def cdl_qgemm_bwd(g, a_idx, b_idx, M, N, K, delta_a, delta_b, d_a_hat=None, d_b_hat=None, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(load().cdl_qgemm_bwd(_ptr(g), _ptr(a_idx), _ptr(b_idx), M, N, K, delta_a, delta_b,
+                                _ptr(d_a_hat), _ptr(d_b_hat), wp, wb, _stream(stream)), "cdl_qgemm_bwd")

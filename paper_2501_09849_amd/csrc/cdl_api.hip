@@ -1,0 +1,179 @@
+// The C boundary of libcdl: argument validation (host only, before any GPU call) and dispatch.
+#include "cdl_internal.h"
+
+#include <atomic>
+#include <cmath>
+
+namespace cdl {
+
+namespace {
+std::atomic<int> g_last_hip_error{0};
+}
+
+int hip_failed(hipError_t e)
+{
+    g_last_hip_error.store((int)e);
+    return CDL_ERR_HIP;
+}
+
+int check_launch()
+{
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? (int)CDL_OK : hip_failed(e);
+}
+
+namespace {
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int check_qparams(const cdl_qparams *p)
+{
+    if (!p) return CDL_ERR_NULL;
+    if (p->n_levels < 2) return CDL_ERR_PARAM;
+    if (!(std::isfinite(p->delta) && p->delta > 0.0f)) return CDL_ERR_PARAM;
+    if (!(std::isfinite(p->alpha) && p->alpha > 0.0f)) return CDL_ERR_PARAM;
+    const int64_t hi = (int64_t)p->lo + (int64_t)p->n_levels - 1;
+    if (p->lo < -128 || hi > 127) return CDL_ERR_RANGE;
+    // derived constants must stay finite in fp32
+    const double kappa = (double)p->alpha * (double)p->delta * (double)p->delta;
+    if (!(kappa < 1e30) || !((double)p->alpha * (double)p->delta < 1e30) || !(1.0 / (double)p->delta < 1e30))
+        return CDL_ERR_PARAM;
+    return CDL_OK;
+}
+
+int check_ws(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return CDL_OK;
+    if (!ws || have < need) return CDL_ERR_WORKSPACE;
+    if (!aligned(ws, 256)) return CDL_ERR_ALIGN;
+    return CDL_OK;
+}
+
+}  // namespace
+}  // namespace cdl
+
+using namespace cdl;
+
+extern "C" {
+
+size_t cdl_quantize_workspace_bytes(int64_t n, int32_t n_levels)
+{
+    if (n < 0 || n_levels < 2 || n_levels > 256) return 0;
+    return quantize_workspace_bytes(n, n_levels);
+}
+
+size_t cdl_qgemm_fwd_workspace_bytes(int32_t M, int32_t N, int32_t K)
+{
+    if (M < 0 || N < 0 || K < 0) return 0;
+    return qgemm_fwd_workspace_bytes(M, N, K);
+}
+
+size_t cdl_qgemm_bwd_workspace_bytes(int32_t M, int32_t N, int32_t K)
+{
+    if (M < 0 || N < 0 || K < 0) return 0;
+    return qgemm_bwd_workspace_bytes(M, N, K);
+}
+
+int cdl_quantize_fwd(const float *theta, int64_t n, const cdl_qparams *p,
+                     int8_t *idx, float *soft, float *marg, float *entropy_bits,
+                     void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_qparams(p);
+    if (rc != CDL_OK) return rc;
+    if (n < 0) return CDL_ERR_PARAM;
+    if (n > 0 && (!theta || !idx)) return CDL_ERR_NULL;
+    if (!aligned(theta, 16) || !aligned(soft, 16) || !aligned(idx, 4) || !aligned(marg, 4) || !aligned(entropy_bits, 4))
+        return CDL_ERR_ALIGN;
+    if (marg || entropy_bits) {
+        rc = check_ws(ws, ws_bytes, quantize_workspace_bytes(n, p->n_levels));
+        if (rc != CDL_OK) return rc;
+    }
+    return launch_quantize_fwd(theta, n, *p, idx, soft, marg, entropy_bits, ws, (hipStream_t)hip_stream);
+}
+
+int cdl_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl_qparams *p,
+                     float *dtheta, float *d_delta, float *d_alpha,
+                     void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_qparams(p);
+    if (rc != CDL_OK) return rc;
+    if (n < 0) return CDL_ERR_PARAM;
+    if (!dtheta && !d_delta && !d_alpha) return CDL_ERR_NULL;
+    if (n > 0 && (!theta || !g)) return CDL_ERR_NULL;
+    if (!aligned(theta, 16) || !aligned(g, 16) || !aligned(dtheta, 16) || !aligned(d_delta, 4) || !aligned(d_alpha, 4))
+        return CDL_ERR_ALIGN;
+    if (d_delta || d_alpha) {
+        rc = check_ws(ws, ws_bytes, quantize_workspace_bytes(n, p->n_levels));
+        if (rc != CDL_OK) return rc;
+    }
+    return launch_quantize_bwd(theta, g, n, *p, dtheta, d_delta, d_alpha, ws, (hipStream_t)hip_stream);
+}
+
+int cdl_marginal_entropy(const float *theta, int64_t n, const cdl_qparams *p,
+                         float *marg, float *entropy_bits,
+                         void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_qparams(p);
+    if (rc != CDL_OK) return rc;
+    if (n < 0) return CDL_ERR_PARAM;
+    if (!marg && !entropy_bits) return CDL_ERR_NULL;
+    if (n > 0 && !theta) return CDL_ERR_NULL;
+    if (!aligned(theta, 16) || !aligned(marg, 4) || !aligned(entropy_bits, 4)) return CDL_ERR_ALIGN;
+    rc = check_ws(ws, ws_bytes, quantize_workspace_bytes(n, p->n_levels));
+    if (rc != CDL_OK) return rc;
+    return launch_quantize_fwd(theta, n, *p, nullptr, nullptr, marg, entropy_bits, ws, (hipStream_t)hip_stream);
+}
+
+int cdl_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
+                  float delta_a, float delta_b, int32_t *acc, float *y,
+                  void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (M < 0 || N < 0 || K < 0) return CDL_ERR_PARAM;
+    if (!(std::isfinite(delta_a) && delta_a > 0.0f) || !(std::isfinite(delta_b) && delta_b > 0.0f)) return CDL_ERR_PARAM;
+    if (!acc && !y) return CDL_ERR_NULL;
+    if ((int64_t)K * 128 * 128 > 2147483647LL) return CDL_ERR_RANGE;
+    if ((int64_t)M * N > 0 && K > 0 && (!a_idx || !b_idx)) return CDL_ERR_NULL;
+    if (!aligned(a_idx, 16) || !aligned(b_idx, 16) || !aligned(acc, 16) || !aligned(y, 16)) return CDL_ERR_ALIGN;
+    int rc = check_ws(ws, ws_bytes, qgemm_fwd_workspace_bytes(M, N, K));
+    if (rc != CDL_OK) return rc;
+    return launch_qgemm_fwd(a_idx, b_idx, M, N, K, delta_a, delta_b, acc, y, ws, (hipStream_t)hip_stream);
+}
+
+int cdl_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
+                  int32_t M, int32_t N, int32_t K, float delta_a, float delta_b,
+                  float *d_a_hat, float *d_b_hat,
+                  void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (M < 0 || N < 0 || K < 0) return CDL_ERR_PARAM;
+    if (!(std::isfinite(delta_a) && delta_a > 0.0f) || !(std::isfinite(delta_b) && delta_b > 0.0f)) return CDL_ERR_PARAM;
+    if (!d_a_hat && !d_b_hat) return CDL_ERR_NULL;
+    // int32 accumulators hold limb (<= 64) x index (<= 128) products over the contraction length
+    if ((d_a_hat && (int64_t)N * 64 * 128 > 2147483647LL) || (d_b_hat && (int64_t)M * 64 * 128 > 2147483647LL))
+        return CDL_ERR_RANGE;
+    if ((int64_t)M * N * K > 0 && (!g || (d_a_hat && !b_idx) || (d_b_hat && !a_idx))) return CDL_ERR_NULL;
+    if (!aligned(g, 16) || !aligned(a_idx, 16) || !aligned(b_idx, 16) || !aligned(d_a_hat, 16) || !aligned(d_b_hat, 16))
+        return CDL_ERR_ALIGN;
+    int rc = check_ws(ws, ws_bytes, qgemm_bwd_workspace_bytes(M, N, K));
+    if (rc != CDL_OK) return rc;
+    return launch_qgemm_bwd(g, a_idx, b_idx, M, N, K, delta_a, delta_b, d_a_hat, d_b_hat, ws, (hipStream_t)hip_stream);
+}
+
+const char *cdl_status_string(int status)
+{
+    switch (status) {
+        case CDL_OK: return "ok";
+        case CDL_ERR_NULL: return "a required pointer is NULL";
+        case CDL_ERR_PARAM: return "invalid size or quantizer parameter";
+        case CDL_ERR_RANGE: return "level set outside int8 or int32 accumulator overflow possible";
+        case CDL_ERR_ALIGN: return "pointer not sufficiently aligned";
+        case CDL_ERR_WORKSPACE: return "workspace missing or too small";
+        case CDL_ERR_HIP: return "a HIP call failed (see cdl_last_hip_error)";
+        default: return "unknown status";
+    }
+}
+
+int cdl_last_hip_error(void) { return cdl::g_last_hip_error.load(); }
+
+int cdl_version(void) { return 100; }
+
+}  // extern "C"

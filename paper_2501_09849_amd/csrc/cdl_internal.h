@@ -1,0 +1,52 @@
+// Internal declarations shared by the translation units of libcdl (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "cdl.h"
+
+namespace cdl {
+
+// Most blocks any quantizer kernel is launched with; also the number of per-block partial
+// results the workspace holds.  256 CUs x 8 resident blocks of 256 threads.
+constexpr int kMaxQuantBlocks = 2048;
+constexpr int kQuantThreads = 256;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Record a failed HIP call; returns CDL_ERR_HIP.
+int hip_failed(hipError_t e);
+
+// Returns CDL_ERR_HIP (and records the code) when the most recent launch failed.
+int check_launch();
+
+// ---- quantizer (cdl_quantizer.hip) -------------------------------------------------------
+size_t quantize_workspace_bytes(int64_t n, int32_t n_levels);
+
+int launch_quantize_fwd(const float *theta, int64_t n, const cdl_qparams &p,
+                        int8_t *idx, float *soft, float *marg, float *entropy_bits,
+                        void *ws, hipStream_t stream);
+
+int launch_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl_qparams &p,
+                        float *dtheta, float *d_delta, float *d_alpha,
+                        void *ws, hipStream_t stream);
+
+// Half-width of the band of levels around the nearest one that the kernels visit for a given
+// kappa = alpha*delta^2 (levels further out carry less than fp32 resolution of the result).
+int quantizer_window(double kappa, int n_levels);
+
+// ---- index GEMMs (cdl_qgemm.hip) ---------------------------------------------------------
+size_t qgemm_fwd_workspace_bytes(int32_t M, int32_t N, int32_t K);
+size_t qgemm_bwd_workspace_bytes(int32_t M, int32_t N, int32_t K);
+
+int launch_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
+                     float delta_a, float delta_b, int32_t *acc, float *y,
+                     void *ws, hipStream_t stream);
+
+int launch_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
+                     int32_t M, int32_t N, int32_t K, float delta_a, float delta_b,
+                     float *d_a_hat, float *d_b_hat, void *ws, hipStream_t stream);
+
+}  // namespace cdl

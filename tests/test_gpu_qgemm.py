@@ -1,0 +1,126 @@
+"""GPU parity of the index GEMMs against the CPU oracle.
+
+Integer accumulators must be bit-exact; fp32 results within 1e-6 + 1e-5|ref|.
+Shapes span several tiles with ragged edges in every dimension, a contraction
+length that is not a multiple of the staging step, and one that is not even a
+multiple of 16 (which takes the padded-copy path).
+"""
+import numpy as np
+import pytest
+
+import cdl_inputs
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+FWD_SHAPES = [(32, 128, 256), (300, 200, 144), (257, 129, 80), (1000, 16, 144), (513, 300, 2304),
+              (70, 50, 100), (1, 1, 16), (5, 3, 7), (256, 128, 64), (700, 130, 1040)]
+
+
+@pytest.mark.parametrize("M,N,K", FWD_SHAPES)
+def test_qgemm_fwd_matches_oracle(oracle, M, N, K):
+    a = cdl_inputs.draw_indices((M, K), -127, 127, seed=M + K)
+    b = cdl_inputs.draw_indices((N, K), -127, 127, seed=N + K + 1)
+    da, db = float(np.float32(0.15092)), float(np.float32(0.0028209))
+    acc, y = gu.qgemm_fwd(a, b, da, db)
+    r_acc, r_y = oracle.qgemm_fwd(a, b, da, db)
+    assert np.array_equal(acc, r_acc), "int32 accumulators differ at %d places" % int((acc != r_acc).sum())
+    gu.assert_close(y, r_y, "y")
+
+
+def test_qgemm_fwd_extreme_indices_do_not_overflow(oracle):
+    M, N, K = 64, 64, 4096
+    a = np.full((M, K), -128, np.int8)
+    b = np.full((N, K), -128, np.int8)
+    b[::2] = 127
+    acc, y = gu.qgemm_fwd(a, b, 1.0, 1.0)
+    r_acc, _ = oracle.qgemm_fwd(a, b, 1.0, 1.0, want_y=False)
+    assert np.array_equal(acc, r_acc)
+
+
+def test_qgemm_fwd_outputs_are_optional(oracle):
+    a = cdl_inputs.draw_indices((130, 96), 0, 15, seed=1)
+    b = cdl_inputs.draw_indices((70, 96), -7, 7, seed=2)
+    acc, y = gu.qgemm_fwd(a, b, 0.5, 0.25)
+    acc2, none_y = gu.qgemm_fwd(a, b, 0.5, 0.25, want_y=False)
+    none_acc, y2 = gu.qgemm_fwd(a, b, 0.5, 0.25, want_acc=False)
+    assert none_y is None and none_acc is None
+    assert np.array_equal(acc, acc2) and np.array_equal(y, y2)
+    assert np.array_equal(y, (acc.astype(np.float32) * np.float32(0.125)))
+
+
+BWD_SHAPES = [(32, 128, 256), (300, 200, 144), (257, 129, 80), (1000, 16, 144), (70, 50, 100), (5, 3, 7),
+              (2048, 96, 320)]
+
+
+@pytest.mark.parametrize("M,N,K", BWD_SHAPES)
+@pytest.mark.parametrize("levels", [(0, 15, -7, 7), (-127, 127, -127, 127)])
+def test_qgemm_bwd_matches_oracle(oracle, M, N, K, levels):
+    a = cdl_inputs.draw_indices((M, K), levels[0], levels[1], seed=M + K)
+    b = cdl_inputs.draw_indices((N, K), levels[2], levels[3], seed=N + K + 1)
+    g = np.random.default_rng(M * 7 + N).standard_normal((M, N)).astype(np.float32)
+    da, db = float(np.float32(0.56419)), float(np.float32(0.016623))
+    d_a, d_b = gu.qgemm_bwd(g, a, b, da, db)
+    r_a, r_b = oracle.qgemm_bwd(g, a, b, da, db)
+    gu.assert_close(d_a, r_a, "d_a_hat")
+    gu.assert_close(d_b, r_b, "d_b_hat")
+
+
+def test_qgemm_bwd_wide_dynamic_range_gradient(oracle):
+    # gradients spanning many binades, a few exact zeros, one large outlier
+    M, N, K = 384, 160, 192
+    rng = np.random.default_rng(4)
+    g = (rng.standard_normal((M, N)) * np.exp(rng.uniform(-12, 2, (M, N)))).astype(np.float32)
+    g[0, :7] = 0.0
+    g[5, 5] = 300.0
+    a = cdl_inputs.draw_indices((M, K), 0, 15, seed=8)
+    b = cdl_inputs.draw_indices((N, K), -7, 7, seed=9)
+    d_a, d_b = gu.qgemm_bwd(g, a, b, 0.25, 0.02)
+    r_a, r_b = oracle.qgemm_bwd(g, a, b, 0.25, 0.02)
+    gu.assert_close(d_a, r_a, "d_a_hat")
+    gu.assert_close(d_b, r_b, "d_b_hat")
+
+
+def test_qgemm_bwd_single_output_and_zero_gradient(oracle):
+    M, N, K = 200, 72, 112
+    a = cdl_inputs.draw_indices((M, K), 0, 15, seed=3)
+    b = cdl_inputs.draw_indices((N, K), -7, 7, seed=4)
+    g = np.random.default_rng(1).standard_normal((M, N)).astype(np.float32)
+    both = gu.qgemm_bwd(g, a, b, 0.5, 0.125)
+    only_a = gu.qgemm_bwd(g, a, b, 0.5, 0.125, want_db=False)
+    only_b = gu.qgemm_bwd(g, a, b, 0.5, 0.125, want_da=False)
+    assert only_a[1] is None and only_b[0] is None
+    assert np.array_equal(both[0], only_a[0]) and np.array_equal(both[1], only_b[1])
+    z = gu.qgemm_bwd(np.zeros((M, N), np.float32), a, b, 0.5, 0.125)
+    assert not z[0].any() and not z[1].any()
+
+
+def test_workload_1_layer_step_end_to_end(oracle):
+    """Quantize W and X, forward product, backward products, quantizer backward: the whole chain on workload 1."""
+    wl = cdl_inputs.workload(1)
+    W, X, G = cdl_inputs.draw_w(wl), cdl_inputs.draw_x(wl), cdl_inputs.draw_g(wl)
+    qw, qx = gu.Quantizer(wl.w_spec), gu.Quantizer(wl.x_spec)
+    wi, _, _, _ = qw.fwd(gu.dev(W.reshape(-1)))
+    xi, _, _, _ = qx.fwd(gu.dev(X.reshape(-1)))
+    wi, xi = wi.reshape(W.shape), xi.reshape(X.shape)
+    r_wi, _, gap_w = oracle.quantize_fwd(W, *qw.args)
+    r_xi, _, gap_x = oracle.quantize_fwd(X, *qx.args)
+    gu.assert_indices(wi, r_wi, gap_w, "w idx")
+    gu.assert_indices(xi, r_xi, gap_x, "x idx")
+    acc, y = gu.qgemm_fwd(xi, wi, wl.x_spec.delta, wl.w_spec.delta)
+    r_acc, r_y = oracle.qgemm_fwd(xi, wi, wl.x_spec.delta, wl.w_spec.delta)
+    assert np.array_equal(acc, r_acc)
+    gu.assert_close(y, r_y, "y")
+    dxh, dwh = gu.qgemm_bwd(G, xi, wi, wl.x_spec.delta, wl.w_spec.delta)
+    r_dxh, r_dwh = oracle.qgemm_bwd(G, xi, wi, wl.x_spec.delta, wl.w_spec.delta)
+    gu.assert_close(dxh, r_dxh, "dL/dQ(x)")
+    gu.assert_close(dwh, r_dwh, "dL/dQ(w)")
+    # quantizer backward fed with the GPU's own fp32 GEMM gradients, oracle fed the same fp32 values
+    dx, ddx, dax = qx.bwd(gu.dev(X.reshape(-1)), gu.dev(dxh.reshape(-1)))
+    dw, ddw, daw = qw.bwd(gu.dev(W.reshape(-1)), gu.dev(dwh.reshape(-1)))
+    rx = oracle.quantize_bwd(X, dxh, *qx.args)
+    rw = oracle.quantize_bwd(W, dwh, *qw.args)
+    gu.assert_close(dx, rx["dtheta"], "dX")
+    gu.assert_close(dw, rw["dtheta"], "dW")
+    gu.assert_close([ddx, ddw], [rx["d_delta"], rw["d_delta"]], "d_delta")
+    gu.assert_close([dax, daw], [rx["d_alpha"], rw["d_alpha"]], "d_alpha")
