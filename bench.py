@@ -1,0 +1,312 @@
+#!/usr/bin/env python3
+"""Benchmark of the CDL quantized layer step on one MI355X.
+
+A "step" is one pass of the whole hot path over one layer-shaped batch of
+seeded synthetic input, in the order of Algorithm 1 of the paper:
+
+    quantize W (indices, soft values, marginal PMF + entropy)
+    quantize X (same)
+    forward product over the indices            Y = dx*dw * Xi . Wi^T
+    backward products                           dL/dQ(X), dL/dQ(W)   (fp32 upstream gradient)
+    quantizer backward for X and for W          dX, dW, d(step), d(sharpness)
+
+All inputs are resident in HBM before the timed region.  The default workload is
+the largest of the five (transformer-MLP-shaped, 8-bit levels).  One JSON line is
+printed; `value` is quantized tensor entries pushed through the whole step per
+second.  Per-kernel times come from HIP events the library records around each
+of its kernels on the launch stream during the timed steps.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload {1,2,3,4,5}]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from collections import OrderedDict
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import cdl_inputs  # noqa: E402
+
+METRIC = "quantizer fwd+bwd Gelem/s (% HBM peak); index-GEMM int8 TOPS (% MFMA peak)"
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def ensure_built():
+    import paper_2501_09849_amd.build as b
+    if not os.path.exists(b.LIB_PATH):
+        log("[bench] libcdl.so missing: building")
+        b.build_lib()
+    import oracle
+    oracle.build(force=False)
+
+
+class Step:
+    """Device buffers and the sequence of library calls of one layer step."""
+
+    def __init__(self, wl, seed=0):
+        import torch
+        import paper_2501_09849_amd as cdl
+        self.torch, self.cdl, self.wl = torch, cdl, wl
+        dev = "cuda:0"
+        t0 = time.time()
+        self.W_host = cdl_inputs.draw_w(wl, seed)
+        self.G_host = cdl_inputs.draw_g(wl, seed)
+        self.X_host = cdl_inputs.draw_x(wl, seed) if wl.has_gemm else None
+        log("[bench] drew inputs in %.1fs" % (time.time() - t0))
+        f32, i8 = torch.float32, torch.int8
+        self.W = torch.from_numpy(self.W_host).to(dev)
+        self.G = torch.from_numpy(self.G_host).to(dev)
+        self.nW = self.W.numel()
+        self.Wi = torch.empty(self.nW, dtype=i8, device=dev)
+        self.Wsoft = torch.empty(self.nW, dtype=f32, device=dev)
+        self.dW = torch.empty(self.nW, dtype=f32, device=dev)
+        self.margW = torch.empty(wl.w_spec.n_levels, dtype=f32, device=dev)
+        self.scal = torch.zeros(8, dtype=f32, device=dev)   # H_w, H_x, d_delta_w, d_alpha_w, d_delta_x, d_alpha_x
+        ws_bytes = cdl.quantize_workspace_bytes(self.nW, wl.w_spec.n_levels)
+        self.nX = 0
+        if wl.has_gemm:
+            M, N, K = wl.M, wl.N, wl.K
+            self.X = torch.from_numpy(self.X_host).to(dev)
+            self.nX = self.X.numel()
+            self.Xi = torch.empty(self.nX, dtype=i8, device=dev)
+            self.Xsoft = torch.empty(self.nX, dtype=f32, device=dev)
+            self.dX = torch.empty(self.nX, dtype=f32, device=dev)
+            self.margX = torch.empty(wl.x_spec.n_levels, dtype=f32, device=dev)
+            self.Y = torch.empty((M, N), dtype=f32, device=dev)
+            self.dXh = torch.empty((M, K), dtype=f32, device=dev)
+            self.dWh = torch.empty((N, K), dtype=f32, device=dev)
+            ws_bytes = max(ws_bytes, cdl.quantize_workspace_bytes(self.nX, wl.x_spec.n_levels),
+                           cdl.qgemm_fwd_workspace_bytes(M, N, K), cdl.qgemm_bwd_workspace_bytes(M, N, K))
+        self.ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+
+    def run(self):
+        cdl, wl, s = self.cdl, self.wl, self.scal
+        w, x = wl.w_spec, wl.x_spec
+        wa = (w.lo, w.n_levels, w.delta, w.alpha)
+        cdl.cdl_quantize_fwd(self.W, self.nW, *wa, self.Wi, self.Wsoft, self.margW, s[0:1], self.ws)
+        if not wl.has_gemm:
+            cdl.cdl_quantize_bwd(self.W, self.G, self.nW, *wa, self.dW, s[2:3], s[3:4], self.ws)
+            return
+        xa = (x.lo, x.n_levels, x.delta, x.alpha)
+        M, N, K = wl.M, wl.N, wl.K
+        cdl.cdl_quantize_fwd(self.X, self.nX, *xa, self.Xi, self.Xsoft, self.margX, s[1:2], self.ws)
+        cdl.cdl_qgemm_fwd(self.Xi, self.Wi, M, N, K, x.delta, w.delta, None, self.Y, self.ws)
+        cdl.cdl_qgemm_bwd(self.G, self.Xi, self.Wi, M, N, K, x.delta, w.delta, self.dXh, self.dWh, self.ws)
+        cdl.cdl_quantize_bwd(self.X, self.dXh, self.nX, *xa, self.dX, s[4:5], s[5:6], self.ws)
+        cdl.cdl_quantize_bwd(self.W, self.dWh, self.nW, *wa, self.dW, s[2:3], s[3:4], self.ws)
+
+
+def kernel_model(wl, name, occurrence):
+    """Algorithmic work of one launch: (bound, amount, unit of rate) - bytes for HBM-bound kernels, int8 ops for GEMMs.
+
+    Quantizer forward: reads theta (4 B), writes index (1 B) and soft value (4 B) = 9 B per entry.
+    Quantizer backward: reads theta and g (8 B), writes dtheta (4 B) = 12 B per entry.
+    Index GEMMs: 2*M*N*K integer operations of the product being formed (for the limb kernels this is the
+    product the caller asked for, not the limbs issued).
+    """
+    nW = wl.flat_n if wl.flat_n else wl.N * wl.K
+    nX = wl.M * wl.K
+    # per step the quantizer kernels run first on W, then on X (forward) and first on X, then on W (backward)
+    if name == "quantize_fwd_kernel":
+        n = nW if occurrence == 0 else nX
+        return "hbm", 9.0 * n, n
+    if name == "quantize_bwd_kernel":
+        n = (nX if occurrence == 0 else nW) if wl.has_gemm else nW
+        return "hbm", 12.0 * n, n
+    if name.startswith("qgemm_kernel"):
+        return "mfma", 2.0 * wl.M * wl.N * wl.K, 0
+    if name == "split_rows_kernel" or name == "split_cols_kernel" or name == "absmax_kernel":
+        return "hbm", 4.0 * wl.M * wl.N, 0          # reads g once (limb planes written on top are scratch traffic)
+    return None, 0.0, 0
+
+
+def cpu_baseline(wl, step):
+    """Times the oracle, as it is, on a bounded sample of the same workload and scales to one step."""
+    import oracle
+    parts = []
+    t_all = time.time()
+
+    def timed(f):
+        t = time.perf_counter()
+        f()
+        return time.perf_counter() - t
+
+    est = 0.0
+    w, x = wl.w_spec, wl.x_spec
+    for name, host, spec, n_full in (("W", step.W_host, w, step.nW),) + ((("X", step.X_host, x, step.nX),) if wl.has_gemm else ()):
+        flat = host.reshape(-1)
+        n_s = int(min(n_full, max(4096, 400_000_000 // spec.n_levels)))
+        th = flat[:n_s]
+        g = step.G_host.reshape(-1)[:n_s]
+        a = (spec.lo, spec.n_levels, spec.delta, spec.alpha)
+        dt = timed(lambda: oracle.quantize_fwd(th, *a)) + timed(lambda: oracle.marginal_entropy(th, *a)) \
+            + timed(lambda: oracle.quantize_bwd(th, g, *a))
+        est += dt * n_full / n_s
+        parts.append("quantizer %s: %d of %d entries %.2fs" % (name, n_s, n_full, dt))
+    if wl.has_gemm:
+        M, N, K = wl.M, wl.N, wl.K
+        rows = int(max(1, min(M, 6.0e9 // (3.0 * N * K))))
+        xi = cdl_inputs.draw_indices((rows, K), x.lo, x.hi, seed=1)   # timing does not depend on the index values
+        wi = cdl_inputs.draw_indices((N, K), w.lo, w.hi, seed=2)
+        g = step.G_host[:rows]
+        dt = timed(lambda: oracle.qgemm_fwd(xi, wi, x.delta, w.delta)) + timed(lambda: oracle.qgemm_bwd(g, xi, wi, x.delta, w.delta))
+        est += dt * M / rows
+        parts.append("GEMM fwd+bwd: %d of %d rows %.2fs" % (rows, M, dt))
+    n_total = step.nW + step.nX
+    return {
+        "value": n_total / est / 1e9, "unit": "Gelem/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": "; ".join(parts) + "; scaled linearly to one full step (%.0fs estimated), measured in %.1fs"
+                  % (est, time.time() - t_all),
+    }
+
+
+def quantizer_only(seed=0, iters=10):
+    """Quantizer fwd+bwd on the 25.6 M-entry flat weight tensor (31 levels): Gelem/s and fraction of HBM peak."""
+    import paper_2501_09849_amd as cdl
+    import torch
+    wl = cdl_inputs.workload(4)
+    st = Step(wl, seed)
+    for _ in range(3):
+        st.run()
+    torch.cuda.synchronize()
+    cdl.cdl_profile_enable(True)
+    for _ in range(iters):
+        st.run()
+    torch.cuda.synchronize()
+    recs = cdl.cdl_profile_collect()
+    cdl.cdl_profile_enable(False)
+    t = {}
+    for k, ms in recs:
+        t.setdefault(k, []).append(ms)
+    fwd = float(np.mean(t["quantize_fwd_kernel"])) + float(np.mean(t["marginal_finalize_kernel"]))
+    bwd = float(np.mean(t["quantize_bwd_kernel"])) + float(np.mean(t["scalar_finalize_kernel"]))
+    n = wl.flat_n
+    gbs = 21.0 * n / ((fwd + bwd) * 1e-3) / 1e9
+    return {"workload": wl.name, "n": n, "levels": wl.w_spec.n_levels, "fwd_us": fwd * 1e3, "bwd_us": bwd * 1e3,
+            "gelem_per_s": n / ((fwd + bwd) * 1e-3) / 1e9, "algorithmic_GBps": gbs, "hbm_frac": gbs / HBM_PEAK_GBS,
+            "kappa": wl.w_spec.alpha * wl.w_spec.delta ** 2}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on one GPU only (no sharding, no collectives); --gpus %d is not supported" % args.gpus)
+        sys.exit(2)
+
+    ensure_built()
+    import torch
+    import paper_2501_09849_amd as cdl
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(3)
+    cdl.load()
+    wl = cdl_inputs.workload(args.workload)
+    st = Step(wl)
+
+    for _ in range(args.warmup):
+        st.run()
+    torch.cuda.synchronize()
+
+    cdl.cdl_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        st.run()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    recs = cdl.cdl_profile_collect()
+    cdl.cdl_profile_enable(False)
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    n_total = st.nW + st.nX
+    value = n_total / (elapsed / args.steps) / 1e9
+
+    # per-kernel table: launches are grouped by (name, position among same-named launches within a step)
+    per_step = len(recs) // args.steps
+    table = OrderedDict()
+    for s in range(args.steps):
+        seen = {}
+        for name, ms in recs[s * per_step:(s + 1) * per_step]:
+            occ = seen.get(name, 0)
+            seen[name] = occ + 1
+            table.setdefault((name, occ), []).append(ms)
+    kernels = []
+    for (name, occ), v in table.items():
+        avg = float(np.mean(v))
+        bound, amount, n_el = kernel_model(wl, name, occ)
+        row = {"kernel": name, "launch": occ, "avg_us": avg * 1e3, "min_us": float(np.min(v)) * 1e3}
+        if bound == "hbm":
+            row.update(bound="hbm", algorithmic_GBps=amount / (avg * 1e-3) / 1e9,
+                       frac=amount / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS)
+        elif bound == "mfma":
+            row.update(bound="mfma", algorithmic_TOPS=amount / (avg * 1e-3) / 1e12,
+                       frac=amount / (avg * 1e-3) / 1e12 / INT8_PEAK_TOPS)
+        kernels.append(row)
+    dom = max(kernels, key=lambda r: r["avg_us"])
+    if dom.get("bound") == "mfma":
+        roofline = {"kernel": "%s #%d" % (dom["kernel"], dom["launch"]), "bound": "mfma", "achieved": dom["algorithmic_TOPS"],
+                    "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": dom["frac"], "traffic": None,
+                    "avg_launch_us": dom["avg_us"]}
+    else:
+        roofline = {"kernel": "%s #%d" % (dom["kernel"], dom["launch"]), "bound": "hbm", "achieved": dom.get("algorithmic_GBps"),
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom.get("frac"), "traffic": None,
+                    "avg_launch_us": dom["avg_us"]}
+
+    out = OrderedDict()
+    out["metric"] = METRIC
+    out["value"] = value
+    out["unit"] = "Gelem/s"
+    out["n_gpus"] = 1
+    out["steps"] = args.steps
+    out["warmup"] = args.warmup
+    out["ms_per_step"] = ms_per_step
+    out["higher_is_better"] = True
+    out["scaling"] = "weak"
+    out["vs_baseline"] = None
+    out["dtype"] = "f32 quantizer, int8 x int8 -> int32 products"
+    out["data"] = "synthetic"
+    cfg = {"workload": "%d:%s" % (wl.number, wl.name), "entries_per_step": n_total,
+           "w_levels": wl.w_spec.n_levels, "kappa": wl.w_spec.alpha * wl.w_spec.delta ** 2}
+    if wl.has_gemm:
+        cfg.update(M=wl.M, N=wl.N, K=wl.K, x_levels=wl.x_spec.n_levels)
+    out["config"] = cfg
+    out["roofline"] = roofline
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, st)
+    out["kernels"] = kernels
+    q_us = sum(r["avg_us"] for r in kernels if r["kernel"] in ("quantize_fwd_kernel", "quantize_bwd_kernel",
+                                                                 "marginal_finalize_kernel", "scalar_finalize_kernel"))
+    out["quantizer_fwd_bwd_gelem_per_s"] = n_total / (q_us * 1e-6) / 1e9 if q_us else None
+    gf = [r for r in kernels if r["kernel"] == "qgemm_kernel(fwd)"]
+    if gf:
+        out["index_gemm_fwd_TOPS"] = gf[0]["algorithmic_TOPS"]
+        out["index_gemm_fwd_frac_of_int8_peak"] = gf[0]["frac"]
+    del st
+    torch.cuda.empty_cache()
+    if not args.no_extra and wl.number != 4:
+        out["quantizer_only_flat_25M"] = quantizer_only()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -126,13 +126,31 @@ int cdl_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N
  * step; these are the dL/dQ_p factors of eq. partialX3 / partialW3).  g: fp32[M,N] = dL/dy.
  *   d_a_hat[m,k] = delta_b * sum_n g[m,n] * b_idx[n,k]                       (fp32[M,K], nullable)
  *   d_b_hat[n,k] = delta_a * sum_m g[m,n] * a_idx[m,k]                       (fp32[N,K], nullable)
- * The gradient stays fp32 (the paper quantizes weights and activations only); the sums are
- * evaluated exactly on integer limbs of g, see the design notes.  At least one output non-NULL.
+ * The gradient stays fp32 (the paper quantizes weights and activations only).  Internally g is
+ * written as sigma * sum_l limb_l * 2^(-7l) with int8 limbs and one power-of-two sigma, each limb
+ * product is accumulated exactly in int32 and the limbs are recombined in double; enough limbs are
+ * taken that the remainder contributes less than 1.5e-7 absolute.  At least one output non-NULL.
  */
 int cdl_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
                   int32_t M, int32_t N, int32_t K, float delta_a, float delta_b,
                   float *d_a_hat, float *d_b_hat,
                   void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Optional per-kernel timing (a measurement aid, not part of the method).  While enabled, every
+ * kernel the library enqueues is bracketed by a pair of HIP events recorded on the caller's
+ * stream.  cdl_profile_collect waits for the recorded events, writes up to max_records entries
+ * (launch order) into `out` (HOST memory), forgets them and returns how many it wrote, or a
+ * negative cdl_status.  Enabling creates HIP events, which is the only place the library
+ * allocates anything; it is off by default.
+ */
+typedef struct cdl_profile_record {
+    char  kernel[56];   /* name of the kernel, NUL-terminated */
+    float ms;           /* elapsed time between its two events */
+} cdl_profile_record;
+
+int cdl_profile_enable(int enable);
+int cdl_profile_collect(cdl_profile_record *out, int max_records);
 
 /* Text for a cdl_status. */
 const char *cdl_status_string(int status);

@@ -17,6 +17,7 @@ _LIB = None
 EXPORTS = (
     "cdl_quantize_workspace_bytes", "cdl_qgemm_fwd_workspace_bytes", "cdl_qgemm_bwd_workspace_bytes",
     "cdl_quantize_fwd", "cdl_quantize_bwd", "cdl_marginal_entropy", "cdl_qgemm_fwd", "cdl_qgemm_bwd",
+    "cdl_profile_enable", "cdl_profile_collect",
     "cdl_status_string", "cdl_last_hip_error", "cdl_version",
 )
 
@@ -34,6 +35,11 @@ class QParams(ctypes.Structure):
     """struct cdl_qparams"""
     _fields_ = [("lo", ctypes.c_int32), ("n_levels", ctypes.c_int32),
                 ("delta", ctypes.c_float), ("alpha", ctypes.c_float)]
+
+
+class ProfileRecord(ctypes.Structure):
+    """struct cdl_profile_record"""
+    _fields_ = [("kernel", ctypes.c_char * 56), ("ms", ctypes.c_float)]
 
 
 def lib_path() -> str:
@@ -66,6 +72,10 @@ def load():
         L.cdl_qgemm_fwd.argtypes = [vp, vp, i32, i32, i32, f32, f32, vp, vp, vp, sz, vp]
         L.cdl_qgemm_bwd.restype = ctypes.c_int
         L.cdl_qgemm_bwd.argtypes = [vp, vp, vp, i32, i32, i32, f32, f32, vp, vp, vp, sz, vp]
+        L.cdl_profile_enable.restype = ctypes.c_int
+        L.cdl_profile_enable.argtypes = [ctypes.c_int]
+        L.cdl_profile_collect.restype = ctypes.c_int
+        L.cdl_profile_collect.argtypes = [ctypes.POINTER(ProfileRecord), ctypes.c_int]
         L.cdl_status_string.restype = ctypes.c_char_p
         L.cdl_status_string.argtypes = [ctypes.c_int]
         L.cdl_last_hip_error.restype = ctypes.c_int
@@ -154,3 +164,16 @@ def cdl_qgemm_bwd(g, a_idx, b_idx, M, N, K, delta_a, delta_b, d_a_hat=None, d_b_
     wp, wb = _ws(ws)
     _check(load().cdl_qgemm_bwd(_ptr(g), _ptr(a_idx), _ptr(b_idx), M, N, K, delta_a, delta_b,
                                 _ptr(d_a_hat), _ptr(d_b_hat), wp, wb, _stream(stream)), "cdl_qgemm_bwd")
+
+
+def cdl_profile_enable(enable: bool) -> None:
+    _check(load().cdl_profile_enable(1 if enable else 0), "cdl_profile_enable")
+
+
+def cdl_profile_collect(max_records: int = 65536):
+    """Waits for the recorded events; returns [(kernel name, milliseconds), ...] in launch order."""
+    buf = (ProfileRecord * max_records)()
+    n = load().cdl_profile_collect(buf, max_records)
+    if n < 0:
+        raise CdlError(n, "cdl_profile_collect")
+    return [(buf[i].kernel.decode(), float(buf[i].ms)) for i in range(n)]

@@ -3,6 +3,9 @@
 
 #include <atomic>
 #include <cmath>
+#include <cstring>
+#include <mutex>
+#include <vector>
 
 namespace cdl {
 
@@ -20,6 +23,48 @@ int check_launch()
 {
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? (int)CDL_OK : hip_failed(e);
+}
+
+// ---- per-kernel timing ---------------------------------------------------------------------
+namespace {
+struct ProfileRec {
+    const char *name;
+    hipEvent_t start, stop;
+};
+std::atomic<bool> g_profile_on{false};
+std::mutex g_profile_mutex;
+std::vector<ProfileRec> g_profile_recs;      // recorded, not yet collected
+std::vector<hipEvent_t> g_profile_free;      // events ready for reuse
+
+hipEvent_t profile_event()
+{
+    if (!g_profile_free.empty()) {
+        hipEvent_t e = g_profile_free.back();
+        g_profile_free.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+}  // namespace
+
+ProfileScope::ProfileScope(const char *name, hipStream_t stream) : slot_(-1), stream_(stream)
+{
+    if (!g_profile_on.load(std::memory_order_relaxed)) return;
+    std::lock_guard<std::mutex> lock(g_profile_mutex);
+    ProfileRec r{name, profile_event(), profile_event()};
+    if (!r.start || !r.stop) return;
+    (void)hipEventRecord(r.start, stream);
+    g_profile_recs.push_back(r);
+    slot_ = (int)g_profile_recs.size() - 1;
+}
+
+ProfileScope::~ProfileScope()
+{
+    if (slot_ < 0) return;
+    std::lock_guard<std::mutex> lock(g_profile_mutex);
+    if (slot_ < (int)g_profile_recs.size()) (void)hipEventRecord(g_profile_recs[slot_].stop, stream_);
 }
 
 namespace {
@@ -156,6 +201,38 @@ int cdl_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
     int rc = check_ws(ws, ws_bytes, qgemm_bwd_workspace_bytes(M, N, K));
     if (rc != CDL_OK) return rc;
     return launch_qgemm_bwd(g, a_idx, b_idx, M, N, K, delta_a, delta_b, d_a_hat, d_b_hat, ws, (hipStream_t)hip_stream);
+}
+
+int cdl_profile_enable(int enable)
+{
+    cdl::g_profile_on.store(enable != 0);
+    return CDL_OK;
+}
+
+int cdl_profile_collect(cdl_profile_record *out, int max_records)
+{
+    if (max_records < 0 || (max_records > 0 && !out)) return CDL_ERR_PARAM;
+    std::lock_guard<std::mutex> lock(cdl::g_profile_mutex);
+    int n = 0;
+    for (const cdl::ProfileRec &r : cdl::g_profile_recs) {
+        float ms = 0.0f;
+        hipError_t e = hipEventSynchronize(r.stop);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.start, r.stop);
+        if (e != hipSuccess) {
+            cdl::g_profile_recs.clear();
+            return hip_failed(e);
+        }
+        if (n < max_records) {
+            std::memset(&out[n], 0, sizeof(out[n]));
+            std::strncpy(out[n].kernel, r.name, sizeof(out[n].kernel) - 1);
+            out[n].ms = ms;
+            ++n;
+        }
+        cdl::g_profile_free.push_back(r.start);
+        cdl::g_profile_free.push_back(r.stop);
+    }
+    cdl::g_profile_recs.clear();
+    return n;
 }
 
 const char *cdl_status_string(int status)

@@ -22,6 +22,25 @@ int hip_failed(hipError_t e);
 // Returns CDL_ERR_HIP (and records the code) when the most recent launch failed.
 int check_launch();
 
+// Brackets the kernels launched during its lifetime with two HIP events when profiling is on.
+class ProfileScope {
+public:
+    ProfileScope(const char *name, hipStream_t stream);
+    ~ProfileScope();
+    ProfileScope(const ProfileScope &) = delete;
+    ProfileScope &operator=(const ProfileScope &) = delete;
+private:
+    int slot_;
+    hipStream_t stream_;
+};
+
+// Launch KERNEL on STREAM, timed under NAME when profiling is on.
+#define CDL_LAUNCH(NAME, STREAM, KERNEL, GRID, BLOCK, LDS, ...)                       \
+    do {                                                                              \
+        ::cdl::ProfileScope cdl_ps_(NAME, STREAM);                                    \
+        hipLaunchKernelGGL(KERNEL, GRID, BLOCK, LDS, STREAM, __VA_ARGS__);            \
+    } while (0)
+
 // ---- quantizer (cdl_quantizer.hip) -------------------------------------------------------
 size_t quantize_workspace_bytes(int64_t n, int32_t n_levels);
 

@@ -223,7 +223,7 @@ int launch_gemm(GemmArgs a, hipStream_t stream)
     const int64_t total = (int64_t)a.tiles_m * a.tiles_n;
     if (total == 0) return CDL_OK;
     const int64_t grid = (total + 7) / 8 * 8;
-    hipLaunchKernelGGL((qgemm_kernel<TM, TN, LIMBS>), dim3((unsigned)grid), dim3(kGemmThreads), 0, stream, a);
+    CDL_LAUNCH(a.plan ? (a.which ? "qgemm_kernel(limbs, d_b_hat)" : "qgemm_kernel(limbs, d_a_hat)") : "qgemm_kernel(fwd)", stream, (qgemm_kernel<TM, TN, LIMBS>), dim3((unsigned)grid), dim3(kGemmThreads), 0, a);
     return check_launch();
 }
 
@@ -437,8 +437,8 @@ int launch_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_
 {
     if ((int64_t)M * N == 0) return CDL_OK;
     if (K == 0) {
-        if (acc) hipLaunchKernelGGL(zero_i32_kernel, dim3(blocks_for((int64_t)M * N, 256, 4096)), dim3(256), 0, stream, acc, (int64_t)M * N);
-        if (y) hipLaunchKernelGGL(zero_f32_kernel, dim3(blocks_for((int64_t)M * N, 256, 4096)), dim3(256), 0, stream, y, (int64_t)M * N);
+        if (acc) CDL_LAUNCH("zero_i32_kernel", stream, zero_i32_kernel, dim3(blocks_for((int64_t)M * N, 256, 4096)), dim3(256), 0, acc, (int64_t)M * N);
+        if (y) CDL_LAUNCH("zero_f32_kernel", stream, zero_f32_kernel, dim3(blocks_for((int64_t)M * N, 256, 4096)), dim3(256), 0, y, (int64_t)M * N);
         return check_launch();
     }
     GemmArgs g{};
@@ -449,8 +449,8 @@ int launch_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_
         const int kp = (int)pad_to(K, 16);
         int8_t *ap = reinterpret_cast<int8_t *>(ws);
         int8_t *bp = ap + align_up((size_t)M * (size_t)kp, 256);
-        hipLaunchKernelGGL(pad_rows_kernel, dim3(blocks_for((int64_t)M * kp, 256, 8192)), dim3(256), 0, stream, a_idx, (int64_t)M, K, ap, kp);
-        hipLaunchKernelGGL(pad_rows_kernel, dim3(blocks_for((int64_t)N * kp, 256, 8192)), dim3(256), 0, stream, b_idx, (int64_t)N, K, bp, kp);
+        CDL_LAUNCH("pad_rows_kernel", stream, pad_rows_kernel, dim3(blocks_for((int64_t)M * kp, 256, 8192)), dim3(256), 0, a_idx, (int64_t)M, K, ap, kp);
+        CDL_LAUNCH("pad_rows_kernel", stream, pad_rows_kernel, dim3(blocks_for((int64_t)N * kp, 256, 8192)), dim3(256), 0, b_idx, (int64_t)N, K, bp, kp);
         int rc = check_launch();
         if (rc != CDL_OK) return rc;
         g.A = ap; g.B = bp; g.lda = kp; g.ldb = kp; g.Kc = kp;
@@ -466,9 +466,9 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
                      float *d_a_hat, float *d_b_hat, void *ws, hipStream_t stream)
 {
     if (d_a_hat && ((int64_t)M * K > 0) && N == 0)
-        hipLaunchKernelGGL(zero_f32_kernel, dim3(blocks_for((int64_t)M * K, 256, 4096)), dim3(256), 0, stream, d_a_hat, (int64_t)M * K);
+        CDL_LAUNCH("zero_f32_kernel", stream, zero_f32_kernel, dim3(blocks_for((int64_t)M * K, 256, 4096)), dim3(256), 0, d_a_hat, (int64_t)M * K);
     if (d_b_hat && ((int64_t)N * K > 0) && M == 0)
-        hipLaunchKernelGGL(zero_f32_kernel, dim3(blocks_for((int64_t)N * K, 256, 4096)), dim3(256), 0, stream, d_b_hat, (int64_t)N * K);
+        CDL_LAUNCH("zero_f32_kernel", stream, zero_f32_kernel, dim3(blocks_for((int64_t)N * K, 256, 4096)), dim3(256), 0, d_b_hat, (int64_t)N * K);
     if ((int64_t)M * N * K == 0) return check_launch();
 
     const BwdLayout L = bwd_layout(M, N, K);
@@ -479,20 +479,20 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
     int8_t *la = reinterpret_cast<int8_t *>(base + L.la);
     int8_t *lb = reinterpret_cast<int8_t *>(base + L.lb);
 
-    hipLaunchKernelGGL(plan_init_kernel, dim3(1), dim3(1), 0, stream, plan);
-    hipLaunchKernelGGL(absmax_kernel, dim3(blocks_for(((int64_t)M * N) >> 2, 256, 2048)), dim3(256), 0, stream, gr, (int64_t)M * N, plan);
+    CDL_LAUNCH("plan_init_kernel", stream, plan_init_kernel, dim3(1), dim3(1), 0, plan);
+    CDL_LAUNCH("absmax_kernel", stream, absmax_kernel, dim3(blocks_for(((int64_t)M * N) >> 2, 256, 2048)), dim3(256), 0, gr, (int64_t)M * N, plan);
     if (d_a_hat)
-        hipLaunchKernelGGL(transpose_i8_kernel, dim3((K + 63) / 64, (unsigned)(L.ldn / 64)), dim3(256), 0, stream,
+        CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel, dim3((K + 63) / 64, (unsigned)(L.ldn / 64)), dim3(256), 0,
                            b_idx, N, K, bt, (int)L.ldn, &plan->sumsq_b);
     if (d_b_hat)
-        hipLaunchKernelGGL(transpose_i8_kernel, dim3((K + 63) / 64, (unsigned)(L.ldm / 64)), dim3(256), 0, stream,
+        CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel, dim3((K + 63) / 64, (unsigned)(L.ldm / 64)), dim3(256), 0,
                            a_idx, M, K, at, (int)L.ldm, &plan->sumsq_a);
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1), 0, stream, plan, M, N, K, delta_a, delta_b);
+    CDL_LAUNCH("plan_kernel", stream, plan_kernel, dim3(1), dim3(1), 0, plan, M, N, K, delta_a, delta_b);
     int rc = check_launch();
     if (rc != CDL_OK) return rc;
 
     if (d_a_hat) {
-        hipLaunchKernelGGL(split_rows_kernel, dim3(blocks_for(L.la_plane, 256, 16384)), dim3(256), 0, stream,
+        CDL_LAUNCH("split_rows_kernel", stream, split_rows_kernel, dim3(blocks_for(L.la_plane, 256, 16384)), dim3(256), 0,
                            gr, M, N, (int)L.ldn, la, L.la_plane, plan);
         GemmArgs g{};
         g.A = la; g.lda = L.ldn; g.a_plane = L.la_plane;
@@ -504,7 +504,7 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
         if (rc != CDL_OK) return rc;
     }
     if (d_b_hat) {
-        hipLaunchKernelGGL(split_cols_kernel, dim3((N + 63) / 64, (unsigned)(L.ldm / 64)), dim3(256), 0, stream,
+        CDL_LAUNCH("split_cols_kernel", stream, split_cols_kernel, dim3((N + 63) / 64, (unsigned)(L.ldm / 64)), dim3(256), 0,
                            gr, M, N, (int)L.ldm, lb, L.lb_plane, plan);
         GemmArgs g{};
         g.A = lb; g.lda = L.ldm; g.a_plane = L.lb_plane;

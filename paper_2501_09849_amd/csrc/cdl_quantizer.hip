@@ -416,8 +416,9 @@ void launch_fwd_w(bool want_idx, bool want_soft, bool want_marg, int grid, size_
                   const float *theta, int64_t n, const QConst &k, int8_t *idx, float *soft, float *partial)
 {
 #define CDL_FWD(I, S, M) \
-    hipLaunchKernelGGL((quantize_fwd_kernel<W, I, S, M>), dim3(grid), dim3(kQuantThreads), (M) ? lds : 0, s, \
-                       theta, n, k, idx, soft, partial)
+    CDL_LAUNCH((I) ? "quantize_fwd_kernel" : "quantize_fwd_kernel(marginal only)", s,                     \
+               (quantize_fwd_kernel<W, I, S, M>), dim3(grid), dim3(kQuantThreads), (M) ? lds : 0,         \
+               theta, n, k, idx, soft, partial)
     if (want_idx && want_soft && want_marg) CDL_FWD(true, true, true);
     else if (want_idx && want_soft) CDL_FWD(true, true, false);
     else if (want_idx && want_marg) CDL_FWD(true, false, true);
@@ -431,7 +432,8 @@ void launch_bwd_w(bool want_dtheta, bool want_scalars, int grid, hipStream_t s, 
                   const float *g, int64_t n, const QConst &k, float *dtheta, double *partial)
 {
 #define CDL_BWD(D, S) \
-    hipLaunchKernelGGL((quantize_bwd_kernel<W, D, S>), dim3(grid), dim3(kQuantThreads), 0, s, theta, g, n, k, dtheta, partial)
+    CDL_LAUNCH("quantize_bwd_kernel", s, (quantize_bwd_kernel<W, D, S>), dim3(grid), dim3(kQuantThreads), 0, \
+               theta, g, n, k, dtheta, partial)
     if (want_dtheta && want_scalars) CDL_BWD(true, true);
     else if (want_dtheta) CDL_BWD(true, false);
     else CDL_BWD(false, true);
@@ -466,7 +468,7 @@ int launch_quantize_fwd(const float *theta, int64_t n, const cdl_qparams &p,
     const bool want_marg = (marg != nullptr) || (entropy_bits != nullptr);
     if (n == 0) {
         if (want_marg) {
-            hipLaunchKernelGGL(zero_floats_kernel, dim3(1), dim3(256), 0, stream, marg, marg ? p.n_levels : 0,
+            CDL_LAUNCH("zero_floats_kernel", stream, zero_floats_kernel, dim3(1), dim3(256), 0, marg, marg ? p.n_levels : 0,
                                entropy_bits, entropy_bits ? 1 : 0, (float *)nullptr, 0);
             return check_launch();
         }
@@ -487,7 +489,7 @@ int launch_quantize_fwd(const float *theta, int64_t n, const cdl_qparams &p,
     int rc = check_launch();
     if (rc != CDL_OK) return rc;
     if (want_marg) {
-        hipLaunchKernelGGL(marginal_finalize_kernel, dim3(1), dim3(1024), 0, stream, partial, grid, p.n_levels,
+        CDL_LAUNCH("marginal_finalize_kernel", stream, marginal_finalize_kernel, dim3(1), dim3(1024), 0, partial, grid, p.n_levels,
                            1.0 / (double)n, marg, entropy_bits);
         rc = check_launch();
     }
@@ -500,7 +502,7 @@ int launch_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl
     const bool want_scalars = (d_delta != nullptr) || (d_alpha != nullptr);
     if (n == 0) {
         if (want_scalars) {
-            hipLaunchKernelGGL(zero_floats_kernel, dim3(1), dim3(64), 0, stream, d_delta, d_delta ? 1 : 0,
+            CDL_LAUNCH("zero_floats_kernel", stream, zero_floats_kernel, dim3(1), dim3(64), 0, d_delta, d_delta ? 1 : 0,
                                d_alpha, d_alpha ? 1 : 0, (float *)nullptr, 0);
             return check_launch();
         }
@@ -521,7 +523,7 @@ int launch_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl
     if (rc != CDL_OK) return rc;
     if (want_scalars) {
         const double d = (double)p.delta;
-        hipLaunchKernelGGL(scalar_finalize_kernel, dim3(1), dim3(256), 0, stream, partial, grid, d * d * d,
+        CDL_LAUNCH("scalar_finalize_kernel", stream, scalar_finalize_kernel, dim3(1), dim3(256), 0, partial, grid, d * d * d,
                            d_delta, d_alpha);
         rc = check_launch();
     }

@@ -1,0 +1,131 @@
+"""Host-side checks of the C boundary that need no GPU: the library loads, exports every symbol the
+header declares, sizes its workspaces sensibly and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def cdl():
+    import paper_2501_09849_amd as pkg
+    import paper_2501_09849_amd.build as b
+    if not os.path.exists(b.LIB_PATH):
+        b.build_lib()
+    pkg.load()
+    return pkg
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "cdl.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cdl_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_entry_point(cdl):
+    lib = cdl.load()
+    declared = _declared_functions()
+    assert {"cdl_quantize_fwd", "cdl_quantize_bwd", "cdl_marginal_entropy", "cdl_qgemm_fwd", "cdl_qgemm_bwd"} <= set(declared)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sorted(cdl.EXPORTS) == declared
+    assert lib.cdl_version() >= 100
+    assert lib.cdl_status_string(0) == b"ok" and lib.cdl_status_string(-3) != lib.cdl_status_string(-2)
+
+
+def test_workspace_queries(cdl):
+    assert cdl.quantize_workspace_bytes(0, 15) > 0
+    assert cdl.quantize_workspace_bytes(10**9, 255) >= cdl.quantize_workspace_bytes(10, 15)
+    assert cdl.quantize_workspace_bytes(10, 1) == 0 and cdl.quantize_workspace_bytes(-1, 15) == 0
+    assert cdl.qgemm_fwd_workspace_bytes(64, 64, 64) == 0
+    assert cdl.qgemm_fwd_workspace_bytes(64, 64, 70) >= (64 + 64) * 80
+    small, big = cdl.qgemm_bwd_workspace_bytes(32, 128, 256), cdl.qgemm_bwd_workspace_bytes(65536, 3072, 768)
+    assert 0 < small < big
+    assert cdl.qgemm_bwd_workspace_bytes(0, 3, 4) == 0
+
+
+def _q(lo, n, delta, alpha):
+    from paper_2501_09849_amd.binding import QParams
+    return ctypes.byref(QParams(lo, n, delta, alpha))
+
+
+OK, NULL, PARAM, RANGE, ALIGN, WS = 0, -1, -2, -3, -4, -5
+FAKE = 0x1000   # a well-aligned non-NULL address that is never dereferenced: every call below must fail first
+
+
+def test_quantizer_argument_validation_happens_before_any_gpu_work(cdl):
+    lib = cdl.load()
+    good = _q(-7, 15, 0.02, 1e4)
+    f = lib.cdl_quantize_fwd
+    assert f(FAKE, 16, None, FAKE, None, None, None, None, 0, None) == NULL
+    assert f(FAKE, 16, _q(-7, 1, 0.02, 1e4), FAKE, None, None, None, None, 0, None) == PARAM
+    assert f(FAKE, 16, _q(-7, 15, 0.0, 1e4), FAKE, None, None, None, None, 0, None) == PARAM
+    assert f(FAKE, 16, _q(-7, 15, 0.02, -1.0), FAKE, None, None, None, None, 0, None) == PARAM
+    assert f(FAKE, 16, _q(-7, 15, float("nan"), 1.0), FAKE, None, None, None, None, 0, None) == PARAM
+    assert f(FAKE, 16, _q(-7, 15, 0.02, float("inf")), FAKE, None, None, None, None, 0, None) == PARAM
+    assert f(FAKE, 16, _q(0, 256, 0.02, 1e4), FAKE, None, None, None, None, 0, None) == RANGE    # the unsigned 8-bit set
+    assert f(FAKE, 16, _q(-129, 4, 0.02, 1e4), FAKE, None, None, None, None, 0, None) == RANGE
+    assert f(FAKE, -1, good, FAKE, None, None, None, None, 0, None) == PARAM
+    assert f(None, 16, good, FAKE, None, None, None, None, 0, None) == NULL
+    assert f(FAKE, 16, good, None, None, None, None, None, 0, None) == NULL
+    assert f(FAKE + 4, 16, good, FAKE, None, None, None, None, 0, None) == ALIGN
+    assert f(FAKE, 16, good, FAKE + 1, None, None, None, None, 0, None) == ALIGN
+    assert f(FAKE, 16, good, FAKE, FAKE + 8, None, None, None, 0, None) == ALIGN
+    assert f(FAKE, 16, good, FAKE, None, FAKE, None, None, 0, None) == WS                       # marginal needs scratch
+    assert f(FAKE, 16, good, FAKE, None, FAKE, None, FAKE, 16, None) == WS
+    need = cdl.quantize_workspace_bytes(16, 15)
+    assert f(FAKE, 16, good, FAKE, None, FAKE, None, FAKE + 64, need, None) == ALIGN
+    b = lib.cdl_quantize_bwd
+    assert b(FAKE, FAKE, 16, good, None, None, None, None, 0, None) == NULL                     # no output requested
+    assert b(FAKE, None, 16, good, FAKE, None, None, None, 0, None) == NULL
+    assert b(FAKE, FAKE, 16, good, FAKE, FAKE, None, None, 0, None) == WS
+    assert b(FAKE, FAKE + 8, 16, good, FAKE, None, None, None, 0, None) == ALIGN
+    m = lib.cdl_marginal_entropy
+    assert m(FAKE, 16, good, None, None, FAKE, need, None) == NULL
+    assert m(FAKE, 16, good, FAKE, None, None, 0, None) == WS
+
+
+def test_gemm_argument_validation_happens_before_any_gpu_work(cdl):
+    lib = cdl.load()
+    f = lib.cdl_qgemm_fwd
+    assert f(FAKE, FAKE, -1, 4, 4, 1.0, 1.0, FAKE, None, None, 0, None) == PARAM
+    assert f(FAKE, FAKE, 4, 4, 16, 0.0, 1.0, FAKE, None, None, 0, None) == PARAM
+    assert f(FAKE, FAKE, 4, 4, 16, 1.0, float("nan"), FAKE, None, None, 0, None) == PARAM
+    assert f(FAKE, FAKE, 4, 4, 16, 1.0, 1.0, None, None, None, 0, None) == NULL
+    assert f(None, FAKE, 4, 4, 16, 1.0, 1.0, FAKE, None, None, 0, None) == NULL
+    assert f(FAKE, FAKE, 4, 4, 131072, 1.0, 1.0, FAKE, None, None, 0, None) == RANGE             # int32 could overflow
+    assert f(FAKE + 4, FAKE, 4, 4, 16, 1.0, 1.0, FAKE, None, None, 0, None) == ALIGN
+    assert f(FAKE, FAKE, 4, 4, 20, 1.0, 1.0, FAKE, None, None, 0, None) == WS                    # ragged K needs staging
+    b = lib.cdl_qgemm_bwd
+    assert b(FAKE, FAKE, FAKE, 4, 4, 16, 1.0, 1.0, None, None, None, 0, None) == NULL
+    assert b(None, FAKE, FAKE, 4, 4, 16, 1.0, 1.0, FAKE, FAKE, None, 0, None) == NULL
+    assert b(FAKE, FAKE, FAKE, 4, 4, 16, 1.0, 1.0, FAKE, FAKE, None, 0, None) == WS
+    assert b(FAKE, FAKE, FAKE, 4, 262145, 16, 1.0, 1.0, FAKE, None, None, 0, None) == RANGE
+    assert b(FAKE, FAKE, FAKE, 262145, 4, 16, 1.0, 1.0, None, FAKE, None, 0, None) == RANGE
+    assert lib.cdl_profile_collect(None, 4) == PARAM
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch):
+    import paper_2501_09849_amd.binding as binding
+    monkeypatch.setattr(binding, "_LIB", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libcdl.so")
+    with pytest.raises(RuntimeError, match="not built"):
+        binding.load()
+
+
+def test_window_rule_matches_the_documented_bound():
+    """Levels beyond the band must carry less than 3e-9 (times m^3) of the weight of the nearest level."""
+    import math
+    for kappa, want in ((1e4, 1), (30.0, 1), (11.0, 1), (10.8, 2), (4.0, 2), (3.8, 3), (2.0, 3), (1.9, 4), (1.3, 4)):
+        W = 1
+        while True:
+            m = W + 1
+            if kappa * m * (m - 1) > 19.6 + 3 * math.log(m):
+                break
+            W += 1
+        assert W == want, (kappa, W, want)
+        m = W + 1
+        assert m ** 3 * math.exp(-kappa * m * (m - 1)) < 3.1e-9
