@@ -3,7 +3,7 @@
 //
 // The conditional PMF of one entry theta over the levels i*delta is
 //     P_i = softmax_i(-alpha (theta - i delta)^2)                       (eq. CPMF, Sec. III-A).
-// Let c be the level nearest to theta (clamped to the set), u = theta - c*delta and
+// Let c be a level next to theta (the nearest one, clamped to the set), u = theta - c*delta and
 // kappa = alpha*delta^2.  Relative to level c the weight of level c+j is
 //     w_j = exp(alpha*delta * j * (2u - j*delta)),          w_0 = 1,
 // which is exp(-kappa j^2 + 2 alpha delta u j) written so that nothing large cancels.  For
@@ -16,6 +16,14 @@
 //     dQd/dtheta = 2 kappa var_j
 //     dQd/ddelta = (c + mu) + 2 kappa ((r - c - 2 mu) var_j - c3_j),   r = u/delta
 //     dQd/dalpha = delta^3 (2 (r - mu) var_j - c3_j)
+//
+// These kernels are bound by plain fp32 ALU work as much as by HBM (one wave instruction costs
+// four cycles, exp and rcp sixteen), so the band is evaluated with as few instructions as the
+// accuracy allows:
+//   W = 1 (kappa > 10.9): two exponentials whose arguments are formed without rounding error;
+//   W = 2 (3.8 < kappa <= 10.9): one exponential t = exp(2 alpha delta u); the five weights are
+//          t^(j) exp(-kappa j^2), all multiplied by t^2 so that they are a polynomial in t;
+//   W = 3, 4: one exponential per level;  larger W: a loop over the band (soft regime).
 #include "cdl_internal.h"
 
 #include <math.h>
@@ -24,11 +32,20 @@ namespace cdl {
 
 namespace {
 
+constexpr int kPad = 4;   // spare histogram bins on each side, so that band offsets never leave the array
+
+// Fixed-point histogram: a block makes at most kMaxHistTrips trips of its loop, each lane adds 4
+// entries per trip, and 64 >> RS lanes share one copy of a bin: at most 2^(6-RS) * 4 * 16 adds of
+// at most 2^s each reach one cell, so s = 31 - (12 - RS) keeps every cell below 2^31.
+constexpr int kMaxHistTrips = 16;
+constexpr int hist_scale_bits(int rs) { return 19 + rs; }
 
 struct QConst {
     float delta;
     float inv_delta;
     float c1;         // alpha * delta * log2(e): base-2 exponent per unit of j*(2u - j delta)
+    float b2;         // 2 alpha delta log2(e): t = exp2(b2 u)
+    float k1, k4;     // exp(-kappa), exp(-4 kappa)
     float two_kappa;  // 2 alpha delta^2
     float lo_f;
     float hi_f;
@@ -37,36 +54,66 @@ struct QConst {
     int wgen;         // band half-width of the generic kernel
 };
 
-// Nearest level to th, lower index on an exact tie, clamped to [lo, hi].
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float clampf(float x, float lo, float hi) { return __builtin_amdgcn_fmed3f(x, lo, hi); }
+
+// Level next to th.  EXACT: the nearest level, lower index on an exact tie, clamped to [lo, hi]:
 // rint(th/delta) can be off by one next to a midpoint; the two fused multiply-adds evaluate
 // 2 th - (2r +- 1) delta with a single rounding, so their signs are those of the exact values.
-__device__ __forceinline__ float nearest_level(float th, const QConst &k)
+// Not EXACT: rint(th/delta) clamped - within 2e-5 of a midpoint it may pick the other neighbour,
+// which changes no moment (the band is centred one level off, u is a hair above delta/2).
+template <bool EXACT>
+__device__ __forceinline__ float anchor_level(float th, const QConst &k)
 {
     float r = rintf(th * k.inv_delta);
-    r = fminf(fmaxf(r, k.lo_f), k.hi_f);
-    const float two_th = 2.0f * th;
-    const float up = fmaf(-(2.0f * r + 1.0f), k.delta, two_th);  // > 0: r+1 is strictly closer
-    const float dn = fmaf(-(2.0f * r - 1.0f), k.delta, two_th);  // <= 0: r-1 is at least as close
-    r = (up > 0.0f) ? r + 1.0f : r;
-    r = (dn <= 0.0f) ? r - 1.0f : r;
-    return fminf(fmaxf(r, k.lo_f), k.hi_f);
+    if (EXACT) {
+        const float two_th = 2.0f * th;
+        const float up = fmaf(-(2.0f * r + 1.0f), k.delta, two_th);  // > 0: r+1 is strictly closer
+        const float dn = fmaf(-(2.0f * r - 1.0f), k.delta, two_th);  // <= 0: r-1 is at least as close
+        const float r_up = r + 1.0f, r_dn = r - 1.0f;
+        r = (up > 0.0f) ? r_up : r;
+        r = (dn <= 0.0f) ? r_dn : r;
+    }
+    return clampf(r, k.lo_f, k.hi_f);
 }
 
-// Weights of the band around the nearest level and their power sums in the offset j.
+// Weights of the band (up to one common factor) and their power sums in the offset j.
 template <int W>
 struct Band {
-    float cf;          // nearest level as a float
+    float cf;          // anchor level as a float
     float u;           // theta - c*delta
-    float up[W > 0 ? W : 1];
-    float dn[W > 0 ? W : 1];
+    float ctr;         // weight of the anchor level
+    float up[W > 0 ? W : 1];   // weight of level c+j at [j-1]
+    float dn[W > 0 ? W : 1];   // weight of level c-j at [j-1]
     float Z, S1, S2, S3;
 };
 
-template <int W, bool THIRD>
+// NMOM: how many of S1, S2, S3 are needed.
+template <int W, bool EXACT, int NMOM>
 __device__ __forceinline__ void band_weights(float th, const QConst &k, Band<W> &b)
 {
-    const float cf = nearest_level(th, k);
+    const float cf = anchor_level<EXACT>(th, k);
     b.cf = cf;
+    if (W == 2) {
+        // t = exp(2 alpha delta u), clamped where the far side has long vanished so that t^4 stays finite
+        const float u = fmaf(-cf, k.delta, th);
+        b.u = u;
+        const float t = fast_exp2(clampf(k.b2 * u, -30.0f, 30.0f));
+        const float t2 = t * t, t3 = t2 * t, t4 = t2 * t2;
+        const float above = k.hi_f - cf, below = cf - k.lo_f;   // levels that exist on each side
+        const float k1u = (above >= 1.0f) ? k.k1 : 0.0f, k4u = (above >= 2.0f) ? k.k4 : 0.0f;
+        const float k1d = (below >= 1.0f) ? k.k1 : 0.0f, k4d = (below >= 2.0f) ? k.k4 : 0.0f;
+        const float A = k4u * t4, B = k1u * t3, C = k1d * t, D = k4d;   // levels +2, +1, -1, -2 (times t^2)
+        const float p = A + D, q = B + C, x = A - D, y = B - C;
+        b.ctr = t2;
+        b.up[0] = B; b.up[1] = A; b.dn[0] = C; b.dn[1] = D;
+        b.Z = (p + q) + t2;
+        b.S1 = fmaf(2.0f, x, y);
+        b.S2 = (NMOM >= 2) ? fmaf(4.0f, p, q) : 0.0f;
+        b.S3 = (NMOM >= 3) ? fmaf(8.0f, x, y) : 0.0f;
+        return;
+    }
     float two_u, corr;
     if (W == 1) {
         // Sharp regime: the exponent of the neighbour next to a midpoint is a small difference
@@ -83,6 +130,7 @@ __device__ __forceinline__ void band_weights(float th, const QConst &k, Band<W> 
         two_u = 2.0f * b.u;
         corr = 0.0f;
     }
+    const float above = k.hi_f - cf, below = cf - k.lo_f;
     float Z = 1.0f, S1 = 0.0f, S2 = 0.0f, S3 = 0.0f;
 #pragma unroll
     for (int j = 1; j <= W; ++j) {
@@ -91,18 +139,19 @@ __device__ __forceinline__ void band_weights(float th, const QConst &k, Band<W> 
         float xu = fmaf(-jf, k.delta, two_u);   // 2u - j delta
         float xd = fmaf(jf, k.delta, two_u);    // 2u + j delta
         if (W == 1) { xu -= corr; xd -= corr; }
-        float wu = __builtin_amdgcn_exp2f(cj * xu);
-        float wd = __builtin_amdgcn_exp2f(-cj * xd);
-        wu = (cf + jf <= k.hi_f) ? wu : 0.0f;   // level c+j exists
-        wd = (cf - jf >= k.lo_f) ? wd : 0.0f;   // level c-j exists
+        float wu = fast_exp2(cj * xu);
+        float wd = fast_exp2(-cj * xd);
+        wu = (above >= jf) ? wu : 0.0f;   // level c+j exists
+        wd = (below >= jf) ? wd : 0.0f;   // level c-j exists
         b.up[j - 1] = wu;
         b.dn[j - 1] = wd;
         const float s = wu + wd, d = wu - wd;
         Z += s;
         S1 = fmaf(jf, d, S1);
-        S2 = fmaf(jf * jf, s, S2);
-        if (THIRD) S3 = fmaf(jf * jf * jf, d, S3);
+        if (NMOM >= 2) S2 = fmaf(jf * jf, s, S2);
+        if (NMOM >= 3) S3 = fmaf(jf * jf * jf, d, S3);
     }
+    b.ctr = 1.0f;
     b.Z = Z; b.S1 = S1; b.S2 = S2; b.S3 = S3;
 }
 
@@ -115,12 +164,13 @@ struct GenericSums {
 __device__ __forceinline__ float generic_weight(int j, float two_u, const QConst &k)
 {
     const float jf = (float)j;
-    return __builtin_amdgcn_exp2f(k.c1 * jf * fmaf(-jf, k.delta, two_u));
+    return fast_exp2(k.c1 * jf * fmaf(-jf, k.delta, two_u));
 }
 
+template <bool EXACT>
 __device__ __forceinline__ void generic_sums(float th, const QConst &k, GenericSums &g)
 {
-    const float cf = nearest_level(th, k);
+    const float cf = anchor_level<EXACT>(th, k);
     g.cf = cf;
     g.u = fmaf(-cf, k.delta, th);
     const int c = (int)cf;
@@ -139,136 +189,165 @@ __device__ __forceinline__ void generic_sums(float th, const QConst &k, GenericS
     g.Z = Z; g.S1 = S1; g.S2 = S2; g.S3 = S3;
 }
 
-__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
-
 // ------------------------------------------------------------------------------------------
 // Forward kernel.  One thread handles four consecutive entries per trip of a grid-stride loop
 // (one 16-byte load, one 16-byte store of soft values, one 4-byte store of indices).
-// MARG: each wave adds the CPMF of its entries into its own LDS histogram; at the end the block
-// sums its waves' histograms in a fixed order and writes one partial histogram to `partial`.
+//
+// MARG: the CPMF of every entry is added into a histogram in LDS, in fixed point: a probability
+// p is added as the integer floor(p * 2^s + 1/2).  (LDS integer atomics run at ~10 lane updates
+// per clock per CU on this chip, fp32 LDS atomics at a thirtieth of that; integer sums are also
+// independent of the order of the adds, so the result is reproducible.)  Each wave owns
+// R = 2^RS interleaved copies of the histogram (bin-major, copy-minor; lane l uses copy l mod R),
+// so lanes of one instruction collide only when they share both copy and bin.  s comes from
+// hist_scale_bits(): with at most kMaxHistTrips trips of the loop a cell never exceeds 2^31.
+// kPad spare bins on each side take the zero weights of levels that do not exist.  At the end
+// the block adds copies and waves into one 64-bit partial histogram row of `partial`; block 0
+// also clears the ticket that the finalize kernel uses.
 // ------------------------------------------------------------------------------------------
-template <int W, bool IDX, bool SOFT, bool MARG>
+// Quantizes four entries: soft values, level indices, and (MARG) their CPMFs into the histogram.
+template <int W, bool IDX, bool MARG, int RS>
+__device__ __forceinline__ void forward4(const float (&th)[4], int cnt, const QConst &k, unsigned int *my_hist,
+                                         float (&sv)[4], int (&ci)[4])
+{
+    constexpr int R = 1 << RS;
+    constexpr float kScale = (float)(1u << hist_scale_bits(RS));
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (W > 0) {
+            Band<W> b;
+            band_weights<W, IDX, 1>(th[e], k, b);
+            const float inv = fast_rcp(b.Z);
+            sv[e] = fmaf(b.S1 * inv, k.delta, b.cf * k.delta);
+            ci[e] = (int)b.cf;
+            if (MARG && e < cnt) {
+                unsigned int *h = my_hist + (ci[e] - k.lo + kPad - W) * R;   // bin of level c-W
+                const float invs = inv * kScale;
+                atomicAdd(h + W * R, (unsigned int)fmaf(b.ctr, invs, 0.5f));
+#pragma unroll
+                for (int j = 1; j <= W; ++j) {
+                    atomicAdd(h + (W + j) * R, (unsigned int)fmaf(b.up[j - 1], invs, 0.5f));
+                    atomicAdd(h + (W - j) * R, (unsigned int)fmaf(b.dn[j - 1], invs, 0.5f));
+                }
+            }
+        } else {
+            GenericSums g;
+            generic_sums<IDX>(th[e], k, g);
+            const float inv = fast_rcp(g.Z);
+            sv[e] = fmaf(g.S1 * inv, k.delta, g.cf * k.delta);
+            ci[e] = (int)g.cf;
+            if (MARG && e < cnt) {
+                unsigned int *h = my_hist + (ci[e] - k.lo + kPad) * R;
+                const float two_u = 2.0f * g.u, invs = inv * kScale;
+                for (int j = g.jlo; j <= g.jhi; ++j)
+                    atomicAdd(h + j * R, (unsigned int)fmaf(generic_weight(j, two_u, k), invs, 0.5f));
+            }
+        }
+    }
+}
+
+template <int W, bool IDX, bool SOFT, bool MARG, int RS>
 __global__ __launch_bounds__(kQuantThreads)
 void quantize_fwd_kernel(const float *__restrict__ theta, int64_t n, QConst k,
                          int8_t *__restrict__ idx, float *__restrict__ soft,
-                         float *__restrict__ partial /* [gridDim.x][n_levels] */)
+                         unsigned long long *__restrict__ partial /* [gridDim.x][n_levels] */,
+                         unsigned int *__restrict__ ticket)
 {
-    extern __shared__ float lds_hist[];  // [waves][n_levels] when MARG
-    const int lane_wave = threadIdx.x >> 6;
-    float *my_hist = lds_hist + lane_wave * k.n_levels;
+    extern __shared__ unsigned int lds_hist[];  // [waves][n_levels + 2 kPad][R] when MARG
+    constexpr int R = 1 << RS;
+    const int bins = k.n_levels + 2 * kPad;
+    unsigned int *my_hist = lds_hist + (threadIdx.x >> 6) * bins * R + (threadIdx.x & (R - 1));
     if (MARG) {
-        for (int i = threadIdx.x; i < (kQuantThreads / 64) * k.n_levels; i += kQuantThreads) lds_hist[i] = 0.0f;
+        for (int i = threadIdx.x; i < (kQuantThreads / 64) * bins * R; i += kQuantThreads) lds_hist[i] = 0u;
+        if (blockIdx.x == 0 && threadIdx.x == 0) *ticket = 0u;
         __syncthreads();
     }
 
     const int64_t n4 = n >> 2;
     const int64_t stride = (int64_t)gridDim.x * kQuantThreads;
-    for (int64_t v = (int64_t)blockIdx.x * kQuantThreads + threadIdx.x; v < n4 + 1; v += stride) {
+    float sv[4];
+    int ci[4];
+    for (int64_t v = (int64_t)blockIdx.x * kQuantThreads + threadIdx.x; v < n4; v += stride) {
+        const float4 t = reinterpret_cast<const float4 *>(theta)[v];
+        const float th[4] = {t.x, t.y, t.z, t.w};
+        forward4<W, IDX, MARG, RS>(th, 4, k, my_hist, sv, ci);
+        if (SOFT) reinterpret_cast<float4 *>(soft)[v] = make_float4(sv[0], sv[1], sv[2], sv[3]);
+        if (IDX) {
+            const uint32_t packed = (uint32_t)(ci[0] & 0xff) | ((uint32_t)(ci[1] & 0xff) << 8) |
+                                    ((uint32_t)(ci[2] & 0xff) << 16) | ((uint32_t)(ci[3] & 0xff) << 24);
+            reinterpret_cast<uint32_t *>(idx)[v] = packed;
+        }
+    }
+    // ragged tail: the last 1..3 entries, one thread of the last block
+    const int cnt = (int)(n - (n4 << 2));
+    if (cnt > 0 && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
         float th[4];
-        int cnt;
-        if (v < n4) {
-            const float4 t = reinterpret_cast<const float4 *>(theta)[v];
-            th[0] = t.x; th[1] = t.y; th[2] = t.z; th[3] = t.w;
-            cnt = 4;
-        } else {
-            cnt = (int)(n - (n4 << 2));   // ragged tail: 0..3 entries, handled by one thread
-            if (cnt == 0) break;
-            for (int e = 0; e < 4; ++e) th[e] = (e < cnt) ? theta[(n4 << 2) + e] : 0.0f;
-        }
-        float sv[4];
-        int ci[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (W > 0) {
-                Band<W> b;
-                band_weights<W, false>(th[e], k, b);
-                const float inv = fast_rcp(b.Z);
-                sv[e] = fmaf(b.S1 * inv, k.delta, b.cf * k.delta);
-                ci[e] = (int)b.cf;
-                if (MARG && e < cnt) {
-                    const int bin = ci[e] - k.lo;
-                    atomicAdd(&my_hist[bin], inv);
-#pragma unroll
-                    for (int j = 1; j <= W; ++j) {
-                        if (b.up[j - 1] > 0.0f) atomicAdd(&my_hist[bin + j], b.up[j - 1] * inv);
-                        if (b.dn[j - 1] > 0.0f) atomicAdd(&my_hist[bin - j], b.dn[j - 1] * inv);
-                    }
-                }
-            } else {
-                GenericSums g;
-                generic_sums(th[e], k, g);
-                const float inv = fast_rcp(g.Z);
-                sv[e] = fmaf(g.S1 * inv, k.delta, g.cf * k.delta);
-                ci[e] = (int)g.cf;
-                if (MARG && e < cnt) {
-                    const int bin = ci[e] - k.lo;
-                    const float two_u = 2.0f * g.u;
-                    for (int j = g.jlo; j <= g.jhi; ++j) {
-                        const float pj = generic_weight(j, two_u, k) * inv;
-                        if (pj > 0.0f) atomicAdd(&my_hist[bin + j], pj);
-                    }
-                }
-            }
-        }
-        if (v < n4) {
-            if (SOFT) reinterpret_cast<float4 *>(soft)[v] = make_float4(sv[0], sv[1], sv[2], sv[3]);
-            if (IDX) {
-                const uint32_t packed = (uint32_t)(ci[0] & 0xff) | ((uint32_t)(ci[1] & 0xff) << 8) |
-                                        ((uint32_t)(ci[2] & 0xff) << 16) | ((uint32_t)(ci[3] & 0xff) << 24);
-                reinterpret_cast<uint32_t *>(idx)[v] = packed;
-            }
-        } else {
-            for (int e = 0; e < cnt; ++e) {
-                if (SOFT) soft[(n4 << 2) + e] = sv[e];
-                if (IDX) idx[(n4 << 2) + e] = (int8_t)ci[e];
-            }
+        for (int e = 0; e < 4; ++e) th[e] = (e < cnt) ? theta[(n4 << 2) + e] : 0.0f;
+        forward4<W, IDX, MARG, RS>(th, cnt, k, my_hist, sv, ci);
+        for (int e = 0; e < cnt; ++e) {
+            if (SOFT) soft[(n4 << 2) + e] = sv[e];
+            if (IDX) idx[(n4 << 2) + e] = (int8_t)ci[e];
         }
     }
 
     if (MARG) {
         __syncthreads();
         for (int i = threadIdx.x; i < k.n_levels; i += kQuantThreads) {
-            float s = 0.0f;
+            unsigned long long s = 0ull;
+            for (int w = 0; w < kQuantThreads / 64; ++w) {
+                const unsigned int *row = lds_hist + (w * bins + i + kPad) * R;
 #pragma unroll
-            for (int w = 0; w < kQuantThreads / 64; ++w) s += lds_hist[w * k.n_levels + i];
+                for (int r = 0; r < R; ++r) s += row[(r + i) & (R - 1)];   // rotated start: no bank conflicts
+            }
             partial[(size_t)blockIdx.x * k.n_levels + i] = s;
         }
     }
 }
 
-// Sums the per-block histograms (fixed order, double), normalises by n and takes the entropy.
+// Sums the per-block fixed-point histograms (exact 64-bit integers), normalises by n * 2^s, and -
+// in the block that finishes last - adds up the entropy terms.  One block per eight levels; thread t handles level
+// t%8 of its block and rows t/8, t/8+128, ...
 __global__ __launch_bounds__(1024)
-void marginal_finalize_kernel(const float *__restrict__ partial, int nblocks, int n_levels, double inv_n,
-                              float *__restrict__ marg, float *__restrict__ entropy_bits)
+void marginal_finalize_kernel(const unsigned long long *__restrict__ partial, int nblocks, int n_levels, double inv_n,
+                              float *__restrict__ marg, float *__restrict__ entropy_bits,
+                              double *hterm /* [256] */, unsigned int *ticket)
 {
-    __shared__ double acc[1024];
-    __shared__ double red[256];
-    // thread t: level t % lpad, slice t / lpad; slice s adds blocks s, s+nslices, ...
-    int lpad = 1;
-    while (lpad < n_levels) lpad <<= 1;
-    const int nslices = 1024 / lpad;
-    const int level = threadIdx.x % lpad, slice = threadIdx.x / lpad;
-    double s = 0.0;
-    if (level < n_levels)
-        for (int b = slice; b < nblocks; b += nslices) s += (double)partial[(size_t)b * n_levels + level];
-    acc[threadIdx.x] = s;
+    __shared__ unsigned long long red[128][8];
+    __shared__ double hsum[256];
+    __shared__ bool is_last;
+    const int b8 = threadIdx.x & 7, grp = threadIdx.x >> 3;
+    const int level = blockIdx.x * 8 + b8;
+    unsigned long long s = 0ull;
+    if (level < n_levels) {
+#pragma unroll 8
+        for (int row = grp; row < nblocks; row += 128) s += partial[(size_t)row * n_levels + level];
+    }
+    red[grp][b8] = s;
     __syncthreads();
-    double h = 0.0;
-    if (threadIdx.x < 256) {
-        double m = 0.0;
-        if ((int)threadIdx.x < n_levels) {
-            for (int q = 0; q < nslices; ++q) m += acc[q * lpad + threadIdx.x];
-            m *= inv_n;
-            if (marg) marg[threadIdx.x] = (float)m;
-            if (m > 0.0) h = -m * log2(m);
-        }
-        red[threadIdx.x] = h;
+    if (threadIdx.x < 8 && level < n_levels) {
+        unsigned long long tot = 0ull;
+        for (int q = 0; q < 128; ++q) tot += red[q][threadIdx.x];
+        const double m = (double)tot * inv_n;
+        if (marg) marg[level] = (float)m;
+        __hip_atomic_store(&hterm[level], m > 0.0 ? -m * log2(m) : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned int t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        is_last = (t == gridDim.x - 1);
     }
     __syncthreads();
-    if (threadIdx.x == 0 && entropy_bits) {
-        double H = 0.0;
-        for (int i = 0; i < n_levels; ++i) H += red[i];
-        *entropy_bits = (float)H;
+    if (is_last && entropy_bits) {
+        __threadfence();
+        if (threadIdx.x < 256)
+            hsum[threadIdx.x] = ((int)threadIdx.x < n_levels)
+                ? __hip_atomic_load(&hterm[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double H = 0.0;
+            for (int i = 0; i < n_levels; ++i) H += hsum[i];
+            *entropy_bits = (float)H;
+        }
     }
 }
 
@@ -309,11 +388,11 @@ void quantize_bwd_kernel(const float *__restrict__ theta, const float *__restric
             float cf, u, Z, S1, S2, S3;
             if (W > 0) {
                 Band<W> b;
-                band_weights<W, SCALARS>(th[e], k, b);
+                band_weights<W, false, SCALARS ? 3 : 2>(th[e], k, b);
                 cf = b.cf; u = b.u; Z = b.Z; S1 = b.S1; S2 = b.S2; S3 = b.S3;
             } else {
                 GenericSums s;
-                generic_sums(th[e], k, s);
+                generic_sums<false>(th[e], k, s);
                 cf = s.cf; u = s.u; Z = s.Z; S1 = s.S1; S2 = s.S2; S3 = s.S3;
             }
             const float inv = fast_rcp(Z);
@@ -386,15 +465,19 @@ QConst make_const(const cdl_qparams &p)
 {
     QConst k;
     const double delta = (double)p.delta, alpha = (double)p.alpha;
+    const double kappa = alpha * delta * delta;
     k.delta = p.delta;
     k.inv_delta = (float)(1.0 / delta);
     k.c1 = (float)(alpha * delta * 1.4426950408889634);
-    k.two_kappa = (float)(2.0 * alpha * delta * delta);
+    k.b2 = (float)(2.0 * alpha * delta * 1.4426950408889634);
+    k.k1 = (float)exp(-kappa);
+    k.k4 = (float)exp(-4.0 * kappa);
+    k.two_kappa = (float)(2.0 * kappa);
     k.lo = p.lo;
     k.n_levels = p.n_levels;
     k.lo_f = (float)p.lo;
     k.hi_f = (float)(p.lo + p.n_levels - 1);
-    k.wgen = quantizer_window(alpha * delta * delta, p.n_levels);
+    k.wgen = quantizer_window(kappa, p.n_levels);
     return k;
 }
 
@@ -407,24 +490,51 @@ int grid_for(int64_t n)
     return (int)blocks;
 }
 
-// offsets inside the workspace
-size_t hist_bytes(int32_t n_levels) { return align_up((size_t)kMaxQuantBlocks * (size_t)n_levels * sizeof(float), 256); }
+// Grid of the histogram kernels: as above, but never more than kMaxHistTrips trips per block.
+int64_t hist_grid_for(int64_t n)
+{
+    const int64_t vecs = (n >> 2) + 1;
+    const int64_t need = (vecs + (int64_t)kQuantThreads * kMaxHistTrips - 1) / ((int64_t)kQuantThreads * kMaxHistTrips);
+    const int64_t g = grid_for(n);
+    return need > g ? need : g;
+}
+
+// workspace layout: [per-block histograms][entropy terms + ticket][per-block scalar partials]
+size_t hist_bytes(int64_t n, int32_t n_levels)
+{
+    return align_up((size_t)hist_grid_for(n) * (size_t)n_levels * sizeof(unsigned long long), 256);
+}
+size_t aux_bytes() { return align_up(256 * sizeof(double) + sizeof(unsigned int), 256); }
 size_t scalar_bytes() { return align_up((size_t)kMaxQuantBlocks * 2 * sizeof(double), 256); }
 
-template <int W>
-void launch_fwd_w(bool want_idx, bool want_soft, bool want_marg, int grid, size_t lds, hipStream_t s,
-                  const float *theta, int64_t n, const QConst &k, int8_t *idx, float *soft, float *partial)
+// histogram copies per wave: 16 for small level sets (heavy collisions), 4 for wide ones
+int copies_shift(int n_levels) { return n_levels <= 64 ? 4 : 2; }
+
+template <int W, int RS>
+void launch_fwd_w(bool want_idx, bool want_soft, bool want_marg, int grid, hipStream_t s,
+                  const float *theta, int64_t n, const QConst &k, int8_t *idx, float *soft,
+                  unsigned long long *partial, unsigned int *ticket)
 {
-#define CDL_FWD(I, S, M) \
+    const size_t lds = (size_t)(kQuantThreads / 64) * (size_t)(k.n_levels + 2 * kPad) * sizeof(float) << RS;
+#define CDL_FWD(I, S, M)                                                                                  \
     CDL_LAUNCH((I) ? "quantize_fwd_kernel" : "quantize_fwd_kernel(marginal only)", s,                     \
-               (quantize_fwd_kernel<W, I, S, M>), dim3(grid), dim3(kQuantThreads), (M) ? lds : 0,         \
-               theta, n, k, idx, soft, partial)
+               (quantize_fwd_kernel<W, I, S, M, (M) ? RS : 0>), dim3(grid), dim3(kQuantThreads), (M) ? lds : 0, \
+               theta, n, k, idx, soft, partial, ticket)
     if (want_idx && want_soft && want_marg) CDL_FWD(true, true, true);
     else if (want_idx && want_soft) CDL_FWD(true, true, false);
     else if (want_idx && want_marg) CDL_FWD(true, false, true);
     else if (want_idx) CDL_FWD(true, false, false);
     else CDL_FWD(false, false, true);
 #undef CDL_FWD
+}
+
+template <int W>
+void launch_fwd(int rs, bool want_idx, bool want_soft, bool want_marg, int grid, hipStream_t s,
+                const float *theta, int64_t n, const QConst &k, int8_t *idx, float *soft,
+                unsigned long long *partial, unsigned int *ticket)
+{
+    if (rs == 4) launch_fwd_w<W, 4>(want_idx, want_soft, want_marg, grid, s, theta, n, k, idx, soft, partial, ticket);
+    else launch_fwd_w<W, 2>(want_idx, want_soft, want_marg, grid, s, theta, n, k, idx, soft, partial, ticket);
 }
 
 template <int W>
@@ -457,8 +567,7 @@ int quantizer_window(double kappa, int n_levels)
 
 size_t quantize_workspace_bytes(int64_t n, int32_t n_levels)
 {
-    (void)n;
-    return hist_bytes(n_levels) + scalar_bytes();
+    return hist_bytes(n, n_levels) + aux_bytes() + scalar_bytes();
 }
 
 int launch_quantize_fwd(const float *theta, int64_t n, const cdl_qparams &p,
@@ -475,22 +584,27 @@ int launch_quantize_fwd(const float *theta, int64_t n, const cdl_qparams &p,
         return CDL_OK;
     }
     const QConst k = make_const(p);
-    const int grid = grid_for(n);
-    float *partial = reinterpret_cast<float *>(ws);
-    const size_t lds = (size_t)(kQuantThreads / 64) * (size_t)p.n_levels * sizeof(float);
+    const int64_t grid64 = want_marg ? hist_grid_for(n) : grid_for(n);
+    if (grid64 > 2147483647LL) return CDL_ERR_PARAM;
+    const int grid = (int)grid64;
+    unsigned long long *partial = reinterpret_cast<unsigned long long *>(ws);
+    double *hterm = want_marg ? reinterpret_cast<double *>(reinterpret_cast<char *>(ws) + hist_bytes(n, p.n_levels)) : nullptr;
+    unsigned int *ticket = want_marg ? reinterpret_cast<unsigned int *>(hterm + 256) : nullptr;
     const bool want_idx = idx != nullptr, want_soft = soft != nullptr;
+    const int rs = copies_shift(p.n_levels);
     switch (k.wgen <= 4 ? k.wgen : 0) {
-        case 1: launch_fwd_w<1>(want_idx, want_soft, want_marg, grid, lds, stream, theta, n, k, idx, soft, partial); break;
-        case 2: launch_fwd_w<2>(want_idx, want_soft, want_marg, grid, lds, stream, theta, n, k, idx, soft, partial); break;
-        case 3: launch_fwd_w<3>(want_idx, want_soft, want_marg, grid, lds, stream, theta, n, k, idx, soft, partial); break;
-        case 4: launch_fwd_w<4>(want_idx, want_soft, want_marg, grid, lds, stream, theta, n, k, idx, soft, partial); break;
-        default: launch_fwd_w<0>(want_idx, want_soft, want_marg, grid, lds, stream, theta, n, k, idx, soft, partial); break;
+        case 1: launch_fwd<1>(rs, want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
+        case 2: launch_fwd<2>(rs, want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
+        case 3: launch_fwd<3>(rs, want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
+        case 4: launch_fwd<4>(rs, want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
+        default: launch_fwd<0>(rs, want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
     }
     int rc = check_launch();
     if (rc != CDL_OK) return rc;
     if (want_marg) {
-        CDL_LAUNCH("marginal_finalize_kernel", stream, marginal_finalize_kernel, dim3(1), dim3(1024), 0, partial, grid, p.n_levels,
-                           1.0 / (double)n, marg, entropy_bits);
+        CDL_LAUNCH("marginal_finalize_kernel", stream, marginal_finalize_kernel, dim3((p.n_levels + 7) / 8), dim3(1024), 0,
+                   partial, grid, p.n_levels, 1.0 / ((double)n * (double)(1u << hist_scale_bits(rs))), marg, entropy_bits,
+                   hterm, ticket);
         rc = check_launch();
     }
     return rc;
@@ -510,7 +624,8 @@ int launch_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl
     }
     const QConst k = make_const(p);
     const int grid = grid_for(n);
-    double *partial = reinterpret_cast<double *>(reinterpret_cast<char *>(ws) + hist_bytes(p.n_levels));
+    double *partial = want_scalars
+        ? reinterpret_cast<double *>(reinterpret_cast<char *>(ws) + hist_bytes(n, p.n_levels) + aux_bytes()) : nullptr;
     const bool want_dtheta = dtheta != nullptr;
     switch (k.wgen <= 4 ? k.wgen : 0) {
         case 1: launch_bwd_w<1>(want_dtheta, want_scalars, grid, stream, theta, g, n, k, dtheta, partial); break;
@@ -524,7 +639,7 @@ int launch_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl
     if (want_scalars) {
         const double d = (double)p.delta;
         CDL_LAUNCH("scalar_finalize_kernel", stream, scalar_finalize_kernel, dim3(1), dim3(256), 0, partial, grid, d * d * d,
-                           d_delta, d_alpha);
+                   d_delta, d_alpha);
         rc = check_launch();
     }
     return rc;
