@@ -126,10 +126,13 @@ def kernel_model(wl, name, occurrence):
     if name == "quantize_bwd_kernel":
         n = (nX if occurrence == 0 else nW) if wl.has_gemm else nW
         return "hbm", 12.0 * n, n
-    if name.startswith("qgemm_kernel"):
+    if name.startswith("qgemm_kernel") or name.startswith("limb_gemm_kernel"):
         return "mfma", 2.0 * wl.M * wl.N * wl.K, 0
-    if name == "split_rows_kernel" or name == "split_cols_kernel" or name == "absmax_kernel":
-        return "hbm", 4.0 * wl.M * wl.N, 0          # reads g once (limb planes written on top are scratch traffic)
+    if name == "absmax_kernel":
+        return "hbm", 4.0 * wl.M * wl.N, 0          # reads g once
+    if name == "transpose_i8_kernel":
+        n = wl.N * wl.K if occurrence == 0 else wl.M * wl.K
+        return "hbm", 2.0 * n, 0                    # reads and writes an index matrix
     return None, 0.0, 0
 
 

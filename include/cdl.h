@@ -66,7 +66,7 @@ size_t cdl_quantize_workspace_bytes(int64_t n, int32_t n_levels);
 /* Scratch needed by cdl_qgemm_fwd (staging copies when K is not a multiple of 16). */
 size_t cdl_qgemm_fwd_workspace_bytes(int32_t M, int32_t N, int32_t K);
 
-/* Scratch needed by cdl_qgemm_bwd (integer limb planes of g, transposed index copies). */
+/* Scratch needed by cdl_qgemm_bwd (transposed index copies, partial sums of the split contraction). */
 size_t cdl_qgemm_bwd_workspace_bytes(int32_t M, int32_t N, int32_t K);
 
 /*
@@ -126,10 +126,13 @@ int cdl_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N
  * step; these are the dL/dQ_p factors of eq. partialX3 / partialW3).  g: fp32[M,N] = dL/dy.
  *   d_a_hat[m,k] = delta_b * sum_n g[m,n] * b_idx[n,k]                       (fp32[M,K], nullable)
  *   d_b_hat[n,k] = delta_a * sum_m g[m,n] * a_idx[m,k]                       (fp32[N,K], nullable)
- * The gradient stays fp32 (the paper quantizes weights and activations only).  Internally g is
- * written as sigma * sum_l limb_l * 2^(-7l) with int8 limbs and one power-of-two sigma, each limb
- * product is accumulated exactly in int32 and the limbs are recombined in double; enough limbs are
- * taken that the remainder contributes less than 1.5e-7 absolute.  At least one output non-NULL.
+ * The gradient stays fp32 (the paper quantizes weights and activations only).  Internally every
+ * g is rounded to q = rint(g * 2^(8L-1) / sigma) for one power-of-two sigma > max|g|, q is written
+ * in L balanced base-256 digits (int8 limbs), each limb product is accumulated exactly in int32 on
+ * the int8 matrix cores and the limbs are recombined in double; L (3..6) is chosen on the device
+ * so that the rounding of q contributes about 1.7e-7 absolute (one standard deviation) or less.
+ * At least one output non-NULL.  CDL_ERR_RANGE if d_a_hat is requested and N > 131071 (int32
+ * accumulators over the contraction; the contraction over M is cut into pieces internally).
  */
 int cdl_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
                   int32_t M, int32_t N, int32_t K, float delta_a, float delta_b,

@@ -1,14 +1,16 @@
 // Layer products over quantized operands on the int8 matrix cores of gfx950
 // (v_mfma_i32_32x32x32_i8, int32 accumulation), rescaled by the step sizes only in the epilogue.
 //
-// One tiled kernel computes C[r, s] = sum_k A[r, k] * B[s, k] for two int8 matrices that both
-// have the contraction index contiguous.  The forward product uses it directly on the index
-// tensors (Sec. IV-A; Algorithm 1, forward step).  The two backward products contract the fp32
-// upstream gradient with an index matrix; the gradient is first written as a short sum of int8
-// "limbs" times powers of 2^-7 relative to one power-of-two scale (every step of that split is
-// exact in fp32), the limb products are exact in int32, and the limbs are recombined in double in
-// the epilogue.  The number of limbs is chosen on the device from the data so that what is cut
-// off stays below the parity tolerance.
+// Forward (Sec. IV-A; Algorithm 1, forward step): C[r, s] = sum_k A[r, k] * B[s, k] on the index
+// tensors, both with the contraction index contiguous.
+//
+// Backward (Algorithm 1, backward step): the fp32 upstream gradient G is contracted with an index
+// matrix.  The entries of G are written, inside the GEMM kernel, as L balanced base-256 digits
+// ("limbs") of q = rint(g * 2^(8L-1) / sigma) for one power-of-two sigma > max|g|: the product
+// g * 2^k is exact, so every entry is represented to within sigma * 2^-8L.  Each limb plane is an
+// int8 matrix; the limb planes of 32 output rows form L x 32 rows of one int8 MFMA tile, the limb
+// products are exact in int32 and are recombined in double in the epilogue.  L (3..6) is chosen on
+// the device so that the rounding of q stays well below the parity tolerance.
 #include "cdl_internal.h"
 
 #include <math.h>
@@ -19,41 +21,39 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef const void __attribute__((address_space(1))) *gptr_t;
+typedef void __attribute__((address_space(3))) *lptr_t;
 
 constexpr int kGemmThreads = 256;
-constexpr int kKT = 64;          // contraction bytes staged per pipeline step
-constexpr int kMaxLimbs = 6;
-constexpr int kLimbBits = 7;     // limbs are integers in [-64, 64]
+constexpr int kKT = 64;          // forward: contraction bytes staged per pipeline step
 
 // Device-side plan of one backward call: scale of the gradient and limb counts.
 struct BwdPlan {
     unsigned int absmax_bits;        // max |g| as fp32 bits (non-negative floats order like unsigned ints)
-    int scale_exp;                   // sigma = 2^scale_exp, with max|g| <= sigma/2
     int limbs_da, limbs_db;          // limbs used for d_a_hat / d_b_hat
+    float gscale_da, gscale_db;      // 2^(8L-1) / sigma
+    double out_scale_da, out_scale_db;  // delta_b * sigma / 2^(8L-1), delta_a * sigma / 2^(8L-1)
     unsigned long long sumsq_a;      // sum of a_idx^2 (all entries)
     unsigned long long sumsq_b;      // sum of b_idx^2
-    double out_scale_da, out_scale_db;  // delta_b * sigma * 2^-7, delta_a * sigma * 2^-7
 };
 
 struct GemmArgs {
-    const int8_t *A;      // [rowsA][lda] (limb mode: planes of that shape, a_plane bytes apart)
+    const int8_t *A;      // [rowsA][lda]
     const int8_t *B;      // [rowsB][ldb]
-    int64_t lda, ldb, a_plane;
+    int64_t lda, ldb;
     int rowsA, rowsB, Kc;  // Kc: contraction length in bytes, multiple of 16
     int tiles_m, tiles_n;
     int32_t *acc_out;     // [rowsA][ldc] or null
     float *y_out;         // [rowsA][ldc] or null
     int64_t ldc;
-    float scale;          // forward: delta_a * delta_b
-    const BwdPlan *plan;  // limb mode
-    int which;            // limb mode: 0 = d_a_hat, 1 = d_b_hat
+    float scale;          // delta_a * delta_b
 };
 
 __device__ __forceinline__ int swz(int row, int q) { return q ^ ((row >> 1) & 3); }
 
 // TM x TN: 32x32 MFMA tiles per wave; the block's four waves form a 2 x 2 grid.
-template <int TM, int TN, bool LIMBS>
-__global__ __launch_bounds__(kGemmThreads, LIMBS ? 1 : 2)
+template <int TM, int TN>
+__global__ __launch_bounds__(kGemmThreads, 2)
 void qgemm_kernel(GemmArgs a)
 {
     constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
@@ -115,34 +115,18 @@ void qgemm_kernel(GemmArgs a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    double run[LIMBS ? TM : 1][LIMBS ? TN : 1][LIMBS ? 16 : 1];
-    int n_limbs = 1;
-    if (LIMBS) {
-        n_limbs = a.which == 0 ? a.plan->limbs_da : a.plan->limbs_db;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) run[i][j][r] = 0.0;
-    }
-
-    const int nk = (a.Kc + kKT - 1) / kKT;
-    const int steps = nk * n_limbs;
+    const int steps = (a.Kc + kKT - 1) / kKT;
     const v4i zero4 = {0, 0, 0, 0};
 
     v4i pa[LA], pb[LB];
-    auto fetch = [&](int step) {
-        const int limb = LIMBS ? (n_limbs - 1 - step / nk) : 0;   // least significant limb first
-        const int kt = LIMBS ? (step % nk) : step;
-        const int64_t aoff = (int64_t)limb * a.a_plane + (int64_t)kt * kKT;
-        const int64_t boff = (int64_t)kt * kKT;
+    auto fetch = [&](int kt) {
+        const int64_t off = (int64_t)kt * kKT;
 #pragma unroll
         for (int i = 0; i < LA; ++i)
-            pa[i] = (kt * kKT + qa[i] < a.Kc) ? *reinterpret_cast<const v4i *>(ga[i] + aoff) : zero4;
+            pa[i] = (kt * kKT + qa[i] < a.Kc) ? *reinterpret_cast<const v4i *>(ga[i] + off) : zero4;
 #pragma unroll
         for (int i = 0; i < LB; ++i)
-            pb[i] = (kt * kKT + qb[i] < a.Kc) ? *reinterpret_cast<const v4i *>(gb[i] + boff) : zero4;
+            pb[i] = (kt * kKT + qb[i] < a.Kc) ? *reinterpret_cast<const v4i *>(gb[i] + off) : zero4;
     };
     auto stash = [&](int stage) {
 #pragma unroll
@@ -175,24 +159,11 @@ void qgemm_kernel(GemmArgs a)
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
-        if (LIMBS && ((step + 1) % nk == 0)) {
-            // one limb finished: run = run / 128 + acc, exact integers into a double
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        run[i][j][r] = fma(run[i][j][r], 1.0 / 128.0, (double)acc[i][j][r]);
-                        acc[i][j][r] = 0;
-                    }
-        }
         if (step + 1 < steps) stash(stage ^ 1);
         __syncthreads();
     }
 
     // epilogue: lane holds column (lane%32) of each 32x32 tile; register r holds row 8(r/4) + 4(lane/32) + r%4
-    const double out_scale = LIMBS ? (a.which == 0 ? a.plan->out_scale_da : a.plan->out_scale_db) : 0.0;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -204,17 +175,13 @@ void qgemm_kernel(GemmArgs a)
                 const int row = tile_m * BM + wm * TM * 32 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                 if (row >= a.rowsA) continue;
                 const int64_t o = (int64_t)row * a.ldc + col;
-                if (LIMBS) {
-                    a.y_out[o] = (float)(run[i][j][r] * out_scale);
-                } else {
-                    if (a.acc_out) a.acc_out[o] = acc[i][j][r];
-                    if (a.y_out) a.y_out[o] = a.scale * (float)acc[i][j][r];
-                }
+                if (a.acc_out) a.acc_out[o] = acc[i][j][r];
+                if (a.y_out) a.y_out[o] = a.scale * (float)acc[i][j][r];
             }
         }
 }
 
-template <int TM, int TN, bool LIMBS>
+template <int TM, int TN>
 int launch_gemm(GemmArgs a, hipStream_t stream)
 {
     constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
@@ -223,8 +190,339 @@ int launch_gemm(GemmArgs a, hipStream_t stream)
     const int64_t total = (int64_t)a.tiles_m * a.tiles_n;
     if (total == 0) return CDL_OK;
     const int64_t grid = (total + 7) / 8 * 8;
-    CDL_LAUNCH(a.plan ? (a.which ? "qgemm_kernel(limbs, d_b_hat)" : "qgemm_kernel(limbs, d_a_hat)") : "qgemm_kernel(fwd)", stream, (qgemm_kernel<TM, TN, LIMBS>), dim3((unsigned)grid), dim3(kGemmThreads), 0, a);
+    CDL_LAUNCH("qgemm_kernel(fwd)", stream, (qgemm_kernel<TM, TN>), dim3((unsigned)grid), dim3(kGemmThreads), 0, a);
     return check_launch();
+}
+
+// ---- backward: limb GEMM ---------------------------------------------------------------------
+
+struct LimbArgs {
+    const float *G;       // [M][N] fp32 upstream gradient
+    int M, N;
+    const int8_t *Bt;     // [cols][ldb] int8 index matrix, contraction index contiguous, zero-filled up to ldb
+    int64_t ldb;          // multiple of kLBK
+    int rows, cols, kc;   // output rows / columns, contraction length
+    int tiles_r, splits, kt_per_split;
+    const BwdPlan *plan;
+    int which;            // 0 = d_a_hat, 1 = d_b_hat
+    float *out;           // [rows][cols] (splits == 1)
+    double *partial;      // [splits][rows][cols] (splits > 1)
+};
+
+constexpr int kLBK = 128;     // contraction bytes per K-tile
+constexpr int kLRows = 32;    // output rows per block
+constexpr int kLPlane = kLRows * kLBK;
+constexpr int kLThreads = 256;
+constexpr int kMinLimbs = 3, kMaxLimbs = 6;
+
+constexpr int limb_tn(int L) { return L <= 5 ? 3 : 2; }          // 32-column tiles per wave
+constexpr int limb_cols(int L) { return 4 * limb_tn(L) * 32; }   // output columns per block
+constexpr int limb_stage_bytes(int L) { return L * kLPlane + limb_cols(L) * kLBK; }
+constexpr int kLimbLdsBytes = 2 * limb_stage_bytes(5);
+static_assert(limb_stage_bytes(3) <= limb_stage_bytes(5) && limb_stage_bytes(4) <= limb_stage_bytes(5) &&
+              limb_stage_bytes(6) <= limb_stage_bytes(5), "LDS sized for five limbs");
+
+__device__ __forceinline__ int lswz(int row) { return (row >> 1) & 7; }
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0f70; }   // s_waitcnt vmcnt(n) only
+constexpr int kLgkmcnt0 = 0xc07f;                                                   // s_waitcnt lgkmcnt(0) only
+
+__device__ __forceinline__ uint32_t bperm(uint32_t hi, uint32_t lo, uint32_t sel) { return __builtin_amdgcn_perm(hi, lo, sel); }
+
+// Digits of four values: out[l] holds digit l (a signed byte, l = 0 least significant) of g[0..3] in
+// its bytes 0..3.  x = g * gscale is exact (gscale is a power of two) and |x| < 0.99 * 2^(8L-1);
+// q = rint(x) = sum_l d_l 256^l with d_l in [-128, 127]: the bytes of (q + 0x80..80) ^ 0x80..80.
+template <int L>
+__device__ __forceinline__ void limbs_of4(const float (&g)[4], float gscale, uint32_t (&out)[L])
+{
+    if (L <= 4) {
+        constexpr uint32_t off = L == 4 ? 0x80808080u : 0x00808080u;
+        uint32_t d[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int q = (int)rintf(g[e] * gscale);
+            d[e] = ((uint32_t)q + off) ^ off;
+        }
+        const uint32_t t0 = bperm(d[1], d[0], 0x05010400u), t2 = bperm(d[3], d[2], 0x05010400u);
+        out[0] = bperm(t2, t0, 0x05040100u);
+        out[1] = bperm(t2, t0, 0x07060302u);
+        const uint32_t t1 = bperm(d[1], d[0], 0x07030602u), t3 = bperm(d[3], d[2], 0x07030602u);
+        out[2] = bperm(t3, t1, 0x05040100u);
+        if (L == 4) out[L - 1] = bperm(t3, t1, 0x07060302u);
+    } else {
+        // q has up to 48 bits: the low 16 (digits 0, 1) and the rest are rounded separately
+        constexpr uint32_t offh = L == 6 ? 0x80808080u : 0x00808080u;
+        uint32_t lo[4], hi[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float x = g[e] * gscale;
+            const float H = rintf(x * (1.0f / 65536.0f));
+            const float r = fmaf(-H, 65536.0f, x);          // exact, |r| <= 32768
+            const int t = (int)rintf(r) + 0x8080;           // in [0x80, 0x10080]
+            lo[e] = (uint32_t)t ^ 0x8080u;                  // bytes 0, 1: digits 0, 1
+            const int h = (int)H + (t >> 16);               // carry out of the low two digits
+            hi[e] = ((uint32_t)h + offh) ^ offh;
+        }
+        const uint32_t a0 = bperm(lo[1], lo[0], 0x05010400u), a2 = bperm(lo[3], lo[2], 0x05010400u);
+        out[0] = bperm(a2, a0, 0x05040100u);
+        out[1] = bperm(a2, a0, 0x07060302u);
+        const uint32_t t0 = bperm(hi[1], hi[0], 0x05010400u), t2 = bperm(hi[3], hi[2], 0x05010400u);
+        out[2] = bperm(t2, t0, 0x05040100u);
+        out[3] = bperm(t2, t0, 0x07060302u);
+        const uint32_t t1 = bperm(hi[1], hi[0], 0x07030602u), t3 = bperm(hi[3], hi[2], 0x07030602u);
+        out[4] = bperm(t3, t1, 0x05040100u);
+        if (L == 6) out[L - 1] = bperm(t3, t1, 0x07060302u);
+    }
+}
+
+// One block: 32 output rows x (4 waves x TN x 32) output columns; every wave holds all L limb tiles
+// of the 32 rows for its TN column tiles.  Per K-tile of 128 contraction entries:
+//   A side: 16 entries of G per thread -> registers -> digits -> L planes [32][128] int8 in LDS;
+//   B side: direct global->LDS loads of the index matrix rows (16-byte chunks, XOR-swizzled).
+// Two LDS stages; the one barrier per K-tile sits in front of the last of the four k-steps, whose
+// MFMAs then cover the refill of the stage just left (tile kt+2) and the first fragment reads of
+// tile kt+1.  TRANS: G is read transposed (rows of the product are columns of G).  VEC: 16-byte
+// loads of G (N % 4 == 0).
+template <int L, int TN, bool TRANS, bool VEC>
+__device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, float gscale, double out_scale)
+{
+    constexpr int NB = 4 * TN * 32;
+    constexpr int STAGE = L * kLPlane + NB * kLBK;
+    constexpr int WLB = NB / 32;          // direct loads per wave per K-tile
+    constexpr int GL = VEC ? 4 : 16;      // G load instructions per thread per K-tile
+    constexpr int KS = kLBK / 32;
+
+    const int tiles_c = (a.cols + NB - 1) / NB;
+    const int64_t items = (int64_t)a.tiles_r * tiles_c * a.splits;
+    const int per_xcd = (int)gridDim.x >> 3;
+    const int64_t logical = (int64_t)((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+    if (logical >= items) return;
+    const int tile_c = (int)(logical % tiles_c);
+    const int64_t rest = logical / tiles_c;
+    const int tile_r = (int)(rest % a.tiles_r);
+    const int split = (int)(rest / a.tiles_r);
+    const int nk_total = (int)(a.ldb / kLBK);
+    const int kt0 = split * a.kt_per_split;
+    const int nk = min(nk_total, kt0 + a.kt_per_split) - kt0;
+    const int row0 = tile_r * kLRows, col0 = tile_c * NB;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    // ---- A side ----
+    float gbuf[16];
+    // !TRANS: thread owns row ar = tid/8 and 16 consecutive contraction entries from 16*(tid%8)
+    //  TRANS: thread owns rows 4*(tid%8)..+3 and 4 consecutive contraction entries from 4*(tid/8)
+    const int ar = TRANS ? 4 * (tid & 7) : (tid >> 3);
+    const int ak = TRANS ? 4 * (tid >> 3) : 16 * (tid & 7);
+    auto load_g = [&](int kt) {
+        const int k0 = (kt0 + kt) * kLBK + ak;
+        if (!TRANS) {
+            const int grow = min(row0 + ar, a.rows - 1);
+            const float *p = a.G + (int64_t)grow * a.N + k0;
+            if (VEC) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (k0 + 4 * j < a.kc) v = *reinterpret_cast<const float4 *>(p + 4 * j);
+                    gbuf[4 * j] = v.x; gbuf[4 * j + 1] = v.y; gbuf[4 * j + 2] = v.z; gbuf[4 * j + 3] = v.w;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) gbuf[j] = (k0 + j < a.kc) ? p[j] : 0.0f;
+            }
+        } else {
+            // gbuf[4 j + i] = G[k0 + j][row0 + ar + i]
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float *p = a.G + (int64_t)min(k0 + j, a.kc - 1) * a.N + row0 + ar;
+                const bool kin = k0 + j < a.kc;
+                if (VEC) {
+                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (kin && row0 + ar < a.rows) v = *reinterpret_cast<const float4 *>(p);
+                    gbuf[4 * j] = v.x; gbuf[4 * j + 1] = v.y; gbuf[4 * j + 2] = v.z; gbuf[4 * j + 3] = v.w;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) gbuf[4 * j + i] = (kin && row0 + ar + i < a.rows) ? p[i] : 0.0f;
+                }
+            }
+        }
+    };
+    auto convert_store = [&](int stage) {
+        int8_t *base = lds + stage * STAGE;
+        if (!TRANS) {
+            uint32_t w[4][L];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float g4[4] = {gbuf[4 * j], gbuf[4 * j + 1], gbuf[4 * j + 2], gbuf[4 * j + 3]};
+                limbs_of4<L>(g4, gscale, w[j]);
+            }
+            const int off = ar * kLBK + (((tid & 7) ^ lswz(ar)) << 4);
+#pragma unroll
+            for (int l = 0; l < L; ++l) {
+                const v4i v = {(int)w[0][l], (int)w[1][l], (int)w[2][l], (int)w[3][l]};
+                *reinterpret_cast<v4i *>(base + l * kLPlane + off) = v;
+            }
+        } else {
+            const int mg = tid >> 3;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float g4[4] = {gbuf[i], gbuf[4 + i], gbuf[8 + i], gbuf[12 + i]};
+                uint32_t w[L];
+                limbs_of4<L>(g4, gscale, w);
+                const int row = ar + i;
+                const int off = row * kLBK + (((mg >> 2) ^ lswz(row)) << 4) + ((mg & 3) << 2);
+#pragma unroll
+                for (int l = 0; l < L; ++l) *reinterpret_cast<uint32_t *>(base + l * kLPlane + off) = w[l];
+            }
+        }
+    };
+
+    // ---- B side ----
+    const int8_t *gb[WLB];
+#pragma unroll
+    for (int i = 0; i < WLB; ++i) {
+        const int s = (wave * WLB + i) * 64 + lane, row = s >> 3;
+        const int q = (s & 7) ^ lswz(row);
+        const int gcol = min(col0 + row, a.cols - 1);
+        gb[i] = a.Bt + (int64_t)gcol * a.ldb + (int64_t)kt0 * kLBK + q * 16;
+    }
+    auto issue_b = [&](int kt) {
+        int8_t *base = lds + (kt & 1) * STAGE + L * kLPlane;
+#pragma unroll
+        for (int i = 0; i < WLB; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)(gb[i] + (int64_t)kt * kLBK), (lptr_t)(base + (wave * WLB + i) * 1024), 16, 0, 0);
+    };
+
+    // ---- fragments ----
+    const int frow = lane & 31;
+    const int fa_off = frow * kLBK;
+    const int fsw = lswz(frow);
+    int fb_off[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb_off[j] = L * kLPlane + ((wave * TN + j) * 32 + frow) * kLBK;   // row 32 t + frow swizzles like frow
+
+    v4i fa[2][L], fb[2][TN];
+    auto read_frags = [&](int buf, int kt, int ks) {
+        const int8_t *base = lds + (kt & 1) * STAGE;
+        const int c = ((2 * ks + (lane >> 5)) ^ fsw) << 4;
+#pragma unroll
+        for (int l = 0; l < L; ++l) fa[buf][l] = *reinterpret_cast<const v4i *>(base + l * kLPlane + fa_off + c);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[buf][j] = *reinterpret_cast<const v4i *>(base + fb_off[j] + c);
+    };
+
+    v16i acc[L][TN];
+#pragma unroll
+    for (int l = 0; l < L; ++l)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[l][j][r] = 0;
+
+    // a bare s_barrier: the waits it needs are spelled out next to it, so that loads of later tiles stay in flight
+    auto barrier = [&]() {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+
+    if (nk > 0) {
+        load_g(0);
+        convert_store(0);
+        asm volatile("" ::: "memory");
+        issue_b(0);
+        if (nk > 1) {
+            load_g(1);
+            convert_store(1);
+            asm volatile("" ::: "memory");
+            issue_b(1);
+        }
+        asm volatile("" ::: "memory");
+        if (nk > 2) load_g(2);
+        asm volatile("" ::: "memory");
+        // B(0) must have landed; younger loads: B(1), G(2)
+        if (nk > 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(WLB + GL));
+        else if (nk > 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(WLB));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        __builtin_amdgcn_s_waitcnt(kLgkmcnt0);   // own LDS writes done
+        barrier();
+        read_frags(0, 0, 0);
+    }
+
+    for (int kt = 0; kt < nk; ++kt) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks + 1 < KS) {
+                read_frags(nxt, kt, ks + 1);
+            } else if (kt + 1 < nk) {
+                // tile kt+1: B landed (younger loads: G(kt+2)); this wave's A planes and fragment reads done
+                if (kt + 2 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm(GL));
+                else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
+                barrier();
+                if (kt + 2 < nk) {
+                    convert_store(kt & 1);      // tile kt+2 into the stage that tile kt has just left
+                    asm volatile("" ::: "memory");
+                    issue_b(kt + 2);
+                    asm volatile("" ::: "memory");
+                    if (kt + 3 < nk) load_g(kt + 3);
+                    asm volatile("" ::: "memory");
+                }
+                read_frags(nxt, kt + 1, 0);
+            }
+#pragma unroll
+            for (int l = 0; l < L; ++l)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[l][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][l], fb[cur][j], acc[l][j], 0, 0, 0);
+        }
+    }
+
+    // ---- epilogue: recombine the limbs; the integers are exact, the Horner steps round at 2^-53 relative ----
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int col = col0 + (wave * TN + j) * 32 + (lane & 31);
+        if (col >= a.cols) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = row0 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            if (row >= a.rows) continue;
+            double run = (double)acc[L - 1][j][r];
+#pragma unroll
+            for (int l = L - 2; l >= 0; --l) run = run * 256.0 + (double)acc[l][j][r];
+            if (a.splits == 1) a.out[(int64_t)row * a.cols + col] = (float)(run * out_scale);
+            else a.partial[((int64_t)split * a.rows + row) * a.cols + col] = run;
+        }
+    }
+}
+
+template <bool TRANS>
+__global__ __launch_bounds__(kLThreads, 1)
+void limb_gemm_kernel(LimbArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) int8_t limb_lds[];
+    const bool vec = (a.N & 3) == 0;
+    const int limbs = a.which == 0 ? a.plan->limbs_da : a.plan->limbs_db;
+    const float gscale = a.which == 0 ? a.plan->gscale_da : a.plan->gscale_db;
+    const double out_scale = a.which == 0 ? a.plan->out_scale_da : a.plan->out_scale_db;
+    switch (limbs) {
+        case 3: if (vec) limb_gemm_body<3, 3, TRANS, true>(a, limb_lds, gscale, out_scale); else limb_gemm_body<3, 3, TRANS, false>(a, limb_lds, gscale, out_scale); break;
+        case 4: if (vec) limb_gemm_body<4, 3, TRANS, true>(a, limb_lds, gscale, out_scale); else limb_gemm_body<4, 3, TRANS, false>(a, limb_lds, gscale, out_scale); break;
+        case 5: if (vec) limb_gemm_body<5, 3, TRANS, true>(a, limb_lds, gscale, out_scale); else limb_gemm_body<5, 3, TRANS, false>(a, limb_lds, gscale, out_scale); break;
+        default: if (vec) limb_gemm_body<6, 2, TRANS, true>(a, limb_lds, gscale, out_scale); else limb_gemm_body<6, 2, TRANS, false>(a, limb_lds, gscale, out_scale); break;
+    }
+}
+
+// out = out_scale * sum over the contraction splits, in split order.
+__global__ __launch_bounds__(256)
+void limb_reduce_kernel(const double *__restrict__ partial, int splits, int64_t n, const BwdPlan *plan, float *__restrict__ out)
+{
+    const double out_scale = plan->out_scale_db;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        double s = 0.0;
+        for (int p = 0; p < splits; ++p) s += partial[(int64_t)p * n + i];
+        out[i] = (float)(s * out_scale);
+    }
 }
 
 // ---- helpers -------------------------------------------------------------------------------
@@ -251,7 +549,9 @@ __global__ __launch_bounds__(256) void absmax_kernel(const float *__restrict__ g
 {
     unsigned int m = 0u;
     const int64_t n4 = n >> 2;
-    for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < n4; v += (int64_t)gridDim.x * 256) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+#pragma unroll 4
+    for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < n4; v += stride) {
         const float4 t = reinterpret_cast<const float4 *>(g)[v];
         m = max(m, __float_as_uint(fabsf(t.x)));
         m = max(m, __float_as_uint(fabsf(t.y)));
@@ -265,112 +565,87 @@ __global__ __launch_bounds__(256) void absmax_kernel(const float *__restrict__ g
     if ((threadIdx.x & 63) == 0 && m != 0u) atomicMax(&plan->absmax_bits, m);
 }
 
-// dst[c][r] = src[r][c] for an int8 matrix [rows][cols]; dst rows are ldd long, zero-filled past
-// `rows`.  Also adds sum(src^2) to *sumsq.  64 x 64 tiles through LDS.
+// dst[c][r] = src[r][c] for an int8 matrix [rows][cols]; dst rows are ldd (a multiple of 128) long,
+// zero-filled past `rows`.  Also adds sum(src^2) to *sumsq.  One block moves a tile of 128 rows x
+// 64 columns: 4-byte loads along the rows into LDS (row stride 17 words), then every thread takes a
+// 4 x 4 byte block, transposes it in registers and stores 4 bytes of four output rows, so that 32
+// lanes write 128 contiguous bytes.  VEC: cols % 4 == 0 (aligned 4-byte loads).
+template <bool VEC>
 __global__ __launch_bounds__(256) void transpose_i8_kernel(const int8_t *__restrict__ src, int rows, int cols,
-                                                           int8_t *__restrict__ dst, int ldd,
+                                                           int8_t *__restrict__ dst, int64_t ldd,
                                                            unsigned long long *sumsq)
 {
-    __shared__ int8_t tile[64][65];
-    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    __shared__ uint32_t tile[128 * 17];
+    const int r0 = blockIdx.y * 128, c0 = blockIdx.x * 64;
+    const int tid = threadIdx.x;
     unsigned int ss = 0u;
-    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
-        const int r = i >> 6, c = i & 63;
-        int8_t v = 0;
-        if (r0 + r < rows && c0 + c < cols) v = src[(int64_t)(r0 + r) * cols + c0 + c];
-        tile[r][c] = v;
-        ss += (unsigned int)((int)v * (int)v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int i = tid + 256 * j, row = i >> 4, cd = i & 15;
+        uint32_t w = 0u;
+        const int r = r0 + row, c = c0 + 4 * cd;
+        if (r < rows) {
+            const int8_t *p = src + (int64_t)r * cols + c;
+            if (VEC) {
+                if (c < cols) w = *reinterpret_cast<const uint32_t *>(p);
+            } else {
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    if (c + b < cols) w |= (uint32_t)(uint8_t)p[b] << (8 * b);
+            }
+        }
+        tile[row * 17 + cd] = w;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int v = (int)(int8_t)(w >> (8 * b));
+            ss += (unsigned int)(v * v);
+        }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
-        const int c = i >> 6, r = i & 63;
-        if (c0 + c < cols && r0 + r < ldd) dst[(int64_t)(c0 + c) * ldd + r0 + r] = tile[r][c];
+    const int rg = tid & 31;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const int cg = (tid >> 5) + 8 * p;
+        const uint32_t d0 = tile[(4 * rg) * 17 + cg], d1 = tile[(4 * rg + 1) * 17 + cg];
+        const uint32_t d2 = tile[(4 * rg + 2) * 17 + cg], d3 = tile[(4 * rg + 3) * 17 + cg];
+        const uint32_t t0 = bperm(d1, d0, 0x05010400u), t2 = bperm(d3, d2, 0x05010400u);
+        const uint32_t t1 = bperm(d1, d0, 0x07030602u), t3 = bperm(d3, d2, 0x07030602u);
+        const uint32_t o[4] = {bperm(t2, t0, 0x05040100u), bperm(t2, t0, 0x07060302u),
+                               bperm(t3, t1, 0x05040100u), bperm(t3, t1, 0x07060302u)};
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int c = c0 + 4 * cg + b;
+            if (c < cols) *reinterpret_cast<uint32_t *>(dst + (int64_t)c * ldd + r0 + 4 * rg) = o[b];
+        }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) ss += (unsigned int)__shfl_down((int)ss, off, 64);
     if ((threadIdx.x & 63) == 0 && ss != 0u) atomicAdd(sumsq, (unsigned long long)ss);
 }
 
-// Chooses the power-of-two scale of g and, for each backward product, the number of limbs:
-// after L limbs each entry of g is known to within sigma*2^(-7L)/2 (uniformly distributed), so a
-// contraction over n_c index entries of mean square q has a random error of about
-// delta * sigma * 2^(-7L) * sqrt(n_c q / 12); L is the smallest count that brings it under 1.5e-7.
+// Chooses the power-of-two scale of g and, for each backward product, the number of limbs.  With
+// sigma = 2^e > 1.01 max|g| and L limbs, q = rint(g 2^(8L-1)/sigma) leaves a rounding error uniform
+// in +-sigma 2^-8L per entry, so a contraction over n_c index entries of mean square s has a random
+// error of about delta sigma 2^(1-8L) sqrt(n_c s / 12); L is the smallest count (3..6) that brings
+// this under 1.7e-7, a sixth of the absolute parity tolerance.
 __global__ void plan_kernel(BwdPlan *plan, int M, int N, int K, float delta_a, float delta_b)
 {
     const float amax = __uint_as_float(plan->absmax_bits);
     int e = 0;
-    if (amax > 0.0f) {
-        frexpf(amax, &e);   // amax = f * 2^e, f in [0.5, 1)  ->  amax < 2^e
-        e += 1;             // sigma = 2^(e+1) > 2 amax
-    }
-    e = max(min(e, 126), -100);
-    plan->scale_exp = e;
-    const double sigma = ldexp(1.0, e);
+    if (amax > 0.0f) frexpf(amax * 1.01f, &e);   // amax * 1.01 = f 2^e with f in [0.5, 1)
+    e = max(min(e, 127), -80);                   // keeps 2^(8L-1-e) a normal float for every L
     const double msq_a = (double)plan->sumsq_a / fmax(1.0, (double)M * (double)K);
     const double msq_b = (double)plan->sumsq_b / fmax(1.0, (double)N * (double)K);
-    const double target = 1.5e-7;
-    int la = 2, lb = 2;
-    while (la < kMaxLimbs && (double)delta_b * sigma * ldexp(1.0, -kLimbBits * la) * sqrt((double)N * msq_b / 12.0) > target) ++la;
-    while (lb < kMaxLimbs && (double)delta_a * sigma * ldexp(1.0, -kLimbBits * lb) * sqrt((double)M * msq_a / 12.0) > target) ++lb;
+    const double target = 1.7e-7;
+    int la = kMinLimbs, lb = kMinLimbs;
+    while (la < kMaxLimbs && (double)delta_b * ldexp(1.0, e + 1 - 8 * la) * sqrt((double)N * msq_b / 12.0) > target) ++la;
+    while (lb < kMaxLimbs && (double)delta_a * ldexp(1.0, e + 1 - 8 * lb) * sqrt((double)M * msq_a / 12.0) > target) ++lb;
     plan->limbs_da = la;
     plan->limbs_db = lb;
-    plan->out_scale_da = (double)delta_b * sigma / 128.0;
-    plan->out_scale_db = (double)delta_a * sigma / 128.0;
-}
-
-// Limb l (1-based) of x = g/sigma, |x| <= 1/2:  v_1 = 128 x, limb_l = rint(v_l), v_(l+1) = 128 (v_l - limb_l).
-// Every operation is exact in fp32 (scaling by a power of two; v - rint(v) needs no rounding).
-__device__ __forceinline__ void split_limbs(float gval, float inv_sigma, int n_limbs, int8_t *out)
-{
-    float v = gval * inv_sigma * 128.0f;
-#pragma unroll
-    for (int l = 0; l < kMaxLimbs; ++l) {
-        const float q = rintf(v);
-        out[l] = (l < n_limbs) ? (int8_t)(int)q : (int8_t)0;
-        v = (v - q) * 128.0f;
-    }
-}
-
-// Row-major limb planes for d_a_hat: plane l, [M][ldn] with zero padding past N.
-__global__ __launch_bounds__(256) void split_rows_kernel(const float *__restrict__ g, int M, int N, int ldn,
-                                                         int8_t *__restrict__ planes, int64_t plane_bytes,
-                                                         const BwdPlan *plan)
-{
-    const int n_limbs = plan->limbs_da;
-    const float inv_sigma = ldexpf(1.0f, -plan->scale_exp);
-    const int64_t total = (int64_t)M * ldn;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-        const int64_t m = i / ldn;
-        const int n = (int)(i - m * ldn);
-        int8_t limb[kMaxLimbs];
-        split_limbs(n < N ? g[m * N + n] : 0.0f, inv_sigma, n_limbs, limb);
-        for (int l = 0; l < n_limbs; ++l) planes[(int64_t)l * plane_bytes + i] = limb[l];
-    }
-}
-
-// Transposed limb planes for d_b_hat: plane l, [N][ldm] with zero padding past M.
-__global__ __launch_bounds__(256) void split_cols_kernel(const float *__restrict__ g, int M, int N, int ldm,
-                                                         int8_t *__restrict__ planes, int64_t plane_bytes,
-                                                         const BwdPlan *plan)
-{
-    __shared__ float tile[64][65];
-    const int n_limbs = plan->limbs_db;
-    const float inv_sigma = ldexpf(1.0f, -plan->scale_exp);
-    const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
-    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
-        const int m = i >> 6, n = i & 63;
-        tile[m][n] = (m0 + m < M && n0 + n < N) ? g[(int64_t)(m0 + m) * N + n0 + n] : 0.0f;
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
-        const int n = i >> 6, m = i & 63;
-        if (n0 + n < N && m0 + m < ldm) {
-            int8_t limb[kMaxLimbs];
-            split_limbs(tile[m][n], inv_sigma, n_limbs, limb);
-            for (int l = 0; l < n_limbs; ++l)
-                planes[(int64_t)l * plane_bytes + (int64_t)(n0 + n) * ldm + m0 + m] = limb[l];
-        }
-    }
+    plan->gscale_da = ldexpf(1.0f, 8 * la - 1 - e);
+    plan->gscale_db = ldexpf(1.0f, 8 * lb - 1 - e);
+    plan->out_scale_da = (double)delta_b * ldexp(1.0, e + 1 - 8 * la);
+    plan->out_scale_db = (double)delta_a * ldexp(1.0, e + 1 - 8 * lb);
 }
 
 __global__ void zero_f32_kernel(float *p, int64_t n)
@@ -395,26 +670,61 @@ inline unsigned blocks_for(int64_t n, int per_block, int cap = 65536)
 
 // workspace layout of a backward call
 struct BwdLayout {
-    size_t plan, bt, at, la, lb, total;
+    size_t plan, bt, at, partial, total;
     int64_t ldn, ldm;             // padded contraction lengths
-    int64_t la_plane, lb_plane;
+    int splits, kt_per_split;     // d_b_hat: splits of the contraction over M
 };
 
 BwdLayout bwd_layout(int32_t M, int32_t N, int32_t K)
 {
     BwdLayout L;
-    L.ldn = pad_to(N, 64);
-    L.ldm = pad_to(M, 64);
-    L.la_plane = (int64_t)M * L.ldn;
-    L.lb_plane = (int64_t)N * L.ldm;
+    L.ldn = pad_to(N, kLBK);
+    L.ldm = pad_to(M, kLBK);
+    // d_b_hat has few output tiles and a long contraction: cut the contraction so that about three
+    // blocks per compute unit exist, each with at least four K-tiles and (int32 accumulators of
+    // products up to 2^14) at most 1023 of them.
+    const int64_t base = (int64_t)((N + kLRows - 1) / kLRows) * ((K + limb_cols(5) - 1) / limb_cols(5));
+    const int64_t nk = L.ldm / kLBK;
+    int64_t splits = (768 + base - 1) / base;
+    if (splits > nk / 4) splits = nk / 4;
+    if (splits < 1) splits = 1;
+    int64_t per = (nk + splits - 1) / splits;
+    if (per > 1023) per = 1023;
+    splits = (nk + per - 1) / per;
+    L.splits = (int)splits;
+    L.kt_per_split = (int)per;
     size_t off = 0;
-    L.plan = off; off += align_up(sizeof(BwdPlan), 256);
-    L.bt = off;   off += align_up((size_t)K * (size_t)L.ldn, 256);           // b_idx^T: [K][ldn]
-    L.at = off;   off += align_up((size_t)K * (size_t)L.ldm, 256);           // a_idx^T: [K][ldm]
-    L.la = off;   off += align_up((size_t)kMaxLimbs * (size_t)L.la_plane, 256);
-    L.lb = off;   off += align_up((size_t)kMaxLimbs * (size_t)L.lb_plane, 256);
+    L.plan = off;    off += align_up(sizeof(BwdPlan), 256);
+    L.bt = off;      off += align_up((size_t)K * (size_t)L.ldn, 256);           // b_idx^T: [K][ldn]
+    L.at = off;      off += align_up((size_t)K * (size_t)L.ldm, 256);           // a_idx^T: [K][ldm]
+    L.partial = off; off += L.splits > 1 ? align_up((size_t)L.splits * (size_t)N * (size_t)K * sizeof(double), 256) : 0;
     L.total = off;
     return L;
+}
+
+int launch_limb_gemm(LimbArgs a, bool trans, hipStream_t stream)
+{
+    // the limb count, hence the column tile, is only known on the device: size the grid for the narrowest tile
+    const int64_t tiles_c = (a.cols + limb_cols(6) - 1) / limb_cols(6);
+    const int64_t items = (int64_t)a.tiles_r * tiles_c * a.splits;
+    if (items > 2147483640LL) return CDL_ERR_PARAM;
+    const unsigned grid = (unsigned)((items + 7) / 8 * 8);
+    {
+        // more than 64 KiB of dynamic LDS has to be allowed per function (and per device: set it every time)
+        const void *fn = trans ? (const void *)limb_gemm_kernel<true> : (const void *)limb_gemm_kernel<false>;
+        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLimbLdsBytes);
+        if (e != hipSuccess) return hip_failed(e);
+    }
+    if (trans) CDL_LAUNCH("limb_gemm_kernel(d_b_hat)", stream, limb_gemm_kernel<true>, dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
+    else CDL_LAUNCH("limb_gemm_kernel(d_a_hat)", stream, limb_gemm_kernel<false>, dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
+    return check_launch();
+}
+
+void launch_transpose(const int8_t *src, int rows, int cols, int8_t *dst, int64_t ldd, unsigned long long *sumsq, hipStream_t stream)
+{
+    const dim3 grid((cols + 63) / 64, (unsigned)(ldd / 128));
+    if (cols % 4 == 0) CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel<true>, grid, dim3(256), 0, src, rows, cols, dst, ldd, sumsq);
+    else CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel<false>, grid, dim3(256), 0, src, rows, cols, dst, ldd, sumsq);
 }
 
 }  // namespace
@@ -442,7 +752,7 @@ int launch_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_
         return check_launch();
     }
     GemmArgs g{};
-    g.A = a_idx; g.B = b_idx; g.lda = K; g.ldb = K; g.a_plane = 0;
+    g.A = a_idx; g.B = b_idx; g.lda = K; g.ldb = K;
     g.rowsA = M; g.rowsB = N; g.Kc = K;
     if (K % 16 != 0) {
         // rows would not start on 16-byte boundaries: stage zero-padded copies
@@ -457,8 +767,7 @@ int launch_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_
     }
     g.acc_out = acc; g.y_out = y; g.ldc = N;
     g.scale = delta_a * delta_b;
-    g.plan = nullptr; g.which = 0;
-    return launch_gemm<4, 2, false>(g, stream);
+    return launch_gemm<4, 2>(g, stream);
 }
 
 int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
@@ -476,46 +785,44 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
     BwdPlan *plan = reinterpret_cast<BwdPlan *>(base + L.plan);
     int8_t *bt = reinterpret_cast<int8_t *>(base + L.bt);
     int8_t *at = reinterpret_cast<int8_t *>(base + L.at);
-    int8_t *la = reinterpret_cast<int8_t *>(base + L.la);
-    int8_t *lb = reinterpret_cast<int8_t *>(base + L.lb);
+    double *partial = reinterpret_cast<double *>(base + L.partial);
 
     CDL_LAUNCH("plan_init_kernel", stream, plan_init_kernel, dim3(1), dim3(1), 0, plan);
-    CDL_LAUNCH("absmax_kernel", stream, absmax_kernel, dim3(blocks_for(((int64_t)M * N) >> 2, 256, 2048)), dim3(256), 0, gr, (int64_t)M * N, plan);
-    if (d_a_hat)
-        CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel, dim3((K + 63) / 64, (unsigned)(L.ldn / 64)), dim3(256), 0,
-                           b_idx, N, K, bt, (int)L.ldn, &plan->sumsq_b);
-    if (d_b_hat)
-        CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel, dim3((K + 63) / 64, (unsigned)(L.ldm / 64)), dim3(256), 0,
-                           a_idx, M, K, at, (int)L.ldm, &plan->sumsq_a);
+    CDL_LAUNCH("absmax_kernel", stream, absmax_kernel, dim3(blocks_for(((int64_t)M * N) >> 2, 256 * 8, 4096)), dim3(256), 0, gr, (int64_t)M * N, plan);
+    if (d_a_hat) launch_transpose(b_idx, N, K, bt, L.ldn, &plan->sumsq_b, stream);
+    if (d_b_hat) launch_transpose(a_idx, M, K, at, L.ldm, &plan->sumsq_a, stream);
     CDL_LAUNCH("plan_kernel", stream, plan_kernel, dim3(1), dim3(1), 0, plan, M, N, K, delta_a, delta_b);
     int rc = check_launch();
     if (rc != CDL_OK) return rc;
 
     if (d_a_hat) {
-        CDL_LAUNCH("split_rows_kernel", stream, split_rows_kernel, dim3(blocks_for(L.la_plane, 256, 16384)), dim3(256), 0,
-                           gr, M, N, (int)L.ldn, la, L.la_plane, plan);
-        GemmArgs g{};
-        g.A = la; g.lda = L.ldn; g.a_plane = L.la_plane;
-        g.B = bt; g.ldb = L.ldn;
-        g.rowsA = M; g.rowsB = K; g.Kc = (int)L.ldn;
-        g.acc_out = nullptr; g.y_out = d_a_hat; g.ldc = K;
-        g.plan = plan; g.which = 0;
-        rc = launch_gemm<2, 2, true>(g, stream);
+        LimbArgs a{};
+        a.G = gr; a.M = M; a.N = N;
+        a.Bt = bt; a.ldb = L.ldn;
+        a.rows = M; a.cols = K; a.kc = N;
+        a.tiles_r = (M + kLRows - 1) / kLRows; a.splits = 1; a.kt_per_split = (int)(L.ldn / kLBK);
+        a.plan = plan; a.which = 0;
+        a.out = d_a_hat; a.partial = nullptr;
+        rc = launch_limb_gemm(a, false, stream);
         if (rc != CDL_OK) return rc;
     }
     if (d_b_hat) {
-        CDL_LAUNCH("split_cols_kernel", stream, split_cols_kernel, dim3((N + 63) / 64, (unsigned)(L.ldm / 64)), dim3(256), 0,
-                           gr, M, N, (int)L.ldm, lb, L.lb_plane, plan);
-        GemmArgs g{};
-        g.A = lb; g.lda = L.ldm; g.a_plane = L.lb_plane;
-        g.B = at; g.ldb = L.ldm;
-        g.rowsA = N; g.rowsB = K; g.Kc = (int)L.ldm;
-        g.acc_out = nullptr; g.y_out = d_b_hat; g.ldc = K;
-        g.plan = plan; g.which = 1;
-        rc = launch_gemm<2, 2, true>(g, stream);
+        LimbArgs a{};
+        a.G = gr; a.M = M; a.N = N;
+        a.Bt = at; a.ldb = L.ldm;
+        a.rows = N; a.cols = K; a.kc = M;
+        a.tiles_r = (N + kLRows - 1) / kLRows; a.splits = L.splits; a.kt_per_split = L.kt_per_split;
+        a.plan = plan; a.which = 1;
+        a.out = d_b_hat; a.partial = partial;
+        rc = launch_limb_gemm(a, true, stream);
         if (rc != CDL_OK) return rc;
+        if (L.splits > 1) {
+            CDL_LAUNCH("limb_reduce_kernel", stream, limb_reduce_kernel, dim3(blocks_for((int64_t)N * K, 256, 4096)), dim3(256), 0,
+                       partial, L.splits, (int64_t)N * K, plan, d_b_hat);
+            rc = check_launch();
+        }
     }
-    return CDL_OK;
+    return rc;
 }
 
 }  // namespace cdl

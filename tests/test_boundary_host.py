@@ -103,8 +103,8 @@ def test_gemm_argument_validation_happens_before_any_gpu_work(cdl):
     assert b(FAKE, FAKE, FAKE, 4, 4, 16, 1.0, 1.0, None, None, None, 0, None) == NULL
     assert b(None, FAKE, FAKE, 4, 4, 16, 1.0, 1.0, FAKE, FAKE, None, 0, None) == NULL
     assert b(FAKE, FAKE, FAKE, 4, 4, 16, 1.0, 1.0, FAKE, FAKE, None, 0, None) == WS
-    assert b(FAKE, FAKE, FAKE, 4, 262145, 16, 1.0, 1.0, FAKE, None, None, 0, None) == RANGE
-    assert b(FAKE, FAKE, FAKE, 262145, 4, 16, 1.0, 1.0, None, FAKE, None, 0, None) == RANGE
+    assert b(FAKE, FAKE, FAKE, 4, 131072, 16, 1.0, 1.0, FAKE, None, None, 0, None) == RANGE      # contraction over N, int32
+    assert b(FAKE, FAKE, FAKE, 262145, 4, 16, 1.0, 1.0, None, FAKE, None, 0, None) == WS         # contraction over M is cut up
     assert lib.cdl_profile_collect(None, 4) == PARAM
 
 
