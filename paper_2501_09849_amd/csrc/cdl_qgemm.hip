@@ -15,6 +15,8 @@
 
 #include <math.h>
 
+#include <type_traits>
+
 namespace cdl {
 
 namespace {
@@ -29,12 +31,9 @@ constexpr int kKT = 64;          // forward: contraction bytes staged per pipeli
 
 // Device-side plan of one backward call: scale of the gradient and limb counts.
 struct BwdPlan {
-    unsigned int absmax_bits;        // max |g| as fp32 bits (non-negative floats order like unsigned ints)
     int limbs_da, limbs_db;          // limbs used for d_a_hat / d_b_hat
     float gscale_da, gscale_db;      // 2^(8L-1) / sigma
     double out_scale_da, out_scale_db;  // delta_b * sigma / 2^(8L-1), delta_a * sigma / 2^(8L-1)
-    unsigned long long sumsq_a;      // sum of a_idx^2 (all entries)
-    unsigned long long sumsq_b;      // sum of b_idx^2
 };
 
 struct GemmArgs {
@@ -199,8 +198,9 @@ int launch_gemm(GemmArgs a, hipStream_t stream)
 struct LimbArgs {
     const float *G;       // [M][N] fp32 upstream gradient
     int M, N;
-    const int8_t *Bt;     // [cols][ldb] int8 index matrix, contraction index contiguous, zero-filled up to ldb
-    int64_t ldb;          // multiple of kLBK
+    const int8_t *Bt;     // [cols][ldb] int8 index matrix, contraction index contiguous, zero-filled up to nk * kLBK
+    int64_t ldb;          // row stride in bytes: an odd multiple of kLBK, so that rows start in different memory channels
+    int nk;               // K-tiles covering the contraction: ceil(kc / kLBK)
     int rows, cols, kc;   // output rows / columns, contraction length
     int tiles_r, splits, kt_per_split;
     const BwdPlan *plan;
@@ -292,15 +292,19 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
     constexpr int KS = kLBK / 32;
 
     const int tiles_c = (a.cols + NB - 1) / NB;
+    // Workgroups go to the eight XCDs round-robin: XCD x takes the x-th eighth of the work items, so that
+    // neighbouring items (same rows of G, next column tile) share an L2.  The grid may hold more blocks
+    // than items (it is sized before the limb count is known).
     const int64_t items = (int64_t)a.tiles_r * tiles_c * a.splits;
-    const int per_xcd = (int)gridDim.x >> 3;
-    const int64_t logical = (int64_t)((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
-    if (logical >= items) return;
+    const int64_t per_xcd = (items + 7) >> 3;
+    const int64_t slot = (int64_t)((int)blockIdx.x >> 3);
+    const int64_t logical = (int64_t)((int)blockIdx.x & 7) * per_xcd + slot;
+    if (slot >= per_xcd || logical >= items) return;
     const int tile_c = (int)(logical % tiles_c);
     const int64_t rest = logical / tiles_c;
     const int tile_r = (int)(rest % a.tiles_r);
     const int split = (int)(rest / a.tiles_r);
-    const int nk_total = (int)(a.ldb / kLBK);
+    const int nk_total = a.nk;
     const int kt0 = split * a.kt_per_split;
     const int nk = min(nk_total, kt0 + a.kt_per_split) - kt0;
     const int row0 = tile_r * kLRows, col0 = tile_c * NB;
@@ -383,13 +387,15 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
         const int s = (wave * WLB + i) * 64 + lane, row = s >> 3;
         const int q = (s & 7) ^ lswz(row);
         const int gcol = min(col0 + row, a.cols - 1);
-        gb[i] = a.Bt + (int64_t)gcol * a.ldb + (int64_t)kt0 * kLBK + q * 16;
+        gb[i] = a.Bt + (int64_t)gcol * a.ldb + q * 16;
     }
+    // (a tile index past the last K-tile of the matrix is clamped: such a tile is loaded into a stage nobody reads)
     auto issue_b = [&](int kt) {
         int8_t *base = lds + (kt & 1) * STAGE + L * kLPlane;
+        const int64_t koff = (int64_t)min(kt0 + kt, nk_total - 1) * kLBK;
 #pragma unroll
         for (int i = 0; i < WLB; ++i)
-            __builtin_amdgcn_global_load_lds((gptr_t)(gb[i] + (int64_t)kt * kLBK), (lptr_t)(base + (wave * WLB + i) * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(gb[i] + koff), (lptr_t)(base + (wave * WLB + i) * 1024), 16, 0, 0);
     };
 
     // ---- fragments ----
@@ -479,19 +485,25 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
     }
 
     // ---- epilogue: recombine the limbs; the integers are exact, the Horner steps round at 2^-53 relative ----
+    // (The lane index passes through an empty asm so that the output addresses are formed here, after the
+    // loop, instead of being kept in registers all the way through it.)
+    int elane = lane;
+    asm volatile("" : "+v"(elane));
+    const int erow = row0 + 4 * (elane >> 5), ecol = col0 + wave * TN * 32 + (elane & 31);
+    const bool full = row0 + kLRows <= a.rows && col0 + NB <= a.cols;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        const int col = col0 + (wave * TN + j) * 32 + (lane & 31);
-        if (col >= a.cols) continue;
+        const int col = ecol + j * 32;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int row = row0 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            if (row >= a.rows) continue;
+            const int row = erow + 8 * (r >> 2) + (r & 3);
             double run = (double)acc[L - 1][j][r];
 #pragma unroll
             for (int l = L - 2; l >= 0; --l) run = run * 256.0 + (double)acc[l][j][r];
-            if (a.splits == 1) a.out[(int64_t)row * a.cols + col] = (float)(run * out_scale);
-            else a.partial[((int64_t)split * a.rows + row) * a.cols + col] = run;
+            if (full || (row < a.rows && col < a.cols)) {
+                if (a.splits == 1) a.out[(int64_t)row * a.cols + col] = (float)(run * out_scale);
+                else a.partial[((int64_t)split * a.rows + row) * a.cols + col] = run;
+            }
         }
     }
 }
@@ -538,45 +550,53 @@ __global__ void pad_rows_kernel(const int8_t *__restrict__ src, int64_t rows, in
     }
 }
 
-__global__ void plan_init_kernel(BwdPlan *plan)
+// max |g| per block (as fp32 bits: non-negative floats order like unsigned ints): each block streams
+// contiguous pieces, eight independent 16-byte loads per thread and trip.  One plain store per block -
+// thousands of atomics on one address would take longer than the pass itself.
+__global__ __launch_bounds__(256) void absmax_kernel(const float *__restrict__ g, int64_t n, unsigned int *__restrict__ block_max)
 {
-    plan->absmax_bits = 0u;
-    plan->sumsq_a = 0ull;
-    plan->sumsq_b = 0ull;
-}
-
-__global__ __launch_bounds__(256) void absmax_kernel(const float *__restrict__ g, int64_t n, BwdPlan *plan)
-{
+    __shared__ unsigned int wave_max[4];
     unsigned int m = 0u;
     const int64_t n4 = n >> 2;
-    const int64_t stride = (int64_t)gridDim.x * 256;
-#pragma unroll 4
-    for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < n4; v += stride) {
-        const float4 t = reinterpret_cast<const float4 *>(g)[v];
-        m = max(m, __float_as_uint(fabsf(t.x)));
-        m = max(m, __float_as_uint(fabsf(t.y)));
-        m = max(m, __float_as_uint(fabsf(t.z)));
-        m = max(m, __float_as_uint(fabsf(t.w)));
+    const float4 *g4 = reinterpret_cast<const float4 *>(g);
+    for (int64_t base = (int64_t)blockIdx.x * 2048; base < n4; base += (int64_t)gridDim.x * 2048) {
+        float4 t[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int64_t v = base + j * 256 + threadIdx.x;
+            t[j] = v < n4 ? g4[v] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            m = max(m, __float_as_uint(fabsf(t[j].x)));
+            m = max(m, __float_as_uint(fabsf(t[j].y)));
+            m = max(m, __float_as_uint(fabsf(t[j].z)));
+            m = max(m, __float_as_uint(fabsf(t[j].w)));
+        }
     }
     if (blockIdx.x == 0 && threadIdx.x == 0)
         for (int64_t e = n4 << 2; e < n; ++e) m = max(m, __float_as_uint(fabsf(g[e])));
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) m = max(m, (unsigned int)__shfl_down((int)m, off, 64));
-    if ((threadIdx.x & 63) == 0 && m != 0u) atomicMax(&plan->absmax_bits, m);
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) block_max[blockIdx.x] = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
 }
 
-// dst[c][r] = src[r][c] for an int8 matrix [rows][cols]; dst rows are ldd (a multiple of 128) long,
-// zero-filled past `rows`.  Also adds sum(src^2) to *sumsq.  One block moves a tile of 128 rows x
+// dst[c][r] = src[r][c] for an int8 matrix [rows][cols]; dst rows are ldd bytes apart and are
+// zero-filled from `rows` up to the next multiple of 128.  Also writes the block's sum(src^2) to
+// block_sumsq[block].  One block moves a tile of 128 rows x
 // 64 columns: 4-byte loads along the rows into LDS (row stride 17 words), then every thread takes a
 // 4 x 4 byte block, transposes it in registers and stores 4 bytes of four output rows, so that 32
 // lanes write 128 contiguous bytes.  VEC: cols % 4 == 0 (aligned 4-byte loads).
 template <bool VEC>
 __global__ __launch_bounds__(256) void transpose_i8_kernel(const int8_t *__restrict__ src, int rows, int cols,
                                                            int8_t *__restrict__ dst, int64_t ldd,
-                                                           unsigned long long *sumsq)
+                                                           unsigned int *__restrict__ block_sumsq)
 {
     __shared__ uint32_t tile[128 * 17];
-    const int r0 = blockIdx.y * 128, c0 = blockIdx.x * 64;
+    __shared__ unsigned int wave_ss[4];
+    const int r0 = blockIdx.x * 128, c0 = blockIdx.y * 64;   // neighbouring blocks write neighbouring 128-byte pieces
     const int tid = threadIdx.x;
     unsigned int ss = 0u;
 #pragma unroll
@@ -620,7 +640,10 @@ __global__ __launch_bounds__(256) void transpose_i8_kernel(const int8_t *__restr
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) ss += (unsigned int)__shfl_down((int)ss, off, 64);
-    if ((threadIdx.x & 63) == 0 && ss != 0u) atomicAdd(sumsq, (unsigned long long)ss);
+    if ((threadIdx.x & 63) == 0) wave_ss[threadIdx.x >> 6] = ss;
+    __syncthreads();   // (the barrier above separates the tile's writes from its reads; this one the partial sums)
+    if (threadIdx.x == 0)   // at most 128 * 64 * 128^2 = 2^27
+        block_sumsq[(size_t)blockIdx.y * gridDim.x + blockIdx.x] = wave_ss[0] + wave_ss[1] + wave_ss[2] + wave_ss[3];
 }
 
 // Chooses the power-of-two scale of g and, for each backward product, the number of limbs.  With
@@ -628,14 +651,35 @@ __global__ __launch_bounds__(256) void transpose_i8_kernel(const int8_t *__restr
 // in +-sigma 2^-8L per entry, so a contraction over n_c index entries of mean square s has a random
 // error of about delta sigma 2^(1-8L) sqrt(n_c s / 12); L is the smallest count (3..6) that brings
 // this under 1.7e-7, a sixth of the absolute parity tolerance.
-__global__ void plan_kernel(BwdPlan *plan, int M, int N, int K, float delta_a, float delta_b)
+__global__ __launch_bounds__(256)
+void plan_kernel(BwdPlan *plan, const unsigned int *__restrict__ block_max, int n_max,
+                 const unsigned int *__restrict__ ss_a, int n_ss_a, const unsigned int *__restrict__ ss_b, int n_ss_b,
+                 int M, int N, int K, float delta_a, float delta_b)
 {
-    const float amax = __uint_as_float(plan->absmax_bits);
+    __shared__ unsigned int red_m[256];
+    __shared__ unsigned long long red_a[256], red_b[256];
+    unsigned int m = 0u;
+    unsigned long long sa = 0ull, sb = 0ull;
+    for (int i = threadIdx.x; i < n_max; i += 256) m = max(m, block_max[i]);
+    for (int i = threadIdx.x; i < n_ss_a; i += 256) sa += ss_a[i];
+    for (int i = threadIdx.x; i < n_ss_b; i += 256) sb += ss_b[i];
+    red_m[threadIdx.x] = m; red_a[threadIdx.x] = sa; red_b[threadIdx.x] = sb;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) {
+            red_m[threadIdx.x] = max(red_m[threadIdx.x], red_m[threadIdx.x + off]);
+            red_a[threadIdx.x] += red_a[threadIdx.x + off];
+            red_b[threadIdx.x] += red_b[threadIdx.x + off];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x != 0) return;
+    const float amax = __uint_as_float(red_m[0]);
     int e = 0;
     if (amax > 0.0f) frexpf(amax * 1.01f, &e);   // amax * 1.01 = f 2^e with f in [0.5, 1)
     e = max(min(e, 127), -80);                   // keeps 2^(8L-1-e) a normal float for every L
-    const double msq_a = (double)plan->sumsq_a / fmax(1.0, (double)M * (double)K);
-    const double msq_b = (double)plan->sumsq_b / fmax(1.0, (double)N * (double)K);
+    const double msq_a = (double)red_a[0] / fmax(1.0, (double)M * (double)K);
+    const double msq_b = (double)red_b[0] / fmax(1.0, (double)N * (double)K);
     const double target = 1.7e-7;
     int la = kMinLimbs, lb = kMinLimbs;
     while (la < kMaxLimbs && (double)delta_b * ldexp(1.0, e + 1 - 8 * la) * sqrt((double)N * msq_b / 12.0) > target) ++la;
@@ -670,21 +714,25 @@ inline unsigned blocks_for(int64_t n, int per_block, int cap = 65536)
 
 // workspace layout of a backward call
 struct BwdLayout {
-    size_t plan, bt, at, partial, total;
-    int64_t ldn, ldm;             // padded contraction lengths
+    size_t plan, block_max, ss_a, ss_b, bt, at, partial, total;
+    int n_max, n_ss_a, n_ss_b;    // per-block partial results of the absmax and the two transpose launches
+    int64_t ldn, ldm;             // row strides of the transposed index copies (odd multiples of kLBK)
+    int nk_n, nk_m;               // K-tiles of the two contractions
     int splits, kt_per_split;     // d_b_hat: splits of the contraction over M
 };
 
 BwdLayout bwd_layout(int32_t M, int32_t N, int32_t K)
 {
     BwdLayout L;
-    L.ldn = pad_to(N, kLBK);
-    L.ldm = pad_to(M, kLBK);
+    L.nk_n = (int)((N + kLBK - 1) / kLBK);
+    L.nk_m = (int)((M + kLBK - 1) / kLBK);
+    L.ldn = (int64_t)(L.nk_n | 1) * kLBK;
+    L.ldm = (int64_t)(L.nk_m | 1) * kLBK;
     // d_b_hat has few output tiles and a long contraction: cut the contraction so that about three
     // blocks per compute unit exist, each with at least four K-tiles and (int32 accumulators of
     // products up to 2^14) at most 1023 of them.
     const int64_t base = (int64_t)((N + kLRows - 1) / kLRows) * ((K + limb_cols(5) - 1) / limb_cols(5));
-    const int64_t nk = L.ldm / kLBK;
+    const int64_t nk = L.nk_m;
     int64_t splits = (768 + base - 1) / base;
     if (splits > nk / 4) splits = nk / 4;
     if (splits < 1) splits = 1;
@@ -693,8 +741,14 @@ BwdLayout bwd_layout(int32_t M, int32_t N, int32_t K)
     splits = (nk + per - 1) / per;
     L.splits = (int)splits;
     L.kt_per_split = (int)per;
+    L.n_max = (int)blocks_for(((int64_t)M * N) >> 2, 2048, 2048);
+    L.n_ss_a = (int)(((int64_t)M + 127) / 128 * ((K + 63) / 64));
+    L.n_ss_b = (int)(((int64_t)N + 127) / 128 * ((K + 63) / 64));
     size_t off = 0;
     L.plan = off;    off += align_up(sizeof(BwdPlan), 256);
+    L.block_max = off; off += align_up((size_t)L.n_max * sizeof(unsigned int), 256);
+    L.ss_a = off;    off += align_up((size_t)L.n_ss_a * sizeof(unsigned int), 256);
+    L.ss_b = off;    off += align_up((size_t)L.n_ss_b * sizeof(unsigned int), 256);
     L.bt = off;      off += align_up((size_t)K * (size_t)L.ldn, 256);           // b_idx^T: [K][ldn]
     L.at = off;      off += align_up((size_t)K * (size_t)L.ldm, 256);           // a_idx^T: [K][ldm]
     L.partial = off; off += L.splits > 1 ? align_up((size_t)L.splits * (size_t)N * (size_t)K * sizeof(double), 256) : 0;
@@ -720,11 +774,11 @@ int launch_limb_gemm(LimbArgs a, bool trans, hipStream_t stream)
     return check_launch();
 }
 
-void launch_transpose(const int8_t *src, int rows, int cols, int8_t *dst, int64_t ldd, unsigned long long *sumsq, hipStream_t stream)
+void launch_transpose(const int8_t *src, int rows, int cols, int8_t *dst, int64_t ldd, unsigned int *block_sumsq, hipStream_t stream)
 {
-    const dim3 grid((cols + 63) / 64, (unsigned)(ldd / 128));
-    if (cols % 4 == 0) CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel<true>, grid, dim3(256), 0, src, rows, cols, dst, ldd, sumsq);
-    else CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel<false>, grid, dim3(256), 0, src, rows, cols, dst, ldd, sumsq);
+    const dim3 grid((rows + 127) / 128, (cols + 63) / 64);
+    if (cols % 4 == 0) CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel<true>, grid, dim3(256), 0, src, rows, cols, dst, ldd, block_sumsq);
+    else CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel<false>, grid, dim3(256), 0, src, rows, cols, dst, ldd, block_sumsq);
 }
 
 }  // namespace
@@ -787,11 +841,14 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
     int8_t *at = reinterpret_cast<int8_t *>(base + L.at);
     double *partial = reinterpret_cast<double *>(base + L.partial);
 
-    CDL_LAUNCH("plan_init_kernel", stream, plan_init_kernel, dim3(1), dim3(1), 0, plan);
-    CDL_LAUNCH("absmax_kernel", stream, absmax_kernel, dim3(blocks_for(((int64_t)M * N) >> 2, 256 * 8, 4096)), dim3(256), 0, gr, (int64_t)M * N, plan);
-    if (d_a_hat) launch_transpose(b_idx, N, K, bt, L.ldn, &plan->sumsq_b, stream);
-    if (d_b_hat) launch_transpose(a_idx, M, K, at, L.ldm, &plan->sumsq_a, stream);
-    CDL_LAUNCH("plan_kernel", stream, plan_kernel, dim3(1), dim3(1), 0, plan, M, N, K, delta_a, delta_b);
+    unsigned int *block_max = reinterpret_cast<unsigned int *>(base + L.block_max);
+    unsigned int *ss_a = reinterpret_cast<unsigned int *>(base + L.ss_a);
+    unsigned int *ss_b = reinterpret_cast<unsigned int *>(base + L.ss_b);
+    CDL_LAUNCH("absmax_kernel", stream, absmax_kernel, dim3(L.n_max), dim3(256), 0, gr, (int64_t)M * N, block_max);
+    if (d_a_hat) launch_transpose(b_idx, N, K, bt, L.ldn, ss_b, stream);
+    if (d_b_hat) launch_transpose(a_idx, M, K, at, L.ldm, ss_a, stream);
+    CDL_LAUNCH("plan_kernel", stream, plan_kernel, dim3(1), dim3(256), 0, plan, block_max, L.n_max,
+               ss_a, d_b_hat ? L.n_ss_a : 0, ss_b, d_a_hat ? L.n_ss_b : 0, M, N, K, delta_a, delta_b);
     int rc = check_launch();
     if (rc != CDL_OK) return rc;
 
@@ -800,7 +857,8 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
         a.G = gr; a.M = M; a.N = N;
         a.Bt = bt; a.ldb = L.ldn;
         a.rows = M; a.cols = K; a.kc = N;
-        a.tiles_r = (M + kLRows - 1) / kLRows; a.splits = 1; a.kt_per_split = (int)(L.ldn / kLBK);
+        a.nk = L.nk_n;
+        a.tiles_r = (M + kLRows - 1) / kLRows; a.splits = 1; a.kt_per_split = L.nk_n;
         a.plan = plan; a.which = 0;
         a.out = d_a_hat; a.partial = nullptr;
         rc = launch_limb_gemm(a, false, stream);
@@ -811,6 +869,7 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
         a.G = gr; a.M = M; a.N = N;
         a.Bt = at; a.ldb = L.ldm;
         a.rows = N; a.cols = K; a.kc = M;
+        a.nk = L.nk_m;
         a.tiles_r = (N + kLRows - 1) / kLRows; a.splits = L.splits; a.kt_per_split = L.kt_per_split;
         a.plan = plan; a.which = 1;
         a.out = d_b_hat; a.partial = partial;
