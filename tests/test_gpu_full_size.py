@@ -1,0 +1,150 @@
+"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+
+The oracle cannot run the large workloads whole in test time, so every output is checked either on
+sampled entries the oracle computes one by one, or through a property that holds at any size:
+
+* quantizer forward / backward, elementwise outputs: a random sample of entries (plus the first and
+  the last ones) against the oracle evaluated on exactly those entries;
+* marginal PMF, entropy and the two scalar gradients are sums over the tensor: the result of the
+  full-size call must equal the (weighted) sum of the results on 16 consecutive pieces, and two of
+  the pieces are compared with the oracle;
+* forward product: sampled rows of y, and of the int32 accumulators (bit-exact);
+* backward products: sampled rows of dL/dQ(x) (each needs one row of g), sampled rows of dL/dQ(w)
+  (each needs one column of g and the whole contraction over the batch).
+
+Tolerances as everywhere: |gpu - oracle| <= 1e-6 + 1e-5 |oracle|, hard indices exact except where the
+oracle's two best level scores differ by less than 1e-6.
+"""
+import numpy as np
+import pytest
+
+import cdl_inputs
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+PIECES = 16
+SAMPLE = 200_000
+
+
+def _sample(n, rng, k=SAMPLE):
+    if n <= k:
+        return np.arange(n)
+    s = rng.choice(n, size=k, replace=False)
+    s[:8] = [0, 1, 2, 3, n - 4, n - 3, n - 2, n - 1]
+    return np.sort(s)
+
+
+def _quantizer_full(oracle, spec, theta_h, g_h, label):
+    """Forward (idx, soft, marginal, entropy) and backward (dtheta, d_delta, d_alpha) of one tensor."""
+    torch = gu.torch_mod()
+    rng = np.random.default_rng(12345)
+    q = gu.Quantizer(spec)
+    n = theta_h.size
+    th_d, g_d = gu.dev(theta_h.reshape(-1)), gu.dev(g_h.reshape(-1))
+    idx, soft, marg, ent = q.fwd(th_d)
+    dth, dd, da = q.bwd(th_d, g_d)
+
+    s = _sample(n, rng)
+    th_s = np.ascontiguousarray(theta_h.reshape(-1)[s])
+    r_idx, r_soft, gap = oracle.quantize_fwd(th_s, *q.args)
+    exempt = gu.assert_indices(idx[s], r_idx, gap, label + " idx")
+    gu.assert_close(soft[s], r_soft, label + " soft")
+    rb = oracle.quantize_bwd(th_s, np.ascontiguousarray(g_h.reshape(-1)[s]), *q.args)
+    gu.assert_close(dth[s], rb["dtheta"], label + " dtheta")
+
+    # sums over the tensor: full call == sum of pieces; two pieces == oracle
+    bounds = np.linspace(0, n, PIECES + 1).astype(np.int64) // 4 * 4    # pieces start on 16-byte boundaries
+    bounds[-1] = n
+    marg_sum = np.zeros(spec.n_levels)
+    dd_sum = da_sum = 0.0
+    check = {1, PIECES - 1}
+    for p in range(PIECES):
+        lo, hi = int(bounds[p]), int(bounds[p + 1])
+        m_p, h_p = q.marginal(th_d[lo:hi])
+        _, dd_p, da_p = q.bwd(th_d[lo:hi], g_d[lo:hi], dtheta=False)
+        marg_sum += m_p.astype(np.float64) * (hi - lo) / n
+        dd_sum += dd_p
+        da_sum += da_p
+        if p in check:
+            r_m, r_h = oracle.marginal_entropy(theta_h.reshape(-1)[lo:hi], *q.args)
+            gu.assert_close(m_p, r_m, "%s marginal of piece %d" % (label, p))
+            gu.assert_close([h_p], [r_h], "%s entropy of piece %d" % (label, p))
+            rp = oracle.quantize_bwd(theta_h.reshape(-1)[lo:hi], g_h.reshape(-1)[lo:hi], *q.args, want_dtheta=False)
+            # the scalar sums cancel heavily: allow what fp32 terms can carry relative to sum |term|
+            assert abs(dd_p - rp["d_delta"]) <= 1e-6 + 1e-5 * abs(rp["d_delta"]) + 2e-7 * rp["abs_sum_delta"], (label, p, dd_p, rp["d_delta"])
+            assert abs(da_p - rp["d_alpha"]) <= 1e-6 + 1e-5 * abs(rp["d_alpha"]) + 2e-7 * rp["abs_sum_alpha"], (label, p, da_p, rp["d_alpha"])
+    # every piece result is an fp32 number: its rounding (6e-8 relative) is what the two sides may differ by
+    assert np.all(np.abs(marg - marg_sum) <= 1e-6 + 1e-5 * marg_sum), label + " marginal: full call differs from the sum of its pieces"
+    h_from_marg = -np.sum(np.where(marg_sum > 0, marg_sum * np.log2(np.maximum(marg_sum, 1e-300)), 0.0))
+    assert abs(ent - h_from_marg) <= 1e-6 + 1e-5 * h_from_marg, (label, ent, h_from_marg)
+    assert abs(marg.astype(np.float64).sum() - 1.0) < 1e-5 and ent <= np.log2(spec.n_levels) + 1e-5
+    scale_d = max(abs(dd_sum), 1.0)
+    assert abs(dd - dd_sum) <= 1e-6 + 2e-5 * scale_d + 1e-6 * PIECES, (label, dd, dd_sum)
+    assert abs(da - da_sum) <= 1e-6 + 2e-5 * max(abs(da_sum), 1e-3), (label, da, da_sum)
+    torch.cuda.empty_cache()
+    return idx, exempt
+
+
+@pytest.mark.parametrize("number", [2, 3, 5])
+def test_layer_step_at_full_size(oracle, number):
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    wl = cdl_inputs.workload(number)
+    M, N, K = wl.M, wl.N, wl.K
+    w, x = wl.w_spec, wl.x_spec
+    rng = np.random.default_rng(777 + number)
+    W, X, G = cdl_inputs.draw_w(wl), cdl_inputs.draw_x(wl), cdl_inputs.draw_g(wl)
+
+    # ---- products on the GPU's own indices (the oracle is fed the same indices) ----
+    qw, qx = gu.Quantizer(w), gu.Quantizer(x)
+    W_d, X_d, G_d = gu.dev(W.reshape(-1)), gu.dev(X.reshape(-1)), gu.dev(G)
+    Wi_d, Xi_d = gu.empty((N * K,), torch.int8), gu.empty((M * K,), torch.int8)
+    cdl.cdl_quantize_fwd(W_d, N * K, *qw.args, Wi_d)
+    cdl.cdl_quantize_fwd(X_d, M * K, *qx.args, Xi_d)
+    ws = gu.workspace(max(cdl.qgemm_fwd_workspace_bytes(M, N, K), cdl.qgemm_bwd_workspace_bytes(M, N, K)))
+    Y = gu.empty((M, N), torch.float32)
+    cdl.cdl_qgemm_fwd(Xi_d, Wi_d, M, N, K, x.delta, w.delta, None, Y, ws)       # as bench.py calls it
+    dXh, dWh = gu.empty((M, K), torch.float32), gu.empty((N, K), torch.float32)
+    cdl.cdl_qgemm_bwd(G_d, Xi_d, Wi_d, M, N, K, x.delta, w.delta, dXh, dWh, ws)
+    torch.cuda.synchronize()
+    xi, wi = Xi_d.cpu().numpy().reshape(M, K), Wi_d.cpu().numpy().reshape(N, K)
+
+    rows = np.sort(np.concatenate([rng.choice(M, size=min(M, 96), replace=False), [0, M - 1]]))
+    rows = np.unique(rows)
+    rows_d = torch.from_numpy(rows).cuda()
+    r_acc, r_y = oracle.qgemm_fwd(np.ascontiguousarray(xi[rows]), wi, x.delta, w.delta)
+    gu.assert_close(Y[rows_d].cpu().numpy(), r_y, "y rows")
+    r_da, _ = oracle.qgemm_bwd(np.ascontiguousarray(G[rows]), np.ascontiguousarray(xi[rows]), wi, x.delta, w.delta, want_db=False)
+    gu.assert_close(dXh[rows_d].cpu().numpy(), r_da, "dL/dQ(x) rows")
+    cols = np.unique(np.concatenate([rng.choice(N, size=min(N, 6), replace=False), [0, N - 1]]))
+    _, r_db = oracle.qgemm_bwd(np.ascontiguousarray(G[:, cols]), xi, np.ascontiguousarray(wi[cols]), x.delta, w.delta, want_da=False)
+    gu.assert_close(dWh[torch.from_numpy(cols).cuda()].cpu().numpy(), r_db, "dL/dQ(w) rows")
+    del Y
+    torch.cuda.empty_cache()
+    acc = gu.empty((M, N), torch.int32)
+    cdl.cdl_qgemm_fwd(Xi_d, Wi_d, M, N, K, x.delta, w.delta, acc, None, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc[rows_d].cpu().numpy(), r_acc), "int32 accumulators differ on the sampled rows"
+    del acc
+    torch.cuda.empty_cache()
+
+    # ---- quantizer forward and backward on W and X, the backward fed with the GPU's own fp32 product gradients ----
+    dXh_h, dWh_h = dXh.cpu().numpy(), dWh.cpu().numpy()
+    del dXh, dWh, G_d, ws
+    torch.cuda.empty_cache()
+    wi_full, ex_w = _quantizer_full(oracle, w, W, dWh_h, "W%d" % number)
+    xi_full, ex_x = _quantizer_full(oracle, x, X, dXh_h, "X%d" % number)
+    assert np.array_equal(wi_full.reshape(N, K), wi) and np.array_equal(xi_full.reshape(M, K), xi)
+    print("workload %d: exempt near-tie indices in the samples: W %d, X %d" % (number, ex_w, ex_x))
+
+
+def test_flat_weight_tensor_at_full_size(oracle):
+    wl = cdl_inputs.workload(4)
+    W, G = cdl_inputs.draw_w(wl), cdl_inputs.draw_g(wl)
+    _, ex = _quantizer_full(oracle, wl.w_spec, W, G, "W4")
+    print("workload 4: exempt near-tie indices in the sample: %d" % ex)
+    # the soft regime of the same tensor (the paper's initial sharpness 500: kappa = 0.008, every level live)
+    soft_spec = wl.w_spec.with_alpha(cdl_inputs.ALPHA_PAPER)
+    n = 2_000_000
+    _quantizer_full(oracle, soft_spec, W[:n], G[:n], "W4 at the paper's initial sharpness")
