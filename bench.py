@@ -203,6 +203,108 @@ def quantizer_only(seed=0, iters=10):
             "kappa": wl.w_spec.alpha * wl.w_spec.delta ** 2}
 
 
+def load_traffic(wl_number):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, calibrated there)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_workload%d.txt" % wl_number)
+    table = {}
+    if not os.path.exists(path):
+        return table
+    for line in open(path):
+        if line.startswith("#") or line.startswith("kernel") or not line.strip():
+            continue
+        name, _, fetch_mb, write_mb = line.rstrip("\n").split("\t")
+        table.setdefault(name, []).append((float(fetch_mb) + float(write_mb)) * 1e6)
+    return table
+
+
+def traffic_of(table, kernel, occurrence):
+    """Maps a name of the library's event records to the kernel name rocprofv3 prints."""
+    if kernel == "limb_gemm_kernel(d_b_hat)":
+        key, occ = "limb_gemm_kernel<true>", 0
+    elif kernel == "limb_gemm_kernel(d_a_hat)":
+        key, occ = "limb_gemm_kernel<false>", 0
+    elif kernel == "qgemm_kernel(fwd)":
+        key, occ = "qgemm_kernel", 0
+    else:
+        key, occ = kernel, occurrence
+    for name, rows in table.items():
+        if name == key or name.startswith(key + "<"):
+            return rows[occ] if occ < len(rows) else None
+    return None
+
+
+def machine_probes():
+    """What the box itself sustains: a plain device copy (HBM) and register-resident int8 MFMAs (matrix cores)."""
+    import torch
+    import paper_2501_09849_amd as cdl
+    out = {}
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+    dst = torch.empty_like(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(2):
+        dst.copy_(src)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    out["copy_1GiB_GBps_read_plus_write"] = 2.0 * src.numel() * 4 / (e0.elapsed_time(e1) / 5 * 1e-3) / 1e9
+    del src, dst
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    for rnd, key in ((False, "int8_mfma_probe_TOPS_constant_operands"), (True, "int8_mfma_probe_TOPS_random_operands")):
+        cdl.cdl_probe_mfma_int8(2000, rnd, 256, sink)
+        torch.cuda.synchronize()
+        cdl.cdl_profile_enable(True)
+        ops = cdl.cdl_probe_mfma_int8(20000, rnd, 256, sink)
+        torch.cuda.synchronize()
+        recs = cdl.cdl_profile_collect()
+        cdl.cdl_profile_enable(False)
+        out[key] = ops / (recs[0][1] * 1e-3) / 1e12
+    return out
+
+
+def gemm_only(number, seed=0, iters=5):
+    """The three index products on another workload's shape (workload 3: the ImageNet conv layer)."""
+    import torch
+    import paper_2501_09849_amd as cdl
+    wl = cdl_inputs.workload(number)
+    M, N, K = wl.M, wl.N, wl.K
+    w, x = wl.w_spec, wl.x_spec
+    dev = "cuda:0"
+    Xi = torch.from_numpy(cdl_inputs.draw_indices((M, K), x.lo, x.hi, seed=seed + 1)).to(dev)
+    Wi = torch.from_numpy(cdl_inputs.draw_indices((N, K), w.lo, w.hi, seed=seed + 2)).to(dev)
+    G = torch.from_numpy(cdl_inputs.draw_g(wl, seed)).to(dev)
+    Y = torch.empty((M, N), dtype=torch.float32, device=dev)
+    dXh = torch.empty((M, K), dtype=torch.float32, device=dev)
+    dWh = torch.empty((N, K), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(256, cdl.qgemm_fwd_workspace_bytes(M, N, K), cdl.qgemm_bwd_workspace_bytes(M, N, K)),
+                     dtype=torch.uint8, device=dev)
+
+    def run():
+        cdl.cdl_qgemm_fwd(Xi, Wi, M, N, K, x.delta, w.delta, None, Y, ws)
+        cdl.cdl_qgemm_bwd(G, Xi, Wi, M, N, K, x.delta, w.delta, dXh, dWh, ws)
+    for _ in range(2):
+        run()
+    torch.cuda.synchronize()
+    cdl.cdl_profile_enable(True)
+    for _ in range(iters):
+        run()
+    torch.cuda.synchronize()
+    recs = cdl.cdl_profile_collect()
+    cdl.cdl_profile_enable(False)
+    t = {}
+    for k, ms in recs:
+        t.setdefault(k, []).append(ms)
+    ops = 2.0 * M * N * K
+    out = {"workload": "%d:%s" % (wl.number, wl.name), "M": M, "N": N, "K": K, "index_values": "uniform over the level sets"}
+    for key, name in (("fwd", "qgemm_kernel(fwd)"), ("d_a_hat", "limb_gemm_kernel(d_a_hat)"), ("d_b_hat", "limb_gemm_kernel(d_b_hat)")):
+        us = float(np.mean(t[name])) * 1e3
+        out[key + "_us"] = us
+        out[key + "_TOPS"] = ops / us / 1e6
+    out["bwd_total_us"] = sum(float(np.mean(v)) for k, v in t.items() if k != "qgemm_kernel(fwd)") * 1e3
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -211,6 +313,8 @@ def main():
     ap.add_argument("--workload", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known HBM traffic, to calibrate rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no sharding, no collectives); --gpus %d is not supported" % args.gpus)
@@ -225,6 +329,13 @@ def main():
     cdl.load()
     wl = cdl_inputs.workload(args.workload)
     st = Step(wl)
+
+    if args.copy_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         st.run()
@@ -266,13 +377,14 @@ def main():
                        frac=amount / (avg * 1e-3) / 1e12 / INT8_PEAK_TOPS)
         kernels.append(row)
     dom = max(kernels, key=lambda r: r["avg_us"])
+    traffic = traffic_of(load_traffic(wl.number), dom["kernel"], dom["launch"])
     if dom.get("bound") == "mfma":
         roofline = {"kernel": "%s #%d" % (dom["kernel"], dom["launch"]), "bound": "mfma", "achieved": dom["algorithmic_TOPS"],
-                    "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": dom["frac"], "traffic": None,
+                    "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": dom["frac"], "traffic": traffic,
                     "avg_launch_us": dom["avg_us"]}
     else:
         roofline = {"kernel": "%s #%d" % (dom["kernel"], dom["launch"]), "bound": "hbm", "achieved": dom.get("algorithmic_GBps"),
-                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom.get("frac"), "traffic": None,
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom.get("frac"), "traffic": traffic,
                     "avg_launch_us": dom["avg_us"]}
 
     out = OrderedDict()
@@ -306,8 +418,12 @@ def main():
         out["index_gemm_fwd_frac_of_int8_peak"] = gf[0]["frac"]
     del st
     torch.cuda.empty_cache()
-    if not args.no_extra and wl.number != 4:
-        out["quantizer_only_flat_25M"] = quantizer_only()
+    if not args.no_extra:
+        if wl.number != 4:
+            out["quantizer_only_flat_25M"] = quantizer_only()
+        if wl.number != 3:
+            out["index_gemms_conv_layer"] = gemm_only(3)
+        out["machine"] = machine_probes()
     print(json.dumps(out), flush=True)
 
 

@@ -152,6 +152,17 @@ typedef struct cdl_profile_record {
     float ms;           /* elapsed time between its two events */
 } cdl_profile_record;
 
+/*
+ * Measurement aid, not part of the method: enqueues a kernel that only issues int8 matrix-core
+ * instructions on register-resident operands (`blocks` workgroups of four waves, `iters` trips of
+ * eight 32x32x32 MFMAs per wave) and writes the number of integer operations it performs to *ops
+ * (HOST double, nullable).  random_operands = 0 keeps the operand bits constant, 1 gives every MFMA
+ * pseudo-random operand bits.  Timed with cdl_profile_* it yields the matrix-core rate the chip
+ * sustains at its power limit, which is what the GEMM kernels' fractions should be read against.
+ * sink: DEVICE int[1], never written in practice.
+ */
+int cdl_probe_mfma_int8(int32_t iters, int32_t random_operands, int32_t blocks, void *sink, double *ops, void *hip_stream);
+
 int cdl_profile_enable(int enable);
 int cdl_profile_collect(cdl_profile_record *out, int max_records);
 

@@ -17,7 +17,7 @@ _LIB = None
 EXPORTS = (
     "cdl_quantize_workspace_bytes", "cdl_qgemm_fwd_workspace_bytes", "cdl_qgemm_bwd_workspace_bytes",
     "cdl_quantize_fwd", "cdl_quantize_bwd", "cdl_marginal_entropy", "cdl_qgemm_fwd", "cdl_qgemm_bwd",
-    "cdl_profile_enable", "cdl_profile_collect",
+    "cdl_profile_enable", "cdl_profile_collect", "cdl_probe_mfma_int8",
     "cdl_status_string", "cdl_last_hip_error", "cdl_version",
 )
 
@@ -164,6 +164,16 @@ def cdl_qgemm_bwd(g, a_idx, b_idx, M, N, K, delta_a, delta_b, d_a_hat=None, d_b_
     wp, wb = _ws(ws)
     _check(load().cdl_qgemm_bwd(_ptr(g), _ptr(a_idx), _ptr(b_idx), M, N, K, delta_a, delta_b,
                                 _ptr(d_a_hat), _ptr(d_b_hat), wp, wb, _stream(stream)), "cdl_qgemm_bwd")
+
+
+def cdl_probe_mfma_int8(iters: int, random_operands: bool, blocks: int, sink, stream=None) -> float:
+    """Enqueues the register-resident int8 MFMA probe; returns the integer operations it performs."""
+    ops = ctypes.c_double(0.0)
+    f = load().cdl_probe_mfma_int8
+    f.restype = ctypes.c_int
+    f.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+    _check(f(iters, 1 if random_operands else 0, blocks, _ptr(sink), ctypes.byref(ops), _stream(stream)), "cdl_probe_mfma_int8")
+    return ops.value
 
 
 def cdl_profile_enable(enable: bool) -> None:

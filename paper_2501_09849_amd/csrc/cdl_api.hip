@@ -203,6 +203,15 @@ int cdl_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
     return launch_qgemm_bwd(g, a_idx, b_idx, M, N, K, delta_a, delta_b, d_a_hat, d_b_hat, ws, (hipStream_t)hip_stream);
 }
 
+int cdl_probe_mfma_int8(int32_t iters, int32_t random_operands, int32_t blocks, void *sink, double *ops, void *hip_stream)
+{
+    if (iters < 1 || blocks < 1 || !sink) return iters < 1 || blocks < 1 ? CDL_ERR_PARAM : CDL_ERR_NULL;
+    if (!aligned(sink, 4)) return CDL_ERR_ALIGN;
+    // 4 waves per block, 8 MFMAs of 32 x 32 x 32 multiply-adds per wave and trip
+    if (ops) *ops = (double)blocks * 4.0 * (double)iters * 8.0 * 2.0 * 32.0 * 32.0 * 32.0;
+    return launch_mfma_probe(iters, random_operands != 0, blocks, reinterpret_cast<int *>(sink), (hipStream_t)hip_stream);
+}
+
 int cdl_profile_enable(int enable)
 {
     cdl::g_profile_on.store(enable != 0);

@@ -68,4 +68,6 @@ int launch_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
                      int32_t M, int32_t N, int32_t K, float delta_a, float delta_b,
                      float *d_a_hat, float *d_b_hat, void *ws, hipStream_t stream);
 
+int launch_mfma_probe(int iters, int random_operands, int blocks, int *sink, hipStream_t stream);
+
 }  // namespace cdl

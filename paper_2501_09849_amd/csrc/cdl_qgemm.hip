@@ -702,6 +702,41 @@ __global__ void zero_i32_kernel(int32_t *p, int64_t n)
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
 }
 
+// ---- measurement aid: register-resident int8 MFMA issue rate ----------------------------------
+// Eight independent accumulators per wave, no memory traffic.  random_operands = 0: the two operand
+// registers never change (the least switching activity the matrix cores can see); 1: every MFMA of
+// the body gets its own pseudo-random operand bits, as dense random int8 data would present them.
+__global__ __launch_bounds__(256)
+void mfma_probe_kernel(int iters, int random_operands, int *sink)
+{
+    v4i xs[8], ys[8];
+    unsigned h = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            h = h * 1664525u + 1013904223u;
+            xs[t][c] = random_operands ? (int)h : 0x01020304;
+            h = h * 1664525u + 1013904223u;
+            ys[t][c] = random_operands ? (int)h : 0x04030201;
+        }
+    v16i acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xs[t], ys[t], acc[t], 0, 0, 0);
+    }
+    int x = 0;
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) x ^= acc[t][r];
+    if (x == 0x7fffffff) *sink = x;   // keeps the MFMAs alive; practically never true
+}
+
 inline int64_t pad_to(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 inline unsigned blocks_for(int64_t n, int per_block, int cap = 65536)
@@ -782,6 +817,12 @@ void launch_transpose(const int8_t *src, int rows, int cols, int8_t *dst, int64_
 }
 
 }  // namespace
+
+int launch_mfma_probe(int iters, int random_operands, int blocks, int *sink, hipStream_t stream)
+{
+    CDL_LAUNCH("mfma_probe_kernel", stream, mfma_probe_kernel, dim3(blocks), dim3(256), 0, iters, random_operands, sink);
+    return check_launch();
+}
 
 size_t qgemm_fwd_workspace_bytes(int32_t M, int32_t N, int32_t K)
 {
