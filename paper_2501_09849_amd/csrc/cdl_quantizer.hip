@@ -303,51 +303,63 @@ void quantize_fwd_kernel(const float *__restrict__ theta, int64_t n, QConst k,
     }
 }
 
-// Sums the per-block fixed-point histograms (exact 64-bit integers), normalises by n * 2^s, and -
-// in the block that finishes last - adds up the entropy terms.  One block per eight levels; thread t handles level
-// t%8 of its block and rows t/8, t/8+128, ...
-__global__ __launch_bounds__(1024)
+// Sums the per-block fixed-point histograms (exact 64-bit integers, so the order does not matter),
+// normalises by n * 2^s and adds up the entropy terms.  Grid: (ceil(levels / 8), chunks <= kFinChunks) with
+// about 64 blocks in all (every block ends with an atomic on one ticket word, and those serialize at
+// roughly 80 ns each); a block sums its share of the rows for eight levels (32 rows at a time, 64 contiguous bytes per row) into
+// second[chunk][level]; the block that finishes last (ticket) adds the chunk sums per level,
+// writes the marginal PMF and sums the entropy terms in level order.
+constexpr int kFinChunks = 16;
+
+__global__ __launch_bounds__(256)
 void marginal_finalize_kernel(const unsigned long long *__restrict__ partial, int nblocks, int n_levels, double inv_n,
                               float *__restrict__ marg, float *__restrict__ entropy_bits,
-                              double *hterm /* [256] */, unsigned int *ticket)
+                              unsigned long long *second /* [kFinChunks][256] */, unsigned int *ticket)
 {
-    __shared__ unsigned long long red[128][8];
+    __shared__ unsigned long long red[32][8];
     __shared__ double hsum[256];
     __shared__ bool is_last;
     const int b8 = threadIdx.x & 7, grp = threadIdx.x >> 3;
     const int level = blockIdx.x * 8 + b8;
+    const int chunks = gridDim.y;
+    const int rows_per = (nblocks + chunks - 1) / chunks;
+    const int r0 = blockIdx.y * rows_per, r1 = min(nblocks, r0 + rows_per);
     unsigned long long s = 0ull;
     if (level < n_levels) {
-#pragma unroll 8
-        for (int row = grp; row < nblocks; row += 128) s += partial[(size_t)row * n_levels + level];
+#pragma unroll 4
+        for (int row = r0 + grp; row < r1; row += 32) s += partial[(size_t)row * n_levels + level];
     }
     red[grp][b8] = s;
     __syncthreads();
     if (threadIdx.x < 8 && level < n_levels) {
         unsigned long long tot = 0ull;
-        for (int q = 0; q < 128; ++q) tot += red[q][threadIdx.x];
-        const double m = (double)tot * inv_n;
-        if (marg) marg[level] = (float)m;
-        __hip_atomic_store(&hterm[level], m > 0.0 ? -m * log2(m) : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int q = 0; q < 32; ++q) tot += red[q][threadIdx.x];
+        __hip_atomic_store(&second[blockIdx.y * 256 + level], tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __threadfence();
     __syncthreads();
     if (threadIdx.x == 0) {
         const unsigned int t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        is_last = (t == gridDim.x - 1);
+        is_last = (t == gridDim.x * gridDim.y - 1);
     }
     __syncthreads();
-    if (is_last && entropy_bits) {
-        __threadfence();
-        if (threadIdx.x < 256)
-            hsum[threadIdx.x] = ((int)threadIdx.x < n_levels)
-                ? __hip_atomic_load(&hterm[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            double H = 0.0;
-            for (int i = 0; i < n_levels; ++i) H += hsum[i];
-            *entropy_bits = (float)H;
-        }
+    if (!is_last) return;
+    __threadfence();
+    double h = 0.0;
+    if ((int)threadIdx.x < n_levels) {
+        unsigned long long tot = 0ull;
+        for (int c = 0; c < chunks; ++c)
+            tot += __hip_atomic_load(&second[c * 256 + threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const double m = (double)tot * inv_n;
+        if (marg) marg[threadIdx.x] = (float)m;
+        h = m > 0.0 ? -m * log2(m) : 0.0;
+    }
+    hsum[threadIdx.x] = h;
+    __syncthreads();
+    if (threadIdx.x == 0 && entropy_bits) {
+        double H = 0.0;
+        for (int i = 0; i < n_levels; ++i) H += hsum[i];
+        *entropy_bits = (float)H;
     }
 }
 
@@ -504,7 +516,7 @@ size_t hist_bytes(int64_t n, int32_t n_levels)
 {
     return align_up((size_t)hist_grid_for(n) * (size_t)n_levels * sizeof(unsigned long long), 256);
 }
-size_t aux_bytes() { return align_up(256 * sizeof(double) + sizeof(unsigned int), 256); }
+size_t aux_bytes() { return align_up((size_t)kFinChunks * 256 * sizeof(unsigned long long) + sizeof(unsigned int), 256); }
 size_t scalar_bytes() { return align_up((size_t)kMaxQuantBlocks * 2 * sizeof(double), 256); }
 
 // histogram copies per wave: 16 for small level sets (heavy collisions), 4 for wide ones
@@ -588,8 +600,9 @@ int launch_quantize_fwd(const float *theta, int64_t n, const cdl_qparams &p,
     if (grid64 > 2147483647LL) return CDL_ERR_PARAM;
     const int grid = (int)grid64;
     unsigned long long *partial = reinterpret_cast<unsigned long long *>(ws);
-    double *hterm = want_marg ? reinterpret_cast<double *>(reinterpret_cast<char *>(ws) + hist_bytes(n, p.n_levels)) : nullptr;
-    unsigned int *ticket = want_marg ? reinterpret_cast<unsigned int *>(hterm + 256) : nullptr;
+    unsigned long long *second = want_marg
+        ? reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(ws) + hist_bytes(n, p.n_levels)) : nullptr;
+    unsigned int *ticket = want_marg ? reinterpret_cast<unsigned int *>(second + kFinChunks * 256) : nullptr;
     const bool want_idx = idx != nullptr, want_soft = soft != nullptr;
     const int rs = copies_shift(p.n_levels);
     switch (k.wgen <= 4 ? k.wgen : 0) {
@@ -602,9 +615,11 @@ int launch_quantize_fwd(const float *theta, int64_t n, const cdl_qparams &p,
     int rc = check_launch();
     if (rc != CDL_OK) return rc;
     if (want_marg) {
-        CDL_LAUNCH("marginal_finalize_kernel", stream, marginal_finalize_kernel, dim3((p.n_levels + 7) / 8), dim3(1024), 0,
+        const int level_blocks = (p.n_levels + 7) / 8;
+        const int chunks = level_blocks >= 64 ? 1 : (64 / level_blocks < kFinChunks ? 64 / level_blocks : kFinChunks);
+        CDL_LAUNCH("marginal_finalize_kernel", stream, marginal_finalize_kernel, dim3(level_blocks, chunks), dim3(256), 0,
                    partial, grid, p.n_levels, 1.0 / ((double)n * (double)(1u << hist_scale_bits(rs))), marg, entropy_bits,
-                   hterm, ticket);
+                   second, ticket);
         rc = check_launch();
     }
     return rc;
