@@ -64,6 +64,29 @@ def lib():
         L.cdl_oracle_quantize_bwd.restype = None
         L.cdl_oracle_quantize_bwd.argtypes = [_f32p, _f32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
                                               ctypes.c_float, ctypes.c_float, _f64p, _f64p, _f64p, _f64p, _f64p]
+        L.cdl_oracle_cpmf_k.restype = ctypes.c_int
+        L.cdl_oracle_cpmf_k.argtypes = [ctypes.c_double, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                        ctypes.c_double, ctypes.c_int, _f64p, _f64p]
+        L.cdl_oracle_element_k.restype = None
+        L.cdl_oracle_element_k.argtypes = [ctypes.c_double, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                           ctypes.c_double, ctypes.c_int, _i32p, _f64p, _f64p, _f64p, _f64p, _f64p]
+        L.cdl_oracle_quantize_fwd_k.restype = None
+        L.cdl_oracle_quantize_fwd_k.argtypes = [_f32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                                ctypes.c_float, ctypes.c_float, ctypes.c_int, _i32p, _f64p, _f64p]
+        L.cdl_oracle_marginal_entropy_k.restype = None
+        L.cdl_oracle_marginal_entropy_k.argtypes = [_f32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                                    ctypes.c_float, ctypes.c_float, ctypes.c_int, _f64p, _f64p]
+        L.cdl_oracle_quantize_bwd_k.restype = None
+        L.cdl_oracle_quantize_bwd_k.argtypes = [_f32p, _f32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                                ctypes.c_float, ctypes.c_float, ctypes.c_int,
+                                                _f64p, _f64p, _f64p, _f64p, _f64p]
+        L.cdl_oracle_quantize_draw.restype = None
+        L.cdl_oracle_quantize_draw.argtypes = [_f32p, _f32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                               ctypes.c_float, ctypes.c_float, ctypes.c_int, _i32p, _f64p]
+        L.cdl_oracle_entropy_bwd.restype = None
+        L.cdl_oracle_entropy_bwd.argtypes = [_f32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                             ctypes.c_float, ctypes.c_float, ctypes.c_int, _f64p, ctypes.c_double,
+                                             _f64p, _f64p, _f64p, _f64p, _f64p]
         L.cdl_oracle_qgemm_fwd.restype = None
         L.cdl_oracle_qgemm_fwd.argtypes = [_i8p, _i8p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_float, ctypes.c_float, _i32p, _f64p]
@@ -89,21 +112,23 @@ def _ptr(a: Optional[np.ndarray], ptype):
 
 # ----------------------------------------------------------------- one element (double in, double out)
 
-def cpmf(theta: float, lo: int, n_levels: int, delta: float, alpha: float) -> Tuple[np.ndarray, int, float]:
-    """CPMF over the levels for one element; returns (P, mode index, top-two score gap)."""
+def cpmf(theta: float, lo: int, n_levels: int, delta: float, alpha: float, top_k: int = 0) -> Tuple[np.ndarray, int, float]:
+    """CPMF over the levels for one element; returns (P, mode index, top-two score gap).
+
+    top_k > 0: the CPMF truncated to its top_k most probable levels and renormalised (the paper uses 5 for activations)."""
     P = np.empty(n_levels, dtype=np.float64)
     gap = ctypes.c_double()
-    mode = lib().cdl_oracle_cpmf(float(theta), lo, n_levels, float(delta), float(alpha),
-                                 _ptr(P, _f64p), ctypes.byref(gap))
+    mode = lib().cdl_oracle_cpmf_k(float(theta), lo, n_levels, float(delta), float(alpha), int(top_k),
+                                   _ptr(P, _f64p), ctypes.byref(gap))
     return P, int(mode), gap.value
 
 
-def element(theta: float, lo: int, n_levels: int, delta: float, alpha: float) -> dict:
+def element(theta: float, lo: int, n_levels: int, delta: float, alpha: float, top_k: int = 0) -> dict:
     """idx, soft value, score gap and the three partial derivatives of Q_d for one element."""
     idx = ctypes.c_int32()
     v = [ctypes.c_double() for _ in range(5)]
-    lib().cdl_oracle_element(float(theta), lo, n_levels, float(delta), float(alpha), ctypes.byref(idx),
-                             *[ctypes.byref(x) for x in v])
+    lib().cdl_oracle_element_k(float(theta), lo, n_levels, float(delta), float(alpha), int(top_k), ctypes.byref(idx),
+                               *[ctypes.byref(x) for x in v])
     return dict(idx=idx.value, soft=v[0].value, gap=v[1].value,
                 dtheta=v[2].value, ddelta=v[3].value, dalpha=v[4].value)
 
@@ -118,39 +143,66 @@ def lemma1_raw(theta: float, lo: int, n_levels: int, delta: float, alpha: float)
 # ----------------------------------------------------------------- tensors (fp32 in, double out)
 
 def quantize_fwd(theta: np.ndarray, lo: int, n_levels: int, delta: float, alpha: float,
-                 want_soft: bool = True, want_gap: bool = True):
+                 want_soft: bool = True, want_gap: bool = True, top_k: int = 0):
     """Returns (idx int32[n], soft float64[n] | None, score_gap float64[n] | None)."""
     th = _c(theta, np.float32).reshape(-1)
     n = th.size
     idx = np.empty(n, dtype=np.int32)
     soft = np.empty(n, dtype=np.float64) if want_soft else None
     gap = np.empty(n, dtype=np.float64) if want_gap else None
-    lib().cdl_oracle_quantize_fwd(_ptr(th, _f32p), n, lo, n_levels, float(delta), float(alpha),
-                                  _ptr(idx, _i32p), _ptr(soft, _f64p), _ptr(gap, _f64p))
+    lib().cdl_oracle_quantize_fwd_k(_ptr(th, _f32p), n, lo, n_levels, float(delta), float(alpha), int(top_k),
+                                    _ptr(idx, _i32p), _ptr(soft, _f64p), _ptr(gap, _f64p))
     return idx, soft, gap
 
 
-def marginal_entropy(theta: np.ndarray, lo: int, n_levels: int, delta: float, alpha: float):
+def marginal_entropy(theta: np.ndarray, lo: int, n_levels: int, delta: float, alpha: float, top_k: int = 0):
     """Returns (marg float64[n_levels], entropy in bits)."""
     th = _c(theta, np.float32).reshape(-1)
     marg = np.empty(n_levels, dtype=np.float64)
     H = ctypes.c_double()
-    lib().cdl_oracle_marginal_entropy(_ptr(th, _f32p), th.size, lo, n_levels, float(delta), float(alpha),
-                                      _ptr(marg, _f64p), ctypes.byref(H))
+    lib().cdl_oracle_marginal_entropy_k(_ptr(th, _f32p), th.size, lo, n_levels, float(delta), float(alpha), int(top_k),
+                                        _ptr(marg, _f64p), ctypes.byref(H))
     return marg, H.value
 
 
 def quantize_bwd(theta: np.ndarray, g: np.ndarray, lo: int, n_levels: int, delta: float, alpha: float,
-                 want_dtheta: bool = True) -> dict:
+                 want_dtheta: bool = True, top_k: int = 0) -> dict:
     """dtheta float64[n], d_delta, d_alpha and the sums of |term| behind the two scalars."""
     th = _c(theta, np.float32).reshape(-1)
     gg = _c(g, np.float32).reshape(-1)
     assert th.size == gg.size
     dth = np.empty(th.size, dtype=np.float64) if want_dtheta else None
     s = [ctypes.c_double() for _ in range(4)]
-    lib().cdl_oracle_quantize_bwd(_ptr(th, _f32p), _ptr(gg, _f32p), th.size, lo, n_levels,
-                                  float(delta), float(alpha), _ptr(dth, _f64p),
-                                  *[ctypes.byref(x) for x in s])
+    lib().cdl_oracle_quantize_bwd_k(_ptr(th, _f32p), _ptr(gg, _f32p), th.size, lo, n_levels,
+                                    float(delta), float(alpha), int(top_k), _ptr(dth, _f64p),
+                                    *[ctypes.byref(x) for x in s])
+    return dict(dtheta=dth, d_delta=s[0].value, d_alpha=s[1].value,
+                abs_sum_delta=s[2].value, abs_sum_alpha=s[3].value)
+
+
+def quantize_draw(theta: np.ndarray, u: np.ndarray, lo: int, n_levels: int, delta: float, alpha: float,
+                  top_k: int = 0):
+    """The probabilistic quantizer Q_p by inversion with the uniforms u in [0,1): (idx int32[n], margin float64[n])."""
+    th = _c(theta, np.float32).reshape(-1)
+    uu = _c(u, np.float32).reshape(-1)
+    assert th.size == uu.size
+    idx = np.empty(th.size, dtype=np.int32)
+    margin = np.empty(th.size, dtype=np.float64)
+    lib().cdl_oracle_quantize_draw(_ptr(th, _f32p), _ptr(uu, _f32p), th.size, lo, n_levels, float(delta), float(alpha),
+                                   int(top_k), _ptr(idx, _i32p), _ptr(margin, _f64p))
+    return idx, margin
+
+
+def entropy_bwd(theta: np.ndarray, marg: np.ndarray, lo: int, n_levels: int, delta: float, alpha: float,
+                scale: float = 1.0, want_dtheta: bool = True, top_k: int = 0) -> dict:
+    """scale * dH/d(theta, delta, alpha) of the entropy of the marginal PMF `marg` (float64[n_levels])."""
+    th = _c(theta, np.float32).reshape(-1)
+    mm = _c(marg, np.float64).reshape(-1)
+    assert mm.size == n_levels
+    dth = np.empty(th.size, dtype=np.float64) if want_dtheta else None
+    s = [ctypes.c_double() for _ in range(4)]
+    lib().cdl_oracle_entropy_bwd(_ptr(th, _f32p), th.size, lo, n_levels, float(delta), float(alpha), int(top_k),
+                                 _ptr(mm, _f64p), float(scale), _ptr(dth, _f64p), *[ctypes.byref(x) for x in s])
     return dict(dtheta=dth, d_delta=s[0].value, d_alpha=s[1].value,
                 abs_sum_delta=s[2].value, abs_sum_alpha=s[3].value)
 

@@ -51,8 +51,8 @@ int cdl_oracle_num_threads(void)
  * Returns the mode (lowest index on an exact tie of scores: the paper does not
  * say) and the gap between the two largest scores.
  * ---------------------------------------------------------------------- */
-int cdl_oracle_cpmf(double theta, int lo, int n_levels, double delta, double alpha,
-                    double *P /* n_levels */, double *score_gap /* nullable */)
+static int cpmf_core(double theta, int lo, int n_levels, double delta, double alpha, int top_k,
+                     double *P /* n_levels */, double *score_gap /* nullable */)
 {
     double s_best = -INFINITY, s_second = -INFINITY;
     int i_best = lo;
@@ -63,11 +63,40 @@ int cdl_oracle_cpmf(double theta, int lo, int n_levels, double delta, double alp
         if (s > s_best) { s_second = s_best; s_best = s; i_best = lo + k; }
         else if (s > s_second) { s_second = s; }
     }
+    if (top_k > 0 && top_k < n_levels) {
+        /*
+         * Truncated CPMF (Sec. V-B, "Quantization operations in a mini-batch"): the CPMF is
+         * "concentrated proportionally on the top five values", the other probabilities are 0.
+         * Reading: keep the top_k levels of largest probability (= largest score; on equal
+         * scores the lower index is kept first), renormalise over them.  The paper uses 5.
+         */
+        char *keep = (char *)calloc((size_t)n_levels, 1);
+        for (int r = 0; r < top_k; ++r) {
+            int pick = -1;
+            for (int k = 0; k < n_levels; ++k)
+                if (!keep[k] && (pick < 0 || P[k] > P[pick])) pick = k;   /* strict >: lower index wins ties */
+            keep[pick] = 1;
+        }
+        for (int k = 0; k < n_levels; ++k) if (!keep[k]) P[k] = -INFINITY;
+        free(keep);
+    }
     double Z = 0.0;
     for (int k = 0; k < n_levels; ++k) { P[k] = exp(P[k] - s_best); Z += P[k]; }
     for (int k = 0; k < n_levels; ++k) P[k] /= Z;
     if (score_gap) *score_gap = s_best - s_second;
     return i_best;
+}
+
+int cdl_oracle_cpmf(double theta, int lo, int n_levels, double delta, double alpha,
+                    double *P /* n_levels */, double *score_gap /* nullable */)
+{
+    return cpmf_core(theta, lo, n_levels, delta, alpha, 0, P, score_gap);
+}
+
+int cdl_oracle_cpmf_k(double theta, int lo, int n_levels, double delta, double alpha, int top_k,
+                      double *P /* n_levels */, double *score_gap /* nullable */)
+{
+    return cpmf_core(theta, lo, n_levels, delta, alpha, top_k, P, score_gap);
 }
 
 /* Soft deterministic quantizer Q_d(theta) = sum_i P(i delta | theta) * i delta  (eq. softQ, Sec. III-B) */
@@ -123,13 +152,13 @@ static moments_t moments(const double *P, double theta, int lo, int n_levels, do
  * dP_i/dalpha = -P_i (d_i^2 - sum_j P_j d_j^2) with d_i = theta - i q, and
  * summing i q dP_i/dalpha gives the covariance above.
  */
-void cdl_oracle_element(double theta, int lo, int n_levels, double delta, double alpha,
-                        int *idx, double *soft, double *score_gap,
-                        double *dsoft_dtheta, double *dsoft_ddelta, double *dsoft_dalpha)
+void cdl_oracle_element_k(double theta, int lo, int n_levels, double delta, double alpha, int top_k,
+                          int *idx, double *soft, double *score_gap,
+                          double *dsoft_dtheta, double *dsoft_ddelta, double *dsoft_dalpha)
 {
     double *P = (double *)malloc(sizeof(double) * (size_t)n_levels);
     double gap;
-    int mode = cdl_oracle_cpmf(theta, lo, n_levels, delta, alpha, P, &gap);
+    int mode = cpmf_core(theta, lo, n_levels, delta, alpha, top_k, P, &gap);
     moments_t m = moments(P, theta, lo, n_levels, delta);
     if (idx) *idx = mode;
     if (soft) *soft = m.mean;
@@ -138,6 +167,13 @@ void cdl_oracle_element(double theta, int lo, int n_levels, double delta, double
     if (dsoft_ddelta) *dsoft_ddelta = (m.mean + 2.0 * alpha * theta * m.var - 2.0 * alpha * m.skew_u) / delta;
     if (dsoft_dalpha) *dsoft_dalpha = -m.cov_x_d2;
     free(P);
+}
+
+void cdl_oracle_element(double theta, int lo, int n_levels, double delta, double alpha,
+                        int *idx, double *soft, double *score_gap,
+                        double *dsoft_dtheta, double *dsoft_ddelta, double *dsoft_dalpha)
+{
+    cdl_oracle_element_k(theta, lo, n_levels, delta, alpha, 0, idx, soft, score_gap, dsoft_dtheta, dsoft_ddelta, dsoft_dalpha);
 }
 
 /* Lemma 1 with Var and Skew_u from raw powers of X exactly as printed. */
@@ -163,10 +199,10 @@ void cdl_oracle_lemma1_raw(double theta, int lo, int n_levels, double delta, dou
  * probability -> 1 as alpha grows, Remark after eq. Qprob) and soft value
  * Q_d (eq. softboth, Sec. IV-B) for every entry.
  * ---------------------------------------------------------------------- */
-void cdl_oracle_quantize_fwd(const float *theta, int64_t n, int lo, int n_levels,
-                             float delta_f, float alpha_f,
-                             int32_t *idx /* n, nullable */, double *soft /* n, nullable */,
-                             double *score_gap /* n, nullable */)
+void cdl_oracle_quantize_fwd_k(const float *theta, int64_t n, int lo, int n_levels,
+                               float delta_f, float alpha_f, int top_k,
+                               int32_t *idx /* n, nullable */, double *soft /* n, nullable */,
+                               double *score_gap /* n, nullable */)
 {
     const double delta = (double)delta_f, alpha = (double)alpha_f;
 #pragma omp parallel
@@ -175,13 +211,21 @@ void cdl_oracle_quantize_fwd(const float *theta, int64_t n, int lo, int n_levels
 #pragma omp for schedule(static)
         for (int64_t e = 0; e < n; ++e) {
             double gap;
-            int mode = cdl_oracle_cpmf((double)theta[e], lo, n_levels, delta, alpha, P, &gap);
+            int mode = cpmf_core((double)theta[e], lo, n_levels, delta, alpha, top_k, P, &gap);
             if (idx) idx[e] = mode;
             if (soft) soft[e] = soft_value(P, lo, n_levels, delta);
             if (score_gap) score_gap[e] = gap;
         }
         free(P);
     }
+}
+
+void cdl_oracle_quantize_fwd(const float *theta, int64_t n, int lo, int n_levels,
+                             float delta_f, float alpha_f,
+                             int32_t *idx /* n, nullable */, double *soft /* n, nullable */,
+                             double *score_gap /* n, nullable */)
+{
+    cdl_oracle_quantize_fwd_k(theta, n, lo, n_levels, delta_f, alpha_f, 0, idx, soft, score_gap);
 }
 
 /* ------------------------------------------------------------------------
@@ -192,9 +236,9 @@ void cdl_oracle_quantize_fwd(const float *theta, int64_t n, int lo, int n_levels
  * marg[k] = 0 contribute 0).  The total for the layer is n*H.
  * One call = one PMF over the whole tensor handed in.
  * ---------------------------------------------------------------------- */
-void cdl_oracle_marginal_entropy(const float *theta, int64_t n, int lo, int n_levels,
-                                 float delta_f, float alpha_f,
-                                 double *marg /* n_levels */, double *entropy_bits /* 1 */)
+void cdl_oracle_marginal_entropy_k(const float *theta, int64_t n, int lo, int n_levels,
+                                   float delta_f, float alpha_f, int top_k,
+                                   double *marg /* n_levels */, double *entropy_bits /* 1 */)
 {
     const double delta = (double)delta_f, alpha = (double)alpha_f;
     int nthreads = cdl_oracle_num_threads();
@@ -210,7 +254,7 @@ void cdl_oracle_marginal_entropy(const float *theta, int64_t n, int lo, int n_le
         double *P = (double *)malloc(sizeof(double) * (size_t)n_levels);
 #pragma omp for schedule(static)
         for (int64_t e = 0; e < n; ++e) {
-            cdl_oracle_cpmf((double)theta[e], lo, n_levels, delta, alpha, P, NULL);
+            cpmf_core((double)theta[e], lo, n_levels, delta, alpha, top_k, P, NULL);
             for (int k = 0; k < n_levels; ++k) mine[k] += P[k];
         }
         free(P);
@@ -226,6 +270,13 @@ void cdl_oracle_marginal_entropy(const float *theta, int64_t n, int lo, int n_le
     free(partial);
 }
 
+void cdl_oracle_marginal_entropy(const float *theta, int64_t n, int lo, int n_levels,
+                                 float delta_f, float alpha_f,
+                                 double *marg /* n_levels */, double *entropy_bits /* 1 */)
+{
+    cdl_oracle_marginal_entropy_k(theta, n, lo, n_levels, delta_f, alpha_f, 0, marg, entropy_bits);
+}
+
 /* ------------------------------------------------------------------------
  * Tensor backward (Sec. IV-B): with g[e] = dL/dQ_p(theta_e) from the layer,
  *   dtheta[e] = g[e] * dQd/dtheta                    (eq. partialX3 / partialW3)
@@ -234,11 +285,11 @@ void cdl_oracle_marginal_entropy(const float *theta, int64_t n, int lo, int n_le
  * Also returns sum_e |term| for the two scalar sums so a caller can judge a
  * difference against the size of what was added up.
  * ---------------------------------------------------------------------- */
-void cdl_oracle_quantize_bwd(const float *theta, const float *g, int64_t n, int lo, int n_levels,
-                             float delta_f, float alpha_f,
-                             double *dtheta /* n, nullable */,
-                             double *d_delta, double *d_alpha,
-                             double *abs_sum_delta /* nullable */, double *abs_sum_alpha /* nullable */)
+void cdl_oracle_quantize_bwd_k(const float *theta, const float *g, int64_t n, int lo, int n_levels,
+                               float delta_f, float alpha_f, int top_k,
+                               double *dtheta /* n, nullable */,
+                               double *d_delta, double *d_alpha,
+                               double *abs_sum_delta /* nullable */, double *abs_sum_alpha /* nullable */)
 {
     const double delta = (double)delta_f, alpha = (double)alpha_f;
     double sd = 0.0, sa = 0.0, ad = 0.0, aa = 0.0;
@@ -248,7 +299,7 @@ void cdl_oracle_quantize_bwd(const float *theta, const float *g, int64_t n, int 
 #pragma omp for schedule(static)
         for (int64_t e = 0; e < n; ++e) {
             double th = (double)theta[e], ge = (double)g[e];
-            cdl_oracle_cpmf(th, lo, n_levels, delta, alpha, P, NULL);
+            cpmf_core(th, lo, n_levels, delta, alpha, top_k, P, NULL);
             moments_t m = moments(P, th, lo, n_levels, delta);
             double d_th = 2.0 * alpha * m.var;
             double d_q = (m.mean + 2.0 * alpha * th * m.var - 2.0 * alpha * m.skew_u) / delta;
@@ -259,6 +310,123 @@ void cdl_oracle_quantize_bwd(const float *theta, const float *g, int64_t n, int 
         }
         free(P);
     }
+    *d_delta = sd;
+    *d_alpha = sa;
+    if (abs_sum_delta) *abs_sum_delta = ad;
+    if (abs_sum_alpha) *abs_sum_alpha = aa;
+}
+
+void cdl_oracle_quantize_bwd(const float *theta, const float *g, int64_t n, int lo, int n_levels,
+                             float delta_f, float alpha_f,
+                             double *dtheta /* n, nullable */,
+                             double *d_delta, double *d_alpha,
+                             double *abs_sum_delta /* nullable */, double *abs_sum_alpha /* nullable */)
+{
+    cdl_oracle_quantize_bwd_k(theta, g, n, lo, n_levels, delta_f, alpha_f, 0, dtheta, d_delta, d_alpha, abs_sum_delta, abs_sum_alpha);
+}
+
+/* ------------------------------------------------------------------------
+ * The probabilistic quantizer itself (eq. Qprob, Sec. III-A): theta is mapped to level i with
+ * probability P(i q | theta).  The draw is made by inversion with one uniform number u in [0,1)
+ * per entry, supplied by the caller: levels are taken in increasing order and the draw is the
+ * first level whose cumulative probability exceeds u (the paper does not say how the draw is
+ * made; any method with the right distribution is the same quantizer, inversion is the one that
+ * can be compared entry by entry).  `margin` is the distance from u to the nearest end of the
+ * chosen level's cumulative interval: a different rounding of the cumulative sums can only
+ * change draws whose margin is of that size.
+ * ---------------------------------------------------------------------- */
+void cdl_oracle_quantize_draw(const float *theta, const float *u, int64_t n, int lo, int n_levels,
+                              float delta_f, float alpha_f, int top_k,
+                              int32_t *idx /* n */, double *margin /* n, nullable */)
+{
+    const double delta = (double)delta_f, alpha = (double)alpha_f;
+#pragma omp parallel
+    {
+        double *P = (double *)malloc(sizeof(double) * (size_t)n_levels);
+#pragma omp for schedule(static)
+        for (int64_t e = 0; e < n; ++e) {
+            cpmf_core((double)theta[e], lo, n_levels, delta, alpha, top_k, P, NULL);
+            const double ue = (double)u[e];
+            double cdf = 0.0, below = 0.0;
+            int pick = -1, last_pos = 0;
+            for (int k = 0; k < n_levels; ++k) {
+                if (P[k] > 0.0) last_pos = k;
+                if (pick < 0) {
+                    below = cdf;
+                    cdf += P[k];
+                    if (cdf > ue) pick = k;
+                }
+            }
+            if (pick < 0) { pick = last_pos; }   /* u beyond the rounded total: the last level that can occur */
+            idx[e] = lo + pick;
+            if (margin) {
+                double a = ue - below, b = cdf - ue;
+                margin[e] = a < b ? a : b;
+            }
+        }
+        free(P);
+    }
+}
+
+/* ------------------------------------------------------------------------
+ * Gradient of the entropy term of the objective (eq. obj / eq. opt4, Sec. IV-D; Algorithm 1, the
+ * step that computes the partials of H(w) and H(x)).  The paper states that these partials "can
+ * be computed analytically" and prints no formula; this is the derivation used.
+ *
+ * H = -sum_k m_k log2 m_k with the marginal PMF m_k = (1/n) sum_e P_k(theta_e)  (eq. approx1/n).
+ * For any parameter x:  dH/dx = -sum_k (log2 m_k + 1/ln 2) dm_k/dx = -sum_k log2(m_k) dm_k/dx,
+ * because sum_k m_k = 1.  dm_k/dx = (1/n) sum_e dP_k(theta_e)/dx, and with d_k = theta - k q the
+ * derivatives of the CPMF are (eq. partialw2 and eq. partialq2 of Appendix B; the third follows
+ * in the same way from eq. CPMF):
+ *   dP_k/dtheta = -2 alpha P_k d_k + 2 alpha P_k sum_j P_j d_j
+ *   dP_k/dq     =  2 alpha P_k k d_k - 2 alpha P_k sum_j P_j j d_j
+ *   dP_k/dalpha = -P_k d_k^2 + P_k sum_j P_j d_j^2
+ * Outputs (each multiplied by `scale`, e.g. lambda * n for the total-bits term lambda * n * H):
+ *   dtheta[e] = dH/dtheta_e,   d_delta = dH/dq,   d_alpha = dH/dalpha.
+ * The marginal PMF is an input (the one the forward pass produced); levels with m_k = 0
+ * contribute nothing (their P_k vanish wherever they are evaluated to working precision).
+ * ---------------------------------------------------------------------- */
+void cdl_oracle_entropy_bwd(const float *theta, int64_t n, int lo, int n_levels,
+                            float delta_f, float alpha_f, int top_k,
+                            const double *marg /* n_levels */, double scale,
+                            double *dtheta /* n, nullable */, double *d_delta, double *d_alpha,
+                            double *abs_sum_delta /* nullable */, double *abs_sum_alpha /* nullable */)
+{
+    const double delta = (double)delta_f, alpha = (double)alpha_f;
+    double *ell = (double *)malloc(sizeof(double) * (size_t)n_levels);
+    for (int k = 0; k < n_levels; ++k) ell[k] = marg[k] > 0.0 ? log2(marg[k]) : 0.0;
+    const double inv_n = n > 0 ? 1.0 / (double)n : 0.0;
+    double sd = 0.0, sa = 0.0, ad = 0.0, aa = 0.0;
+#pragma omp parallel reduction(+ : sd, sa, ad, aa)
+    {
+        double *P = (double *)malloc(sizeof(double) * (size_t)n_levels);
+#pragma omp for schedule(static)
+        for (int64_t e = 0; e < n; ++e) {
+            const double th = (double)theta[e];
+            cpmf_core(th, lo, n_levels, delta, alpha, top_k, P, NULL);
+            double e_d = 0.0, e_jd = 0.0, e_d2 = 0.0;
+            for (int k = 0; k < n_levels; ++k) {
+                const double j = (double)(lo + k), d = th - j * delta;
+                e_d += P[k] * d; e_jd += P[k] * j * d; e_d2 += P[k] * d * d;
+            }
+            double g_th = 0.0, g_q = 0.0, g_al = 0.0;
+            for (int k = 0; k < n_levels; ++k) {
+                const double j = (double)(lo + k), d = th - j * delta;
+                const double dP_th = -2.0 * alpha * P[k] * d + 2.0 * alpha * P[k] * e_d;
+                const double dP_q = 2.0 * alpha * P[k] * j * d - 2.0 * alpha * P[k] * e_jd;
+                const double dP_al = -P[k] * d * d + P[k] * e_d2;
+                g_th -= ell[k] * dP_th;
+                g_q -= ell[k] * dP_q;
+                g_al -= ell[k] * dP_al;
+            }
+            g_th *= inv_n * scale; g_q *= inv_n * scale; g_al *= inv_n * scale;
+            if (dtheta) dtheta[e] = g_th;
+            sd += g_q; ad += fabs(g_q);
+            sa += g_al; aa += fabs(g_al);
+        }
+        free(P);
+    }
+    free(ell);
     *d_delta = sd;
     *d_alpha = sa;
     if (abs_sum_delta) *abs_sum_delta = ad;
