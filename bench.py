@@ -263,6 +263,53 @@ def machine_probes():
     return out
 
 
+def extensions_bench(seed=0, iters=5):
+    """The rows next to the core path, on the flat 25.6 M-entry tensor: the probabilistic draw, the entropy-term
+    gradient, and the truncated (top-5) CPMF in the soft regime of the paper's initial sharpness."""
+    import torch
+    import paper_2501_09849_amd as cdl
+    wl = cdl_inputs.workload(4)
+    spec = wl.w_spec
+    n = wl.flat_n
+    dev = "cuda:0"
+    th = torch.from_numpy(cdl_inputs.draw_w(wl, seed)).to(dev)
+    g = torch.from_numpy(cdl_inputs.draw_g(wl, seed)).to(dev)
+    u = torch.rand(n, device=dev)
+    idx = torch.empty(n, dtype=torch.int8, device=dev)
+    soft = torch.empty(n, device=dev)
+    dth = torch.empty(n, device=dev)
+    marg = torch.empty(spec.n_levels, device=dev)
+    sc = torch.zeros(4, device=dev)
+    ws = torch.empty(cdl.quantize_workspace_bytes(n, spec.n_levels), dtype=torch.uint8, device=dev)
+    a = (spec.lo, spec.n_levels, spec.delta, spec.alpha)
+    soft_a = (spec.lo, spec.n_levels, spec.delta, cdl_inputs.ALPHA_PAPER)
+    cdl.cdl_marginal_entropy(th, n, *a, marg, sc[0:1], ws)
+
+    def timed(f):
+        for _ in range(2):
+            f()
+        torch.cuda.synchronize()
+        cdl.cdl_profile_enable(True)
+        for _ in range(iters):
+            f()
+        torch.cuda.synchronize()
+        recs = cdl.cdl_profile_collect()
+        cdl.cdl_profile_enable(False)
+        return sum(ms for _, ms in recs) / iters * 1e3
+
+    out = {"workload": wl.name, "n": n, "levels": spec.n_levels}
+    t = timed(lambda: cdl.cdl_quantize_draw(th, u, n, *a, idx))
+    out["draw_us"], out["draw_GBps"] = t, 9.0 * n / t / 1e3                      # reads theta, u; writes one byte
+    t = timed(lambda: cdl.cdl_entropy_bwd(th, marg, n, *a, 1.0, g, dth, sc[1:2], sc[2:3], ws))
+    out["entropy_bwd_us"], out["entropy_bwd_GBps"] = t, 12.0 * n / t / 1e3        # reads theta, g; writes dtheta
+    for key, k in (("full_cpmf", 0), ("top5", 5)):
+        t = timed(lambda: (cdl.cdl_quantize_fwd(th, n, *soft_a, idx, soft, marg, sc[0:1], ws, top_k=k),
+                           cdl.cdl_quantize_bwd(th, g, n, *soft_a, dth, sc[1:2], sc[2:3], ws, top_k=k)))
+        out["soft_regime_fwd_bwd_us_" + key] = t
+    out["soft_regime_kappa"] = cdl_inputs.ALPHA_PAPER * spec.delta ** 2
+    return out
+
+
 def gemm_only(number, seed=0, iters=5):
     """The three index products on another workload's shape (workload 3: the ImageNet conv layer)."""
     import torch
@@ -423,6 +470,7 @@ def main():
             out["quantizer_only_flat_25M"] = quantizer_only()
         if wl.number != 3:
             out["index_gemms_conv_layer"] = gemm_only(3)
+        out["extensions_flat_25M"] = extensions_bench()
         out["machine"] = machine_probes()
     print(json.dumps(out), flush=True)
 

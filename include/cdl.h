@@ -42,12 +42,18 @@ extern "C" {
  * sharpness alpha (the paper's alpha_l / beta_l).  The paper's signed b-bit set is
  * lo = -2^(b-1), n_levels = 2^b; its unsigned set is lo = 0, n_levels = 2^b; any contiguous set
  * inside [-128, 127] is accepted, so indices always fit an int8.
+ * top_k = 0: the CPMF of eq. CPMF over all levels.  top_k = 1, 3, 5, 7 or 9: the CPMF "concentrated
+ * proportionally on the top" top_k values (Sec. V-B, where the paper uses five for activations):
+ * the top_k most probable levels - the nearest ones, lower index first on a tie - keep their
+ * probabilities renormalised to sum 1, all others get 0; every entry point then works with that
+ * truncated CPMF.  A top_k of n_levels or more is the full CPMF.
  */
 typedef struct cdl_qparams {
     int32_t lo;
     int32_t n_levels;
     float   delta;
     float   alpha;
+    int32_t top_k;
 } cdl_qparams;
 
 typedef enum cdl_status {
@@ -108,6 +114,35 @@ int cdl_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl_qp
 int cdl_marginal_entropy(const float *theta, int64_t n, const cdl_qparams *p,
                          float *marg, float *entropy_bits,
                          void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * The probabilistic quantizer Q_p itself (eq. Qprob, Sec. III-A; Algorithm 1 quantizes with it):
+ * theta[e] is mapped to level i with probability P(i delta | theta[e]).  The draw is made by
+ * inversion with the caller's uniform numbers u[e] in [0,1): idx[e] is the first level, in
+ * increasing order, whose cumulative probability exceeds u[e].  theta, u: DEVICE fp32[n], 16-byte
+ * aligned; idx: DEVICE int8[n], 4-byte aligned.  Entries whose u lies within fp32 rounding
+ * (about 1e-6) of a boundary of the cumulative distribution may come out one level off.
+ */
+int cdl_quantize_draw(const float *theta, const float *u, int64_t n, const cdl_qparams *p,
+                      int8_t *idx, void *hip_stream);
+
+/*
+ * Gradient of the entropy term of the objective (eq. obj, eq. opt4, Sec. IV-D; Algorithm 1, the
+ * step that forms the partials of H(w) and H(x)).  With H = -sum_k m_k log2 m_k the entropy in
+ * bits of the marginal PMF m (eq. approx1/n) of the tensor theta,
+ *   dtheta[e] = g_in[e] + scale * dH/dtheta[e]     (fp32[n], nullable; g_in nullable = 0)
+ *   d_delta   = scale * dH/d delta,  d_alpha = scale * dH/d alpha   (DEVICE fp32[1], nullable)
+ * marg: DEVICE fp32[n_levels], the marginal PMF the forward pass produced for this tensor and
+ * these parameters (levels with marg = 0 contribute nothing).  scale: e.g. lambda * n for the
+ * total-bits term lambda * n * H added to a loss whose gradient is g_in.  The paper says these
+ * partials "can be computed analytically" without printing them; they follow from
+ * dH = -sum_k log2(m_k) dm_k and the CPMF derivatives of Appendix B.  Workspace as for
+ * cdl_quantize_bwd when a scalar output is requested.  At least one output non-NULL.
+ */
+int cdl_entropy_bwd(const float *theta, const float *marg, const float *g_in, int64_t n,
+                    const cdl_qparams *p, float scale,
+                    float *dtheta, float *d_delta, float *d_alpha,
+                    void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * Forward layer product over quantized operands (Sec. IV-A; Algorithm 1, forward step):

@@ -17,6 +17,7 @@ _LIB = None
 EXPORTS = (
     "cdl_quantize_workspace_bytes", "cdl_qgemm_fwd_workspace_bytes", "cdl_qgemm_bwd_workspace_bytes",
     "cdl_quantize_fwd", "cdl_quantize_bwd", "cdl_marginal_entropy", "cdl_qgemm_fwd", "cdl_qgemm_bwd",
+    "cdl_quantize_draw", "cdl_entropy_bwd",
     "cdl_profile_enable", "cdl_profile_collect", "cdl_probe_mfma_int8",
     "cdl_status_string", "cdl_last_hip_error", "cdl_version",
 )
@@ -34,7 +35,7 @@ class CdlError(RuntimeError):
 class QParams(ctypes.Structure):
     """struct cdl_qparams"""
     _fields_ = [("lo", ctypes.c_int32), ("n_levels", ctypes.c_int32),
-                ("delta", ctypes.c_float), ("alpha", ctypes.c_float)]
+                ("delta", ctypes.c_float), ("alpha", ctypes.c_float), ("top_k", ctypes.c_int32)]
 
 
 class ProfileRecord(ctypes.Structure):
@@ -68,6 +69,10 @@ def load():
         L.cdl_quantize_bwd.argtypes = [vp, vp, i64, qp, vp, vp, vp, vp, sz, vp]
         L.cdl_marginal_entropy.restype = ctypes.c_int
         L.cdl_marginal_entropy.argtypes = [vp, i64, qp, vp, vp, vp, sz, vp]
+        L.cdl_quantize_draw.restype = ctypes.c_int
+        L.cdl_quantize_draw.argtypes = [vp, vp, i64, qp, vp, vp]
+        L.cdl_entropy_bwd.restype = ctypes.c_int
+        L.cdl_entropy_bwd.argtypes = [vp, vp, vp, i64, qp, f32, vp, vp, vp, vp, sz, vp]
         L.cdl_qgemm_fwd.restype = ctypes.c_int
         L.cdl_qgemm_fwd.argtypes = [vp, vp, i32, i32, i32, f32, f32, vp, vp, vp, sz, vp]
         L.cdl_qgemm_bwd.restype = ctypes.c_int
@@ -110,8 +115,8 @@ def _stream(stream) -> Optional[int]:
     return stream.cuda_stream or None
 
 
-def _qp(lo: int, n_levels: int, delta: float, alpha: float) -> QParams:
-    return QParams(int(lo), int(n_levels), float(delta), float(alpha))
+def _qp(lo: int, n_levels: int, delta: float, alpha: float, top_k: int = 0) -> QParams:
+    return QParams(int(lo), int(n_levels), float(delta), float(alpha), int(top_k))
 
 
 def quantize_workspace_bytes(n: int, n_levels: int) -> int:
@@ -132,26 +137,42 @@ def _check(rc: int, where: str):
 
 
 def cdl_quantize_fwd(theta, n, lo, n_levels, delta, alpha, idx, soft=None, marg=None, entropy_bits=None,
-                     ws=None, stream=None):
+                     ws=None, stream=None, top_k=0):
     wp, wb = _ws(ws)
-    q = _qp(lo, n_levels, delta, alpha)
+    q = _qp(lo, n_levels, delta, alpha, top_k)
     _check(load().cdl_quantize_fwd(_ptr(theta), n, ctypes.byref(q), _ptr(idx), _ptr(soft), _ptr(marg),
                                    _ptr(entropy_bits), wp, wb, _stream(stream)), "cdl_quantize_fwd")
 
 
 def cdl_quantize_bwd(theta, g, n, lo, n_levels, delta, alpha, dtheta=None, d_delta=None, d_alpha=None,
-                     ws=None, stream=None):
+                     ws=None, stream=None, top_k=0):
     wp, wb = _ws(ws)
-    q = _qp(lo, n_levels, delta, alpha)
+    q = _qp(lo, n_levels, delta, alpha, top_k)
     _check(load().cdl_quantize_bwd(_ptr(theta), _ptr(g), n, ctypes.byref(q), _ptr(dtheta), _ptr(d_delta),
                                    _ptr(d_alpha), wp, wb, _stream(stream)), "cdl_quantize_bwd")
 
 
-def cdl_marginal_entropy(theta, n, lo, n_levels, delta, alpha, marg=None, entropy_bits=None, ws=None, stream=None):
+def cdl_marginal_entropy(theta, n, lo, n_levels, delta, alpha, marg=None, entropy_bits=None, ws=None, stream=None,
+                         top_k=0):
     wp, wb = _ws(ws)
-    q = _qp(lo, n_levels, delta, alpha)
+    q = _qp(lo, n_levels, delta, alpha, top_k)
     _check(load().cdl_marginal_entropy(_ptr(theta), n, ctypes.byref(q), _ptr(marg), _ptr(entropy_bits),
                                        wp, wb, _stream(stream)), "cdl_marginal_entropy")
+
+
+def cdl_quantize_draw(theta, u, n, lo, n_levels, delta, alpha, idx, stream=None, top_k=0):
+    q = _qp(lo, n_levels, delta, alpha, top_k)
+    _check(load().cdl_quantize_draw(_ptr(theta), _ptr(u), n, ctypes.byref(q), _ptr(idx), _stream(stream)),
+           "cdl_quantize_draw")
+
+
+def cdl_entropy_bwd(theta, marg, n, lo, n_levels, delta, alpha, scale=1.0, g_in=None, dtheta=None, d_delta=None,
+                    d_alpha=None, ws=None, stream=None, top_k=0):
+    wp, wb = _ws(ws)
+    q = _qp(lo, n_levels, delta, alpha, top_k)
+    _check(load().cdl_entropy_bwd(_ptr(theta), _ptr(marg), _ptr(g_in), n, ctypes.byref(q), float(scale),
+                                  _ptr(dtheta), _ptr(d_delta), _ptr(d_alpha), wp, wb, _stream(stream)),
+           "cdl_entropy_bwd")
 
 
 def cdl_qgemm_fwd(a_idx, b_idx, M, N, K, delta_a, delta_b, acc=None, y=None, ws=None, stream=None):

@@ -79,6 +79,7 @@ int check_qparams(const cdl_qparams *p)
     if (!(std::isfinite(p->alpha) && p->alpha > 0.0f)) return CDL_ERR_PARAM;
     const int64_t hi = (int64_t)p->lo + (int64_t)p->n_levels - 1;
     if (p->lo < -128 || hi > 127) return CDL_ERR_RANGE;
+    if (!(p->top_k == 0 || (p->top_k >= 1 && p->top_k <= 9 && (p->top_k & 1)))) return CDL_ERR_PARAM;
     // derived constants must stay finite in fp32
     const double kappa = (double)p->alpha * (double)p->delta * (double)p->delta;
     if (!(kappa < 1e30) || !((double)p->alpha * (double)p->delta < 1e30) || !(1.0 / (double)p->delta < 1e30))
@@ -167,6 +168,33 @@ int cdl_marginal_entropy(const float *theta, int64_t n, const cdl_qparams *p,
     rc = check_ws(ws, ws_bytes, quantize_workspace_bytes(n, p->n_levels));
     if (rc != CDL_OK) return rc;
     return launch_quantize_fwd(theta, n, *p, nullptr, nullptr, marg, entropy_bits, ws, (hipStream_t)hip_stream);
+}
+
+int cdl_quantize_draw(const float *theta, const float *u, int64_t n, const cdl_qparams *p, int8_t *idx, void *hip_stream)
+{
+    int rc = check_qparams(p);
+    if (rc != CDL_OK) return rc;
+    if (n < 0) return CDL_ERR_PARAM;
+    if (n > 0 && (!theta || !u || !idx)) return CDL_ERR_NULL;
+    if (!aligned(theta, 16) || !aligned(u, 16) || !aligned(idx, 4)) return CDL_ERR_ALIGN;
+    return launch_quantize_draw(theta, u, n, *p, idx, (hipStream_t)hip_stream);
+}
+
+int cdl_entropy_bwd(const float *theta, const float *marg, const float *g_in, int64_t n, const cdl_qparams *p, float scale,
+                    float *dtheta, float *d_delta, float *d_alpha, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_qparams(p);
+    if (rc != CDL_OK) return rc;
+    if (n < 0 || !std::isfinite(scale)) return CDL_ERR_PARAM;
+    if (!dtheta && !d_delta && !d_alpha) return CDL_ERR_NULL;
+    if (n > 0 && (!theta || !marg)) return CDL_ERR_NULL;
+    if (!aligned(theta, 16) || !aligned(g_in, 16) || !aligned(dtheta, 16) || !aligned(marg, 4) || !aligned(d_delta, 4) || !aligned(d_alpha, 4))
+        return CDL_ERR_ALIGN;
+    if (d_delta || d_alpha) {
+        rc = check_ws(ws, ws_bytes, quantize_workspace_bytes(n, p->n_levels));
+        if (rc != CDL_OK) return rc;
+    }
+    return launch_entropy_bwd(theta, marg, g_in, n, *p, scale, dtheta, d_delta, d_alpha, ws, (hipStream_t)hip_stream);
 }
 
 int cdl_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,

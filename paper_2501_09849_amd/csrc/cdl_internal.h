@@ -52,6 +52,11 @@ int launch_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl
                         float *dtheta, float *d_delta, float *d_alpha,
                         void *ws, hipStream_t stream);
 
+int launch_quantize_draw(const float *theta, const float *u, int64_t n, const cdl_qparams &p, int8_t *idx, hipStream_t stream);
+
+int launch_entropy_bwd(const float *theta, const float *marg, const float *g_in, int64_t n, const cdl_qparams &p,
+                       float scale, float *dtheta, float *d_delta, float *d_alpha, void *ws, hipStream_t stream);
+
 // Half-width of the band of levels around the nearest one that the kernels visit for a given
 // kappa = alpha*delta^2 (levels further out carry less than fp32 resolution of the result).
 int quantizer_window(double kappa, int n_levels);

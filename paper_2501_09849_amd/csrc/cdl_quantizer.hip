@@ -52,6 +52,7 @@ struct QConst {
     int lo;
     int n_levels;
     int wgen;         // band half-width of the generic kernel
+    int slide;        // 1: truncated CPMF - the band of 2 wgen + 1 levels slides at the ends of the level set instead of being cut
 };
 
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
@@ -167,15 +168,31 @@ __device__ __forceinline__ float generic_weight(int j, float two_u, const QConst
     return fast_exp2(k.c1 * jf * fmaf(-jf, k.delta, two_u));
 }
 
+// Offsets (relative to the nearest level c) of the levels the generic kernels visit.  Full CPMF: the band
+// c-wgen..c+wgen cut at the ends of the set.  Truncated CPMF (Sec. V-B: the top 2 wgen + 1 values, which are
+// the nearest ones): the same band, slid inwards at the ends so that it always holds 2 wgen + 1 levels.
+__device__ __forceinline__ void generic_window(int c, const QConst &k, int &jlo, int &jhi)
+{
+    const int hi = k.lo + k.n_levels - 1;
+    if (k.slide) {
+        const int centre = min(max(c, k.lo + k.wgen), hi - k.wgen);   // host guarantees n_levels >= 2 wgen + 1
+        jlo = centre - k.wgen - c;
+        jhi = centre + k.wgen - c;
+    } else {
+        jlo = max(k.lo - c, -k.wgen);
+        jhi = min(hi - c, k.wgen);
+    }
+}
+
 template <bool EXACT>
 __device__ __forceinline__ void generic_sums(float th, const QConst &k, GenericSums &g)
 {
-    const float cf = anchor_level<EXACT>(th, k);
+    // (with a truncated CPMF the kept levels change at the midpoints, so the nearest level has to be exact)
+    const float cf = k.slide ? anchor_level<true>(th, k) : anchor_level<EXACT>(th, k);
     g.cf = cf;
     g.u = fmaf(-cf, k.delta, th);
     const int c = (int)cf;
-    g.jlo = max(k.lo - c, -k.wgen);
-    g.jhi = min(k.lo + k.n_levels - 1 - c, k.wgen);
+    generic_window(c, k, g.jlo, g.jhi);
     const float two_u = 2.0f * g.u;
     float Z = 0.0f, S1 = 0.0f, S2 = 0.0f, S3 = 0.0f;
     for (int j = g.jlo; j <= g.jhi; ++j) {
@@ -445,9 +462,9 @@ void quantize_bwd_kernel(const float *__restrict__ theta, const float *__restric
     }
 }
 
-// d_delta = sum of partials; d_alpha = delta^3 * sum of partials.  Fixed summation order.
+// d_delta = mul_d * sum of partials; d_alpha = mul_a * sum of partials.  Fixed summation order.
 __global__ __launch_bounds__(256)
-void scalar_finalize_kernel(const double *__restrict__ partial, int nblocks, double delta_cubed,
+void scalar_finalize_kernel(const double *__restrict__ partial, int nblocks, double mul_d, double mul_a,
                             float *__restrict__ d_delta, float *__restrict__ d_alpha)
 {
     __shared__ double sd[256], sa[256];
@@ -460,8 +477,184 @@ void scalar_finalize_kernel(const double *__restrict__ partial, int nblocks, dou
         __syncthreads();
     }
     if (threadIdx.x == 0) {
-        if (d_delta) *d_delta = (float)sd[0];
-        if (d_alpha) *d_alpha = (float)(sa[0] * delta_cubed);
+        if (d_delta) *d_delta = (float)(sd[0] * mul_d);
+        if (d_alpha) *d_alpha = (float)(sa[0] * mul_a);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// The probabilistic quantizer Q_p (eq. Qprob, Sec. III-A) by inversion: with one uniform number
+// u in [0,1) per entry the draw is the first level, in increasing order, whose cumulative
+// probability exceeds u.  The comparison is made on un-normalised weights (cumulative weight against
+// u * Z), which spares the division.  Reads theta and u, writes one index byte per entry.
+// ------------------------------------------------------------------------------------------
+template <int W>
+__device__ __forceinline__ int draw_one(float th, float u, const QConst &k)
+{
+    if (W > 0) {
+        Band<W> b;
+        band_weights<W, false, 1>(th, k, b);
+        const float target = u * b.Z;
+        float cum = 0.0f;
+        int pick = -W - 1, last = 0;
+#pragma unroll
+        for (int i = 0; i <= 2 * W; ++i) {
+            const int j = i - W;
+            const float w = j < 0 ? b.dn[-j - 1] : (j == 0 ? b.ctr : b.up[j - 1]);
+            cum += w;
+            if (w > 0.0f) last = j;
+            if (pick < -W && cum > target) pick = j;
+        }
+        if (pick < -W) pick = last;
+        return (int)b.cf + pick;
+    } else {
+        GenericSums g;
+        generic_sums<false>(th, k, g);
+        const float target = u * g.Z, two_u = 2.0f * g.u;
+        float cum = 0.0f;
+        int pick = g.jlo - 1, last = g.jlo;
+        for (int j = g.jlo; j <= g.jhi; ++j) {
+            const float w = generic_weight(j, two_u, k);
+            cum += w;
+            if (w > 0.0f) last = j;
+            if (pick < g.jlo && cum > target) pick = j;
+        }
+        if (pick < g.jlo) pick = last;
+        return (int)g.cf + pick;
+    }
+}
+
+template <int W>
+__global__ __launch_bounds__(kQuantThreads)
+void quantize_draw_kernel(const float *__restrict__ theta, const float *__restrict__ u, int64_t n, QConst k,
+                          int8_t *__restrict__ idx)
+{
+    const int64_t n4 = n >> 2;
+    const int64_t stride = (int64_t)gridDim.x * kQuantThreads;
+    for (int64_t v = (int64_t)blockIdx.x * kQuantThreads + threadIdx.x; v < n4; v += stride) {
+        const float4 t = reinterpret_cast<const float4 *>(theta)[v];
+        const float4 r = reinterpret_cast<const float4 *>(u)[v];
+        const int c0 = draw_one<W>(t.x, r.x, k), c1 = draw_one<W>(t.y, r.y, k);
+        const int c2 = draw_one<W>(t.z, r.z, k), c3 = draw_one<W>(t.w, r.w, k);
+        reinterpret_cast<uint32_t *>(idx)[v] = (uint32_t)(c0 & 0xff) | ((uint32_t)(c1 & 0xff) << 8) |
+                                               ((uint32_t)(c2 & 0xff) << 16) | ((uint32_t)(c3 & 0xff) << 24);
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0)
+        for (int64_t e = n4 << 2; e < n; ++e) idx[e] = (int8_t)draw_one<W>(theta[e], u[e], k);
+}
+
+// ------------------------------------------------------------------------------------------
+// Gradient of the entropy term (Sec. IV-D; Algorithm 1, the step that forms the partials of H).
+// With l_k = log2 of the marginal PMF (0 where the marginal is 0), for one entry
+//     dH/dtheta = -(2 alpha delta / n) Cov_P(k, l_k)
+//     dH/dq     = -(2 alpha / n) (theta Cov_P(k, l) - delta Cov_P(k^2, l))
+//     dH/dalpha =  (1 / n) (-2 theta delta Cov_P(k, l) + delta^2 Cov_P(k^2, l))
+// (differentiate H = -sum m log2 m through m_k = mean of P_k, with the CPMF derivatives of App. B).
+// In band offsets j = k - c, lam_j = l_(c+j) - l_c:  C1 = Cov(j, lam),  C2 = Cov(j^2, lam),
+// Cov(k^2, l) = 2 c C1 + C2, so with r = u / delta
+//     dH/dq     = -(2 alpha delta / n) sum_e ((r - c) C1 - C2)
+//     dH/dalpha =  (delta^2 / n)       sum_e (C2 - 2 r C1)
+// The table of l_k sits in LDS with kPad zeros on both sides.  dtheta = g_in + scale * dH/dtheta.
+// ------------------------------------------------------------------------------------------
+template <int W, bool DTHETA, bool SCALARS, bool ADD>
+__global__ __launch_bounds__(kQuantThreads)
+void entropy_bwd_kernel(const float *__restrict__ theta, const float *__restrict__ marg, const float *__restrict__ g_in,
+                        int64_t n, QConst k, float dtheta_mul /* scale * (-2 alpha delta / n) */,
+                        float *__restrict__ dtheta, double *__restrict__ partial /* [gridDim.x][2] */)
+{
+    __shared__ float ell[256 + 2 * kPad];
+    for (int i = threadIdx.x; i < k.n_levels + 2 * kPad; i += kQuantThreads) {
+        const int lv = i - kPad;
+        float v = 0.0f;
+        if (lv >= 0 && lv < k.n_levels) { const float m = marg[lv]; v = m > 0.0f ? log2f(m) : 0.0f; }
+        ell[i] = v;
+    }
+    __syncthreads();
+    const float *ell0 = ell + kPad - k.lo;    // ell0[level] for level in [lo - kPad, hi + kPad]
+
+    double acc_d = 0.0, acc_a = 0.0;
+    const int64_t n4 = n >> 2;
+    const int64_t stride = (int64_t)gridDim.x * kQuantThreads;
+    for (int64_t v = (int64_t)blockIdx.x * kQuantThreads + threadIdx.x; v < n4 + 1; v += stride) {
+        float th[4], ge[4];
+        int cnt;
+        if (v < n4) {
+            const float4 t = reinterpret_cast<const float4 *>(theta)[v];
+            th[0] = t.x; th[1] = t.y; th[2] = t.z; th[3] = t.w;
+            if (ADD) { const float4 q = reinterpret_cast<const float4 *>(g_in)[v]; ge[0] = q.x; ge[1] = q.y; ge[2] = q.z; ge[3] = q.w; }
+            cnt = 4;
+        } else {
+            cnt = (int)(n - (n4 << 2));
+            if (cnt == 0) break;
+            for (int e = 0; e < 4; ++e) {
+                th[e] = (e < cnt) ? theta[(n4 << 2) + e] : 0.0f;
+                if (ADD) ge[e] = (e < cnt) ? g_in[(n4 << 2) + e] : 0.0f;
+            }
+        }
+        float dv[4];
+        float sum_d = 0.0f, sum_a = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float cf, u, Z, S1, S2, B0 = 0.0f, B1 = 0.0f, B2 = 0.0f;
+            if (W > 0) {
+                Band<W> b;
+                band_weights<W, false, 2>(th[e], k, b);
+                cf = b.cf; u = b.u; Z = b.Z; S1 = b.S1; S2 = b.S2;
+                const float *lp = ell0 + (int)cf;
+                const float l0 = lp[0];
+#pragma unroll
+                for (int j = 1; j <= W; ++j) {
+                    const float jf = (float)j;
+                    const float xu = b.up[j - 1] * (lp[j] - l0), xd = b.dn[j - 1] * (lp[-j] - l0);
+                    B0 += xu + xd;
+                    B1 = fmaf(jf, xu - xd, B1);
+                    B2 = fmaf(jf * jf, xu + xd, B2);
+                }
+            } else {
+                GenericSums s;
+                generic_sums<false>(th[e], k, s);
+                cf = s.cf; u = s.u; Z = s.Z; S1 = s.S1; S2 = s.S2;
+                const float *lp = ell0 + (int)cf;
+                const float l0 = lp[0], two_u = 2.0f * u;
+                for (int j = s.jlo; j <= s.jhi; ++j) {
+                    const float jf = (float)j;
+                    const float x = generic_weight(j, two_u, k) * (lp[j] - l0);
+                    B0 += x;
+                    B1 = fmaf(jf, x, B1);
+                    B2 = fmaf(jf * jf, x, B2);
+                }
+            }
+            const float inv = fast_rcp(Z);
+            const float mu = S1 * inv, m2 = S2 * inv, b0 = B0 * inv;
+            const float C1 = fmaf(-mu, b0, B1 * inv), C2 = fmaf(-m2, b0, B2 * inv);
+            dv[e] = ADD ? fmaf(dtheta_mul, C1, ge[e]) : dtheta_mul * C1;
+            if (SCALARS && e < cnt) {
+                const float r = u * k.inv_delta;
+                sum_d += fmaf(r - cf, C1, -C2);
+                sum_a += fmaf(-2.0f * r, C1, C2);
+            }
+        }
+        if (SCALARS) { acc_d += (double)sum_d; acc_a += (double)sum_a; }
+        if (DTHETA) {
+            if (v < n4) reinterpret_cast<float4 *>(dtheta)[v] = make_float4(dv[0], dv[1], dv[2], dv[3]);
+            else for (int e = 0; e < cnt; ++e) dtheta[(n4 << 2) + e] = dv[e];
+        }
+    }
+    if (SCALARS) {
+        __shared__ double red_d[kQuantThreads / 64], red_a[kQuantThreads / 64];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            acc_d += __shfl_down(acc_d, off, 64);
+            acc_a += __shfl_down(acc_a, off, 64);
+        }
+        if ((threadIdx.x & 63) == 0) { red_d[threadIdx.x >> 6] = acc_d; red_a[threadIdx.x >> 6] = acc_a; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double sd = 0.0, sa = 0.0;
+            for (int w = 0; w < kQuantThreads / 64; ++w) { sd += red_d[w]; sa += red_a[w]; }
+            partial[2 * (size_t)blockIdx.x] = sd;
+            partial[2 * (size_t)blockIdx.x + 1] = sa;
+        }
     }
 }
 
@@ -472,6 +665,9 @@ __global__ void zero_floats_kernel(float *a, int na, float *b, int nb, float *c,
     if (b && i < nb) b[i] = 0.0f;
     if (c && i < nc) c[i] = 0.0f;
 }
+
+// Which unrolled band kernel serves these parameters (0: the generic loop).
+int band_template(const QConst &k) { return (!k.slide && k.wgen <= 4) ? k.wgen : 0; }
 
 QConst make_const(const cdl_qparams &p)
 {
@@ -490,6 +686,14 @@ QConst make_const(const cdl_qparams &p)
     k.lo_f = (float)p.lo;
     k.hi_f = (float)(p.lo + p.n_levels - 1);
     k.wgen = quantizer_window(kappa, p.n_levels);
+    k.slide = 0;
+    if (p.top_k > 0 && p.top_k < p.n_levels) {
+        // Truncated CPMF.  Where the band that kappa asks for is no wider than the top_k nearest levels the
+        // truncation drops nothing above fp32 resolution and the ordinary kernels serve; otherwise the generic
+        // kernels run on exactly the top_k nearest levels.
+        const int wt = (p.top_k - 1) / 2;
+        if (k.wgen > wt) { k.wgen = wt; k.slide = 1; }
+    }
     return k;
 }
 
@@ -605,7 +809,7 @@ int launch_quantize_fwd(const float *theta, int64_t n, const cdl_qparams &p,
     unsigned int *ticket = want_marg ? reinterpret_cast<unsigned int *>(second + kFinChunks * 256) : nullptr;
     const bool want_idx = idx != nullptr, want_soft = soft != nullptr;
     const int rs = copies_shift(p.n_levels);
-    switch (k.wgen <= 4 ? k.wgen : 0) {
+    switch (band_template(k)) {
         case 1: launch_fwd<1>(rs, want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
         case 2: launch_fwd<2>(rs, want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
         case 3: launch_fwd<3>(rs, want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
@@ -642,7 +846,7 @@ int launch_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl
     double *partial = want_scalars
         ? reinterpret_cast<double *>(reinterpret_cast<char *>(ws) + hist_bytes(n, p.n_levels) + aux_bytes()) : nullptr;
     const bool want_dtheta = dtheta != nullptr;
-    switch (k.wgen <= 4 ? k.wgen : 0) {
+    switch (band_template(k)) {
         case 1: launch_bwd_w<1>(want_dtheta, want_scalars, grid, stream, theta, g, n, k, dtheta, partial); break;
         case 2: launch_bwd_w<2>(want_dtheta, want_scalars, grid, stream, theta, g, n, k, dtheta, partial); break;
         case 3: launch_bwd_w<3>(want_dtheta, want_scalars, grid, stream, theta, g, n, k, dtheta, partial); break;
@@ -653,8 +857,79 @@ int launch_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl
     if (rc != CDL_OK) return rc;
     if (want_scalars) {
         const double d = (double)p.delta;
-        CDL_LAUNCH("scalar_finalize_kernel", stream, scalar_finalize_kernel, dim3(1), dim3(256), 0, partial, grid, d * d * d,
+        CDL_LAUNCH("scalar_finalize_kernel", stream, scalar_finalize_kernel, dim3(1), dim3(256), 0, partial, grid, 1.0, d * d * d,
                    d_delta, d_alpha);
+        rc = check_launch();
+    }
+    return rc;
+}
+
+int launch_quantize_draw(const float *theta, const float *u, int64_t n, const cdl_qparams &p, int8_t *idx, hipStream_t stream)
+{
+    if (n == 0) return CDL_OK;
+    const QConst k = make_const(p);
+    const int grid = grid_for(n);
+#define CDL_DRAW(WW) CDL_LAUNCH("quantize_draw_kernel", stream, (quantize_draw_kernel<WW>), dim3(grid), dim3(kQuantThreads), 0, theta, u, n, k, idx)
+    switch (band_template(k)) {
+        case 1: CDL_DRAW(1); break;
+        case 2: CDL_DRAW(2); break;
+        case 3: CDL_DRAW(3); break;
+        case 4: CDL_DRAW(4); break;
+        default: CDL_DRAW(0); break;
+    }
+#undef CDL_DRAW
+    return check_launch();
+}
+
+namespace {
+template <int W>
+void launch_entropy_bwd_w(bool want_dtheta, bool want_scalars, bool add, int grid, hipStream_t s, const float *theta,
+                          const float *marg, const float *g_in, int64_t n, const QConst &k, float mul,
+                          float *dtheta, double *partial)
+{
+#define CDL_EB(D, S, A) \
+    CDL_LAUNCH("entropy_bwd_kernel", s, (entropy_bwd_kernel<W, D, S, A>), dim3(grid), dim3(kQuantThreads), 0, \
+               theta, marg, g_in, n, k, mul, dtheta, partial)
+    if (want_dtheta && want_scalars && add) CDL_EB(true, true, true);
+    else if (want_dtheta && want_scalars) CDL_EB(true, true, false);
+    else if (want_dtheta && add) CDL_EB(true, false, true);
+    else if (want_dtheta) CDL_EB(true, false, false);
+    else CDL_EB(false, true, false);
+#undef CDL_EB
+}
+}  // namespace
+
+int launch_entropy_bwd(const float *theta, const float *marg, const float *g_in, int64_t n, const cdl_qparams &p,
+                       float scale, float *dtheta, float *d_delta, float *d_alpha, void *ws, hipStream_t stream)
+{
+    const bool want_scalars = (d_delta != nullptr) || (d_alpha != nullptr);
+    if (n == 0) {
+        if (want_scalars) {
+            CDL_LAUNCH("zero_floats_kernel", stream, zero_floats_kernel, dim3(1), dim3(64), 0, d_delta, d_delta ? 1 : 0,
+                               d_alpha, d_alpha ? 1 : 0, (float *)nullptr, 0);
+            return check_launch();
+        }
+        return CDL_OK;
+    }
+    const QConst k = make_const(p);
+    const int grid = grid_for(n);
+    double *partial = want_scalars
+        ? reinterpret_cast<double *>(reinterpret_cast<char *>(ws) + hist_bytes(n, p.n_levels) + aux_bytes()) : nullptr;
+    const bool want_dtheta = dtheta != nullptr;
+    const double alpha = (double)p.alpha, delta = (double)p.delta;
+    const double mul_theta = (double)scale * (-2.0 * alpha * delta / (double)n);
+    switch (band_template(k)) {
+        case 1: launch_entropy_bwd_w<1>(want_dtheta, want_scalars, g_in != nullptr, grid, stream, theta, marg, g_in, n, k, (float)mul_theta, dtheta, partial); break;
+        case 2: launch_entropy_bwd_w<2>(want_dtheta, want_scalars, g_in != nullptr, grid, stream, theta, marg, g_in, n, k, (float)mul_theta, dtheta, partial); break;
+        case 3: launch_entropy_bwd_w<3>(want_dtheta, want_scalars, g_in != nullptr, grid, stream, theta, marg, g_in, n, k, (float)mul_theta, dtheta, partial); break;
+        case 4: launch_entropy_bwd_w<4>(want_dtheta, want_scalars, g_in != nullptr, grid, stream, theta, marg, g_in, n, k, (float)mul_theta, dtheta, partial); break;
+        default: launch_entropy_bwd_w<0>(want_dtheta, want_scalars, g_in != nullptr, grid, stream, theta, marg, g_in, n, k, (float)mul_theta, dtheta, partial); break;
+    }
+    int rc = check_launch();
+    if (rc != CDL_OK) return rc;
+    if (want_scalars) {
+        CDL_LAUNCH("scalar_finalize_kernel", stream, scalar_finalize_kernel, dim3(1), dim3(256), 0, partial, grid,
+                   mul_theta, (double)scale * delta * delta / (double)n, d_delta, d_alpha);
         rc = check_launch();
     }
     return rc;

@@ -47,9 +47,9 @@ def test_workspace_queries(cdl):
     assert cdl.qgemm_bwd_workspace_bytes(0, 3, 4) == 0
 
 
-def _q(lo, n, delta, alpha):
+def _q(lo, n, delta, alpha, top_k=0):
     from paper_2501_09849_amd.binding import QParams
-    return ctypes.byref(QParams(lo, n, delta, alpha))
+    return ctypes.byref(QParams(lo, n, delta, alpha, top_k))
 
 
 OK, NULL, PARAM, RANGE, ALIGN, WS = 0, -1, -2, -3, -4, -5
@@ -86,6 +86,28 @@ def test_quantizer_argument_validation_happens_before_any_gpu_work(cdl):
     m = lib.cdl_marginal_entropy
     assert m(FAKE, 16, good, None, None, FAKE, need, None) == NULL
     assert m(FAKE, 16, good, FAKE, None, None, 0, None) == WS
+
+
+def test_extension_argument_validation_happens_before_any_gpu_work(cdl):
+    lib = cdl.load()
+    good = _q(-7, 15, 0.02, 1e4)
+    for k in (2, 4, 10, 11, -1):
+        bad = _q(0, 16, 0.25, 64.0, top_k=k)
+        assert lib.cdl_quantize_fwd(FAKE, 16, bad, FAKE, None, None, None, None, 0, None) == PARAM
+    d = lib.cdl_quantize_draw
+    assert d(FAKE, FAKE, 16, None, FAKE, None) == NULL
+    assert d(FAKE, None, 16, good, FAKE, None) == NULL
+    assert d(FAKE, FAKE, 16, good, None, None) == NULL
+    assert d(FAKE, FAKE, -2, good, FAKE, None) == PARAM
+    assert d(FAKE, FAKE + 4, 16, good, FAKE, None) == ALIGN
+    assert d(FAKE, FAKE, 16, good, FAKE + 2, None) == ALIGN
+    e = lib.cdl_entropy_bwd
+    assert e(FAKE, FAKE, None, 16, good, 1.0, None, None, None, None, 0, None) == NULL          # no output requested
+    assert e(FAKE, None, None, 16, good, 1.0, FAKE, None, None, None, 0, None) == NULL
+    assert e(None, FAKE, None, 16, good, 1.0, FAKE, None, None, None, 0, None) == NULL
+    assert e(FAKE, FAKE, None, 16, good, float("nan"), FAKE, None, None, None, 0, None) == PARAM
+    assert e(FAKE, FAKE, FAKE + 4, 16, good, 1.0, FAKE, None, None, None, 0, None) == ALIGN
+    assert e(FAKE, FAKE, None, 16, good, 1.0, FAKE, FAKE, None, None, 0, None) == WS            # scalar outputs need scratch
 
 
 def test_gemm_argument_validation_happens_before_any_gpu_work(cdl):

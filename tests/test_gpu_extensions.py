@@ -1,0 +1,173 @@
+"""GPU parity of the extensions of the path: truncated (top-k) CPMF, the probabilistic draw Q_p, and the
+gradient of the entropy term, each against the CPU oracle on the same seeded inputs.
+
+Tolerances as for the core path.  The draw is an integer decision made on fp32 cumulative sums: entries
+whose uniform number lies within 1e-6 of a boundary of the oracle's cumulative distribution are exempt
+(counted, and still have to be a neighbouring level).
+"""
+import numpy as np
+import pytest
+
+import cdl_inputs
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+SPECS = [(-7, 15, 0.02), (0, 16, 0.25), (-15, 31, 0.004), (-127, 255, 0.15092)]
+
+
+def _theta(lo, n_levels, delta, n, seed):
+    rng = np.random.default_rng(seed)
+    th = rng.normal(0.0, 0.3 * n_levels * delta, n)
+    if lo == 0:
+        th = np.abs(th)
+    th[:16] = np.linspace((lo - 3) * delta, (lo + n_levels + 2) * delta, 16)      # beyond both ends
+    th[16:32] = (np.arange(16) + lo + 0.5) * delta                                  # exact midpoints
+    return th.astype(np.float32)
+
+
+def _call(fn, *a, **kw):
+    fn(*a, **kw)
+    gu.torch_mod().cuda.synchronize()
+
+
+@pytest.mark.parametrize("lo,n_levels,delta", SPECS)
+@pytest.mark.parametrize("kappa", [0.05, 0.7, 4.0, 50.0])
+@pytest.mark.parametrize("top_k", [1, 3, 5])
+def test_truncated_cpmf_forward_backward_marginal(oracle, lo, n_levels, delta, kappa, top_k):
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    n = 20003
+    spec = cdl_inputs.QuantSpec(lo, n_levels, float(np.float32(delta)), float(np.float32(kappa / np.float32(delta) ** 2)))
+    a = (spec.lo, spec.n_levels, spec.delta, spec.alpha)
+    th = _theta(lo, n_levels, spec.delta, n, seed=n_levels + top_k)
+    g = np.random.default_rng(1).normal(0, 1, n).astype(np.float32)
+    th_d, g_d = gu.dev(th), gu.dev(g)
+    idx, soft, dth = gu.empty((n,), torch.int8), gu.empty((n,), torch.float32), gu.empty((n,), torch.float32)
+    marg, sc = gu.empty((n_levels,), torch.float32), gu.empty((4,), torch.float32)
+    ws = gu.workspace(cdl.quantize_workspace_bytes(n, n_levels))
+    _call(cdl.cdl_quantize_fwd, th_d, n, *a, idx, soft, marg, sc[0:1], ws, top_k=top_k)
+    _call(cdl.cdl_quantize_bwd, th_d, g_d, n, *a, dth, sc[1:2], sc[2:3], ws, top_k=top_k)
+    r_idx, r_soft, gap = oracle.quantize_fwd(th, *a, top_k=top_k)
+    gu.assert_indices(idx.cpu().numpy(), r_idx, gap, "idx")
+    gu.assert_close(soft.cpu().numpy(), r_soft, "soft")
+    r_m, r_h = oracle.marginal_entropy(th, *a, top_k=top_k)
+    gu.assert_close(marg.cpu().numpy(), r_m, "marginal")
+    gu.assert_close([float(sc[0])], [r_h], "entropy")
+    rb = oracle.quantize_bwd(th, g, *a, top_k=top_k)
+    gu.assert_close(dth.cpu().numpy(), rb["dtheta"], "dtheta")
+    assert abs(float(sc[1]) - rb["d_delta"]) <= 1e-6 + 1e-5 * abs(rb["d_delta"]) + 2e-7 * rb["abs_sum_delta"]
+    assert abs(float(sc[2]) - rb["d_alpha"]) <= 1e-6 + 1e-5 * abs(rb["d_alpha"]) + 2e-7 * rb["abs_sum_alpha"]
+    # marginal-only entry point
+    m2, h2 = gu.empty((n_levels,), torch.float32), gu.empty((1,), torch.float32)
+    _call(cdl.cdl_marginal_entropy, th_d, n, *a, m2, h2, ws, top_k=top_k)
+    gu.assert_close(m2.cpu().numpy(), r_m, "marginal (marginal-only call)")
+
+
+def test_truncation_wider_than_the_level_set_is_the_full_cpmf(oracle):
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    n = 4099
+    a = (-2, 5, 0.1, 3.0)
+    th = _theta(-2, 5, 0.1, n, seed=3)
+    th_d = gu.dev(th)
+    idx, s5, s0 = gu.empty((n,), torch.int8), gu.empty((n,), torch.float32), gu.empty((n,), torch.float32)
+    _call(cdl.cdl_quantize_fwd, th_d, n, *a, idx, s5, top_k=5)
+    _call(cdl.cdl_quantize_fwd, th_d, n, *a, idx, s0)
+    assert torch.equal(s5, s0)
+    with pytest.raises(cdl.CdlError):
+        cdl.cdl_quantize_fwd(th_d, n, *a, idx, s5, top_k=4)
+
+
+@pytest.mark.parametrize("lo,n_levels,delta", SPECS)
+@pytest.mark.parametrize("kappa", [0.05, 0.7, 4.0, 30.0, 1e4])
+@pytest.mark.parametrize("top_k", [0, 5])
+def test_draw_matches_oracle(oracle, lo, n_levels, delta, kappa, top_k):
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    n = 50003
+    spec = cdl_inputs.QuantSpec(lo, n_levels, float(np.float32(delta)), float(np.float32(kappa / np.float32(delta) ** 2)))
+    a = (spec.lo, spec.n_levels, spec.delta, spec.alpha)
+    th = _theta(lo, n_levels, spec.delta, n, seed=7 + n_levels)
+    u = np.random.default_rng(2).random(n, dtype=np.float32)
+    u[:4] = [0.0, 1.0 - 2.0 ** -24, 0.5, 0.25]
+    idx = gu.empty((n,), torch.int8)
+    _call(cdl.cdl_quantize_draw, gu.dev(th), gu.dev(u), n, *a, idx, top_k=top_k)
+    got = idx.cpu().numpy().astype(np.int64)
+    ref, margin = oracle.quantize_draw(th, u, *a, top_k=top_k)
+    diff = got != ref
+    exempt = diff & (margin < 1e-6)
+    assert not (diff & ~exempt).any(), "%d draws differ with a margin >= 1e-6 (first %d: gpu %d ref %d margin %.3g)" % (
+        int((diff & ~exempt).sum()), int(np.argmax(diff & ~exempt)), got[np.argmax(diff & ~exempt)],
+        ref[np.argmax(diff & ~exempt)], margin[np.argmax(diff & ~exempt)])
+    assert np.all(np.abs(got[exempt] - ref[exempt]) == 1)
+    assert exempt.sum() <= 20
+    assert got.min() >= lo and got.max() <= lo + n_levels - 1
+
+
+def test_draw_frequencies_follow_the_cpmf(oracle):
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    lo, n_levels, d, a = -4, 8, 0.1, 150.0
+    N = 200000
+    u = ((np.arange(N) + 0.5) / N).astype(np.float32)
+    for theta in (0.03, -0.17, 0.249):
+        idx = gu.empty((N,), torch.int8)
+        _call(cdl.cdl_quantize_draw, gu.dev(np.full(N, theta, np.float32)), gu.dev(u), N, lo, n_levels, d, a, idx)
+        counts = np.bincount(idx.cpu().numpy().astype(np.int64) - lo, minlength=n_levels)
+        P, _, _ = oracle.cpmf(float(np.float32(theta)), lo, n_levels, float(np.float32(d)), float(np.float32(a)))
+        assert np.all(np.abs(counts - N * P) <= 3.0), (counts, N * P)
+
+
+@pytest.mark.parametrize("lo,n_levels,delta", SPECS)
+@pytest.mark.parametrize("kappa", [0.2, 1.0, 4.0, 30.0])
+@pytest.mark.parametrize("top_k", [0, 5])
+def test_entropy_gradient_matches_oracle(oracle, lo, n_levels, delta, kappa, top_k):
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    n = 30001
+    spec = cdl_inputs.QuantSpec(lo, n_levels, float(np.float32(delta)), float(np.float32(kappa / np.float32(delta) ** 2)))
+    a = (spec.lo, spec.n_levels, spec.delta, spec.alpha)
+    th = _theta(lo, n_levels, spec.delta, n, seed=11 + n_levels)
+    g = np.random.default_rng(3).normal(0, 1, n).astype(np.float32)
+    th_d, g_d = gu.dev(th), gu.dev(g)
+    marg, H = gu.empty((n_levels,), torch.float32), gu.empty((1,), torch.float32)
+    ws = gu.workspace(cdl.quantize_workspace_bytes(n, n_levels))
+    _call(cdl.cdl_marginal_entropy, th_d, n, *a, marg, H, ws, top_k=top_k)
+    # lambda * n for the total-bits term, with lambda chosen so that the entry gradients are of order one
+    # (dH/dtheta = -(2 alpha delta / n) Cov(k, log2 m), and the covariance is of order one)
+    scale = n / (2.0 * spec.alpha * spec.delta)
+    dth, dth_add, sc = gu.empty((n,), torch.float32), gu.empty((n,), torch.float32), gu.empty((2,), torch.float32)
+    _call(cdl.cdl_entropy_bwd, th_d, marg, n, *a, scale, None, dth, sc[0:1], sc[1:2], ws, top_k=top_k)
+    _call(cdl.cdl_entropy_bwd, th_d, marg, n, *a, scale, g_d, dth_add, None, None, None, top_k=top_k)
+    r = oracle.entropy_bwd(th, marg.cpu().numpy().astype(np.float64), *a, scale=scale, top_k=top_k)
+    gu.assert_close(dth.cpu().numpy(), r["dtheta"], "dH/dtheta")
+    gu.assert_close(dth_add.cpu().numpy(), g.astype(np.float64) + r["dtheta"], "g + dH/dtheta")
+    assert abs(float(sc[0]) - r["d_delta"]) <= 1e-6 + 1e-5 * abs(r["d_delta"]) + 2e-7 * r["abs_sum_delta"], (float(sc[0]), r["d_delta"])
+    assert abs(float(sc[1]) - r["d_alpha"]) <= 1e-6 + 1e-5 * abs(r["d_alpha"]) + 2e-7 * r["abs_sum_alpha"], (float(sc[1]), r["d_alpha"])
+    # scalars only
+    sc2 = gu.empty((2,), torch.float32)
+    _call(cdl.cdl_entropy_bwd, th_d, marg, n, *a, scale, None, None, sc2[0:1], sc2[1:2], ws, top_k=top_k)
+    assert torch.equal(sc, sc2)
+
+
+def test_extension_entry_points_on_tiny_and_empty_tensors(oracle):
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    a = (-7, 15, 0.02, 1e4)
+    for n in (0, 1, 3, 5):
+        th = _theta(-7, 15, 0.02, 64, seed=n)[32:32 + n]
+        u = np.random.default_rng(n).random(n, dtype=np.float32)
+        th_d, u_d = gu.dev(np.ascontiguousarray(th)) if n else gu.empty((4,), torch.float32), gu.dev(u) if n else gu.empty((4,), torch.float32)
+        idx = gu.empty((max(n, 4),), torch.int8)
+        _call(cdl.cdl_quantize_draw, th_d, u_d, n, *a, idx)
+        marg = gu.dev(np.full(15, 1 / 15, np.float32))
+        dth, sc = gu.empty((max(n, 4),), torch.float32), gu.empty((2,), torch.float32).fill_(7.0)
+        ws = gu.workspace(cdl.quantize_workspace_bytes(n, 15))
+        _call(cdl.cdl_entropy_bwd, th_d, marg, n, *a, 1.0, None, dth, sc[0:1], sc[1:2], ws)
+        if n:
+            ref, margin = oracle.quantize_draw(th, u, *a)
+            ok = (idx.cpu().numpy()[:n] == ref) | (margin < 1e-6)
+            assert ok.all()
+            assert float(dth[:n].abs().max()) < 1e-6        # uniform marginal: zero gradient
+        assert abs(float(sc[0])) < 1e-6 and abs(float(sc[1])) < 1e-6
