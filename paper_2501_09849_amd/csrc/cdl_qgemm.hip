@@ -228,6 +228,133 @@ constexpr int kLgkmcnt0 = 0xc07f;                                               
 
 __device__ __forceinline__ uint32_t bperm(uint32_t hi, uint32_t lo, uint32_t sel) { return __builtin_amdgcn_perm(hi, lo, sel); }
 
+// Forward product, fast path for contraction lengths that are multiples of 128: 512 threads = 2 x 4 waves,
+// 256 x 256 block tile (wave tile 128 x 64: eight 32x32 accumulators), K-tiles of 128 bytes brought in by
+// direct global->LDS loads (no staging registers) into two LDS stages of 64 KiB, 16-byte chunks XOR-swizzled
+// over the eight chunks of a row so that the fragment reads are free of bank conflicts.  The barrier is a
+// bare s_barrier with the one wait it needs written out: the loads of the next tile are issued right after
+// it and have the whole K-tile of MFMAs to land.
+constexpr int kFBK = 128;
+constexpr int kFThreads = 512;
+constexpr int kFTile = 256;
+constexpr int kFStage = 2 * kFTile * kFBK;
+constexpr int kFLdsBytes = 2 * kFStage;
+
+__global__ __launch_bounds__(kFThreads, 1)
+void qgemm_dma_kernel(GemmArgs a)
+{
+    constexpr int WN = 4, TM = 4, TN = 2, CH = kFBK / 16, KS = kFBK / 32;
+    constexpr int WL = kFTile * CH / 64 / 8;      // wave-level loads per wave, per operand and K-tile: 4
+    extern __shared__ __attribute__((aligned(16))) int8_t flds[];
+
+    const int total = a.tiles_m * a.tiles_n;
+    const int per_xcd = (int)gridDim.x >> 3;
+    const int logical = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+    if (logical >= total) return;
+    const int tile_m = logical / a.tiles_n, tile_n = logical % a.tiles_n;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+
+    // wave-level load i of this wave fills LDS slots (wave * WL + i) * 64 + lane: row slot / 8, chunk slot % 8
+    const int8_t *ga[WL];
+    const int8_t *gb[WL];
+#pragma unroll
+    for (int i = 0; i < WL; ++i) {
+        const int sidx = (wave * WL + i) * 64 + lane, row = sidx / CH;
+        const int q = (sidx % CH) ^ lswz(row);
+        ga[i] = a.A + (int64_t)min(tile_m * kFTile + row, a.rowsA - 1) * a.lda + q * 16;
+        gb[i] = a.B + (int64_t)min(tile_n * kFTile + row, a.rowsB - 1) * a.ldb + q * 16;
+    }
+    int ra[TM], rb[TN], sa[TM], sb[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int row = (wm * TM + i) * 32 + (lane & 31);
+        ra[i] = row * kFBK;
+        sa[i] = lswz(row);
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int row = (wn * TN + j) * 32 + (lane & 31);
+        rb[j] = kFTile * kFBK + row * kFBK;
+        sb[j] = lswz(row);
+    }
+
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    const int nk = a.Kc / kFBK;
+    auto issue = [&](int kt) {
+        int8_t *base = flds + (kt & 1) * kFStage;
+        const int64_t off = (int64_t)kt * kFBK;
+#pragma unroll
+        for (int i = 0; i < WL; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)(ga[i] + off), (lptr_t)(base + (wave * WL + i) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < WL; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)(gb[i] + off), (lptr_t)(base + kFTile * kFBK + (wave * WL + i) * 1024), 16, 0, 0);
+    };
+
+    issue(0);
+    for (int kt = 0; kt < nk; ++kt) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // tile kt has landed (nothing younger is in flight)
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();               // ... for every wave, and every wave has left the other stage
+        asm volatile("" ::: "memory");
+        if (kt + 1 < nk) issue(kt + 1);
+        const int8_t *base = flds + (kt & 1) * kFStage;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            v4i fa[TM], fb[TN];
+            const int q = 2 * ks + (lane >> 5);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const v4i *>(base + ra[i] + ((q ^ sa[i]) << 4));
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const v4i *>(base + rb[j] + ((q ^ sb[j]) << 4));
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    const bool full = (tile_m + 1) * kFTile <= a.rowsA && (tile_n + 1) * kFTile <= a.rowsB;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = tile_n * kFTile + (wn * TN + j) * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = tile_m * kFTile + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (full || (row < a.rowsA && col < a.rowsB)) {
+                    const int64_t o = (int64_t)row * a.ldc + col;
+                    if (a.acc_out) a.acc_out[o] = acc[i][j][r];
+                    if (a.y_out) a.y_out[o] = a.scale * (float)acc[i][j][r];
+                }
+            }
+        }
+}
+
+int launch_gemm_dma(GemmArgs a, hipStream_t stream)
+{
+    a.tiles_m = (a.rowsA + kFTile - 1) / kFTile;
+    a.tiles_n = (a.rowsB + kFTile - 1) / kFTile;
+    const int64_t total = (int64_t)a.tiles_m * a.tiles_n;
+    if (total == 0) return CDL_OK;
+    const int64_t grid = (total + 7) / 8 * 8;
+    const hipError_t e = hipFuncSetAttribute((const void *)qgemm_dma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kFLdsBytes);
+    if (e != hipSuccess) return hip_failed(e);
+    CDL_LAUNCH("qgemm_kernel(fwd)", stream, qgemm_dma_kernel, dim3((unsigned)grid), dim3(kFThreads), kFLdsBytes, a);
+    return check_launch();
+}
+
 // Digits of four values: out[l] holds digit l (a signed byte, l = 0 least significant) of g[0..3] in
 // its bytes 0..3.  x = g * gscale is exact (gscale is a power of two) and |x| < 0.99 * 2^(8L-1);
 // q = rint(x) = sum_l d_l 256^l with d_l in [-128, 127]: the bytes of (q + 0x80..80) ^ 0x80..80.
@@ -862,6 +989,9 @@ int launch_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_
     }
     g.acc_out = acc; g.y_out = y; g.ldc = N;
     g.scale = delta_a * delta_b;
+    // contraction lengths that are whole 128-byte K-tiles take the direct-load kernel (a tile grid of 256 x 256
+    // needs enough rows to be worth it)
+    if (g.Kc % kFBK == 0 && (int64_t)M * N >= (int64_t)kFTile * kFTile * 64) return launch_gemm_dma(g, stream);
     return launch_gemm<4, 2>(g, stream);
 }
 

@@ -28,6 +28,18 @@ def test_qgemm_fwd_matches_oracle(oracle, M, N, K):
     gu.assert_close(y, r_y, "y")
 
 
+def test_qgemm_fwd_large_tiles_path_matches_oracle(oracle):
+    """Contraction lengths that are multiples of 128 on at least 64 tiles of 256 x 256 take the direct-load kernel;
+    ragged edges in both output dimensions."""
+    M, N, K = 2310, 2050, 256
+    a = cdl_inputs.draw_indices((M, K), -127, 127, seed=21)
+    b = cdl_inputs.draw_indices((N, K), -127, 127, seed=22)
+    acc, y = gu.qgemm_fwd(a, b, 0.15092, 0.0028209)
+    r_acc, r_y = oracle.qgemm_fwd(a, b, 0.15092, 0.0028209)
+    assert np.array_equal(acc, r_acc), "int32 accumulators differ at %d places" % int((acc != r_acc).sum())
+    gu.assert_close(y, r_y, "y")
+
+
 def test_qgemm_fwd_extreme_indices_do_not_overflow(oracle):
     M, N, K = 64, 64, 4096
     a = np.full((M, K), -128, np.int8)
