@@ -652,15 +652,24 @@ void limb_gemm_kernel(LimbArgs a)
     }
 }
 
-// out = out_scale * sum over the contraction splits, in split order.
+// out = out_scale * sum over the contraction splits.  Four partial sums per output (splits p = 0, 4, 8, ...;
+// 1, 5, ...; ...), combined in a fixed order, keep four loads in flight per thread: with a few hundred splits
+// a single dependent chain is all latency.
 __global__ __launch_bounds__(256)
 void limb_reduce_kernel(const double *__restrict__ partial, int splits, int64_t n, const BwdPlan *plan, float *__restrict__ out)
 {
     const double out_scale = plan->out_scale_db;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-        double s = 0.0;
-        for (int p = 0; p < splits; ++p) s += partial[(int64_t)p * n + i];
-        out[i] = (float)(s * out_scale);
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+        int p = 0;
+        for (; p + 3 < splits; p += 4) {
+            s0 += partial[(int64_t)p * n + i];
+            s1 += partial[(int64_t)(p + 1) * n + i];
+            s2 += partial[(int64_t)(p + 2) * n + i];
+            s3 += partial[(int64_t)(p + 3) * n + i];
+        }
+        for (; p < splits; ++p) s0 += partial[(int64_t)p * n + i];
+        out[i] = (float)(((s0 + s1) + (s2 + s3)) * out_scale);
     }
 }
 

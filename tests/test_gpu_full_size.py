@@ -148,3 +148,84 @@ def test_flat_weight_tensor_at_full_size(oracle):
     soft_spec = wl.w_spec.with_alpha(cdl_inputs.ALPHA_PAPER)
     n = 2_000_000
     _quantizer_full(oracle, soft_spec, W[:n], G[:n], "W4 at the paper's initial sharpness")
+
+
+def _extensions_full(oracle, spec, theta_h, label, top_k=0):
+    """The probabilistic draw and the entropy-term gradient at full size: sampled entries against the oracle,
+    the two scalar gradients through additivity over pieces (two pieces against the oracle)."""
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    rng = np.random.default_rng(4321)
+    a = (spec.lo, spec.n_levels, spec.delta, spec.alpha)
+    n = theta_h.size
+    flat = theta_h.reshape(-1)
+    th_d = gu.dev(flat)
+    u_h = rng.random(n, dtype=np.float32)
+    u_d = gu.dev(u_h)
+    idx = gu.empty((n,), torch.int8)
+    cdl.cdl_quantize_draw(th_d, u_d, n, *a, idx, top_k=top_k)
+    marg, H = gu.empty((spec.n_levels,), torch.float32), gu.empty((1,), torch.float32)
+    ws = gu.workspace(cdl.quantize_workspace_bytes(n, spec.n_levels))
+    cdl.cdl_marginal_entropy(th_d, n, *a, marg, H, ws, top_k=top_k)
+    scale = n / (2.0 * spec.alpha * spec.delta)        # entry gradients of order one
+    dth, sc = gu.empty((n,), torch.float32), gu.empty((2,), torch.float32)
+    cdl.cdl_entropy_bwd(th_d, marg, n, *a, scale, None, dth, sc[0:1], sc[1:2], ws, top_k=top_k)
+    torch.cuda.synchronize()
+    marg_h = marg.cpu().numpy().astype(np.float64)
+
+    s = _sample(n, rng)
+    th_s = np.ascontiguousarray(flat[s])
+    ref, margin = oracle.quantize_draw(th_s, np.ascontiguousarray(u_h[s]), *a, top_k=top_k)
+    got = idx.cpu().numpy()[s].astype(np.int64)
+    diff = got != ref
+    assert not (diff & (margin >= 1e-6)).any(), label + ": draws differ away from the boundaries of the cumulative distribution"
+    assert np.all(np.abs(got[diff] - ref[diff]) == 1) and diff.sum() <= 20
+    # scale / n_sample: the oracle divides by the size of the tensor it is given
+    r = oracle.entropy_bwd(th_s, marg_h, *a, scale=scale * th_s.size / n, top_k=top_k)
+    gu.assert_close(dth.cpu().numpy()[s], r["dtheta"], label + " dH/dtheta")
+
+    bounds = np.linspace(0, n, PIECES + 1).astype(np.int64) // 4 * 4
+    bounds[-1] = n
+    dd_sum = da_sum = 0.0
+    for p in range(PIECES):
+        lo, hi = int(bounds[p]), int(bounds[p + 1])
+        sp = gu.empty((2,), torch.float32)
+        # the piece's own 1/n is (hi - lo): rescale so that the pieces add up to the full call
+        cdl.cdl_entropy_bwd(th_d[lo:hi], marg, hi - lo, *a, scale * (hi - lo) / n, None, None, sp[0:1], sp[1:2], ws, top_k=top_k)
+        torch.cuda.synchronize()
+        dd_sum += float(sp[0])
+        da_sum += float(sp[1])
+        if p in (2, PIECES - 1):
+            rp = oracle.entropy_bwd(flat[lo:hi], marg_h, *a, scale=scale * (hi - lo) / n, want_dtheta=False, top_k=top_k)
+            assert abs(float(sp[0]) - rp["d_delta"]) <= 1e-6 + 1e-5 * abs(rp["d_delta"]) + 2e-7 * rp["abs_sum_delta"], (label, p)
+            assert abs(float(sp[1]) - rp["d_alpha"]) <= 1e-6 + 1e-5 * abs(rp["d_alpha"]) + 2e-7 * rp["abs_sum_alpha"], (label, p)
+    assert abs(float(sc[0]) - dd_sum) <= 1e-6 + 2e-5 * max(abs(dd_sum), 1.0) + 1e-6 * PIECES, (label, float(sc[0]), dd_sum)
+    assert abs(float(sc[1]) - da_sum) <= 1e-6 + 2e-5 * max(abs(da_sum), 1e-3), (label, float(sc[1]), da_sum)
+    torch.cuda.empty_cache()
+
+
+def test_draw_and_entropy_gradient_at_full_size(oracle):
+    wl4, wl5 = cdl_inputs.workload(4), cdl_inputs.workload(5)
+    _extensions_full(oracle, wl4.w_spec, cdl_inputs.draw_w(wl4), "W4")
+    _extensions_full(oracle, wl5.x_spec, cdl_inputs.draw_x(wl5), "X5")
+    # the truncated CPMF in the soft regime (the paper's initial sharpness on workload 4, its top five values)
+    W = cdl_inputs.draw_w(wl4)
+    G = cdl_inputs.draw_g(wl4)
+    soft = wl4.w_spec.with_alpha(cdl_inputs.ALPHA_PAPER)
+    _extensions_full(oracle, soft, W, "W4 top-5 at the paper's initial sharpness", top_k=5)
+    # forward / backward of the truncated quantizer itself at full size, sampled
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    n = W.size
+    a = (soft.lo, soft.n_levels, soft.delta, soft.alpha)
+    th_d, g_d = gu.dev(W), gu.dev(G)
+    idx, sv, dth = gu.empty((n,), torch.int8), gu.empty((n,), torch.float32), gu.empty((n,), torch.float32)
+    cdl.cdl_quantize_fwd(th_d, n, *a, idx, sv, top_k=5)
+    cdl.cdl_quantize_bwd(th_d, g_d, n, *a, dth, top_k=5)
+    torch.cuda.synchronize()
+    s = _sample(n, np.random.default_rng(99))
+    r_idx, r_soft, gap = oracle.quantize_fwd(W[s], *a, top_k=5)
+    gu.assert_indices(idx.cpu().numpy()[s], r_idx, gap, "top-5 idx")
+    gu.assert_close(sv.cpu().numpy()[s], r_soft, "top-5 soft")
+    rb = oracle.quantize_bwd(W[s], G[s], *a, top_k=5)
+    gu.assert_close(dth.cpu().numpy()[s], rb["dtheta"], "top-5 dtheta")
