@@ -302,6 +302,12 @@ def extensions_bench(seed=0, iters=5):
     out["draw_us"], out["draw_GBps"] = t, 9.0 * n / t / 1e3                      # reads theta, u; writes one byte
     t = timed(lambda: cdl.cdl_entropy_bwd(th, marg, n, *a, 1.0, g, dth, sc[1:2], sc[2:3], ws))
     out["entropy_bwd_us"], out["entropy_bwd_GBps"] = t, 12.0 * n / t / 1e3        # reads theta, g; writes dtheta
+    cdl.cdl_quantize_fwd(th, n, *a, idx)
+    hws = torch.empty(cdl.huffman_workspace_bytes(n), dtype=torch.uint8, device=dev)
+    hc = torch.empty(spec.n_levels, dtype=torch.int64, device=dev)
+    hb = torch.zeros(1, device=dev)
+    t = timed(lambda: cdl.cdl_huffman_bits(idx, n, spec.lo, spec.n_levels, hc, None, hb, hws))
+    out["huffman_bits_us"], out["huffman_bits_GBps"], out["huffman_bits_per_weight"] = t, 1.0 * n / t / 1e3, float(hb.item())
     for key, k in (("full_cpmf", 0), ("top5", 5)):
         t = timed(lambda: (cdl.cdl_quantize_fwd(th, n, *soft_a, idx, soft, marg, sc[0:1], ws, top_k=k),
                            cdl.cdl_quantize_bwd(th, g, n, *soft_a, dth, sc[1:2], sc[2:3], ws, top_k=k)))

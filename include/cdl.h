@@ -145,6 +145,22 @@ int cdl_entropy_bwd(const float *theta, const float *marg, const float *g_in, in
                     void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * Size of a quantized tensor under Huffman coding of its level indices (Sec. V-A, eq. Nofbits: the
+ * paper reports bits per weight and per activation as average Huffman code lengths).
+ *   counts[k]      = number of entries equal to level lo + k       (DEVICE uint64[n_levels], nullable)
+ *   total_bits     = total code length of an optimal prefix code   (DEVICE uint64[1], nullable)
+ *   bits_per_entry = total_bits / n                                (DEVICE fp32[1], nullable)
+ * idx: DEVICE int8[n], 16-byte aligned (the hard indices or the draws of the quantizer); entries
+ * outside [lo, lo + n_levels) are ignored.  The total is the same for every Huffman tree of the
+ * counts.  A tensor in which a single level occurs costs one bit per entry (the paper does not
+ * treat the case); n = 0 gives zeros.  Scratch: cdl_huffman_workspace_bytes(n), 256-byte aligned.
+ */
+size_t cdl_huffman_workspace_bytes(int64_t n);
+int cdl_huffman_bits(const int8_t *idx, int64_t n, int32_t lo, int32_t n_levels,
+                     unsigned long long *counts, unsigned long long *total_bits, float *bits_per_entry,
+                     void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * Forward layer product over quantized operands (Sec. IV-A; Algorithm 1, forward step):
  *   acc[m,n] = sum_k a_idx[m,k] * b_idx[n,k]        exact int32             (int32[M,N], nullable)
  *   y[m,n]   = (delta_a * delta_b) * acc[m,n]       one fp32 multiply       (fp32[M,N],  nullable)

@@ -87,6 +87,9 @@ def lib():
         L.cdl_oracle_entropy_bwd.argtypes = [_f32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
                                              ctypes.c_float, ctypes.c_float, ctypes.c_int, _f64p, ctypes.c_double,
                                              _f64p, _f64p, _f64p, _f64p, _f64p]
+        L.cdl_oracle_huffman_bits.restype = None
+        L.cdl_oracle_huffman_bits.argtypes = [_i8p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                              ctypes.POINTER(ctypes.c_int64), _f64p, _f64p]
         L.cdl_oracle_qgemm_fwd.restype = None
         L.cdl_oracle_qgemm_fwd.argtypes = [_i8p, _i8p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_float, ctypes.c_float, _i32p, _f64p]
@@ -205,6 +208,16 @@ def entropy_bwd(theta: np.ndarray, marg: np.ndarray, lo: int, n_levels: int, del
                                  _ptr(mm, _f64p), float(scale), _ptr(dth, _f64p), *[ctypes.byref(x) for x in s])
     return dict(dtheta=dth, d_delta=s[0].value, d_alpha=s[1].value,
                 abs_sum_delta=s[2].value, abs_sum_alpha=s[3].value)
+
+
+def huffman_bits(idx: np.ndarray, lo: int, n_levels: int):
+    """Huffman-coded size of a tensor of level indices: (counts int64[n_levels], total bits, bits per entry)."""
+    ii = _c(idx, np.int8).reshape(-1)
+    counts = np.zeros(n_levels, dtype=np.int64)
+    tot, avg = ctypes.c_double(), ctypes.c_double()
+    lib().cdl_oracle_huffman_bits(_ptr(ii, _i8p), ii.size, lo, n_levels,
+                                  counts.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), ctypes.byref(tot), ctypes.byref(avg))
+    return counts, tot.value, avg.value
 
 
 def qgemm_fwd(a_idx: np.ndarray, b_idx: np.ndarray, delta_a: float, delta_b: float,

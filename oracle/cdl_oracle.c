@@ -494,3 +494,46 @@ void cdl_oracle_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_i
             }
     }
 }
+
+/* ------------------------------------------------------------------------
+ * Bits per entry of a quantized tensor under Huffman coding of its level indices (Sec. V-A,
+ * eq. Nofbits: the paper reports the average number of bits per weight / activation "required to
+ * represent the layer using Huffman coding").  counts[k] = number of entries equal to level lo+k.
+ * A Huffman code is built by repeatedly merging the two least frequent nodes; the total code
+ * length in bits is the sum of the weights of all merged nodes, and it is the same for every
+ * Huffman tree of the same counts (ties may be broken either way), so only the total is returned
+ * besides the counts.  Reading for the degenerate case the paper does not mention: a tensor in
+ * which a single level occurs costs one bit per entry; an empty tensor costs 0.
+ * ---------------------------------------------------------------------- */
+void cdl_oracle_huffman_bits(const int8_t *idx, int64_t n, int lo, int n_levels,
+                             int64_t *counts /* n_levels */, double *total_bits, double *bits_per_entry)
+{
+    for (int k = 0; k < n_levels; ++k) counts[k] = 0;
+    for (int64_t e = 0; e < n; ++e) {
+        int k = (int)idx[e] - lo;
+        if (k >= 0 && k < n_levels) counts[k] += 1;
+    }
+    int64_t *w = (int64_t *)malloc(sizeof(int64_t) * (size_t)n_levels);
+    int m = 0;
+    for (int k = 0; k < n_levels; ++k) if (counts[k] > 0) w[m++] = counts[k];
+    double total = 0.0;
+    if (m == 1) total = (double)w[0];
+    while (m > 1) {
+        /* the two smallest weights */
+        int a = 0, b = 1;
+        if (w[b] < w[a]) { a = 1; b = 0; }
+        for (int i = 2; i < m; ++i) {
+            if (w[i] < w[a]) { b = a; a = i; }
+            else if (w[i] < w[b]) { b = i; }
+        }
+        int64_t merged = w[a] + w[b];
+        total += (double)merged;
+        /* replace a by the merged node, remove b */
+        w[a] = merged;
+        w[b] = w[m - 1];
+        --m;
+    }
+    free(w);
+    *total_bits = total;
+    *bits_per_entry = n > 0 ? total / (double)n : 0.0;
+}

@@ -17,7 +17,7 @@ _LIB = None
 EXPORTS = (
     "cdl_quantize_workspace_bytes", "cdl_qgemm_fwd_workspace_bytes", "cdl_qgemm_bwd_workspace_bytes",
     "cdl_quantize_fwd", "cdl_quantize_bwd", "cdl_marginal_entropy", "cdl_qgemm_fwd", "cdl_qgemm_bwd",
-    "cdl_quantize_draw", "cdl_entropy_bwd",
+    "cdl_quantize_draw", "cdl_entropy_bwd", "cdl_huffman_workspace_bytes", "cdl_huffman_bits",
     "cdl_profile_enable", "cdl_profile_collect", "cdl_probe_mfma_int8",
     "cdl_status_string", "cdl_last_hip_error", "cdl_version",
 )
@@ -73,6 +73,10 @@ def load():
         L.cdl_quantize_draw.argtypes = [vp, vp, i64, qp, vp, vp]
         L.cdl_entropy_bwd.restype = ctypes.c_int
         L.cdl_entropy_bwd.argtypes = [vp, vp, vp, i64, qp, f32, vp, vp, vp, vp, sz, vp]
+        L.cdl_huffman_workspace_bytes.restype = sz
+        L.cdl_huffman_workspace_bytes.argtypes = [i64]
+        L.cdl_huffman_bits.restype = ctypes.c_int
+        L.cdl_huffman_bits.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, sz, vp]
         L.cdl_qgemm_fwd.restype = ctypes.c_int
         L.cdl_qgemm_fwd.argtypes = [vp, vp, i32, i32, i32, f32, f32, vp, vp, vp, sz, vp]
         L.cdl_qgemm_bwd.restype = ctypes.c_int
@@ -173,6 +177,16 @@ def cdl_entropy_bwd(theta, marg, n, lo, n_levels, delta, alpha, scale=1.0, g_in=
     _check(load().cdl_entropy_bwd(_ptr(theta), _ptr(marg), _ptr(g_in), n, ctypes.byref(q), float(scale),
                                   _ptr(dtheta), _ptr(d_delta), _ptr(d_alpha), wp, wb, _stream(stream)),
            "cdl_entropy_bwd")
+
+
+def huffman_workspace_bytes(n: int) -> int:
+    return int(load().cdl_huffman_workspace_bytes(n))
+
+
+def cdl_huffman_bits(idx, n, lo, n_levels, counts=None, total_bits=None, bits_per_entry=None, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(load().cdl_huffman_bits(_ptr(idx), n, lo, n_levels, _ptr(counts), _ptr(total_bits), _ptr(bits_per_entry),
+                                   wp, wb, _stream(stream)), "cdl_huffman_bits")
 
 
 def cdl_qgemm_fwd(a_idx, b_idx, M, N, K, delta_a, delta_b, acc=None, y=None, ws=None, stream=None):

@@ -197,6 +197,26 @@ int cdl_entropy_bwd(const float *theta, const float *marg, const float *g_in, in
     return launch_entropy_bwd(theta, marg, g_in, n, *p, scale, dtheta, d_delta, d_alpha, ws, (hipStream_t)hip_stream);
 }
 
+size_t cdl_huffman_workspace_bytes(int64_t n)
+{
+    if (n < 0) return 0;
+    return huffman_workspace_bytes(n);
+}
+
+int cdl_huffman_bits(const int8_t *idx, int64_t n, int32_t lo, int32_t n_levels,
+                     unsigned long long *counts, unsigned long long *total_bits, float *bits_per_entry,
+                     void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (n < 0 || n_levels < 1) return CDL_ERR_PARAM;
+    if (lo < -128 || (int64_t)lo + n_levels - 1 > 127) return CDL_ERR_RANGE;
+    if (!counts && !total_bits && !bits_per_entry) return CDL_ERR_NULL;
+    if (n > 0 && !idx) return CDL_ERR_NULL;
+    if (!aligned(idx, 16) || !aligned(counts, 8) || !aligned(total_bits, 8) || !aligned(bits_per_entry, 4)) return CDL_ERR_ALIGN;
+    const int rc = check_ws(ws, ws_bytes, huffman_workspace_bytes(n));
+    if (rc != CDL_OK) return rc;
+    return launch_huffman_bits(idx, n, lo, n_levels, counts, total_bits, bits_per_entry, ws, (hipStream_t)hip_stream);
+}
+
 int cdl_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
                   float delta_a, float delta_b, int32_t *acc, float *y,
                   void *ws, size_t ws_bytes, void *hip_stream)

@@ -73,6 +73,12 @@ int launch_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
                      int32_t M, int32_t N, int32_t K, float delta_a, float delta_b,
                      float *d_a_hat, float *d_b_hat, void *ws, hipStream_t stream);
 
+// ---- Huffman-coded size (cdl_huffman.hip) --------------------------------------------------
+size_t huffman_workspace_bytes(int64_t n);
+
+int launch_huffman_bits(const int8_t *idx, int64_t n, int lo, int n_levels, unsigned long long *counts,
+                        unsigned long long *total_bits, float *bits_per_entry, void *ws, hipStream_t stream);
+
 int launch_mfma_probe(int iters, int random_operands, int blocks, int *sink, hipStream_t stream);
 
 }  // namespace cdl

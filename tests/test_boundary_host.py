@@ -101,6 +101,14 @@ def test_extension_argument_validation_happens_before_any_gpu_work(cdl):
     assert d(FAKE, FAKE, -2, good, FAKE, None) == PARAM
     assert d(FAKE, FAKE + 4, 16, good, FAKE, None) == ALIGN
     assert d(FAKE, FAKE, 16, good, FAKE + 2, None) == ALIGN
+    h = lib.cdl_huffman_bits
+    assert h(FAKE, 16, 0, 16, None, None, None, FAKE, 4096, None) == NULL                       # no output requested
+    assert h(None, 16, 0, 16, FAKE, None, None, FAKE, 4096, None) == NULL
+    assert h(FAKE, -1, 0, 16, FAKE, None, None, FAKE, 4096, None) == PARAM
+    assert h(FAKE, 16, 0, 257, FAKE, None, None, FAKE, 4096, None) == RANGE
+    assert h(FAKE + 8, 16, 0, 16, FAKE, None, None, FAKE, 4096, None) == ALIGN
+    assert h(FAKE, 16, 0, 16, FAKE, None, None, None, 0, None) == WS
+    assert cdl.huffman_workspace_bytes(0) > 0 and cdl.huffman_workspace_bytes(10**9) >= cdl.huffman_workspace_bytes(100)
     e = lib.cdl_entropy_bwd
     assert e(FAKE, FAKE, None, 16, good, 1.0, None, None, None, None, 0, None) == NULL          # no output requested
     assert e(FAKE, None, None, 16, good, 1.0, FAKE, None, None, None, 0, None) == NULL

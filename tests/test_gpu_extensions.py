@@ -171,3 +171,61 @@ def test_extension_entry_points_on_tiny_and_empty_tensors(oracle):
             assert ok.all()
             assert float(dth[:n].abs().max()) < 1e-6        # uniform marginal: zero gradient
         assert abs(float(sc[0])) < 1e-6 and abs(float(sc[1])) < 1e-6
+
+
+def _huffman_gpu(idx_h, lo, n_levels):
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    n = idx_h.size
+    idx_d = gu.dev(idx_h) if n else gu.empty((16,), torch.int8)
+    counts = gu.empty((n_levels,), torch.int64)
+    total = gu.empty((1,), torch.int64)
+    avg = gu.empty((1,), torch.float32)
+    ws = gu.workspace(cdl.huffman_workspace_bytes(n))
+    cdl.cdl_huffman_bits(idx_d, n, lo, n_levels, counts, total, avg, ws)
+    torch.cuda.synchronize()
+    return counts.cpu().numpy(), int(total.item()), float(avg.item())
+
+
+@pytest.mark.parametrize("lo,n_levels", [(-7, 15), (0, 16), (-15, 31), (-127, 255), (-128, 256)])
+@pytest.mark.parametrize("n", [0, 1, 17, 4099, 1_000_003])
+def test_huffman_bits_match_oracle(oracle, lo, n_levels, n):
+    rng = np.random.default_rng(n_levels * 7 + n % 1000)
+    p = rng.dirichlet(np.full(n_levels, 0.25))
+    idx = (rng.choice(n_levels, size=n, p=p) + lo).astype(np.int8)
+    counts, total, avg = _huffman_gpu(idx, lo, n_levels)
+    r_counts, r_total, r_avg = oracle.huffman_bits(idx, lo, n_levels)
+    assert np.array_equal(counts, r_counts)
+    assert total == int(r_total)
+    assert abs(avg - r_avg) <= 1e-6 + 1e-5 * r_avg
+
+
+def test_huffman_bits_degenerate_and_out_of_set_entries(oracle):
+    # a single level; two levels; entries outside the level set are ignored
+    assert _huffman_gpu(np.full(1000, 3, np.int8), 0, 16)[1:] == (1000, 1.0)
+    assert _huffman_gpu(np.int8([1, 2] * 500), 0, 16)[1] == 1000
+    idx = np.int8([0, 1, 1, 2, 2, 2, 40, -40] * 64)
+    counts, total, _ = _huffman_gpu(idx, 0, 4)
+    r_counts, r_total, _ = oracle.huffman_bits(idx, 0, 4)
+    assert np.array_equal(counts, r_counts) and total == int(r_total)
+
+
+def test_huffman_bits_of_the_quantized_flat_tensor(oracle):
+    """Workload 4 at full size: bits per weight of the hard indices, against the oracle on the same indices,
+    and between the entropy of the index histogram and that entropy plus one."""
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    wl = cdl_inputs.workload(4)
+    spec = wl.w_spec
+    W = cdl_inputs.draw_w(wl)
+    n = W.size
+    idx = gu.empty((n,), torch.int8)
+    cdl.cdl_quantize_fwd(gu.dev(W), n, spec.lo, spec.n_levels, spec.delta, spec.alpha, idx)
+    torch.cuda.synchronize()
+    idx_h = idx.cpu().numpy()
+    counts, total, avg = _huffman_gpu(idx_h, spec.lo, spec.n_levels)
+    r_counts, r_total, r_avg = oracle.huffman_bits(idx_h, spec.lo, spec.n_levels)
+    assert np.array_equal(counts, r_counts) and total == int(r_total)
+    q = counts[counts > 0] / n
+    H = -np.sum(q * np.log2(q))
+    assert H <= avg + 1e-6 < H + 1.0

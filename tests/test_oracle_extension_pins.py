@@ -253,3 +253,49 @@ def test_entropy_gradient_with_truncated_cpmf_matches_finite_differences(oracle)
     h = 1e-7
     assert r["d_delta"] == pytest.approx((H_of(th, d + h, a)[0] - H_of(th, d - h, a)[0]) / (2 * h), rel=1e-5, abs=1e-7)
     assert r["d_alpha"] == pytest.approx((H_of(th, d, a + h)[0] - H_of(th, d, a - h)[0]) / (2 * h), rel=1e-5, abs=1e-8)
+
+
+# ------------------------------------------------------------------ Huffman-coded size (Sec. V-A, eq. Nofbits)
+
+def _huffman_total_heapq(counts):
+    """Independent restatement with the standard library's heap: total code length = sum of merged weights."""
+    import heapq
+    h = [int(c) for c in counts if c > 0]
+    if len(h) == 1:
+        return h[0]
+    heapq.heapify(h)
+    total = 0
+    while len(h) > 1:
+        a, b = heapq.heappop(h), heapq.heappop(h)
+        total += a + b
+        heapq.heappush(h, a + b)
+    return total
+
+
+def test_huffman_textbook_example(oracle):
+    # the classic six-symbol example: frequencies 5, 9, 12, 13, 16, 45 -> code lengths 4, 4, 3, 3, 3, 1 = 224 bits
+    freq = [5, 9, 12, 13, 16, 45]
+    idx = np.concatenate([np.full(f, k - 3, np.int8) for k, f in enumerate(freq)])
+    counts, total, avg = oracle.huffman_bits(idx, -3, 6)
+    assert list(counts) == freq and total == 224 and avg == pytest.approx(2.24)
+
+
+def test_huffman_bounds_and_special_cases(oracle):
+    rng = np.random.default_rng(0)
+    for lo, n_levels in ((-7, 15), (0, 16), (-127, 255)):
+        p = rng.dirichlet(np.full(n_levels, 0.3))
+        idx = (rng.choice(n_levels, size=20000, p=p) + lo).astype(np.int8)
+        counts, total, avg = oracle.huffman_bits(idx, lo, n_levels)
+        assert counts.sum() == idx.size and np.array_equal(counts, np.bincount(idx.astype(int) - lo, minlength=n_levels))
+        assert total == _huffman_total_heapq(counts)
+        q = counts[counts > 0] / idx.size
+        H = -np.sum(q * np.log2(q))
+        assert H <= avg + 1e-12 and avg < H + 1.0          # Shannon's bounds for an optimal prefix code
+    # dyadic distribution: the code meets the entropy exactly
+    idx = np.concatenate([np.full(8, 0), np.full(4, 1), np.full(2, 2), np.full(1, 3), np.full(1, 4)]).astype(np.int8)
+    _, total, avg = oracle.huffman_bits(idx, 0, 16)
+    assert total == 8 * 1 + 4 * 2 + 2 * 3 + 4 + 4 and avg == pytest.approx(30 / 16)
+    # two equally likely levels: one bit each; a single level: one bit each (reading); nothing: zero
+    assert oracle.huffman_bits(np.int8([1, 2, 1, 2]), 0, 4)[1:] == (4.0, 1.0)
+    assert oracle.huffman_bits(np.int8([3, 3, 3]), 0, 4)[1:] == (3.0, 1.0)
+    assert oracle.huffman_bits(np.zeros(0, np.int8), 0, 4)[1:] == (0.0, 0.0)
