@@ -402,13 +402,21 @@ __device__ __forceinline__ void limbs_of4(const float (&g)[4], float gscale, uin
 }
 
 // One block: 32 output rows x (4 waves x TN x 32) output columns; every wave holds all L limb tiles
-// of the 32 rows for its TN column tiles.  Per K-tile of 128 contraction entries:
+// of the 32 rows for its TN column tiles (one wave per SIMD, accumulators in the AGPRs).  Per K-tile
+// of 128 contraction entries:
 //   A side: 16 entries of G per thread -> registers -> digits -> L planes [32][128] int8 in LDS;
 //   B side: direct global->LDS loads of the index matrix rows (16-byte chunks, XOR-swizzled).
-// Two LDS stages; the one barrier per K-tile sits in front of the last of the four k-steps, whose
-// MFMAs then cover the refill of the stage just left (tile kt+2) and the first fragment reads of
-// tile kt+1.  TRANS: G is read transposed (rows of the product are columns of G).  VEC: 16-byte
-// loads of G (N % 4 == 0).
+// Two LDS stages and two register sets for G.  While the MFMAs of tile kt run (four k-steps of
+// L*TN MFMAs), the same wave
+//   k-steps 0, 1: turns G(kt+1), loaded two tiles ago, into digit words (VALU only),
+//   k-step 2:     writes them to the other stage and issues the loads of G(kt+3),
+//   barrier       (tile kt+1 complete in LDS for everyone, every read of tile kt issued and done),
+//   k-step 3:     issues the direct loads of B(kt+2) into the stage tile kt has just left.
+// Every k-step is one basic block: loads never branch (addresses are clamped, the index matrix is
+// zero beyond the contraction length, so whatever G value is read there multiplies a zero), which
+// lets the scheduler put the VALU and LDS work into the shadow of the MFMAs.
+// TRANS: G is read transposed (rows of the product are columns of G).  VEC: 16-byte loads of G
+// (N % 4 == 0).
 template <int L, int TN, bool TRANS, bool VEC>
 __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, float gscale, double out_scale)
 {
@@ -416,7 +424,7 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
     constexpr int STAGE = L * kLPlane + NB * kLBK;
     constexpr int WLB = NB / 32;          // direct loads per wave per K-tile
     constexpr int GL = VEC ? 4 : 16;      // G load instructions per thread per K-tile
-    constexpr int KS = kLBK / 32;
+    constexpr int NM = L * TN;            // MFMAs per k-step
 
     const int tiles_c = (a.cols + NB - 1) / NB;
     // Workgroups go to the eight XCDs round-robin: XCD x takes the x-th eighth of the work items, so that
@@ -436,111 +444,112 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
     const int nk = min(nk_total, kt0 + a.kt_per_split) - kt0;
     const int row0 = tile_r * kLRows, col0 = tile_c * NB;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     // ---- A side ----
-    float gbuf[16];
-    // !TRANS: thread owns row ar = tid/8 and 16 consecutive contraction entries from 16*(tid%8)
-    //  TRANS: thread owns rows 4*(tid%8)..+3 and 4 consecutive contraction entries from 4*(tid/8)
-    const int ar = TRANS ? 4 * (tid & 7) : (tid >> 3);
-    const int ak = TRANS ? 4 * (tid >> 3) : 16 * (tid & 7);
-    auto load_g = [&](int kt) {
-        const int k0 = (kt0 + kt) * kLBK + ak;
+    // Each thread owns four groups q = 0..3 of four consecutive contraction entries (one float4 of G, or
+    // one column of a 4 x 4 patch of G^T), laid out so that one load instruction of a wave covers whole
+    // 128-byte lines of G:
+    // !TRANS: group q is row 8 q + tid / 32, entries 4 (tid % 32) .. +3
+    //  TRANS: the patch is rows 4 (tid % 8) .. +3 by entries 4 (tid / 8) .. +3; group q is its row q
+    float gbuf[2][16];
+    const int ar = TRANS ? 4 * (tid & 7) : (tid >> 5);       // row of group 0
+    const int ak = TRANS ? 4 * (tid >> 3) : 4 * (tid & 31);  // first contraction entry inside the K-tile
+    // (a tile index past the last K-tile of the matrix is clamped, and so is every address inside a tile)
+    auto load_g = [&](float (&g)[16], int kt) {
+        const int k0 = min(kt0 + kt, nk_total - 1) * kLBK + ak;
         if (!TRANS) {
-            const int grow = min(row0 + ar, a.rows - 1);
-            const float *p = a.G + (int64_t)grow * a.N + k0;
-            if (VEC) {
+            // g[4 q + e] = G[row0 + ar + 8 q][k0 + e]
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (k0 + 4 * j < a.kc) v = *reinterpret_cast<const float4 *>(p + 4 * j);
-                    gbuf[4 * j] = v.x; gbuf[4 * j + 1] = v.y; gbuf[4 * j + 2] = v.z; gbuf[4 * j + 3] = v.w;
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 16; ++j) gbuf[j] = (k0 + j < a.kc) ? p[j] : 0.0f;
-            }
-        } else {
-            // gbuf[4 j + i] = G[k0 + j][row0 + ar + i]
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float *p = a.G + (int64_t)min(k0 + j, a.kc - 1) * a.N + row0 + ar;
-                const bool kin = k0 + j < a.kc;
+            for (int q = 0; q < 4; ++q) {
+                const float *p = a.G + (int64_t)min(row0 + ar + 8 * q, a.rows - 1) * a.N;
                 if (VEC) {
-                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (kin && row0 + ar < a.rows) v = *reinterpret_cast<const float4 *>(p);
-                    gbuf[4 * j] = v.x; gbuf[4 * j + 1] = v.y; gbuf[4 * j + 2] = v.z; gbuf[4 * j + 3] = v.w;
+                    const float4 v = *reinterpret_cast<const float4 *>(p + min(k0, a.kc - 4));
+                    g[4 * q] = v.x; g[4 * q + 1] = v.y; g[4 * q + 2] = v.z; g[4 * q + 3] = v.w;
                 } else {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) gbuf[4 * j + i] = (kin && row0 + ar + i < a.rows) ? p[i] : 0.0f;
+                    for (int e = 0; e < 4; ++e) g[4 * q + e] = p[min(k0 + e, a.kc - 1)];
+                }
+            }
+        } else {
+            // g[4 e + q] = G[k0 + e][row0 + ar + q]
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float *p = a.G + (int64_t)min(k0 + e, a.kc - 1) * a.N;
+                if (VEC) {
+                    const float4 v = *reinterpret_cast<const float4 *>(p + min(row0 + ar, a.rows - 4));
+                    g[4 * e] = v.x; g[4 * e + 1] = v.y; g[4 * e + 2] = v.z; g[4 * e + 3] = v.w;
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) g[4 * e + q] = p[min(row0 + ar + q, a.rows - 1)];
                 }
             }
         }
     };
-    auto convert_store = [&](int stage) {
-        int8_t *base = lds + stage * STAGE;
-        if (!TRANS) {
-            uint32_t w[4][L];
+    // digit words of the four groups, w[q][l] = digit l of the group's four entries; two groups at a time
+    uint32_t w[4][L];
+    auto convert_half = [&](const float (&g)[16], int h) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float g4[4] = {gbuf[4 * j], gbuf[4 * j + 1], gbuf[4 * j + 2], gbuf[4 * j + 3]};
-                limbs_of4<L>(g4, gscale, w[j]);
+        for (int q = 2 * h; q < 2 * h + 2; ++q) {
+            if (!TRANS) {
+                const float g4[4] = {g[4 * q], g[4 * q + 1], g[4 * q + 2], g[4 * q + 3]};
+                limbs_of4<L>(g4, gscale, w[q]);
+            } else {
+                const float g4[4] = {g[q], g[4 + q], g[8 + q], g[12 + q]};
+                limbs_of4<L>(g4, gscale, w[q]);
             }
-            const int off = ar * kLBK + (((tid & 7) ^ lswz(ar)) << 4);
+        }
+    };
+    // where the word of group q goes inside a plane: row * 128 + (swizzled 16-byte chunk) + word in chunk.
+    // The rows of a thread's groups are 8 apart from a row below 8 (!TRANS: the swizzle of rows +8, +24 is
+    // that of row +0 with bit 2 flipped) or consecutive from a multiple of 4 (TRANS: rows +2, +3 flip bit 0).
+    const int aw_row = ar * kLBK + ((ak >> 2) & 3) * 4;
+    const int aw_chunk = ((ak >> 4) ^ lswz(ar)) << 4;
+    auto store_digits = [&](int stage) {
+        int8_t *base = lds + stage * STAGE + aw_row;
 #pragma unroll
-            for (int l = 0; l < L; ++l) {
-                const v4i v = {(int)w[0][l], (int)w[1][l], (int)w[2][l], (int)w[3][l]};
-                *reinterpret_cast<v4i *>(base + l * kLPlane + off) = v;
-            }
-        } else {
-            const int mg = tid >> 3;
+        for (int q = 0; q < 4; ++q) {
+            int8_t *d = TRANS ? base + (q >> 1 ? aw_chunk ^ 16 : aw_chunk) + q * kLBK
+                              : base + (q & 1 ? aw_chunk ^ 64 : aw_chunk) + q * 8 * kLBK;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float g4[4] = {gbuf[i], gbuf[4 + i], gbuf[8 + i], gbuf[12 + i]};
-                uint32_t w[L];
-                limbs_of4<L>(g4, gscale, w);
-                const int row = ar + i;
-                const int off = row * kLBK + (((mg >> 2) ^ lswz(row)) << 4) + ((mg & 3) << 2);
-#pragma unroll
-                for (int l = 0; l < L; ++l) *reinterpret_cast<uint32_t *>(base + l * kLPlane + off) = w[l];
-            }
+            for (int l = 0; l < L; ++l) *reinterpret_cast<uint32_t *>(d + l * kLPlane) = w[q][l];
         }
     };
 
-    // ---- B side ----
-    const int8_t *gb[WLB];
+    // ---- B side: one uniform base that moves along the contraction, a 32-bit offset per lane ----
+    const int8_t *bbase = a.Bt + (int64_t)col0 * a.ldb + (int64_t)kt0 * kLBK;
+    uint32_t boff[WLB];
 #pragma unroll
     for (int i = 0; i < WLB; ++i) {
         const int s = (wave * WLB + i) * 64 + lane, row = s >> 3;
         const int q = (s & 7) ^ lswz(row);
-        const int gcol = min(col0 + row, a.cols - 1);
-        gb[i] = a.Bt + (int64_t)gcol * a.ldb + q * 16;
+        boff[i] = (uint32_t)(min(row, a.cols - 1 - col0) * a.ldb + q * 16);
     }
-    // (a tile index past the last K-tile of the matrix is clamped: such a tile is loaded into a stage nobody reads)
-    auto issue_b = [&](int kt) {
-        int8_t *base = lds + (kt & 1) * STAGE + L * kLPlane;
-        const int64_t koff = (int64_t)min(kt0 + kt, nk_total - 1) * kLBK;
+    auto issue_b = [&](int stage, int kt) {
+        int8_t *base = lds + stage * STAGE + L * kLPlane + wave * (WLB * 1024);
+        const int8_t *src = bbase + (int64_t)min(kt, nk_total - 1 - kt0) * kLBK;
 #pragma unroll
         for (int i = 0; i < WLB; ++i)
-            __builtin_amdgcn_global_load_lds((gptr_t)(gb[i] + koff), (lptr_t)(base + (wave * WLB + i) * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(src + boff[i]), (lptr_t)(base + i * 1024), 16, 0, 0);
     };
 
     // ---- fragments ----
     const int frow = lane & 31;
-    const int fa_off = frow * kLBK;
     const int fsw = lswz(frow);
-    int fb_off[TN];
+    const int fa_off = frow * kLBK;
+    const int fb_off = L * kLPlane + (wave * TN * 32 + frow) * kLBK;   // row 32 t + frow swizzles like frow
+    int fc[4];                                                         // the 32-byte slice of k-step ks, per lane half
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb_off[j] = L * kLPlane + ((wave * TN + j) * 32 + frow) * kLBK;   // row 32 t + frow swizzles like frow
+    for (int ks = 0; ks < 4; ++ks) fc[ks] = ((2 * ks + (lane >> 5)) ^ fsw) << 4;
 
     v4i fa[2][L], fb[2][TN];
-    auto read_frags = [&](int buf, int kt, int ks) {
-        const int8_t *base = lds + (kt & 1) * STAGE;
-        const int c = ((2 * ks + (lane >> 5)) ^ fsw) << 4;
+    auto read_frags = [&](int buf, int stage, int ks) {
+        const int8_t *base = lds + stage * STAGE + fc[ks];
 #pragma unroll
-        for (int l = 0; l < L; ++l) fa[buf][l] = *reinterpret_cast<const v4i *>(base + l * kLPlane + fa_off + c);
+        for (int l = 0; l < L; ++l) fa[buf][l] = *reinterpret_cast<const v4i *>(base + l * kLPlane + fa_off);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) fb[buf][j] = *reinterpret_cast<const v4i *>(base + fb_off[j] + c);
+        for (int j = 0; j < TN; ++j) fb[buf][j] = *reinterpret_cast<const v4i *>(base + fb_off + j * 32 * kLBK);
     };
 
     v16i acc[L][TN];
@@ -550,6 +559,13 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[l][j][r] = 0;
+    auto mfma_all = [&](int buf) {
+#pragma unroll
+        for (int l = 0; l < L; ++l)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[l][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[buf][l], fb[buf][j], acc[l][j], 0, 0, 0);
+    };
 
     // a bare s_barrier: the waits it needs are spelled out next to it, so that loads of later tiles stay in flight
     auto barrier = [&]() {
@@ -557,59 +573,80 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
     };
+    // Scheduling recipe for one k-step: after every MFMA, up to `ds` LDS accesses, `vm` memory loads and
+    // `va` VALU instructions go into its shadow.
+#define CDL_INTERLEAVE(ds, vm, va)                                                          \
+    _Pragma("unroll") for (int i_ = 0; i_ < NM; ++i_) {                                     \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                  \
+        if ((ds) > 0) __builtin_amdgcn_sched_group_barrier(0x080, (ds), 0);                 \
+        if ((vm) > 0) __builtin_amdgcn_sched_group_barrier(0x020, (vm), 0);                 \
+        if ((va) > 0) __builtin_amdgcn_sched_group_barrier(0x002, (va), 0);                 \
+    }
+    constexpr int kDs2 = (L + TN + 4 * L + NM - 1) / NM;    // k-step 2: fragment reads + digit writes
+    constexpr int kVm2 = (GL + NM - 1) / NM;
+    constexpr int kVm3 = (WLB + NM - 1) / NM;
+
+    // tile kt (its parity P picks the LDS stage and the register set of G) under the schedule above
+    auto tile_step = [&](auto parity, int kt) {
+        constexpr int P = decltype(parity)::value;
+        // k-step 0
+        read_frags(1, P, 1);
+        convert_half(gbuf[P ^ 1], 0);
+        mfma_all(0);
+        CDL_INTERLEAVE(1, 0, 8)
+        __builtin_amdgcn_sched_barrier(0);
+        // k-step 1
+        read_frags(0, P, 2);
+        convert_half(gbuf[P ^ 1], 1);
+        mfma_all(1);
+        CDL_INTERLEAVE(1, 0, 8)
+        __builtin_amdgcn_sched_barrier(0);
+        // k-step 2
+        store_digits(P ^ 1);
+        read_frags(1, P, 3);
+        load_g(gbuf[P ^ 1], kt + 3);
+        mfma_all(0);
+        CDL_INTERLEAVE(kDs2, kVm2, 4)
+        __builtin_amdgcn_sched_barrier(0);
+        // B(kt+1) has landed (younger loads: G(kt+3)); own LDS writes and fragment reads are done
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(GL));
+        __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
+        barrier();
+        // k-step 3
+        read_frags(0, P ^ 1, 0);
+        issue_b(P, kt + 2);
+        mfma_all(1);
+        CDL_INTERLEAVE(1, kVm3, 4)
+        __builtin_amdgcn_sched_barrier(0);
+    };
 
     if (nk > 0) {
-        load_g(0);
-        convert_store(0);
+        load_g(gbuf[0], 0);
+        load_g(gbuf[1], 1);
+        issue_b(0, 0);
+        convert_half(gbuf[0], 0);
+        convert_half(gbuf[0], 1);
+        store_digits(0);
         asm volatile("" ::: "memory");
-        issue_b(0);
-        if (nk > 1) {
-            load_g(1);
-            convert_store(1);
-            asm volatile("" ::: "memory");
-            issue_b(1);
-        }
+        load_g(gbuf[0], 2);
+        issue_b(1, 1);
         asm volatile("" ::: "memory");
-        if (nk > 2) load_g(2);
-        asm volatile("" ::: "memory");
-        // B(0) must have landed; younger loads: B(1), G(2)
-        if (nk > 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(WLB + GL));
-        else if (nk > 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(WLB));
-        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        __builtin_amdgcn_s_waitcnt(kLgkmcnt0);   // own LDS writes done
+        // B(0) has landed (younger loads: G(2), B(1)); own LDS writes are done
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(GL + WLB));
+        __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
         barrier();
         read_frags(0, 0, 0);
-    }
-
-    for (int kt = 0; kt < nk; ++kt) {
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const int cur = ks & 1, nxt = cur ^ 1;
-            if (ks + 1 < KS) {
-                read_frags(nxt, kt, ks + 1);
-            } else if (kt + 1 < nk) {
-                // tile kt+1: B landed (younger loads: G(kt+2)); this wave's A planes and fragment reads done
-                if (kt + 2 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm(GL));
-                else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-                __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
-                barrier();
-                if (kt + 2 < nk) {
-                    convert_store(kt & 1);      // tile kt+2 into the stage that tile kt has just left
-                    asm volatile("" ::: "memory");
-                    issue_b(kt + 2);
-                    asm volatile("" ::: "memory");
-                    if (kt + 3 < nk) load_g(kt + 3);
-                    asm volatile("" ::: "memory");
-                }
-                read_frags(nxt, kt + 1, 0);
-            }
-#pragma unroll
-            for (int l = 0; l < L; ++l)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[l][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][l], fb[cur][j], acc[l][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        int kt = 0;
+        for (; kt + 1 < nk; kt += 2) {
+            tile_step(std::integral_constant<int, 0>{}, kt);
+            tile_step(std::integral_constant<int, 1>{}, kt + 1);
         }
+        if (kt < nk) tile_step(std::integral_constant<int, 0>{}, kt);
+        // the loads issued for tiles past the end write LDS: they must be done before this wave ends
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     }
+#undef CDL_INTERLEAVE
 
     // ---- epilogue: recombine the limbs; the integers are exact, the Horner steps round at 2^-53 relative ----
     // (The lane index passes through an empty asm so that the output addresses are formed here, after the
@@ -933,6 +970,8 @@ int launch_limb_gemm(LimbArgs a, bool trans, hipStream_t stream)
     const int64_t tiles_c = (a.cols + limb_cols(6) - 1) / limb_cols(6);
     const int64_t items = (int64_t)a.tiles_r * tiles_c * a.splits;
     if (items > 2147483640LL) return CDL_ERR_PARAM;
+    // the kernel addresses the rows of one column tile of the index matrix with 32-bit offsets
+    if ((int64_t)limb_cols(3) * a.ldb > 0xffffffffLL) return CDL_ERR_RANGE;
     const unsigned grid = (unsigned)((items + 7) / 8 * 8);
     {
         // more than 64 KiB of dynamic LDS has to be allowed per function (and per device: set it every time)
