@@ -408,10 +408,15 @@ __device__ __forceinline__ void limbs_of4(const float (&g)[4], float gscale, uin
 //   B side: direct global->LDS loads of the index matrix rows (16-byte chunks, XOR-swizzled).
 // Two LDS stages and two register sets for G.  While the MFMAs of tile kt run (four k-steps of
 // L*TN MFMAs), the same wave
-//   k-steps 0, 1: turns G(kt+1), loaded two tiles ago, into digit words (VALU only),
-//   k-step 2:     writes them to the other stage and issues the loads of G(kt+3),
+//   k-steps 0, 1: turns G(kt+1), loaded two tiles ago, into digit words (VALU only) and issues the second
+//                 half of the direct loads of B(kt+1),
+//   k-step 2:     writes the digits to the other stage and issues the loads of G(kt+3),
 //   barrier       (tile kt+1 complete in LDS for everyone, every read of tile kt issued and done),
-//   k-step 3:     issues the direct loads of B(kt+2) into the stage tile kt has just left.
+//   k-step 3:     reads the first fragments of tile kt+1 and issues the first half of the direct loads of
+//                 B(kt+2) into the stage tile kt has just left.
+// A wave runs its instructions in order: an MFMA occupies the matrix pipe for 32 cycles and about seven
+// VALU or LDS instructions issued behind it are free (measured), more are not.  Hence the recipe per
+// k-step below, which hands the scheduler the numbers of LDS, memory and VALU instructions per MFMA.
 // Every k-step is one basic block: loads never branch (addresses are clamped, the index matrix is
 // zero beyond the contraction length, so whatever G value is read there multiplies a zero), which
 // lets the scheduler put the VALU and LDS work into the shadow of the MFMAs.
@@ -526,11 +531,13 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
         const int q = (s & 7) ^ lswz(row);
         boff[i] = (uint32_t)(min(row, a.cols - 1 - col0) * a.ldb + q * 16);
     }
-    auto issue_b = [&](int stage, int kt) {
+    // half h of the direct loads of tile kt: a wave that issues all of them back to back outruns the
+    // address unit (1 KiB per instruction, 64 bytes per cycle per CU) and stalls behind its own loads
+    auto issue_b = [&](int stage, int kt, int h) {
         int8_t *base = lds + stage * STAGE + L * kLPlane + wave * (WLB * 1024);
         const int8_t *src = bbase + (int64_t)min(kt, nk_total - 1 - kt0) * kLBK;
 #pragma unroll
-        for (int i = 0; i < WLB; ++i)
+        for (int i = h * (WLB / 2); i < (h + 1) * (WLB / 2); ++i)
             __builtin_amdgcn_global_load_lds((gptr_t)(src + boff[i]), (lptr_t)(base + i * 1024), 16, 0, 0);
     };
 
@@ -584,22 +591,22 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
     }
     constexpr int kDs2 = (L + TN + 4 * L + NM - 1) / NM;    // k-step 2: fragment reads + digit writes
     constexpr int kVm2 = (GL + NM - 1) / NM;
-    constexpr int kVm3 = (WLB + NM - 1) / NM;
 
     // tile kt (its parity P picks the LDS stage and the register set of G) under the schedule above
     auto tile_step = [&](auto parity, int kt) {
         constexpr int P = decltype(parity)::value;
         // k-step 0
         read_frags(1, P, 1);
+        issue_b(P ^ 1, kt + 1, 1);
         convert_half(gbuf[P ^ 1], 0);
         mfma_all(0);
-        CDL_INTERLEAVE(1, 0, 8)
+        CDL_INTERLEAVE(1, 1, 5)
         __builtin_amdgcn_sched_barrier(0);
         // k-step 1
         read_frags(0, P, 2);
         convert_half(gbuf[P ^ 1], 1);
         mfma_all(1);
-        CDL_INTERLEAVE(1, 0, 8)
+        CDL_INTERLEAVE(1, 0, 5)
         __builtin_amdgcn_sched_barrier(0);
         // k-step 2
         store_digits(P ^ 1);
@@ -614,25 +621,26 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
         barrier();
         // k-step 3
         read_frags(0, P ^ 1, 0);
-        issue_b(P, kt + 2);
+        issue_b(P, kt + 2, 0);
         mfma_all(1);
-        CDL_INTERLEAVE(1, kVm3, 4)
+        CDL_INTERLEAVE(1, 1, 4)
         __builtin_amdgcn_sched_barrier(0);
     };
 
     if (nk > 0) {
         load_g(gbuf[0], 0);
         load_g(gbuf[1], 1);
-        issue_b(0, 0);
+        issue_b(0, 0, 0);
+        issue_b(0, 0, 1);
         convert_half(gbuf[0], 0);
         convert_half(gbuf[0], 1);
         store_digits(0);
         asm volatile("" ::: "memory");
         load_g(gbuf[0], 2);
-        issue_b(1, 1);
+        issue_b(1, 1, 0);
         asm volatile("" ::: "memory");
-        // B(0) has landed (younger loads: G(2), B(1)); own LDS writes are done
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(GL + WLB));
+        // B(0) has landed (younger loads: G(2), the first half of B(1)); own LDS writes are done
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(GL + WLB / 2));
         __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
         barrier();
         read_frags(0, 0, 0);
