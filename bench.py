@@ -224,7 +224,7 @@ def traffic_of(table, kernel, occurrence):
     elif kernel == "limb_gemm_kernel(d_a_hat)":
         key, occ = "limb_gemm_kernel<false>", 0
     elif kernel == "qgemm_kernel(fwd)":
-        key, occ = "qgemm_kernel", 0
+        key, occ = ("qgemm_dma_kernel" if "qgemm_dma_kernel" in table else "qgemm_kernel"), 0
     else:
         key, occ = kernel, occurrence
     for name, rows in table.items():
