@@ -203,6 +203,7 @@ struct LimbArgs {
     int nk;               // K-tiles covering the contraction: ceil(kc / kLBK)
     int rows, cols, kc;   // output rows / columns, contraction length
     int tiles_r, splits, kt_per_split;
+    int units_per_block;  // consecutive row tiles one block works through
     const BwdPlan *plan;
     int which;            // 0 = d_a_hat, 1 = d_b_hat
     float *out;           // [rows][cols] (splits == 1)
@@ -401,19 +402,25 @@ __device__ __forceinline__ void limbs_of4(const float (&g)[4], float gscale, uin
     }
 }
 
-// One block: 32 output rows x (4 waves x TN x 32) output columns; every wave holds all L limb tiles
-// of the 32 rows for its TN column tiles (one wave per SIMD, accumulators in the AGPRs).  Per K-tile
-// of 128 contraction entries:
+// One output tile is 32 rows x (4 waves x TN x 32) columns; every wave holds all L limb tiles of the
+// 32 rows for its TN column tiles (one wave per SIMD, accumulators in the AGPRs).  A block takes
+// `units_per_block` consecutive row tiles of one column tile (and one piece of the contraction) and
+// runs them as ONE sequence of K-tile steps: the loads and conversions for the first K-tiles of the
+// next row tile are already under way while the last K-tile of the current one is multiplied, so the
+// start-up of a block (plan and argument loads, first G latency from HBM, LDS fill: about 9 us,
+// measured) is paid once per block instead of once per output tile.  Per K-tile of 128 contraction
+// entries:
 //   A side: 16 entries of G per thread -> registers -> digits -> L planes [32][128] int8 in LDS;
 //   B side: direct global->LDS loads of the index matrix rows (16-byte chunks, XOR-swizzled).
-// Two LDS stages and two register sets for G.  While the MFMAs of tile kt run (four k-steps of
-// L*TN MFMAs), the same wave
-//   k-steps 0, 1: turns G(kt+1), loaded two tiles ago, into digit words (VALU only) and issues the second
-//                 half of the direct loads of B(kt+1),
-//   k-step 2:     writes the digits to the other stage and issues the loads of G(kt+3),
-//   barrier       (tile kt+1 complete in LDS for everyone, every read of tile kt issued and done),
-//   k-step 3:     reads the first fragments of tile kt+1 and issues the first half of the direct loads of
-//                 B(kt+2) into the stage tile kt has just left.
+// Two LDS stages and two register sets for G.  While the MFMAs of step s run (four k-steps of L*TN
+// MFMAs), the same wave
+//   k-steps 0, 1: turns G(s+1), loaded two steps ago, into digit words (VALU only) and issues the second
+//                 half of the direct loads of B(s+1),
+//   k-step 2:     writes the digits to the other stage and issues the loads of G(s+3),
+//   barrier       (step s+1 complete in LDS for everyone, every read of step s issued and done),
+//   k-step 3:     reads the first fragments of step s+1 and issues the first half of the direct loads of
+//                 B(s+2) into the stage step s has just left;
+//   after the last K-tile of a row tile: recombination of the limbs and the stores of that tile.
 // A wave runs its instructions in order: an MFMA occupies the matrix pipe for 32 cycles and about seven
 // VALU or LDS instructions issued behind it are free (measured), more are not.  Hence the recipe per
 // k-step below, which hands the scheduler the numbers of LDS, memory and VALU instructions per MFMA.
@@ -422,7 +429,7 @@ __device__ __forceinline__ void limbs_of4(const float (&g)[4], float gscale, uin
 // lets the scheduler put the VALU and LDS work into the shadow of the MFMAs.
 // TRANS: G is read transposed (rows of the product are columns of G).  VEC: 16-byte loads of G
 // (N % 4 == 0).
-template <int L, int TN, bool TRANS, bool VEC>
+template <int L, int TN, bool TRANS, bool VEC, bool LONG_RUNS>
 __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, float gscale, double out_scale)
 {
     constexpr int NB = 4 * TN * 32;
@@ -431,23 +438,34 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
     constexpr int GL = VEC ? 4 : 16;      // G load instructions per thread per K-tile
     constexpr int NM = L * TN;            // MFMAs per k-step
 
+    // RUNS: a block takes `units_per_block` consecutive row tiles and, for each of them, every column tile
+    // in turn (the rows of G just read for one column tile are still in L2 for the next).  With five or six
+    // limbs the accumulators fill the AGPRs and a write-out inside the loop makes the register allocator
+    // spill in the k-steps: then, and when the launcher does not ask for runs, a block takes one row tile
+    // and one column tile and writes it after the loop.
+    constexpr bool RUNS = LONG_RUNS && L <= 4;
     const int tiles_c = (a.cols + NB - 1) / NB;
+    const int R = RUNS ? a.units_per_block : 1;
+    const int runs = (a.tiles_r + R - 1) / R;        // runs of row tiles per contraction piece
+    const int c_per_block = RUNS ? tiles_c : 1;
     // Workgroups go to the eight XCDs round-robin: XCD x takes the x-th eighth of the work items, so that
-    // neighbouring items (same rows of G, next column tile) share an L2.  The grid may hold more blocks
-    // than items (it is sized before the limb count is known).
-    const int64_t items = (int64_t)a.tiles_r * tiles_c * a.splits;
+    // neighbouring items (neighbouring rows of G, same K-tiles of the index matrix) share an L2.  The grid
+    // may hold more blocks than items (it is sized before the limb count is known).
+    const int64_t items = (int64_t)runs * (tiles_c / c_per_block) * a.splits;
     const int64_t per_xcd = (items + 7) >> 3;
     const int64_t slot = (int64_t)((int)blockIdx.x >> 3);
     const int64_t logical = (int64_t)((int)blockIdx.x & 7) * per_xcd + slot;
     if (slot >= per_xcd || logical >= items) return;
-    const int tile_c = (int)(logical % tiles_c);
-    const int64_t rest = logical / tiles_c;
-    const int tile_r = (int)(rest % a.tiles_r);
-    const int split = (int)(rest / a.tiles_r);
+    const int c_begin = RUNS ? 0 : (int)(logical % tiles_c);
+    const int64_t rest = RUNS ? logical : logical / tiles_c;
+    const int run = (int)(rest % runs);
+    const int split = (int)(rest / runs);
     const int nk_total = a.nk;
     const int kt0 = split * a.kt_per_split;
-    const int nk = min(nk_total, kt0 + a.kt_per_split) - kt0;
-    const int row0 = tile_r * kLRows, col0 = tile_c * NB;
+    const int nk = min(nk_total, kt0 + a.kt_per_split) - kt0;   // K-tiles per output tile (at least one)
+    const int tile_r0 = run * R;
+    const int U = min(R, a.tiles_r - tile_r0);                   // row tiles of this block
+    const int S = U * c_per_block * nk;                          // steps
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -461,9 +479,11 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
     float gbuf[2][16];
     const int ar = TRANS ? 4 * (tid & 7) : (tid >> 5);       // row of group 0
     const int ak = TRANS ? 4 * (tid >> 3) : 4 * (tid & 31);  // first contraction entry inside the K-tile
-    // (a tile index past the last K-tile of the matrix is clamped, and so is every address inside a tile)
-    auto load_g = [&](float (&g)[16], int kt) {
-        const int k0 = min(kt0 + kt, nk_total - 1) * kLBK + ak;
+    // (every address inside a tile is clamped to the matrix)
+    // (r, kt): row tile inside the block and K-tile inside the contraction piece, both valid
+    auto load_g = [&](float (&g)[16], int r, int kt) {
+        const int row0 = (tile_r0 + r) * kLRows;
+        const int k0 = (kt0 + kt) * kLBK + ak;
         if (!TRANS) {
             // g[4 q + e] = G[row0 + ar + 8 q][k0 + e]
 #pragma unroll
@@ -522,23 +542,24 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
         }
     };
 
-    // ---- B side: one uniform base that moves along the contraction, a 32-bit offset per lane ----
-    const int8_t *bbase = a.Bt + (int64_t)col0 * a.ldb + (int64_t)kt0 * kLBK;
-    uint32_t boff[WLB];
-#pragma unroll
-    for (int i = 0; i < WLB; ++i) {
-        const int s = (wave * WLB + i) * 64 + lane, row = s >> 3;
-        const int q = (s & 7) ^ lswz(row);
-        boff[i] = (uint32_t)(min(row, a.cols - 1 - col0) * a.ldb + q * 16);
-    }
-    // half h of the direct loads of tile kt: a wave that issues all of them back to back outruns the
-    // address unit (1 KiB per instruction, 64 bytes per cycle per CU) and stalls behind its own loads
-    auto issue_b = [&](int stage, int kt, int h) {
+    // ---- B side: a uniform base per (column tile, K-tile) and a 32-bit offset per lane.  Load i of a wave
+    // covers rows brow + 8 i of the column tile (clamped to the matrix), lane % 8 picks the 16-byte chunk,
+    // XOR-swizzled with the row: the swizzle of row brow + 8 i is that of brow with bit 2 flipped for odd i. ----
+    const int brow = wave * (WLB * 8) + (lane >> 3);
+    const int bq16 = ((lane & 7) ^ lswz(brow)) << 4;
+    const uint32_t ldb32 = (uint32_t)a.ldb;
+    // half h of the direct loads of K-tile kt of column tile c: a wave that issues all of them back to back
+    // outruns the address unit (1 KiB per instruction, 64 bytes per cycle per CU) and stalls behind its own loads
+    auto issue_b = [&](int stage, int c, int kt, int h) {
         int8_t *base = lds + stage * STAGE + L * kLPlane + wave * (WLB * 1024);
-        const int8_t *src = bbase + (int64_t)min(kt, nk_total - 1 - kt0) * kLBK;
+        const int col0 = (c_begin + c) * NB;
+        const int8_t *src = a.Bt + (int64_t)col0 * a.ldb + (int64_t)(kt0 + kt) * kLBK;
+        const int lim = a.cols - 1 - col0;
 #pragma unroll
-        for (int i = h * (WLB / 2); i < (h + 1) * (WLB / 2); ++i)
-            __builtin_amdgcn_global_load_lds((gptr_t)(src + boff[i]), (lptr_t)(base + i * 1024), 16, 0, 0);
+        for (int i = h * (WLB / 2); i < (h + 1) * (WLB / 2); ++i) {
+            const uint32_t off = (uint32_t)min(brow + 8 * i, lim) * ldb32 + (uint32_t)(i & 1 ? bq16 ^ 64 : bq16);
+            __builtin_amdgcn_global_load_lds((gptr_t)(src + off), (lptr_t)(base + i * 1024), 16, 0, 0);
+        }
     };
 
     // ---- fragments ----
@@ -592,16 +613,74 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
     constexpr int kDs2 = (L + TN + 4 * L + NM - 1) / NM;    // k-step 2: fragment reads + digit writes
     constexpr int kVm2 = (GL + NM - 1) / NM;
 
-    // tile kt (its parity P picks the LDS stage and the register set of G) under the schedule above
-    auto tile_step = [&](auto parity, int kt) {
+    // ---- recombination of the limbs of row tile u: the integers are exact, the Horner steps round at
+    // 2^-53 relative.  (The lane index passes through an empty asm so that the output addresses are formed
+    // here instead of being kept in registers all the way through the loop.) ----
+    auto write_tile = [&](int r, int c) {
+        int elane = lane;
+        asm volatile("" : "+v"(elane));
+        const int row0 = (tile_r0 + r) * kLRows, col0 = (c_begin + c) * NB;
+        const int erow = row0 + 4 * (elane >> 5), ecol = col0 + wave * TN * 32 + (elane & 31);
+        const bool full = row0 + kLRows <= a.rows && col0 + NB <= a.cols;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = ecol + j * 32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = erow + 8 * (r >> 2) + (r & 3);
+                double run = (double)acc[L - 1][j][r];
+#pragma unroll
+                for (int l = L - 2; l >= 0; --l) run = run * 256.0 + (double)acc[l][j][r];
+                if (full || (row < a.rows && col < a.cols)) {
+                    if (a.splits == 1) a.out[(int64_t)row * a.cols + col] = (float)(run * out_scale);
+                    else a.partial[((int64_t)split * a.rows + row) * a.cols + col] = run;
+                }
+            }
+        }
+    };
+
+    // positions of the steps s, s+1, s+2, s+3 in the block's sequence: (row tile, column tile, K-tile), the
+    // K-tile running fastest; past the end they stay on the last valid step (such loads go to registers or
+    // to an LDS stage nobody reads)
+    struct Pos { int r, c, kt; };
+    auto advance = [&](Pos &q) {
+        if (q.kt < nk - 1) { ++q.kt; }
+        else if (q.c < c_per_block - 1) { q.kt = 0; ++q.c; }
+        else if (q.r < U - 1) { q.kt = 0; q.c = 0; ++q.r; }
+    };
+    Pos p0{0, 0, 0}, p1 = p0;
+    advance(p1);
+    Pos p2 = p1;
+    advance(p2);
+    Pos p3 = p2;
+    advance(p3);
+
+    // k-step 0 of a step; FIRST: the first K-tile of a row tile starts from zero accumulators
+    auto kstep0 = [&](auto parity, auto first) {
         constexpr int P = decltype(parity)::value;
-        // k-step 0
+        constexpr bool FIRST = decltype(first)::value;
         read_frags(1, P, 1);
-        issue_b(P ^ 1, kt + 1, 1);
+        issue_b(P ^ 1, p1.c, p1.kt, 1);
         convert_half(gbuf[P ^ 1], 0);
-        mfma_all(0);
+        if (FIRST) {
+            const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int l = 0; l < L; ++l)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[l][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[0][l], fb[0][j], zero, 0, 0, 0);
+        } else {
+            mfma_all(0);
+        }
         CDL_INTERLEAVE(1, 1, 5)
         __builtin_amdgcn_sched_barrier(0);
+    };
+    // one step (its parity P picks the LDS stage and the register set of G) under the schedule above
+    auto step = [&](auto parity) {
+        constexpr int P = decltype(parity)::value;
+        // k-step 0
+        if (RUNS && p0.kt == 0) kstep0(parity, std::true_type{});
+        else kstep0(parity, std::false_type{});
         // k-step 1
         read_frags(0, P, 2);
         convert_half(gbuf[P ^ 1], 1);
@@ -611,76 +690,57 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
         // k-step 2
         store_digits(P ^ 1);
         read_frags(1, P, 3);
-        load_g(gbuf[P ^ 1], kt + 3);
+        load_g(gbuf[P ^ 1], p3.r, p3.kt);
         mfma_all(0);
         CDL_INTERLEAVE(kDs2, kVm2, 4)
         __builtin_amdgcn_sched_barrier(0);
-        // B(kt+1) has landed (younger loads: G(kt+3)); own LDS writes and fragment reads are done
+        // B(s+1) has landed (younger loads: G(s+3)); own LDS writes and fragment reads are done
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(GL));
         __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
         barrier();
         // k-step 3
         read_frags(0, P ^ 1, 0);
-        issue_b(P, kt + 2, 0);
+        issue_b(P, p2.c, p2.kt, 0);
         mfma_all(1);
         CDL_INTERLEAVE(1, 1, 4)
         __builtin_amdgcn_sched_barrier(0);
+        if (RUNS && p0.kt == nk - 1) write_tile(p0.r, p0.c);
+        advance(p0);
+        advance(p1);
+        advance(p2);
+        advance(p3);
     };
 
-    if (nk > 0) {
-        load_g(gbuf[0], 0);
-        load_g(gbuf[1], 1);
-        issue_b(0, 0, 0);
-        issue_b(0, 0, 1);
-        convert_half(gbuf[0], 0);
-        convert_half(gbuf[0], 1);
-        store_digits(0);
-        asm volatile("" ::: "memory");
-        load_g(gbuf[0], 2);
-        issue_b(1, 1, 0);
-        asm volatile("" ::: "memory");
-        // B(0) has landed (younger loads: G(2), the first half of B(1)); own LDS writes are done
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(GL + WLB / 2));
-        __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
-        barrier();
-        read_frags(0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        int kt = 0;
-        for (; kt + 1 < nk; kt += 2) {
-            tile_step(std::integral_constant<int, 0>{}, kt);
-            tile_step(std::integral_constant<int, 1>{}, kt + 1);
-        }
-        if (kt < nk) tile_step(std::integral_constant<int, 0>{}, kt);
-        // the loads issued for tiles past the end write LDS: they must be done before this wave ends
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    load_g(gbuf[0], p0.r, p0.kt);
+    load_g(gbuf[1], p1.r, p1.kt);
+    issue_b(0, p0.c, p0.kt, 0);
+    issue_b(0, p0.c, p0.kt, 1);
+    convert_half(gbuf[0], 0);
+    convert_half(gbuf[0], 1);
+    store_digits(0);
+    asm volatile("" ::: "memory");
+    load_g(gbuf[0], p2.r, p2.kt);
+    issue_b(1, p1.c, p1.kt, 0);
+    asm volatile("" ::: "memory");
+    // B(0) has landed (younger loads: G(2), the first half of B(1)); own LDS writes are done
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(GL + WLB / 2));
+    __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
+    barrier();
+    read_frags(0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    int st = 0;
+    for (; st + 1 < S; st += 2) {
+        step(std::integral_constant<int, 0>{});
+        step(std::integral_constant<int, 1>{});
     }
+    if (st < S) step(std::integral_constant<int, 0>{});
+    // the loads issued for steps past the end write LDS: they must be done before this wave ends
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
 #undef CDL_INTERLEAVE
-
-    // ---- epilogue: recombine the limbs; the integers are exact, the Horner steps round at 2^-53 relative ----
-    // (The lane index passes through an empty asm so that the output addresses are formed here, after the
-    // loop, instead of being kept in registers all the way through it.)
-    int elane = lane;
-    asm volatile("" : "+v"(elane));
-    const int erow = row0 + 4 * (elane >> 5), ecol = col0 + wave * TN * 32 + (elane & 31);
-    const bool full = row0 + kLRows <= a.rows && col0 + NB <= a.cols;
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int col = ecol + j * 32;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = erow + 8 * (r >> 2) + (r & 3);
-            double run = (double)acc[L - 1][j][r];
-#pragma unroll
-            for (int l = L - 2; l >= 0; --l) run = run * 256.0 + (double)acc[l][j][r];
-            if (full || (row < a.rows && col < a.cols)) {
-                if (a.splits == 1) a.out[(int64_t)row * a.cols + col] = (float)(run * out_scale);
-                else a.partial[((int64_t)split * a.rows + row) * a.cols + col] = run;
-            }
-        }
-    }
+    if (!RUNS) write_tile(0, 0);
 }
 
-template <bool TRANS>
+template <bool TRANS, bool LONG_RUNS>
 __global__ __launch_bounds__(kLThreads, 1)
 void limb_gemm_kernel(LimbArgs a)
 {
@@ -690,10 +750,10 @@ void limb_gemm_kernel(LimbArgs a)
     const float gscale = a.which == 0 ? a.plan->gscale_da : a.plan->gscale_db;
     const double out_scale = a.which == 0 ? a.plan->out_scale_da : a.plan->out_scale_db;
     switch (limbs) {
-        case 3: if (vec) limb_gemm_body<3, 3, TRANS, true>(a, limb_lds, gscale, out_scale); else limb_gemm_body<3, 3, TRANS, false>(a, limb_lds, gscale, out_scale); break;
-        case 4: if (vec) limb_gemm_body<4, 3, TRANS, true>(a, limb_lds, gscale, out_scale); else limb_gemm_body<4, 3, TRANS, false>(a, limb_lds, gscale, out_scale); break;
-        case 5: if (vec) limb_gemm_body<5, 3, TRANS, true>(a, limb_lds, gscale, out_scale); else limb_gemm_body<5, 3, TRANS, false>(a, limb_lds, gscale, out_scale); break;
-        default: if (vec) limb_gemm_body<6, 2, TRANS, true>(a, limb_lds, gscale, out_scale); else limb_gemm_body<6, 2, TRANS, false>(a, limb_lds, gscale, out_scale); break;
+        case 3: if (vec) limb_gemm_body<3, 3, TRANS, true, LONG_RUNS>(a, limb_lds, gscale, out_scale); else limb_gemm_body<3, 3, TRANS, false, LONG_RUNS>(a, limb_lds, gscale, out_scale); break;
+        case 4: if (vec) limb_gemm_body<4, 3, TRANS, true, LONG_RUNS>(a, limb_lds, gscale, out_scale); else limb_gemm_body<4, 3, TRANS, false, LONG_RUNS>(a, limb_lds, gscale, out_scale); break;
+        case 5: if (vec) limb_gemm_body<5, 3, TRANS, true, false>(a, limb_lds, gscale, out_scale); else limb_gemm_body<5, 3, TRANS, false, false>(a, limb_lds, gscale, out_scale); break;
+        default: if (vec) limb_gemm_body<6, 2, TRANS, true, false>(a, limb_lds, gscale, out_scale); else limb_gemm_body<6, 2, TRANS, false, false>(a, limb_lds, gscale, out_scale); break;
     }
 }
 
@@ -974,21 +1034,35 @@ BwdLayout bwd_layout(int32_t M, int32_t N, int32_t K)
 
 int launch_limb_gemm(LimbArgs a, bool trans, hipStream_t stream)
 {
-    // the limb count, hence the column tile, is only known on the device: size the grid for the narrowest tile
-    const int64_t tiles_c = (a.cols + limb_cols(6) - 1) / limb_cols(6);
-    const int64_t items = (int64_t)a.tiles_r * tiles_c * a.splits;
+    // About one block per compute unit: each works through a run of consecutive row tiles.  The limb count,
+    // hence the column tile, is only known on the device: the run length is chosen for the wide tile, the
+    // grid is sized for the narrowest.
+    if (a.tiles_r <= 0 || a.cols <= 0) return CDL_OK;
+    int dev = 0, n_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
+        n_cu = 256;
+    const int64_t runs_wanted = n_cu / a.splits > 0 ? n_cu / a.splits : 1;
+    a.units_per_block = (int)((a.tiles_r + runs_wanted - 1) / runs_wanted);
+    // (five and six limbs: one row tile per block, and six limbs have the narrower column tile)
+    const int64_t items = (int64_t)a.tiles_r * ((a.cols + limb_cols(6) - 1) / limb_cols(6)) * a.splits;
     if (items > 2147483640LL) return CDL_ERR_PARAM;
     // the kernel addresses the rows of one column tile of the index matrix with 32-bit offsets
     if ((int64_t)limb_cols(3) * a.ldb > 0xffffffffLL) return CDL_ERR_RANGE;
     const unsigned grid = (unsigned)((items + 7) / 8 * 8);
-    {
-        // more than 64 KiB of dynamic LDS has to be allowed per function (and per device: set it every time)
-        const void *fn = trans ? (const void *)limb_gemm_kernel<true> : (const void *)limb_gemm_kernel<false>;
-        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLimbLdsBytes);
-        if (e != hipSuccess) return hip_failed(e);
-    }
-    if (trans) CDL_LAUNCH("limb_gemm_kernel(d_b_hat)", stream, limb_gemm_kernel<true>, dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
-    else CDL_LAUNCH("limb_gemm_kernel(d_a_hat)", stream, limb_gemm_kernel<false>, dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
+    // Runs pay off for short contractions (measured against one tile per block: -12 % at two K-tiles, -20 % at
+    // one, +10 % at 24, where the start-up they save is small and the blocks, all in the same phase for the
+    // whole launch, ask L2 for the same lines at the same moments).
+    const bool long_runs = a.kt_per_split <= 4;
+    const void *fn = trans ? (long_runs ? (const void *)limb_gemm_kernel<true, true> : (const void *)limb_gemm_kernel<true, false>)
+                           : (long_runs ? (const void *)limb_gemm_kernel<false, true> : (const void *)limb_gemm_kernel<false, false>);
+    // more than 64 KiB of dynamic LDS has to be allowed per function (and per device: set it every time)
+    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLimbLdsBytes);
+    if (e != hipSuccess) return hip_failed(e);
+    const char *name = trans ? "limb_gemm_kernel(d_b_hat)" : "limb_gemm_kernel(d_a_hat)";
+    if (trans && long_runs) CDL_LAUNCH(name, stream, (limb_gemm_kernel<true, true>), dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
+    else if (trans) CDL_LAUNCH(name, stream, (limb_gemm_kernel<true, false>), dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
+    else if (long_runs) CDL_LAUNCH(name, stream, (limb_gemm_kernel<false, true>), dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
+    else CDL_LAUNCH(name, stream, (limb_gemm_kernel<false, false>), dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
     return check_launch();
 }
 

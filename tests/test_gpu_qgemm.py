@@ -78,6 +78,21 @@ def test_qgemm_bwd_matches_oracle(oracle, M, N, K, levels):
     gu.assert_close(d_b, r_b, "d_b_hat")
 
 
+@pytest.mark.parametrize("M,N,K", [(20000, 200, 500), (300, 9000, 500)])
+def test_qgemm_bwd_runs_of_row_tiles(oracle, M, N, K):
+    """Short contractions with more row tiles than compute units: one block works through a run of row tiles
+    and every column tile (dL/dQ(x) in the first shape: 625 row tiles, two K-tiles, two column tiles, all
+    ragged; dL/dQ(w) in the second); the other product of each shape takes the one-tile-per-block path."""
+    a = cdl_inputs.draw_indices((M, K), 0, 15, seed=M + 3)
+    b = cdl_inputs.draw_indices((N, K), -7, 7, seed=N + 5)
+    g = np.random.default_rng(M + N).standard_normal((M, N)).astype(np.float32)
+    da, db = float(np.float32(0.56419)), float(np.float32(0.016623))
+    d_a, d_b = gu.qgemm_bwd(g, a, b, da, db)
+    r_a, r_b = oracle.qgemm_bwd(g, a, b, da, db)
+    gu.assert_close(d_a, r_a, "d_a_hat")
+    gu.assert_close(d_b, r_b, "d_b_hat")
+
+
 def test_qgemm_bwd_wide_dynamic_range_gradient(oracle):
     # gradients spanning many binades, a few exact zeros, one large outlier
     M, N, K = 384, 160, 192
