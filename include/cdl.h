@@ -183,7 +183,8 @@ int cdl_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N
  * the int8 matrix cores and the limbs are recombined in double; L (3..6) is chosen on the device
  * so that the rounding of q contributes about 1.7e-7 absolute (one standard deviation) or less.
  * At least one output non-NULL.  CDL_ERR_RANGE if d_a_hat is requested and N > 131071 (int32
- * accumulators over the contraction; the contraction over M is cut into pieces internally).
+ * accumulators over the contraction; the contraction over M is cut into pieces internally), or if
+ * d_b_hat is requested and M > 11 000 000 (32-bit offsets into the transposed copy of a_idx).
  */
 int cdl_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
                   int32_t M, int32_t N, int32_t K, float delta_a, float delta_b,

@@ -243,6 +243,8 @@ int cdl_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
     // int32 accumulators hold limb (<= 128) x index (<= 128) products over the contraction length; the
     // contraction over M is cut into pieces by the library, the one over N is not
     if (d_a_hat && (int64_t)N * 128 * 128 > 2147483647LL) return CDL_ERR_RANGE;
+    // the kernels address 384 rows of the transposed copy of a_idx (row length M, padded) with 32-bit offsets
+    if (d_b_hat && (int64_t)M > 11000000LL) return CDL_ERR_RANGE;
     if ((int64_t)M * N * K > 0 && (!g || (d_a_hat && !b_idx) || (d_b_hat && !a_idx))) return CDL_ERR_NULL;
     if (!aligned(g, 16) || !aligned(a_idx, 16) || !aligned(b_idx, 16) || !aligned(d_a_hat, 16) || !aligned(d_b_hat, 16))
         return CDL_ERR_ALIGN;

@@ -135,6 +135,7 @@ def test_gemm_argument_validation_happens_before_any_gpu_work(cdl):
     assert b(FAKE, FAKE, FAKE, 4, 4, 16, 1.0, 1.0, FAKE, FAKE, None, 0, None) == WS
     assert b(FAKE, FAKE, FAKE, 4, 131072, 16, 1.0, 1.0, FAKE, None, None, 0, None) == RANGE      # contraction over N, int32
     assert b(FAKE, FAKE, FAKE, 262145, 4, 16, 1.0, 1.0, None, FAKE, None, 0, None) == WS         # contraction over M is cut up
+    assert b(FAKE, FAKE, FAKE, 11000001, 4, 16, 1.0, 1.0, None, FAKE, None, 0, None) == RANGE    # 32-bit offsets inside
     assert lib.cdl_profile_collect(None, 4) == PARAM
 
 
