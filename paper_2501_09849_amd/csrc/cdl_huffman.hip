@@ -44,27 +44,56 @@ void index_hist_kernel(const int8_t *__restrict__ idx, int64_t n, unsigned int *
     rows[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(1024)
 void huffman_kernel(const unsigned int *__restrict__ rows, int nrows, int64_t n, int lo, int n_levels,
                     unsigned long long *__restrict__ counts /* [n_levels], nullable */,
                     unsigned long long *__restrict__ total_bits /* nullable */, float *__restrict__ bits_per_entry /* nullable */)
 {
     __shared__ unsigned long long key[256];
     __shared__ unsigned long long merged[256];
+    __shared__ unsigned long long part[16][256];
+    // 1024 threads = 16 groups of 64: a group takes every sixteenth row, a thread four neighbouring bins
+    // (one 16-byte load), four loads in flight each (one thread per bin walking all rows one after the other
+    // is nothing but memory latency)
+    {
+        const int q = threadIdx.x & 63, grp = threadIdx.x >> 6;
+        unsigned long long c[4][4] = {};
+        const uint4 *rows4 = reinterpret_cast<const uint4 *>(rows);
+        int r = grp;
+        for (; r + 48 < nrows; r += 64) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint4 v = rows4[(size_t)(r + 16 * u) * 64 + q];
+                c[u][0] += v.x; c[u][1] += v.y; c[u][2] += v.z; c[u][3] += v.w;
+            }
+        }
+        for (; r < nrows; r += 16) {
+            const uint4 v = rows4[(size_t)r * 64 + q];
+            c[0][0] += v.x; c[0][1] += v.y; c[0][2] += v.z; c[0][3] += v.w;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) part[grp][4 * q + e] = (c[0][e] + c[1][e]) + (c[2][e] + c[3][e]);
+    }
+    __syncthreads();
+    // from here on the first 256 threads work, thread t on byte value t, i.e. level (int8)t; the others
+    // only keep the barriers company
     const int t = threadIdx.x;
-    unsigned long long c = 0ull;
-    for (int r = 0; r < nrows; ++r) c += rows[(size_t)r * 256 + t];
-    // thread t holds the count of byte value t, i.e. of level (int8)t
-    const int level = (int)(int8_t)(uint8_t)t;
-    const bool in_set = level >= lo && level < lo + n_levels;
-    if (counts && in_set) counts[level - lo] = c;
-    key[t] = in_set ? c : 0ull;
+    const bool act = t < 256;
+    if (act) {
+        unsigned long long c = 0ull;
+#pragma unroll
+        for (int g = 0; g < 16; ++g) c += part[g][t];
+        const int level = (int)(int8_t)(uint8_t)t;
+        const bool in_set = level >= lo && level < lo + n_levels;
+        if (counts && in_set) counts[level - lo] = c;
+        key[t] = in_set ? c : 0ull;
+    }
     __syncthreads();
     // bitonic sort, ascending
     for (int k = 2; k <= 256; k <<= 1)
         for (int j = k >> 1; j > 0; j >>= 1) {
             const int p = t ^ j;
-            if (p > t) {
+            if (act && p > t) {
                 const unsigned long long a = key[t], b = key[p];
                 const bool up = (t & k) == 0;
                 if ((a > b) == up) { key[t] = b; key[p] = a; }
@@ -74,6 +103,7 @@ void huffman_kernel(const unsigned int *__restrict__ rows, int nrows, int64_t n,
     if (t != 0) return;
     // two queues: the sorted leaves (zeros skipped) and the merged nodes, which come out in nondecreasing order
     int i = 0;
+    while (i + 8 <= 256 && key[i + 7] == 0ull) i += 8;     // the zeros sort to the front
     while (i < 256 && key[i] == 0ull) ++i;
     const int leaves = 256 - i;
     unsigned long long total = 0ull;
@@ -117,7 +147,7 @@ int launch_huffman_bits(const int8_t *idx, int64_t n, int lo, int n_levels, unsi
     const int blocks = hist_blocks(n);
     unsigned int *rows = reinterpret_cast<unsigned int *>(ws);
     CDL_LAUNCH("index_hist_kernel", stream, index_hist_kernel, dim3(blocks), dim3(kHistThreads), 0, idx, n, rows);
-    CDL_LAUNCH("huffman_kernel", stream, huffman_kernel, dim3(1), dim3(256), 0, rows, blocks, n, lo, n_levels, counts, total_bits,
+    CDL_LAUNCH("huffman_kernel", stream, huffman_kernel, dim3(1), dim3(1024), 0, rows, blocks, n, lo, n_levels, counts, total_bits,
                bits_per_entry);
     return check_launch();
 }

@@ -50,6 +50,21 @@ def test_qgemm_fwd_extreme_indices_do_not_overflow(oracle):
     assert np.array_equal(acc, r_acc)
 
 
+def test_qgemm_fwd_longest_contraction_with_extreme_indices(oracle):
+    """K = 131071 is the longest contraction the boundary accepts: (-128) x (-128) summed that often is
+    2147467264, sixteen thousand below the int32 limit."""
+    M, N, K = 40, 24, 131071
+    a = np.full((M, K), -128, np.int8)
+    b = np.full((N, K), -128, np.int8)
+    b[1::2] = 127
+    a[3, ::5] = 5
+    acc, y = gu.qgemm_fwd(a, b, 0.5, 0.25)
+    r_acc, r_y = oracle.qgemm_fwd(a, b, 0.5, 0.25)
+    assert int(r_acc.max()) == 131071 * 16384
+    assert np.array_equal(acc, r_acc)
+    gu.assert_close(y, r_y, "y")
+
+
 def test_qgemm_fwd_outputs_are_optional(oracle):
     a = cdl_inputs.draw_indices((130, 96), 0, 15, seed=1)
     b = cdl_inputs.draw_indices((70, 96), -7, 7, seed=2)
@@ -89,6 +104,22 @@ def test_qgemm_bwd_runs_of_row_tiles(oracle, M, N, K):
     da, db = float(np.float32(0.56419)), float(np.float32(0.016623))
     d_a, d_b = gu.qgemm_bwd(g, a, b, da, db)
     r_a, r_b = oracle.qgemm_bwd(g, a, b, da, db)
+    gu.assert_close(d_a, r_a, "d_a_hat")
+    gu.assert_close(d_b, r_b, "d_b_hat")
+
+
+def test_qgemm_bwd_longest_contraction_with_extreme_operands(oracle):
+    """N = 131071 is the longest contraction dL/dQ(a) accepts (one int32 accumulator per limb over all of it):
+    every gradient at the top of its binade and every index at -128 drives the accumulators to their bound."""
+    M, N, K = 40, 131071, 48
+    g = np.full((M, N), 0.99, np.float32)
+    g[::3] = -0.99
+    g[5, ::7] = 0.123
+    a = cdl_inputs.draw_indices((M, K), -128, 127, seed=11)
+    b = np.full((N, K), -128, np.int8)
+    b[:, 1::2] = 127
+    d_a, d_b = gu.qgemm_bwd(g, a, b, 0.25, 0.5)
+    r_a, r_b = oracle.qgemm_bwd(g, a, b, 0.25, 0.5)
     gu.assert_close(d_a, r_a, "d_a_hat")
     gu.assert_close(d_b, r_b, "d_b_hat")
 
