@@ -757,24 +757,34 @@ void limb_gemm_kernel(LimbArgs a)
     }
 }
 
-// out = out_scale * sum over the contraction splits.  Four partial sums per output (splits p = 0, 4, 8, ...;
-// 1, 5, ...; ...), combined in a fixed order, keep four loads in flight per thread: with a few hundred splits
-// a single dependent chain is all latency.
+// out = out_scale * sum over the contraction splits.  Four partial sums per lane, combined in a fixed order,
+// keep four loads in flight: with a few hundred splits a single dependent chain is all latency.  LANES lanes
+// share one output (lane j takes the splits j, j + LANES, ...; butterfly over the lanes at the end): used
+// when there are few outputs and many splits, where one lane per output leaves most of the chip idle.
+template <int LANES>
 __global__ __launch_bounds__(256)
 void limb_reduce_kernel(const double *__restrict__ partial, int splits, int64_t n, const BwdPlan *plan, float *__restrict__ out)
 {
     const double out_scale = plan->out_scale_db;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int sub = threadIdx.x % LANES;
+    const int64_t per_block = 256 / LANES;
+    // whole groups of LANES run every trip (the index is clamped), so that the shuffles see all their lanes
+    const int64_t n_round = (n + per_block - 1) / per_block * per_block;
+    for (int64_t i = (int64_t)blockIdx.x * per_block + threadIdx.x / LANES; i < n_round; i += (int64_t)gridDim.x * per_block) {
+        const int64_t ii = i < n ? i : n - 1;
         double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-        int p = 0;
-        for (; p + 3 < splits; p += 4) {
-            s0 += partial[(int64_t)p * n + i];
-            s1 += partial[(int64_t)(p + 1) * n + i];
-            s2 += partial[(int64_t)(p + 2) * n + i];
-            s3 += partial[(int64_t)(p + 3) * n + i];
+        int p = sub;
+        for (; p + 3 * LANES < splits; p += 4 * LANES) {
+            s0 += partial[(int64_t)p * n + ii];
+            s1 += partial[(int64_t)(p + LANES) * n + ii];
+            s2 += partial[(int64_t)(p + 2 * LANES) * n + ii];
+            s3 += partial[(int64_t)(p + 3 * LANES) * n + ii];
         }
-        for (; p < splits; ++p) s0 += partial[(int64_t)p * n + i];
-        out[i] = (float)(((s0 + s1) + (s2 + s3)) * out_scale);
+        for (; p < splits; p += LANES) s0 += partial[(int64_t)p * n + ii];
+        double s = (s0 + s1) + (s2 + s3);
+#pragma unroll
+        for (int off = LANES / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+        if (sub == 0 && i < n) out[i] = (float)(s * out_scale);
     }
 }
 
@@ -892,25 +902,40 @@ __global__ __launch_bounds__(256) void transpose_i8_kernel(const int8_t *__restr
 // in +-sigma 2^-8L per entry, so a contraction over n_c index entries of mean square s has a random
 // error of about delta sigma 2^(1-8L) sqrt(n_c s / 12); L is the smallest count (3..6) that brings
 // this under 1.7e-7, a sixth of the absolute parity tolerance.
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(1024)
 void plan_kernel(BwdPlan *plan, const unsigned int *__restrict__ block_max, int n_max,
                  const unsigned int *__restrict__ ss_a, int n_ss_a, const unsigned int *__restrict__ ss_b, int n_ss_b,
                  int M, int N, int K, float delta_a, float delta_b)
 {
-    __shared__ unsigned int red_m[256];
-    __shared__ unsigned long long red_a[256], red_b[256];
+    __shared__ unsigned int red_m[1024];
+    __shared__ unsigned long long red_a[1024], red_b[1024];
+    // one block of 1024 threads, four independent loads per thread and trip (the arrays hold up to a few ten
+    // thousand per-block results; a single dependent chain per thread is all latency)
+    const int t = threadIdx.x;
     unsigned int m = 0u;
     unsigned long long sa = 0ull, sb = 0ull;
-    for (int i = threadIdx.x; i < n_max; i += 256) m = max(m, block_max[i]);
-    for (int i = threadIdx.x; i < n_ss_a; i += 256) sa += ss_a[i];
-    for (int i = threadIdx.x; i < n_ss_b; i += 256) sb += ss_b[i];
-    red_m[threadIdx.x] = m; red_a[threadIdx.x] = sa; red_b[threadIdx.x] = sb;
+    for (int i = t; i < n_max; i += 4096) {
+        const unsigned int v0 = block_max[i], v1 = i + 1024 < n_max ? block_max[i + 1024] : 0u;
+        const unsigned int v2 = i + 2048 < n_max ? block_max[i + 2048] : 0u, v3 = i + 3072 < n_max ? block_max[i + 3072] : 0u;
+        m = max(max(m, v0), max(max(v1, v2), v3));
+    }
+    for (int i = t; i < n_ss_a; i += 4096) {
+        const unsigned int v0 = ss_a[i], v1 = i + 1024 < n_ss_a ? ss_a[i + 1024] : 0u;
+        const unsigned int v2 = i + 2048 < n_ss_a ? ss_a[i + 2048] : 0u, v3 = i + 3072 < n_ss_a ? ss_a[i + 3072] : 0u;
+        sa += ((unsigned long long)v0 + v1) + ((unsigned long long)v2 + v3);
+    }
+    for (int i = t; i < n_ss_b; i += 4096) {
+        const unsigned int v0 = ss_b[i], v1 = i + 1024 < n_ss_b ? ss_b[i + 1024] : 0u;
+        const unsigned int v2 = i + 2048 < n_ss_b ? ss_b[i + 2048] : 0u, v3 = i + 3072 < n_ss_b ? ss_b[i + 3072] : 0u;
+        sb += ((unsigned long long)v0 + v1) + ((unsigned long long)v2 + v3);
+    }
+    red_m[t] = m; red_a[t] = sa; red_b[t] = sb;
     __syncthreads();
-    for (int off = 128; off > 0; off >>= 1) {
-        if ((int)threadIdx.x < off) {
-            red_m[threadIdx.x] = max(red_m[threadIdx.x], red_m[threadIdx.x + off]);
-            red_a[threadIdx.x] += red_a[threadIdx.x + off];
-            red_b[threadIdx.x] += red_b[threadIdx.x + off];
+    for (int off = 512; off > 0; off >>= 1) {
+        if (t < off) {
+            red_m[t] = max(red_m[t], red_m[t + off]);
+            red_a[t] += red_a[t + off];
+            red_b[t] += red_b[t + off];
         }
         __syncthreads();
     }
@@ -1148,7 +1173,7 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
     CDL_LAUNCH("absmax_kernel", stream, absmax_kernel, dim3(L.n_max), dim3(256), 0, gr, (int64_t)M * N, block_max);
     if (d_a_hat) launch_transpose(b_idx, N, K, bt, L.ldn, ss_b, stream);
     if (d_b_hat) launch_transpose(a_idx, M, K, at, L.ldm, ss_a, stream);
-    CDL_LAUNCH("plan_kernel", stream, plan_kernel, dim3(1), dim3(256), 0, plan, block_max, L.n_max,
+    CDL_LAUNCH("plan_kernel", stream, plan_kernel, dim3(1), dim3(1024), 0, plan, block_max, L.n_max,
                ss_a, d_b_hat ? L.n_ss_a : 0, ss_b, d_a_hat ? L.n_ss_b : 0, M, N, K, delta_a, delta_b);
     int rc = check_launch();
     if (rc != CDL_OK) return rc;
@@ -1177,8 +1202,12 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
         rc = launch_limb_gemm(a, true, stream);
         if (rc != CDL_OK) return rc;
         if (L.splits > 1) {
-            CDL_LAUNCH("limb_reduce_kernel", stream, limb_reduce_kernel, dim3(blocks_for((int64_t)N * K, 256, 4096)), dim3(256), 0,
-                       partial, L.splits, (int64_t)N * K, plan, d_b_hat);
+            if ((int64_t)N * K <= 65536 && L.splits >= 32)
+                CDL_LAUNCH("limb_reduce_kernel", stream, limb_reduce_kernel<16>, dim3(blocks_for((int64_t)N * K * 16, 256, 4096)), dim3(256), 0,
+                           partial, L.splits, (int64_t)N * K, plan, d_b_hat);
+            else
+                CDL_LAUNCH("limb_reduce_kernel", stream, limb_reduce_kernel<1>, dim3(blocks_for((int64_t)N * K, 256, 4096)), dim3(256), 0,
+                           partial, L.splits, (int64_t)N * K, plan, d_b_hat);
             rc = check_launch();
         }
     }
