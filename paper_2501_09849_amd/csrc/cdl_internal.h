@@ -41,6 +41,34 @@ private:
         hipLaunchKernelGGL(KERNEL, GRID, BLOCK, LDS, STREAM, __VA_ARGS__);            \
     } while (0)
 
+// ---- streaming loads and stores ------------------------------------------------------------
+// Large tensors that a pass reads or writes exactly once go through non-temporal accesses: they are not
+// kept in the caches, and a pass over data that is not cached anyway runs faster that way (a reduction over
+// 805 MB: 183 us with ordinary loads, 122 us with these; quantizer forward and backward on 50 M entries:
+// -10 %).  A tensor that fits the 256 MB last-level cache and is visited again soon is better off with
+// ordinary accesses (25.6 M entries back to back: +7 % with these), hence the flag.
+#if defined(__HIPCC__)
+typedef float cdl_v4f __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_stream4(const float *p, bool stream = true)
+{
+    if (!stream) return *reinterpret_cast<const float4 *>(p);
+    const cdl_v4f v = __builtin_nontemporal_load(reinterpret_cast<const cdl_v4f *>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_stream4(float *p, float a, float b, float c, float d, bool stream = true)
+{
+    if (!stream) { *reinterpret_cast<float4 *>(p) = make_float4(a, b, c, d); return; }
+    const cdl_v4f v = {a, b, c, d};
+    __builtin_nontemporal_store(v, reinterpret_cast<cdl_v4f *>(p));
+}
+// entries from which a tensor counts as large (128 MiB of fp32)
+constexpr long long kStreamFrom = 1ll << 25;
+__device__ __forceinline__ void store_stream_u32(void *p, unsigned int v)
+{
+    __builtin_nontemporal_store(v, reinterpret_cast<unsigned int *>(p));
+}
+#endif
+
 // ---- quantizer (cdl_quantizer.hip) -------------------------------------------------------
 size_t quantize_workspace_bytes(int64_t n, int32_t n_levels);
 

@@ -815,7 +815,12 @@ __global__ __launch_bounds__(256) void absmax_kernel(const float *__restrict__ g
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int64_t v = base + j * 256 + threadIdx.x;
-            t[j] = v < n4 ? g4[v] : make_float4(0.f, 0.f, 0.f, 0.f);
+            t[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (v < n4) {
+                // streaming loads (183 -> 122 us on 805 MB): g is far larger than the last-level cache, and the
+                // index matrices that the products read next should stay there
+                t[j] = load_stream4(reinterpret_cast<const float *>(g4 + v));
+            }
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {

@@ -52,6 +52,7 @@ struct QConst {
     int lo;
     int n_levels;
     int wgen;         // band half-width of the generic kernel
+    int stream;       // 1: the tensor is large, read and write it with non-temporal accesses
     int slide;        // 1: truncated CPMF - the band of 2 wgen + 1 levels slides at the ends of the level set instead of being cut
 };
 
@@ -284,14 +285,14 @@ void quantize_fwd_kernel(const float *__restrict__ theta, int64_t n, QConst k,
     float sv[4];
     int ci[4];
     for (int64_t v = (int64_t)blockIdx.x * kQuantThreads + threadIdx.x; v < n4; v += stride) {
-        const float4 t = reinterpret_cast<const float4 *>(theta)[v];
+        const float4 t = load_stream4(theta + 4 * v, k.stream);
         const float th[4] = {t.x, t.y, t.z, t.w};
         forward4<W, IDX, MARG, RS>(th, 4, k, my_hist, sv, ci);
-        if (SOFT) reinterpret_cast<float4 *>(soft)[v] = make_float4(sv[0], sv[1], sv[2], sv[3]);
+        if (SOFT) store_stream4(soft + 4 * v, sv[0], sv[1], sv[2], sv[3], k.stream);
         if (IDX) {
             const uint32_t packed = (uint32_t)(ci[0] & 0xff) | ((uint32_t)(ci[1] & 0xff) << 8) |
                                     ((uint32_t)(ci[2] & 0xff) << 16) | ((uint32_t)(ci[3] & 0xff) << 24);
-            reinterpret_cast<uint32_t *>(idx)[v] = packed;
+            reinterpret_cast<uint32_t *>(idx)[v] = packed;   // (ordinary store: the products read the indices next)
         }
     }
     // ragged tail: the last 1..3 entries, one thread of the last block
@@ -397,8 +398,8 @@ void quantize_bwd_kernel(const float *__restrict__ theta, const float *__restric
         float th[4], ge[4];
         int cnt;
         if (v < n4) {
-            const float4 t = reinterpret_cast<const float4 *>(theta)[v];
-            const float4 q = reinterpret_cast<const float4 *>(g)[v];
+            const float4 t = load_stream4(theta + 4 * v, k.stream);
+            const float4 q = load_stream4(g + 4 * v, k.stream);
             th[0] = t.x; th[1] = t.y; th[2] = t.z; th[3] = t.w;
             ge[0] = q.x; ge[1] = q.y; ge[2] = q.z; ge[3] = q.w;
             cnt = 4;
@@ -440,7 +441,7 @@ void quantize_bwd_kernel(const float *__restrict__ theta, const float *__restric
         }
         if (SCALARS) { acc_d += (double)sum_d; acc_a += (double)sum_a; }
         if (DTHETA) {
-            if (v < n4) reinterpret_cast<float4 *>(dtheta)[v] = make_float4(dv[0], dv[1], dv[2], dv[3]);
+            if (v < n4) store_stream4(dtheta + 4 * v, dv[0], dv[1], dv[2], dv[3], k.stream);
             else for (int e = 0; e < cnt; ++e) dtheta[(n4 << 2) + e] = dv[e];
         }
     }
@@ -532,8 +533,8 @@ void quantize_draw_kernel(const float *__restrict__ theta, const float *__restri
     const int64_t n4 = n >> 2;
     const int64_t stride = (int64_t)gridDim.x * kQuantThreads;
     for (int64_t v = (int64_t)blockIdx.x * kQuantThreads + threadIdx.x; v < n4; v += stride) {
-        const float4 t = reinterpret_cast<const float4 *>(theta)[v];
-        const float4 r = reinterpret_cast<const float4 *>(u)[v];
+        const float4 t = load_stream4(theta + 4 * v, k.stream);
+        const float4 r = load_stream4(u + 4 * v, k.stream);
         const int c0 = draw_one<W>(t.x, r.x, k), c1 = draw_one<W>(t.y, r.y, k);
         const int c2 = draw_one<W>(t.z, r.z, k), c3 = draw_one<W>(t.w, r.w, k);
         reinterpret_cast<uint32_t *>(idx)[v] = (uint32_t)(c0 & 0xff) | ((uint32_t)(c1 & 0xff) << 8) |
@@ -579,9 +580,9 @@ void entropy_bwd_kernel(const float *__restrict__ theta, const float *__restrict
         float th[4], ge[4];
         int cnt;
         if (v < n4) {
-            const float4 t = reinterpret_cast<const float4 *>(theta)[v];
+            const float4 t = load_stream4(theta + 4 * v, k.stream);
             th[0] = t.x; th[1] = t.y; th[2] = t.z; th[3] = t.w;
-            if (ADD) { const float4 q = reinterpret_cast<const float4 *>(g_in)[v]; ge[0] = q.x; ge[1] = q.y; ge[2] = q.z; ge[3] = q.w; }
+            if (ADD) { const float4 q = load_stream4(g_in + 4 * v, k.stream); ge[0] = q.x; ge[1] = q.y; ge[2] = q.z; ge[3] = q.w; }
             cnt = 4;
         } else {
             cnt = (int)(n - (n4 << 2));
@@ -636,7 +637,7 @@ void entropy_bwd_kernel(const float *__restrict__ theta, const float *__restrict
         }
         if (SCALARS) { acc_d += (double)sum_d; acc_a += (double)sum_a; }
         if (DTHETA) {
-            if (v < n4) reinterpret_cast<float4 *>(dtheta)[v] = make_float4(dv[0], dv[1], dv[2], dv[3]);
+            if (v < n4) store_stream4(dtheta + 4 * v, dv[0], dv[1], dv[2], dv[3], k.stream);
             else for (int e = 0; e < cnt; ++e) dtheta[(n4 << 2) + e] = dv[e];
         }
     }
@@ -687,6 +688,7 @@ QConst make_const(const cdl_qparams &p)
     k.hi_f = (float)(p.lo + p.n_levels - 1);
     k.wgen = quantizer_window(kappa, p.n_levels);
     k.slide = 0;
+    k.stream = 0;
     if (p.top_k > 0 && p.top_k < p.n_levels) {
         // Truncated CPMF.  Where the band that kappa asks for is no wider than the top_k nearest levels the
         // truncation drops nothing above fp32 resolution and the ordinary kernels serve; otherwise the generic
@@ -799,7 +801,8 @@ int launch_quantize_fwd(const float *theta, int64_t n, const cdl_qparams &p,
         }
         return CDL_OK;
     }
-    const QConst k = make_const(p);
+    QConst k = make_const(p);
+    k.stream = n >= kStreamFrom;
     const int64_t grid64 = want_marg ? hist_grid_for(n) : grid_for(n);
     if (grid64 > 2147483647LL) return CDL_ERR_PARAM;
     const int grid = (int)grid64;
@@ -841,7 +844,8 @@ int launch_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl
         }
         return CDL_OK;
     }
-    const QConst k = make_const(p);
+    QConst k = make_const(p);
+    k.stream = n >= kStreamFrom;
     const int grid = grid_for(n);
     double *partial = want_scalars
         ? reinterpret_cast<double *>(reinterpret_cast<char *>(ws) + hist_bytes(n, p.n_levels) + aux_bytes()) : nullptr;
@@ -867,7 +871,8 @@ int launch_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl
 int launch_quantize_draw(const float *theta, const float *u, int64_t n, const cdl_qparams &p, int8_t *idx, hipStream_t stream)
 {
     if (n == 0) return CDL_OK;
-    const QConst k = make_const(p);
+    QConst k = make_const(p);
+    k.stream = n >= kStreamFrom;
     const int grid = grid_for(n);
 #define CDL_DRAW(WW) CDL_LAUNCH("quantize_draw_kernel", stream, (quantize_draw_kernel<WW>), dim3(grid), dim3(kQuantThreads), 0, theta, u, n, k, idx)
     switch (band_template(k)) {
@@ -911,7 +916,8 @@ int launch_entropy_bwd(const float *theta, const float *marg, const float *g_in,
         }
         return CDL_OK;
     }
-    const QConst k = make_const(p);
+    QConst k = make_const(p);
+    k.stream = n >= kStreamFrom;
     const int grid = grid_for(n);
     double *partial = want_scalars
         ? reinterpret_cast<double *>(reinterpret_cast<char *>(ws) + hist_bytes(n, p.n_levels) + aux_bytes()) : nullptr;
