@@ -218,17 +218,17 @@ def load_traffic(wl_number):
 
 
 def traffic_of(table, kernel, occurrence):
-    """Maps a name of the library's event records to the kernel name rocprofv3 prints."""
+    """Maps a name of the library's event records to the kernel name rocprofv3 prints (template arguments vary)."""
     if kernel == "limb_gemm_kernel(d_b_hat)":
-        key, occ = "limb_gemm_kernel<true>", 0
+        prefix, occ = "limb_gemm_kernel<true", 0
     elif kernel == "limb_gemm_kernel(d_a_hat)":
-        key, occ = "limb_gemm_kernel<false>", 0
+        prefix, occ = "limb_gemm_kernel<false", 0
     elif kernel == "qgemm_kernel(fwd)":
-        key, occ = ("qgemm_dma_kernel" if "qgemm_dma_kernel" in table else "qgemm_kernel"), 0
+        prefix, occ = ("qgemm_dma_kernel" if any(n.startswith("qgemm_dma_kernel") for n in table) else "qgemm_kernel"), 0
     else:
-        key, occ = kernel, occurrence
+        prefix, occ = kernel, occurrence
     for name, rows in table.items():
-        if name == key or name.startswith(key + "<"):
+        if name == prefix or name.startswith(prefix + "<") or name.startswith(prefix + ",") or name.startswith(prefix + ">"):
             return rows[occ] if occ < len(rows) else None
     return None
 
