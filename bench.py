@@ -130,6 +130,8 @@ def kernel_model(wl, name, occurrence):
         return "mfma", 2.0 * wl.M * wl.N * wl.K, 0
     if name == "absmax_kernel":
         return "hbm", 4.0 * wl.M * wl.N, 0          # reads g once
+    if name == "da_direct_kernel":
+        return "hbm", 4.0 * wl.M * wl.N + 1.0 * wl.N * wl.K + 4.0 * wl.M * wl.K, 0   # reads g and b_idx, writes d_a_hat
     if name == "transpose_i8_kernel":
         n = wl.N * wl.K if occurrence == 0 else wl.M * wl.K
         return "hbm", 2.0 * n, 0                    # reads and writes an index matrix

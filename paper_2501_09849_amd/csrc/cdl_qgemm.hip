@@ -788,6 +788,41 @@ void limb_reduce_kernel(const double *__restrict__ partial, int splits, int64_t 
     }
 }
 
+// dL/dQ(a) for a very short contraction (N <= 32: the first stages of a small CNN have 16 or 32 output
+// channels): d_a_hat[m][k] = delta_b * sum_n g[m][n] * b_idx[n][k].  One K-tile of the limb kernel would be
+// at least three quarters padding there; here a block takes 64 rows of g (kept in LDS as doubles), a thread
+// one output column, whose N index values it keeps in registers as doubles, and every output is a chain of N
+// fused multiply-adds in double: products of a float and an int8 are exact in double and N <= 32 additions
+// round at 2^-53 relative.  Bound by the fp32 output it writes.
+constexpr int kDirectMaxN = 32;
+constexpr int kDirectRows = 64;
+
+template <int NN>
+__global__ __launch_bounds__(256)
+void da_direct_kernel(const float *__restrict__ g, const int8_t *__restrict__ b_idx, int M, int N, int K,
+                      double delta_b, float *__restrict__ out)
+{
+    __shared__ double gs[kDirectRows][NN];
+    const int row0 = blockIdx.x * kDirectRows;
+    const int k = blockIdx.y * 256 + threadIdx.x;
+    const int rows = min(kDirectRows, M - row0);
+    for (int i = threadIdx.x; i < kDirectRows * NN; i += 256) {
+        const int r = i / NN, n = i - r * NN;
+        gs[r][n] = (r < rows && n < N) ? (double)g[(int64_t)(row0 + r) * N + n] : 0.0;
+    }
+    double b[NN];
+#pragma unroll
+    for (int n = 0; n < NN; ++n) b[n] = (n < N && k < K) ? (double)b_idx[(int64_t)n * K + k] : 0.0;
+    __syncthreads();
+    if (k >= K) return;
+    for (int r = 0; r < rows; ++r) {
+        double acc = 0.0;
+#pragma unroll
+        for (int n = 0; n < NN; ++n) acc = fma(gs[r][n], b[n], acc);
+        out[(int64_t)(row0 + r) * K + k] = (float)(acc * delta_b);
+    }
+}
+
 // ---- helpers -------------------------------------------------------------------------------
 
 // dst[r][0..ldd) = src[r][0..cols) followed by zeros.
@@ -1164,6 +1199,14 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
     if (d_b_hat && ((int64_t)N * K > 0) && M == 0)
         CDL_LAUNCH("zero_f32_kernel", stream, zero_f32_kernel, dim3(blocks_for((int64_t)N * K, 256, 4096)), dim3(256), 0, d_b_hat, (int64_t)N * K);
     if ((int64_t)M * N * K == 0) return check_launch();
+
+    if (d_a_hat && N <= kDirectMaxN) {
+        const dim3 grid((M + kDirectRows - 1) / kDirectRows, (K + 255) / 256);
+        if (N <= 16) CDL_LAUNCH("da_direct_kernel", stream, da_direct_kernel<16>, grid, dim3(256), 0, gr, b_idx, M, N, K, (double)delta_b, d_a_hat);
+        else CDL_LAUNCH("da_direct_kernel", stream, da_direct_kernel<32>, grid, dim3(256), 0, gr, b_idx, M, N, K, (double)delta_b, d_a_hat);
+        d_a_hat = nullptr;           // done; what follows is for the other product only
+        if (!d_b_hat) return check_launch();
+    }
 
     const BwdLayout L = bwd_layout(M, N, K);
     char *base = reinterpret_cast<char *>(ws);
