@@ -273,11 +273,21 @@ def _huffman_total_heapq(counts):
 
 
 def test_huffman_textbook_example(oracle):
-    # the classic six-symbol example: frequencies 5, 9, 12, 13, 16, 45 -> code lengths 4, 4, 3, 3, 3, 1 = 224 bits
-    freq = [5, 9, 12, 13, 16, 45]
+    # the classic six-symbol example (tests/golden/huffman_six_symbols.txt): frequencies 45, 13, 12, 16, 9, 5 have
+    # optimal code lengths 1, 3, 3, 3, 4, 4, i.e. 224 bits
+    import os
+    freq, lengths, want_total = [], [], None
+    for line in open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "huffman_six_symbols.txt")):
+        f = line.split("#")[0].split()
+        if len(f) == 2 and f[0] == "total_bits":
+            want_total = int(f[1])
+        elif len(f) == 2:
+            freq.append(int(f[0]))
+            lengths.append(int(f[1]))
+    assert want_total == sum(a * b for a, b in zip(freq, lengths)) == 224
     idx = np.concatenate([np.full(f, k - 3, np.int8) for k, f in enumerate(freq)])
     counts, total, avg = oracle.huffman_bits(idx, -3, 6)
-    assert list(counts) == freq and total == 224 and avg == pytest.approx(2.24)
+    assert list(counts) == freq and total == want_total and avg == pytest.approx(want_total / sum(freq))
 
 
 def test_huffman_bounds_and_special_cases(oracle):

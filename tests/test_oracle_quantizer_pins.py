@@ -173,7 +173,19 @@ def test_proposition_1_distortion_decomposition(oracle, lo, L):
 
 # ---------------------------------------------------------------- Lemma 1 and d/dalpha by finite differences
 
-FIG1 = [(-4, 8, 0.1, a) for a in (100.0, 300.0, 500.0, 700.0)]   # the parameter set of Figs. 1-2: b=3, q=0.1
+def _paper_parameter_sets(prefix):
+    """(lo, n_levels, delta, alpha) of the rows of tests/golden/paper_parameters.txt whose name starts with prefix."""
+    import os
+    rows = []
+    for line in open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_parameters.txt")):
+        f = line.split("#")[0].split()
+        if len(f) == 5 and f[0].startswith(prefix):
+            rows.append((int(f[1]), int(f[2]), float(f[3]), float(f[4])))
+    return rows
+
+
+FIG1 = _paper_parameter_sets("fig1_")   # the parameter set of Figs. 1-2: b=3, q=0.1, four sharpness values
+assert len(FIG1) == 4
 OTHER = [(-7, 15, 0.02, 1e4), (0, 16, 0.25, 64.0), (0, 16, 0.25, 500.0), (-15, 31, 0.004, 2.5e5),
          (-15, 31, 0.004, 500.0), (-127, 255, 0.15, 4 / 0.15 ** 2), (-8, 16, 0.3, 0.7)]
 
