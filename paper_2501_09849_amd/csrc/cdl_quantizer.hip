@@ -34,11 +34,13 @@ namespace {
 
 constexpr int kPad = 4;   // spare histogram bins on each side, so that band offsets never leave the array
 
-// Fixed-point histogram: a block makes at most kMaxHistTrips trips of its loop, each lane adds 4
-// entries per trip, and 64 >> RS lanes share one copy of a bin: at most 2^(6-RS) * 4 * 16 adds of
-// at most 2^s each reach one cell, so s = 31 - (12 - RS) keeps every cell below 2^31.
+// Fixed-point histogram: a block of kMargThreads threads (8 waves) makes at most kMaxHistTrips trips of
+// its loop, each lane adds 4 entries per trip, and the 2 * 8 lanes with the same lane % 32 share one
+// copy of a bin: at most 16 * 4 * 16 = 2^10 adds of at most 2^s each reach one cell, so s = 21 keeps
+// every cell at or below 2^31.
 constexpr int kMaxHistTrips = 16;
-constexpr int hist_scale_bits(int rs) { return 19 + rs; }
+constexpr int kMargThreads = 512;   // threads of a block that builds a histogram
+constexpr int kHistScaleBits = 21;
 
 struct QConst {
     float delta;
@@ -214,21 +216,23 @@ __device__ __forceinline__ void generic_sums(float th, const QConst &k, GenericS
 // MARG: the CPMF of every entry is added into a histogram in LDS, in fixed point: a probability
 // p is added as the integer floor(p * 2^s + 1/2).  (LDS integer atomics run at ~10 lane updates
 // per clock per CU on this chip, fp32 LDS atomics at a thirtieth of that; integer sums are also
-// independent of the order of the adds, so the result is reproducible.)  Each wave owns
-// R = 2^RS interleaved copies of the histogram (bin-major, copy-minor; lane l uses copy l mod R),
-// so lanes of one instruction collide only when they share both copy and bin.  s comes from
-// hist_scale_bits(): with at most kMaxHistTrips trips of the loop a cell never exceeds 2^31.
+// independent of the order of the adds, so the result is reproducible.)  The block keeps 32 copies of
+// the histogram, bin-major and copy-minor, and lane l uses copy l mod 32: the copy is the LDS bank, so
+// the lanes of one instruction never meet in a bank except lane l with lane l + 32 (measured against
+// 4 or 16 copies per wave, where different bins fall into the same bank: -8 % on the whole forward
+// kernel at 255 levels, -22 % on the pass that only builds the histogram).  s comes from
+// kHistScaleBits: with at most kMaxHistTrips trips of the loop a cell never exceeds 2^31.
 // kPad spare bins on each side take the zero weights of levels that do not exist.  At the end
-// the block adds copies and waves into one 64-bit partial histogram row of `partial`; block 0
+// the block adds the copies into one 64-bit partial histogram row of `partial`; block 0
 // also clears the ticket that the finalize kernel uses.
 // ------------------------------------------------------------------------------------------
 // Quantizes four entries: soft values, level indices, and (MARG) their CPMFs into the histogram.
-template <int W, bool IDX, bool MARG, int RS>
+template <int W, bool IDX, bool MARG>
 __device__ __forceinline__ void forward4(const float (&th)[4], int cnt, const QConst &k, unsigned int *my_hist,
                                          float (&sv)[4], int (&ci)[4])
 {
-    constexpr int R = 1 << RS;
-    constexpr float kScale = (float)(1u << hist_scale_bits(RS));
+    constexpr int R = 32;
+    constexpr float kScale = (float)(1u << kHistScaleBits);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         if (W > 0) {
@@ -263,31 +267,32 @@ __device__ __forceinline__ void forward4(const float (&th)[4], int cnt, const QC
     }
 }
 
-template <int W, bool IDX, bool SOFT, bool MARG, int RS>
-__global__ __launch_bounds__(kQuantThreads)
+template <int W, bool IDX, bool SOFT, bool MARG>
+__global__ __launch_bounds__(MARG ? kMargThreads : kQuantThreads)
 void quantize_fwd_kernel(const float *__restrict__ theta, int64_t n, QConst k,
                          int8_t *__restrict__ idx, float *__restrict__ soft,
                          unsigned long long *__restrict__ partial /* [gridDim.x][n_levels] */,
                          unsigned int *__restrict__ ticket)
 {
-    extern __shared__ unsigned int lds_hist[];  // [waves][n_levels + 2 kPad][R] when MARG
-    constexpr int R = 1 << RS;
+    extern __shared__ unsigned int lds_hist[];  // [n_levels + 2 kPad][32] when MARG
+    constexpr int R = 32;
+    constexpr int T = MARG ? kMargThreads : kQuantThreads;
     const int bins = k.n_levels + 2 * kPad;
-    unsigned int *my_hist = lds_hist + (threadIdx.x >> 6) * bins * R + (threadIdx.x & (R - 1));
+    unsigned int *my_hist = lds_hist + (threadIdx.x & (R - 1));
     if (MARG) {
-        for (int i = threadIdx.x; i < (kQuantThreads / 64) * bins * R; i += kQuantThreads) lds_hist[i] = 0u;
+        for (int i = threadIdx.x; i < bins * R; i += T) lds_hist[i] = 0u;
         if (blockIdx.x == 0 && threadIdx.x == 0) *ticket = 0u;
         __syncthreads();
     }
 
     const int64_t n4 = n >> 2;
-    const int64_t stride = (int64_t)gridDim.x * kQuantThreads;
+    const int64_t stride = (int64_t)gridDim.x * T;
     float sv[4];
     int ci[4];
-    for (int64_t v = (int64_t)blockIdx.x * kQuantThreads + threadIdx.x; v < n4; v += stride) {
+    for (int64_t v = (int64_t)blockIdx.x * T + threadIdx.x; v < n4; v += stride) {
         const float4 t = load_stream4(theta + 4 * v, k.stream);
         const float th[4] = {t.x, t.y, t.z, t.w};
-        forward4<W, IDX, MARG, RS>(th, 4, k, my_hist, sv, ci);
+        forward4<W, IDX, MARG>(th, 4, k, my_hist, sv, ci);
         if (SOFT) store_stream4(soft + 4 * v, sv[0], sv[1], sv[2], sv[3], k.stream);
         if (IDX) {
             const uint32_t packed = (uint32_t)(ci[0] & 0xff) | ((uint32_t)(ci[1] & 0xff) << 8) |
@@ -300,7 +305,7 @@ void quantize_fwd_kernel(const float *__restrict__ theta, int64_t n, QConst k,
     if (cnt > 0 && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
         float th[4];
         for (int e = 0; e < 4; ++e) th[e] = (e < cnt) ? theta[(n4 << 2) + e] : 0.0f;
-        forward4<W, IDX, MARG, RS>(th, cnt, k, my_hist, sv, ci);
+        forward4<W, IDX, MARG>(th, cnt, k, my_hist, sv, ci);
         for (int e = 0; e < cnt; ++e) {
             if (SOFT) soft[(n4 << 2) + e] = sv[e];
             if (IDX) idx[(n4 << 2) + e] = (int8_t)ci[e];
@@ -309,13 +314,11 @@ void quantize_fwd_kernel(const float *__restrict__ theta, int64_t n, QConst k,
 
     if (MARG) {
         __syncthreads();
-        for (int i = threadIdx.x; i < k.n_levels; i += kQuantThreads) {
+        for (int i = threadIdx.x; i < k.n_levels; i += T) {
             unsigned long long s = 0ull;
-            for (int w = 0; w < kQuantThreads / 64; ++w) {
-                const unsigned int *row = lds_hist + (w * bins + i + kPad) * R;
+            const unsigned int *row = lds_hist + (i + kPad) * R;
 #pragma unroll
-                for (int r = 0; r < R; ++r) s += row[(r + i) & (R - 1)];   // rotated start: no bank conflicts
-            }
+            for (int r = 0; r < R; ++r) s += row[(r + i) & (R - 1)];   // rotated start: no bank conflicts
             partial[(size_t)blockIdx.x * k.n_levels + i] = s;
         }
     }
@@ -712,8 +715,8 @@ int grid_for(int64_t n)
 int64_t hist_grid_for(int64_t n)
 {
     const int64_t vecs = (n >> 2) + 1;
-    const int64_t need = (vecs + (int64_t)kQuantThreads * kMaxHistTrips - 1) / ((int64_t)kQuantThreads * kMaxHistTrips);
-    const int64_t g = grid_for(n);
+    const int64_t need = (vecs + (int64_t)kMargThreads * kMaxHistTrips - 1) / ((int64_t)kMargThreads * kMaxHistTrips);
+    const int64_t g = (grid_for(n) + 1) / 2;
     return need > g ? need : g;
 }
 
@@ -725,18 +728,15 @@ size_t hist_bytes(int64_t n, int32_t n_levels)
 size_t aux_bytes() { return align_up((size_t)kFinChunks * 256 * sizeof(unsigned long long) + sizeof(unsigned int), 256); }
 size_t scalar_bytes() { return align_up((size_t)kMaxQuantBlocks * 2 * sizeof(double), 256); }
 
-// histogram copies per wave: 16 for small level sets (heavy collisions), 4 for wide ones
-int copies_shift(int n_levels) { return n_levels <= 64 ? 4 : 2; }
-
-template <int W, int RS>
+template <int W>
 void launch_fwd_w(bool want_idx, bool want_soft, bool want_marg, int grid, hipStream_t s,
                   const float *theta, int64_t n, const QConst &k, int8_t *idx, float *soft,
                   unsigned long long *partial, unsigned int *ticket)
 {
-    const size_t lds = (size_t)(kQuantThreads / 64) * (size_t)(k.n_levels + 2 * kPad) * sizeof(float) << RS;
+    const size_t lds = (size_t)(k.n_levels + 2 * kPad) * sizeof(float) * 32;
 #define CDL_FWD(I, S, M)                                                                                  \
     CDL_LAUNCH((I) ? "quantize_fwd_kernel" : "quantize_fwd_kernel(marginal only)", s,                     \
-               (quantize_fwd_kernel<W, I, S, M, (M) ? RS : 0>), dim3(grid), dim3(kQuantThreads), (M) ? lds : 0, \
+               (quantize_fwd_kernel<W, I, S, M>), dim3(grid), dim3((M) ? kMargThreads : kQuantThreads), (M) ? lds : 0, \
                theta, n, k, idx, soft, partial, ticket)
     if (want_idx && want_soft && want_marg) CDL_FWD(true, true, true);
     else if (want_idx && want_soft) CDL_FWD(true, true, false);
@@ -747,12 +747,11 @@ void launch_fwd_w(bool want_idx, bool want_soft, bool want_marg, int grid, hipSt
 }
 
 template <int W>
-void launch_fwd(int rs, bool want_idx, bool want_soft, bool want_marg, int grid, hipStream_t s,
+void launch_fwd(bool want_idx, bool want_soft, bool want_marg, int grid, hipStream_t s,
                 const float *theta, int64_t n, const QConst &k, int8_t *idx, float *soft,
                 unsigned long long *partial, unsigned int *ticket)
 {
-    if (rs == 4) launch_fwd_w<W, 4>(want_idx, want_soft, want_marg, grid, s, theta, n, k, idx, soft, partial, ticket);
-    else launch_fwd_w<W, 2>(want_idx, want_soft, want_marg, grid, s, theta, n, k, idx, soft, partial, ticket);
+    launch_fwd_w<W>(want_idx, want_soft, want_marg, grid, s, theta, n, k, idx, soft, partial, ticket);
 }
 
 template <int W>
@@ -811,13 +810,12 @@ int launch_quantize_fwd(const float *theta, int64_t n, const cdl_qparams &p,
         ? reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(ws) + hist_bytes(n, p.n_levels)) : nullptr;
     unsigned int *ticket = want_marg ? reinterpret_cast<unsigned int *>(second + kFinChunks * 256) : nullptr;
     const bool want_idx = idx != nullptr, want_soft = soft != nullptr;
-    const int rs = copies_shift(p.n_levels);
     switch (band_template(k)) {
-        case 1: launch_fwd<1>(rs, want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
-        case 2: launch_fwd<2>(rs, want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
-        case 3: launch_fwd<3>(rs, want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
-        case 4: launch_fwd<4>(rs, want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
-        default: launch_fwd<0>(rs, want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
+        case 1: launch_fwd<1>(want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
+        case 2: launch_fwd<2>(want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
+        case 3: launch_fwd<3>(want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
+        case 4: launch_fwd<4>(want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
+        default: launch_fwd<0>(want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
     }
     int rc = check_launch();
     if (rc != CDL_OK) return rc;
@@ -825,7 +823,7 @@ int launch_quantize_fwd(const float *theta, int64_t n, const cdl_qparams &p,
         const int level_blocks = (p.n_levels + 7) / 8;
         const int chunks = level_blocks >= 64 ? 1 : (64 / level_blocks < kFinChunks ? 64 / level_blocks : kFinChunks);
         CDL_LAUNCH("marginal_finalize_kernel", stream, marginal_finalize_kernel, dim3(level_blocks, chunks), dim3(256), 0,
-                   partial, grid, p.n_levels, 1.0 / ((double)n * (double)(1u << hist_scale_bits(rs))), marg, entropy_bits,
+                   partial, grid, p.n_levels, 1.0 / ((double)n * (double)(1u << kHistScaleBits)), marg, entropy_bits,
                    second, ticket);
         rc = check_launch();
     }
