@@ -71,6 +71,31 @@ def test_quantize_bwd_matches_oracle(oracle, lo, L, kappa):
             name, got, want, abs(got - want), tol, mass)
 
 
+@pytest.mark.parametrize("lo,L", [(0, 2), (-1, 3), (-128, 256), (100, 28), (-128, 9)])
+@pytest.mark.parametrize("kappa", (0.05, 4.0, 1e4))
+def test_smallest_widest_and_off_centre_level_sets(oracle, lo, L, kappa):
+    """Two levels, three levels, all 256 int8 levels, and sets that sit at either end of the int8 range."""
+    n = 12007 if L < 256 or kappa >= 1.0 else 4003
+    spec = _spec(lo, L, 0.0731, kappa)
+    theta = _theta(lo, L, spec.delta, n, seed=abs(lo) * 7 + L)
+    g = np.random.default_rng(8).standard_normal(n).astype(np.float32)
+    q = gu.Quantizer(spec)
+    idx, soft, marg, H = q.fwd(gu.dev(theta))
+    r_idx, r_soft, r_gap = oracle.quantize_fwd(theta, *q.args)
+    r_marg, r_H = oracle.marginal_entropy(theta, *q.args)
+    gu.assert_indices(idx, r_idx, r_gap, "idx")
+    gu.assert_close(soft, r_soft, "soft")
+    gu.assert_close(marg, r_marg, "marg")
+    gu.assert_close([H], [r_H], "entropy")
+    dth, dd, da = q.bwd(gu.dev(theta), gu.dev(g))
+    ref = oracle.quantize_bwd(theta, g, *q.args)
+    gu.assert_close(dth, ref["dtheta"], "dtheta")
+    for name, got, want, mass in (("d_delta", dd, ref["d_delta"], ref["abs_sum_delta"]),
+                                  ("d_alpha", da, ref["d_alpha"], ref["abs_sum_alpha"])):
+        tol = max(gu.ABS_TOL + gu.REL_TOL * abs(want), 2e-7 * mass)
+        assert abs(got - want) <= tol, (name, got, want, tol)
+
+
 @pytest.mark.parametrize("lo,L,kappa", [(-7, 15, 4.0), (0, 16, 31.25), (-15, 31, 0.008), (-127, 255, 4.0)])
 def test_marginal_entropy_entry_point_matches_oracle(oracle, lo, L, kappa):
     spec = _spec(lo, L, 0.02, kappa)
