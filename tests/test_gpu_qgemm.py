@@ -40,6 +40,19 @@ def test_qgemm_fwd_large_tiles_path_matches_oracle(oracle):
     gu.assert_close(y, r_y, "y")
 
 
+@pytest.mark.parametrize("K", [128, 384])
+def test_qgemm_fwd_more_tiles_than_compute_units(oracle, K):
+    """306 tiles of 256 x 256 for the direct-load kernel, more than there are compute units, one and three
+    K-tiles per tile; ragged edges in both output dimensions."""
+    M, N = 4400, 4200
+    a = cdl_inputs.draw_indices((M, K), -127, 127, seed=31 + K)
+    b = cdl_inputs.draw_indices((N, K), -127, 127, seed=32 + K)
+    acc, y = gu.qgemm_fwd(a, b, 0.15092, 0.0028209)
+    r_acc, r_y = oracle.qgemm_fwd(a, b, 0.15092, 0.0028209)
+    assert np.array_equal(acc, r_acc), "int32 accumulators differ at %d places" % int((acc != r_acc).sum())
+    gu.assert_close(y, r_y, "y")
+
+
 def test_qgemm_fwd_extreme_indices_do_not_overflow(oracle):
     M, N, K = 64, 64, 4096
     a = np.full((M, K), -128, np.int8)
