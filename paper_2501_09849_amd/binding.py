@@ -54,6 +54,13 @@ def load():
         if not os.path.exists(_LIB_PATH):
             raise RuntimeError("libcdl.so is not built: run `python -m paper_2501_09849_amd.build` "
                                "(or __graft_entry__.build()) first; there is no fallback path")
+        # PyTorch-ROCm carries its own copy of the HIP runtime and loads it by path.  If libcdl.so came first,
+        # the system's copy would be in the process as well, the two would not share a device context, and
+        # every launch on torch's memory would fail with hipErrorNoDevice: let torch's be the first one.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(_LIB_PATH)
         vp, i64, i32, f32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
         qp = ctypes.POINTER(QParams)

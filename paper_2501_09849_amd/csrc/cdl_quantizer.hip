@@ -331,13 +331,14 @@ void quantize_fwd_kernel(const float *__restrict__ theta, int64_t n, QConst k,
 // second[chunk][level]; the block that finishes last (ticket) adds the chunk sums per level,
 // writes the marginal PMF and sums the entropy terms in level order.
 constexpr int kFinChunks = 16;
+constexpr int kFinThreads = 256, kFinGroups = kFinThreads / 8;
 
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(kFinThreads)
 void marginal_finalize_kernel(const unsigned long long *__restrict__ partial, int nblocks, int n_levels, double inv_n,
                               float *__restrict__ marg, float *__restrict__ entropy_bits,
                               unsigned long long *second /* [kFinChunks][256] */, unsigned int *ticket)
 {
-    __shared__ unsigned long long red[32][8];
+    __shared__ unsigned long long red[kFinGroups][8];
     __shared__ double hsum[256];
     __shared__ bool is_last;
     const int b8 = threadIdx.x & 7, grp = threadIdx.x >> 3;
@@ -347,14 +348,14 @@ void marginal_finalize_kernel(const unsigned long long *__restrict__ partial, in
     const int r0 = blockIdx.y * rows_per, r1 = min(nblocks, r0 + rows_per);
     unsigned long long s = 0ull;
     if (level < n_levels) {
-#pragma unroll 4
-        for (int row = r0 + grp; row < r1; row += 32) s += partial[(size_t)row * n_levels + level];
+#pragma unroll 8
+        for (int row = r0 + grp; row < r1; row += kFinGroups) s += partial[(size_t)row * n_levels + level];
     }
     red[grp][b8] = s;
     __syncthreads();
     if (threadIdx.x < 8 && level < n_levels) {
         unsigned long long tot = 0ull;
-        for (int q = 0; q < 32; ++q) tot += red[q][threadIdx.x];
+        for (int q = 0; q < kFinGroups; ++q) tot += red[q][threadIdx.x];
         __hip_atomic_store(&second[blockIdx.y * 256 + level], tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __threadfence();
@@ -375,7 +376,7 @@ void marginal_finalize_kernel(const unsigned long long *__restrict__ partial, in
         if (marg) marg[threadIdx.x] = (float)m;
         h = m > 0.0 ? -m * log2(m) : 0.0;
     }
-    hsum[threadIdx.x] = h;
+    if (threadIdx.x < 256) hsum[threadIdx.x] = h;
     __syncthreads();
     if (threadIdx.x == 0 && entropy_bits) {
         double H = 0.0;
@@ -711,13 +712,20 @@ int grid_for(int64_t n)
     return (int)blocks;
 }
 
-// Grid of the histogram kernels: as above, but never more than kMaxHistTrips trips per block.
+// Grid of the histogram kernels: as above, but never more than kMaxHistTrips trips per block, and - once
+// the chip is full - a whole number of rounds: 256 CUs hold four 512-thread blocks each (2048 threads; the
+// histogram of 256 levels takes 33 KB of the 160 KB of LDS), and a last round that fills half of them
+// cost 10-18 % on 50 M entries.
+constexpr int64_t kHistResident = 256 * 4;
+
 int64_t hist_grid_for(int64_t n)
 {
     const int64_t vecs = (n >> 2) + 1;
     const int64_t need = (vecs + (int64_t)kMargThreads * kMaxHistTrips - 1) / ((int64_t)kMargThreads * kMaxHistTrips);
-    const int64_t g = (grid_for(n) + 1) / 2;
-    return need > g ? need : g;
+    int64_t g = (grid_for(n) + 1) / 2;
+    if (need > g) g = need;
+    if (g > kHistResident) g = (g + kHistResident - 1) / kHistResident * kHistResident;
+    return g;
 }
 
 // workspace layout: [per-block histograms][entropy terms + ticket][per-block scalar partials]
@@ -822,7 +830,7 @@ int launch_quantize_fwd(const float *theta, int64_t n, const cdl_qparams &p,
     if (want_marg) {
         const int level_blocks = (p.n_levels + 7) / 8;
         const int chunks = level_blocks >= 64 ? 1 : (64 / level_blocks < kFinChunks ? 64 / level_blocks : kFinChunks);
-        CDL_LAUNCH("marginal_finalize_kernel", stream, marginal_finalize_kernel, dim3(level_blocks, chunks), dim3(256), 0,
+        CDL_LAUNCH("marginal_finalize_kernel", stream, marginal_finalize_kernel, dim3(level_blocks, chunks), dim3(kFinThreads), 0,
                    partial, grid, p.n_levels, 1.0 / ((double)n * (double)(1u << kHistScaleBits)), marg, entropy_bits,
                    second, ticket);
         rc = check_launch();
