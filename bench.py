@@ -497,6 +497,12 @@ def main():
     if gf:
         out["index_gemm_fwd_TOPS"] = gf[0]["algorithmic_TOPS"]
         out["index_gemm_fwd_frac_of_int8_peak"] = gf[0]["frac"]
+        # the forward product writes M*N fp32 and reads both index matrices once: what HBM alone allows
+        # (8 TB/s), and the smaller of the two ceilings as the launch's roofline
+        t_hbm = (4.0 * wl.M * wl.N + 1.0 * (wl.M + wl.N) * wl.K) / (HBM_PEAK_GBS * 1e9)
+        t_mfma = 2.0 * wl.M * wl.N * wl.K / (INT8_PEAK_TOPS * 1e12)
+        out["index_gemm_fwd_frac_of_roofline"] = max(t_hbm, t_mfma) / (gf[0]["avg_us"] * 1e-6)
+        out["index_gemm_fwd_roofline_bound"] = "hbm" if t_hbm > t_mfma else "mfma"
     if not args.no_extra:
         out["step_as_hip_graph"] = graph_replay(st, args.steps)
     del st
