@@ -622,20 +622,40 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
         const int row0 = (tile_r0 + r) * kLRows, col0 = (c_begin + c) * NB;
         const int erow = row0 + 4 * (elane >> 5), ecol = col0 + wave * TN * 32 + (elane & 31);
         const bool full = row0 + kLRows <= a.rows && col0 + NB <= a.cols;
+        // register rr of an accumulator is row 8 (rr / 4) + rr % 4 (+ 4 for the upper half of the lanes)
+        auto combined = [&](int j, int rr) {
+            double run = (double)acc[L - 1][j][rr];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = ecol + j * 32;
+            for (int l = L - 2; l >= 0; --l) run = __builtin_fma(run, 256.0, (double)acc[l][j][rr]);   // run * 256 is exact
+            return run;
+        };
+        // one address per row, the TN column tiles of a wave at fixed distances from it; tiles that do not reach
+        // the edge of the matrix (FULL) store without a test
+        const int64_t first = (int64_t)erow * a.cols + ecol;
+        auto emit = [&](auto full_c, auto *base) {
+            constexpr bool FULL = decltype(full_c)::value;
+            using T = std::remove_pointer_t<decltype(base)>;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = erow + 8 * (r >> 2) + (r & 3);
-                double run = (double)acc[L - 1][j][r];
+            for (int rr = 0; rr < 16; ++rr) {
+                const int dr = 8 * (rr >> 2) + (rr & 3);
+                T *p = base + (int64_t)dr * a.cols;
+                const bool row_ok = FULL || erow + dr < a.rows;
 #pragma unroll
-                for (int l = L - 2; l >= 0; --l) run = run * 256.0 + (double)acc[l][j][r];
-                if (full || (row < a.rows && col < a.cols)) {
-                    if (a.splits == 1) a.out[(int64_t)row * a.cols + col] = (float)(run * out_scale);
-                    else a.partial[((int64_t)split * a.rows + row) * a.cols + col] = run;
+                for (int j = 0; j < TN; ++j) {
+                    if (FULL || (row_ok && ecol + j * 32 < a.cols)) {
+                        if (std::is_same<T, float>::value) p[j * 32] = (T)(combined(j, rr) * out_scale);
+                        else p[j * 32] = (T)combined(j, rr);
+                    }
                 }
             }
+        };
+        if (a.splits == 1) {
+            if (full) emit(std::true_type{}, a.out + first);
+            else emit(std::false_type{}, a.out + first);
+        } else {
+            double *base = a.partial + (int64_t)split * a.rows * a.cols + first;
+            if (full) emit(std::true_type{}, base);
+            else emit(std::false_type{}, base);
         }
     };
 
