@@ -612,6 +612,11 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
     }
     constexpr int kDs2 = (L + TN + 4 * L + NM - 1) / NM;    // k-step 2: fragment reads + digit writes
     constexpr int kVm2 = (GL + NM - 1) / NM;
+    // VALU instructions per MFMA: enough slots for the k-step's conversion work, spread as evenly as the
+    // count allows (12 MFMAs and about 30 VALU instructions with up to four limbs: three each measured 2-3 %
+    // faster than five, two slower; 15 MFMAs and the longer conversion of five limbs: five, four in the
+    // k-steps that convert nothing)
+    constexpr int kVaConv = L <= 4 ? 3 : 5, kVaRest = L <= 4 ? 3 : 4;
 
     // ---- recombination of the limbs of row tile u: the integers are exact, the Horner steps round at
     // 2^-53 relative.  (The lane index passes through an empty asm so that the output addresses are formed
@@ -692,7 +697,7 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
         } else {
             mfma_all(0);
         }
-        CDL_INTERLEAVE(1, 1, 5)
+        CDL_INTERLEAVE(1, 1, kVaConv)
         __builtin_amdgcn_sched_barrier(0);
     };
     // one step (its parity P picks the LDS stage and the register set of G) under the schedule above
@@ -705,14 +710,14 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
         read_frags(0, P, 2);
         convert_half(gbuf[P ^ 1], 1);
         mfma_all(1);
-        CDL_INTERLEAVE(1, 0, 5)
+        CDL_INTERLEAVE(1, 0, kVaConv)
         __builtin_amdgcn_sched_barrier(0);
         // k-step 2
         store_digits(P ^ 1);
         read_frags(1, P, 3);
         load_g(gbuf[P ^ 1], p3.r, p3.kt);
         mfma_all(0);
-        CDL_INTERLEAVE(kDs2, kVm2, 4)
+        CDL_INTERLEAVE(kDs2, kVm2, kVaRest)
         __builtin_amdgcn_sched_barrier(0);
         // B(s+1) has landed (younger loads: G(s+3)); own LDS writes and fragment reads are done
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(GL));
@@ -722,7 +727,7 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
         read_frags(0, P ^ 1, 0);
         issue_b(P, p2.c, p2.kt, 0);
         mfma_all(1);
-        CDL_INTERLEAVE(1, 1, 4)
+        CDL_INTERLEAVE(1, 1, kVaRest)
         __builtin_amdgcn_sched_barrier(0);
         if (RUNS && p0.kt == nk - 1) write_tile(p0.r, p0.c);
         advance(p0);
