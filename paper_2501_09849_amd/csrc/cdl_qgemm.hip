@@ -385,7 +385,8 @@ __device__ __forceinline__ void limbs_of4(const float (&g)[4], float gscale, uin
             const float x = g[e] * gscale;
             const float H = rintf(x * (1.0f / 65536.0f));
             const float r = fmaf(-H, 65536.0f, x);          // exact, |r| <= 32768
-            const int t = (int)rintf(r) + 0x8080;           // in [0x80, 0x10080]
+            // r + 1.5 * 2^23 has unit spacing: its mantissa bits are those of the constant plus rint(r), ties to even
+            const int t = (int)(__float_as_uint(r + 12582912.0f) + (0x8080u - 0x4B400000u));   // rint(r) + 0x8080, in [0x80, 0x10080]
             lo[e] = (uint32_t)t ^ 0x8080u;                  // bytes 0, 1: digits 0, 1
             const int h = (int)H + (t >> 16);               // carry out of the low two digits
             hi[e] = ((uint32_t)h + offh) ^ offh;
