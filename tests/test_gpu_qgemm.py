@@ -195,3 +195,41 @@ def test_workload_1_layer_step_end_to_end(oracle):
     gu.assert_close(dw, rw["dtheta"], "dW")
     gu.assert_close([ddx, ddw], [rx["d_delta"], rw["d_delta"]], "d_delta")
     gu.assert_close([dax, daw], [rx["d_alpha"], rw["d_alpha"]], "d_alpha")
+
+
+def _sweep_shapes():
+    """Forty seeded shapes: sizes either side of what switches a code path (contractions of 32 / 33 for the
+    direct kernel, multiples of 4, 16, 64 and 128 plus one, 32-row and 384-column tile edges, one to five
+    K-tiles), mixed with sizes drawn at random."""
+    rng = np.random.default_rng(20250109)
+    pool_m = [1, 31, 32, 33, 63, 65, 127, 129, 255, 257, 383, 385, 700]
+    pool_n = [1, 15, 16, 17, 31, 32, 33, 64, 127, 128, 129, 255, 257, 385, 513]
+    pool_k = [1, 3, 4, 15, 16, 17, 63, 64, 65, 127, 128, 129, 383, 384, 385, 640]
+    shapes = []
+    for i in range(40):
+        if i % 2 == 0:
+            shapes.append((int(rng.choice(pool_m)), int(rng.choice(pool_n)), int(rng.choice(pool_k))))
+        else:
+            shapes.append((int(rng.integers(1, 600)), int(rng.integers(1, 600)), int(rng.integers(1, 600))))
+    return shapes
+
+
+@pytest.mark.parametrize("M,N,K", _sweep_shapes())
+def test_qgemm_all_three_products_on_seeded_random_shapes(oracle, M, N, K):
+    """Every product of one layer on the same operands; the scale of the gradient varies over twelve orders of
+    magnitude from case to case (the limb count and the scale are chosen on the device from max|g|)."""
+    rng = np.random.default_rng(M * 1000003 + N * 1009 + K)
+    lo_a, hi_a = (0, 15) if (M + K) % 3 else (-128, 127)
+    lo_b, hi_b = (-7, 7) if (N + K) % 2 else (-128, 127)
+    a = cdl_inputs.draw_indices((M, K), lo_a, hi_a, seed=M + 11 * K)
+    b = cdl_inputs.draw_indices((N, K), lo_b, hi_b, seed=N + 13 * K)
+    g = (rng.standard_normal((M, N)) * 10.0 ** int(rng.integers(-6, 7))).astype(np.float32)
+    da, db = float(np.float32(0.56419)), float(np.float32(0.016623))
+    acc, y = gu.qgemm_fwd(a, b, da, db)
+    r_acc, r_y = oracle.qgemm_fwd(a, b, da, db)
+    assert np.array_equal(acc, r_acc), "int32 accumulators differ at %d places" % int((acc != r_acc).sum())
+    gu.assert_close(y, r_y, "y")
+    d_a, d_b = gu.qgemm_bwd(g, a, b, da, db)
+    r_a, r_b = oracle.qgemm_bwd(g, a, b, da, db)
+    gu.assert_close(d_a, r_a, "d_a_hat")
+    gu.assert_close(d_b, r_b, "d_b_hat")
