@@ -282,8 +282,15 @@ void cdl_oracle_marginal_entropy(const float *theta, int64_t n, int lo, int n_le
  *   dtheta[e] = g[e] * dQd/dtheta                    (eq. partialX3 / partialW3)
  *   d_delta   = sum_e g[e] * dQd/dq                  (eq. Jgradqw / Jgradqx)
  *   d_alpha   = sum_e g[e] * dQd/dalpha              (eq. Jgradq_alpha_w / Jgrad_alpha_q)
- * Also returns sum_e |term| for the two scalar sums so a caller can judge a
- * difference against the size of what was added up.
+ * Also returns, for the two scalar sums, the size of what has to be added up:
+ * sum_e |g[e]| times the magnitudes of the pieces of each partial taken about
+ * the mean,
+ *   dQd/dq     = (E + 2 alpha (theta - 2 E) Var - 2 alpha C3) / q     (eq. partialQ with Skew_u = C3 + 2 E Var)
+ *   dQd/dalpha = 2 (theta - E) Var - C3                               (C3: third central moment)
+ * so that a caller can judge a difference against it.  In the soft regime Q_d
+ * tends to theta, which does not depend on q: the pieces of dQd/dq, each of
+ * the size of E/q, cancel almost completely, and an evaluation in single
+ * precision is as good as the pieces are large, not as the result is.
  * ---------------------------------------------------------------------- */
 void cdl_oracle_quantize_bwd_k(const float *theta, const float *g, int64_t n, int lo, int n_levels,
                                float delta_f, float alpha_f, int top_k,
@@ -305,8 +312,11 @@ void cdl_oracle_quantize_bwd_k(const float *theta, const float *g, int64_t n, in
             double d_q = (m.mean + 2.0 * alpha * th * m.var - 2.0 * alpha * m.skew_u) / delta;
             double d_al = -m.cov_x_d2;
             if (dtheta) dtheta[e] = ge * d_th;
-            sd += ge * d_q;  ad += fabs(ge * d_q);
-            sa += ge * d_al; aa += fabs(ge * d_al);
+            double c3 = m.skew_u - 2.0 * m.mean * m.var;
+            sd += ge * d_q;
+            ad += fabs(ge) * (fabs(m.mean) + 2.0 * alpha * fabs(th - 2.0 * m.mean) * m.var + 2.0 * alpha * fabs(c3)) / delta;
+            sa += ge * d_al;
+            aa += fabs(ge) * (2.0 * fabs(th - m.mean) * m.var + fabs(c3));
         }
         free(P);
     }

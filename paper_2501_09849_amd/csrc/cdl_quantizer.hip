@@ -56,6 +56,7 @@ struct QConst {
     int wgen;         // band half-width of the generic kernel
     int stream;       // 1: the tensor is large, read and write it with non-temporal accesses
     int slide;        // 1: truncated CPMF - the band of 2 wgen + 1 levels slides at the ends of the level set instead of being cut
+    float r_clamp;    // |u / delta| beyond which the W = 2 kernels hold the offset fixed (see band_weights), else infinity
 };
 
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
@@ -100,7 +101,11 @@ __device__ __forceinline__ void band_weights(float th, const QConst &k, Band<W> 
     const float cf = anchor_level<EXACT>(th, k);
     b.cf = cf;
     if (W == 2) {
-        // t = exp(2 alpha delta u), clamped where the far side has long vanished so that t^4 stays finite
+        // t = exp(2 alpha delta u), clamped where the far side has long vanished so that t^4 stays finite.
+        // Beyond the clamp (theta more than 30 / (2 kappa log2 e) steps outside the level set) the near
+        // neighbour keeps a weight of 2^-30 e^-kappa where the true one goes on falling: harmless by itself,
+        // but not once it is multiplied by an offset that goes on growing - the scalar gradients therefore
+        // hold u / delta at k.r_clamp there, which bounds that product by 3e-11.
         const float u = fmaf(-cf, k.delta, th);
         b.u = u;
         const float t = fast_exp2(clampf(k.b2 * u, -30.0f, 30.0f));
@@ -436,7 +441,7 @@ void quantize_bwd_kernel(const float *__restrict__ theta, const float *__restric
             if (SCALARS) {
                 const float m3 = S3 * inv;
                 const float c3 = fmaf(-mu, fmaf(-2.0f * mu, mu, 3.0f * m2), m3);   // m3 - 3 mu m2 + 2 mu^3
-                const float r = u * k.inv_delta;
+                const float r = clampf(u * k.inv_delta, -k.r_clamp, k.r_clamp);
                 const float t_d = (cf + mu) + k.two_kappa * fmaf(r - cf - 2.0f * mu, var, -c3);
                 const float t_a = fmaf(2.0f * (r - mu), var, -c3);
                 sum_d = fmaf(ge[e], t_d, sum_d);
@@ -634,7 +639,7 @@ void entropy_bwd_kernel(const float *__restrict__ theta, const float *__restrict
             const float C1 = fmaf(-mu, b0, B1 * inv), C2 = fmaf(-m2, b0, B2 * inv);
             dv[e] = ADD ? fmaf(dtheta_mul, C1, ge[e]) : dtheta_mul * C1;
             if (SCALARS && e < cnt) {
-                const float r = u * k.inv_delta;
+                const float r = clampf(u * k.inv_delta, -k.r_clamp, k.r_clamp);
                 sum_d += fmaf(r - cf, C1, -C2);
                 sum_a += fmaf(-2.0f * r, C1, C2);
             }
@@ -693,6 +698,7 @@ QConst make_const(const cdl_qparams &p)
     k.wgen = quantizer_window(kappa, p.n_levels);
     k.slide = 0;
     k.stream = 0;
+    k.r_clamp = INFINITY;
     if (p.top_k > 0 && p.top_k < p.n_levels) {
         // Truncated CPMF.  Where the band that kappa asks for is no wider than the top_k nearest levels the
         // truncation drops nothing above fp32 resolution and the ordinary kernels serve; otherwise the generic
@@ -700,6 +706,7 @@ QConst make_const(const cdl_qparams &p)
         const int wt = (p.top_k - 1) / 2;
         if (k.wgen > wt) { k.wgen = wt; k.slide = 1; }
     }
+    if (band_template(k) == 2) k.r_clamp = (float)(30.0 / (2.0 * kappa * 1.4426950408889634));
     return k;
 }
 

@@ -188,3 +188,42 @@ def test_outputs_are_optional():
     b_t = q.bwd(th_d, g_d, scalars=False)
     b_s = q.bwd(th_d, g_d, dtheta=False)
     assert np.array_equal(b_full[0], b_t[0]) and b_full[1] == b_s[1] and b_full[2] == b_s[2]
+
+
+def _sweep_cases():
+    """Thirty seeded parameter sets: level sets anywhere in the int8 range, step sizes over three decades,
+    sharpness either side of every band width the kernels are specialised for, odd tensor lengths."""
+    rng = np.random.default_rng(2501)
+    edges = [1.25, 1.3, 1.35, 1.85, 1.9, 1.95, 3.7, 3.8, 3.9, 10.7, 10.9, 11.1]
+    cases = []
+    for i in range(30):
+        L = int(rng.integers(2, 257))
+        lo = int(rng.integers(-128, 128 - L + 1))
+        delta = float(10.0 ** rng.uniform(-3, 0))
+        kappa = float(edges[i // 2]) if i < 24 else float(10.0 ** rng.uniform(-1.7, 4))
+        n = int(rng.integers(1, 9000))
+        cases.append((lo, L, delta, kappa, n))
+    return cases
+
+
+@pytest.mark.parametrize("lo,L,delta,kappa,n", _sweep_cases())
+def test_forward_and_backward_on_seeded_random_parameters(oracle, lo, L, delta, kappa, n):
+    spec = _spec(lo, L, delta, kappa)
+    n = max(n, 80)   # the input recipe plants 70 special values
+    theta = _theta(lo, L, spec.delta, n, seed=n + L)
+    g = np.random.default_rng(n).standard_normal(n).astype(np.float32)
+    q = gu.Quantizer(spec)
+    idx, soft, marg, H = q.fwd(gu.dev(theta))
+    r_idx, r_soft, r_gap = oracle.quantize_fwd(theta, *q.args)
+    r_marg, r_H = oracle.marginal_entropy(theta, *q.args)
+    gu.assert_indices(idx, r_idx, r_gap, "idx")
+    gu.assert_close(soft, r_soft, "soft")
+    gu.assert_close(marg, r_marg, "marg")
+    gu.assert_close([H], [r_H], "entropy")
+    dth, dd, da = q.bwd(gu.dev(theta), gu.dev(g))
+    ref = oracle.quantize_bwd(theta, g, *q.args)
+    gu.assert_close(dth, ref["dtheta"], "dtheta")
+    for name, got, want, mass in (("d_delta", dd, ref["d_delta"], ref["abs_sum_delta"]),
+                                  ("d_alpha", da, ref["d_alpha"], ref["abs_sum_alpha"])):
+        tol = max(gu.ABS_TOL + gu.REL_TOL * abs(want), 2e-7 * mass)
+        assert abs(got - want) <= tol, (name, got, want, tol)

@@ -278,3 +278,28 @@ def test_tensor_backward_is_elementwise_product_and_sum_of_element_partials(orac
             return F(t, delta, alpha)
         assert out["dtheta"][j] == pytest.approx(_fd(Fj, th64[j], 1e-6 * delta), rel=1e-6, abs=1e-9)
     assert out["abs_sum_delta"] >= abs(out["d_delta"]) and out["abs_sum_alpha"] >= abs(out["d_alpha"])
+
+
+def test_size_of_the_scalar_sums_in_two_closed_form_cases(oracle):
+    """What the oracle reports as the size of the two scalar sums, where it has a closed form.
+    Sharp regime, theta on a level: the CPMF is one-hot, variance and third moment vanish, dQd/dq is the index
+    itself, so the size is sum |g| |index| and that of the alpha sum is 0.  Soft regime, level set far from
+    zero: E is about theta and 2 alpha Var about 1, so the three pieces of dQd/dq are E/q, -E/q and ~0 and the
+    size is about 2 sum |g theta| / q while the sum itself is far smaller."""
+    delta = float(np.float32(0.25))
+    idx = np.array([3, -5, 0, 7], dtype=np.float64)
+    theta = (idx * delta).astype(np.float32)
+    g = np.array([1.5, -2.0, 4.0, 0.5], dtype=np.float32)
+    out = oracle.quantize_bwd(theta, g, -8, 16, delta, float(np.float32(1e4 / delta ** 2)))
+    assert out["abs_sum_delta"] == pytest.approx(float(np.sum(np.abs(g) * np.abs(idx))), rel=1e-12)
+    assert out["abs_sum_alpha"] == pytest.approx(0.0, abs=1e-12)
+    assert out["d_delta"] == pytest.approx(float(np.sum(g * idx)), rel=1e-12)
+
+    rng = np.random.default_rng(4)
+    lo, L = 60, 60                                             # levels 60 .. 119
+    theta = (rng.uniform(80.0, 100.0, 500) * delta).astype(np.float32)
+    g = rng.normal(0, 1, 500).astype(np.float32)
+    out = oracle.quantize_bwd(theta, g, lo, L, delta, float(np.float32(0.3 / delta ** 2)))
+    size = 2.0 * float(np.sum(np.abs(g.astype(np.float64) * theta.astype(np.float64)))) / delta
+    assert out["abs_sum_delta"] == pytest.approx(size, rel=1e-3)
+    assert abs(out["d_delta"]) < 1e-6 * out["abs_sum_delta"]
