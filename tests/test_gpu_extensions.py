@@ -229,3 +229,70 @@ def test_huffman_bits_of_the_quantized_flat_tensor(oracle):
     q = counts[counts > 0] / n
     H = -np.sum(q * np.log2(q))
     assert H <= avg + 1e-6 < H + 1.0
+
+
+def _sweep_cases():
+    """Twenty-four seeded parameter sets for the extensions: level sets anywhere in the int8 range, step sizes
+    over three decades, sharpness either side of the band widths the kernels are specialised for, every
+    truncation width, odd tensor lengths."""
+    rng = np.random.default_rng(985)
+    edges = [1.3, 1.9, 3.8, 10.9]
+    cases = []
+    for i in range(24):
+        L = int(rng.integers(2, 257))
+        lo = int(rng.integers(-128, 128 - L + 1))
+        delta = float(10.0 ** rng.uniform(-3, 0))
+        kappa = float(edges[i % 4] * (0.97 if i % 8 < 4 else 1.03)) if i < 16 else float(10.0 ** rng.uniform(-1.5, 3.5))
+        top_k = int(rng.choice([0, 1, 3, 5, 7, 9]))   # (the widths the boundary accepts)
+        if top_k >= L:
+            top_k = 0
+        cases.append((lo, L, delta, kappa, top_k, int(rng.integers(100, 7000))))
+    return cases
+
+
+@pytest.mark.parametrize("lo,n_levels,delta,kappa,top_k,n", _sweep_cases())
+def test_extensions_on_seeded_random_parameters(oracle, lo, n_levels, delta, kappa, top_k, n):
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    spec = cdl_inputs.QuantSpec(lo, n_levels, float(np.float32(delta)), float(np.float32(kappa / np.float32(delta) ** 2)))
+    a = (spec.lo, spec.n_levels, spec.delta, spec.alpha)
+    rng = np.random.default_rng(n)
+    hi = lo + n_levels - 1
+    th = rng.uniform((lo - 2.5) * spec.delta, (hi + 2.5) * spec.delta, n)
+    th[:4] = [(hi + 40.0) * spec.delta, (lo - 40.0) * spec.delta, (hi + 1e5) * spec.delta, (lo - 1e5) * spec.delta]
+    th = th.astype(np.float32)
+    g = rng.normal(0, 1, n).astype(np.float32)
+    u = rng.random(n, dtype=np.float32)
+    th_d, g_d = gu.dev(th), gu.dev(g)
+    ws = gu.workspace(cdl.quantize_workspace_bytes(n, n_levels))
+    # truncated (or full) forward, marginal, backward
+    idx, soft, dth = gu.empty((n,), torch.int8), gu.empty((n,), torch.float32), gu.empty((n,), torch.float32)
+    marg, sc = gu.empty((n_levels,), torch.float32), gu.empty((6,), torch.float32)
+    _call(cdl.cdl_quantize_fwd, th_d, n, *a, idx, soft, marg, sc[0:1], ws, top_k=top_k)
+    _call(cdl.cdl_quantize_bwd, th_d, g_d, n, *a, dth, sc[1:2], sc[2:3], ws, top_k=top_k)
+    r_idx, r_soft, gap = oracle.quantize_fwd(th, *a, top_k=top_k)
+    gu.assert_indices(idx.cpu().numpy(), r_idx, gap, "idx")
+    gu.assert_close(soft.cpu().numpy(), r_soft, "soft")
+    r_m, r_h = oracle.marginal_entropy(th, *a, top_k=top_k)
+    gu.assert_close(marg.cpu().numpy(), r_m, "marginal")
+    gu.assert_close([float(sc[0])], [r_h], "entropy")
+    rb = oracle.quantize_bwd(th, g, *a, top_k=top_k)
+    gu.assert_close(dth.cpu().numpy(), rb["dtheta"], "dtheta")
+    assert abs(float(sc[1]) - rb["d_delta"]) <= 1e-6 + 1e-5 * abs(rb["d_delta"]) + 2e-7 * rb["abs_sum_delta"], ("d_delta", float(sc[1]), rb["d_delta"])
+    assert abs(float(sc[2]) - rb["d_alpha"]) <= 1e-6 + 1e-5 * abs(rb["d_alpha"]) + 2e-7 * rb["abs_sum_alpha"], ("d_alpha", float(sc[2]), rb["d_alpha"])
+    # the draw
+    didx = gu.empty((n,), torch.int8)
+    _call(cdl.cdl_quantize_draw, th_d, gu.dev(u), n, *a, didx, top_k=top_k)
+    got = didx.cpu().numpy().astype(np.int64)
+    ref, margin = oracle.quantize_draw(th, u, *a, top_k=top_k)
+    diff = got != ref
+    assert not (diff & (margin >= 1e-6)).any(), "draws differ with a margin >= 1e-6"
+    assert np.all(np.abs(got[diff] - ref[diff]) == 1) and diff.sum() <= 20
+    # the gradient of the entropy term
+    scale = n / (2.0 * spec.alpha * spec.delta)
+    eth = gu.empty((n,), torch.float32)
+    _call(cdl.cdl_entropy_bwd, th_d, marg, n, *a, scale, None, eth, sc[3:4], sc[4:5], ws, top_k=top_k)
+    r = oracle.entropy_bwd(th, marg.cpu().numpy().astype(np.float64), *a, scale=scale, top_k=top_k)
+    gu.assert_close(eth.cpu().numpy(), r["dtheta"], "dH/dtheta")
+    assert abs(float(sc[3]) - r["d_delta"]) <= 1e-6 + 1e-5 * abs(r["d_delta"]) + 2e-7 * r["abs_sum_delta"], ("dH/d_delta", float(sc[3]), r["d_delta"])
+    assert abs(float(sc[4]) - r["d_alpha"]) <= 1e-6 + 1e-5 * abs(r["d_alpha"]) + 2e-7 * r["abs_sum_alpha"], ("dH/d_alpha", float(sc[4]), r["d_alpha"])
