@@ -287,7 +287,9 @@ void cdl_oracle_marginal_entropy(const float *theta, int64_t n, int lo, int n_le
  * the mean,
  *   dQd/dq     = (E + 2 alpha (theta - 2 E) Var - 2 alpha C3) / q     (eq. partialQ with Skew_u = C3 + 2 E Var)
  *   dQd/dalpha = 2 (theta - E) Var - C3                               (C3: third central moment)
- * so that a caller can judge a difference against it.  In the soft regime Q_d
+ * so that a caller can judge a difference against it; theta - E counts as the two distances |theta - c q|
+ * and |E - c q| from the nearest level c q, which is how far apart theta and E can be told at all when
+ * theta sits next to a midpoint in the sharp regime (both about q/2 from c q, their difference far smaller).  In the soft regime Q_d
  * tends to theta, which does not depend on q: the pieces of dQd/dq, each of
  * the size of E/q, cancel almost completely, and an evaluation in single
  * precision is as good as the pieces are large, not as the result is.
@@ -316,7 +318,10 @@ void cdl_oracle_quantize_bwd_k(const float *theta, const float *g, int64_t n, in
             sd += ge * d_q;
             ad += fabs(ge) * (fabs(m.mean) + 2.0 * alpha * fabs(th - 2.0 * m.mean) * m.var + 2.0 * alpha * fabs(c3)) / delta;
             sa += ge * d_al;
-            aa += fabs(ge) * (2.0 * fabs(th - m.mean) * m.var + fabs(c3));
+            double cl = nearbyint(th / delta);
+            if (cl < (double)lo) cl = (double)lo;
+            if (cl > (double)(lo + n_levels - 1)) cl = (double)(lo + n_levels - 1);
+            aa += fabs(ge) * (2.0 * (fabs(th - cl * delta) + fabs(m.mean - cl * delta)) * m.var + fabs(c3));
         }
         free(P);
     }

@@ -572,15 +572,21 @@ void entropy_bwd_kernel(const float *__restrict__ theta, const float *__restrict
                         int64_t n, QConst k, float dtheta_mul /* scale * (-2 alpha delta / n) */,
                         float *__restrict__ dtheta, double *__restrict__ partial /* [gridDim.x][2] */)
 {
-    __shared__ float ell[256 + 2 * kPad];
+    // l_k as a sum of two floats: only differences of l enter, between levels a few apart, and the scalar
+    // sums multiply them by the anchor index - with a level set around index 100 the 2^-24 of a single float
+    // l_k (about -5) showed as 2e-4 of dH/dq
+    __shared__ float ell[256 + 2 * kPad], ell_fine[256 + 2 * kPad];
     for (int i = threadIdx.x; i < k.n_levels + 2 * kPad; i += kQuantThreads) {
         const int lv = i - kPad;
-        float v = 0.0f;
-        if (lv >= 0 && lv < k.n_levels) { const float m = marg[lv]; v = m > 0.0f ? log2f(m) : 0.0f; }
-        ell[i] = v;
+        double v = 0.0;
+        if (lv >= 0 && lv < k.n_levels) { const float m = marg[lv]; v = m > 0.0f ? log2((double)m) : 0.0; }
+        const float hi = (float)v;
+        ell[i] = hi;
+        ell_fine[i] = (float)(v - (double)hi);
     }
     __syncthreads();
     const float *ell0 = ell + kPad - k.lo;    // ell0[level] for level in [lo - kPad, hi + kPad]
+    const float *fine0 = ell_fine + kPad - k.lo;
 
     double acc_d = 0.0, acc_a = 0.0;
     const int64_t n4 = n >> 2;
@@ -610,12 +616,12 @@ void entropy_bwd_kernel(const float *__restrict__ theta, const float *__restrict
                 Band<W> b;
                 band_weights<W, false, 2>(th[e], k, b);
                 cf = b.cf; u = b.u; Z = b.Z; S1 = b.S1; S2 = b.S2;
-                const float *lp = ell0 + (int)cf;
-                const float l0 = lp[0];
+                const float *lp = ell0 + (int)cf, *fp = fine0 + (int)cf;
+                const float l0 = lp[0], f0 = fp[0];
 #pragma unroll
                 for (int j = 1; j <= W; ++j) {
                     const float jf = (float)j;
-                    const float xu = b.up[j - 1] * (lp[j] - l0), xd = b.dn[j - 1] * (lp[-j] - l0);
+                    const float xu = b.up[j - 1] * ((lp[j] - l0) + (fp[j] - f0)), xd = b.dn[j - 1] * ((lp[-j] - l0) + (fp[-j] - f0));
                     B0 += xu + xd;
                     B1 = fmaf(jf, xu - xd, B1);
                     B2 = fmaf(jf * jf, xu + xd, B2);
@@ -624,11 +630,11 @@ void entropy_bwd_kernel(const float *__restrict__ theta, const float *__restrict
                 GenericSums s;
                 generic_sums<false>(th[e], k, s);
                 cf = s.cf; u = s.u; Z = s.Z; S1 = s.S1; S2 = s.S2;
-                const float *lp = ell0 + (int)cf;
-                const float l0 = lp[0], two_u = 2.0f * u;
+                const float *lp = ell0 + (int)cf, *fp = fine0 + (int)cf;
+                const float l0 = lp[0], f0 = fp[0], two_u = 2.0f * u;
                 for (int j = s.jlo; j <= s.jhi; ++j) {
                     const float jf = (float)j;
-                    const float x = generic_weight(j, two_u, k) * (lp[j] - l0);
+                    const float x = generic_weight(j, two_u, k) * ((lp[j] - l0) + (fp[j] - f0));
                     B0 += x;
                     B1 = fmaf(jf, x, B1);
                     B2 = fmaf(jf * jf, x, B2);

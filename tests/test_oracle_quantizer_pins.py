@@ -295,6 +295,13 @@ def test_size_of_the_scalar_sums_in_two_closed_form_cases(oracle):
     assert out["abs_sum_alpha"] == pytest.approx(0.0, abs=1e-12)
     assert out["d_delta"] == pytest.approx(float(np.sum(g * idx)), rel=1e-12)
 
+    # sharp regime, theta on a midpoint: P = (1/2, 1/2), Var = q^2 / 4, C3 = 0, E = theta: the term vanishes, and
+    # its size is 2 (q/2 + q/2) q^2/4 = q^3 / 2 per unit of |g|
+    mid = np.array([2.5 * delta], dtype=np.float32)
+    out = oracle.quantize_bwd(mid, np.array([3.0], np.float32), -8, 16, delta, float(np.float32(1e4 / delta ** 2)))
+    assert out["abs_sum_alpha"] == pytest.approx(3.0 * delta ** 3 / 2.0, rel=1e-9)
+    assert abs(out["d_alpha"]) < 1e-12
+
     rng = np.random.default_rng(4)
     lo, L = 60, 60                                             # levels 60 .. 119
     theta = (rng.uniform(80.0, 100.0, 500) * delta).astype(np.float32)
