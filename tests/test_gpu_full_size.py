@@ -290,3 +290,42 @@ def test_tensor_of_more_than_2_to_the_31_entries(oracle):
         want = reps * r_all[name] + r_tail[name]
         size = reps * r_all["abs_sum_" + name[2:]] + r_tail["abs_sum_" + name[2:]]
         assert abs(got - want) <= 1e-6 + 1e-5 * abs(want) + 2e-7 * size, (name, got, want, size)
+
+
+def test_products_with_more_than_2_to_the_31_outputs(oracle):
+    """M x N = 1 050 007 x 2050 > 2^31: the forward output and the upstream gradient are addressed with 64-bit
+    offsets everywhere.  g is a seeded pattern of 1 000 003 values tiled over the matrix on the device, so any row
+    or column of it can be rebuilt on the host; sampled rows of y and dL/dQ(x) (first, last, either side of the
+    2^31st output) and sampled rows of dL/dQ(w), each a contraction over all M rows, against the oracle."""
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    M, N, K, P = 1_050_007, 2050, 70, 1_000_003
+    assert M * N > 1 << 31
+    a = cdl_inputs.draw_indices((M, K), 0, 15, seed=41)
+    b = cdl_inputs.draw_indices((N, K), -7, 7, seed=42)
+    base = np.random.default_rng(43).standard_normal(P).astype(np.float32)
+    total = M * N
+    reps, tail = divmod(total, P)
+    base_d = gu.dev(base)
+    g_d = gu.empty((total,), torch.float32)
+    g_d[: reps * P].view(reps, P).copy_(base_d.unsqueeze(0).expand(reps, P))
+    g_d[reps * P:].copy_(base_d[:tail])
+    a_d, b_d = gu.dev(a), gu.dev(b)
+    y, dxh, dwh = gu.empty((M, N), torch.float32), gu.empty((M, K), torch.float32), gu.empty((N, K), torch.float32)
+    ws = gu.workspace(max(cdl.qgemm_fwd_workspace_bytes(M, N, K), cdl.qgemm_bwd_workspace_bytes(M, N, K)))
+    da, db = float(np.float32(0.25)), float(np.float32(0.016623))
+    cdl.cdl_qgemm_fwd(a_d, b_d, M, N, K, da, db, None, y, ws)
+    cdl.cdl_qgemm_bwd(g_d, a_d, b_d, M, N, K, da, db, dxh, dwh, ws)
+    torch.cuda.synchronize()
+
+    split = (1 << 31) // N      # the row that holds the 2^31st output
+    rows = np.array([0, 1, 31, 32, 255, 256, split - 1, split, split + 1, 1048575, 1048576, M - 33, M - 2, M - 1])
+    g_rows = np.stack([base[(r * N + np.arange(N, dtype=np.int64)) % P] for r in rows])
+    _, r_y = oracle.qgemm_fwd(a[rows], b, da, db)
+    gu.assert_close(y[torch.from_numpy(rows).cuda()].cpu().numpy(), r_y, "y rows")
+    r_da, _ = oracle.qgemm_bwd(g_rows, a[rows], b, da, db)
+    gu.assert_close(dxh[torch.from_numpy(rows).cuda()].cpu().numpy(), r_da, "dL/dQ(x) rows")
+    cols = np.array([0, 1, 1023, 1024, N - 2, N - 1])
+    g_cols = np.stack([base[(np.arange(M, dtype=np.int64) * N + c) % P] for c in cols], axis=1)   # [M][6]
+    _, r_db = oracle.qgemm_bwd(g_cols, a, b[cols], da, db)
+    gu.assert_close(dwh[torch.from_numpy(cols).cuda()].cpu().numpy(), r_db, "dL/dQ(w) rows")
