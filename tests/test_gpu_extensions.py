@@ -296,3 +296,45 @@ def test_extensions_on_seeded_random_parameters(oracle, lo, n_levels, delta, kap
     gu.assert_close(eth.cpu().numpy(), r["dtheta"], "dH/dtheta")
     assert abs(float(sc[3]) - r["d_delta"]) <= 1e-6 + 1e-5 * abs(r["d_delta"]) + 2e-7 * r["abs_sum_delta"], ("dH/d_delta", float(sc[3]), r["d_delta"])
     assert abs(float(sc[4]) - r["d_alpha"]) <= 1e-6 + 1e-5 * abs(r["d_alpha"]) + 2e-7 * r["abs_sum_alpha"], ("dH/d_alpha", float(sc[4]), r["d_alpha"])
+
+
+def _indices_with_counts(counts, lo, seed):
+    idx = np.repeat(np.arange(len(counts)) + lo, counts).astype(np.int8)
+    np.random.default_rng(seed).shuffle(idx)
+    return idx
+
+
+@pytest.mark.parametrize("shape", ["equal", "fibonacci", "powers_of_two", "one_heavy", "two_symbols_of_256"])
+def test_huffman_bits_on_count_profiles_that_stress_the_merge(oracle, shape):
+    """Equal counts on all 256 levels (every merge is a tie: the coded size is unique even where the tree is
+    not); Fibonacci counts (the deepest tree a given total allows, codes longer than 32 bits); powers of two
+    (a comb); one level holding almost everything; two used levels of 256."""
+    lo, n_levels = -128, 256
+    if shape == "equal":
+        counts = np.full(256, 37)
+    elif shape == "fibonacci":
+        f = [1, 1]
+        while len(f) < 40:
+            f.append(f[-1] + f[-2])          # 40 levels, 267 914 295 entries in all would be too many: scale down
+        counts = np.zeros(256, dtype=np.int64)
+        counts[100:100 + 32] = f[:32]        # 32 levels, total 5 702 886, code lengths up to 31
+        counts[10:14] = [1, 1, 1, 1]         # and a few more leaves at the bottom: lengths beyond 32
+    elif shape == "powers_of_two":
+        counts = np.zeros(256, dtype=np.int64)
+        counts[:21] = 2 ** np.arange(21)
+    elif shape == "one_heavy":
+        counts = np.ones(256, dtype=np.int64)
+        counts[77] = 3_000_000
+    else:
+        counts = np.zeros(256, dtype=np.int64)
+        counts[3], counts[250] = 12345, 678
+    idx = _indices_with_counts(counts, lo, seed=len(shape))
+    got_counts, total, avg = _huffman_gpu(idx, lo, n_levels)
+    r_counts, r_total, r_avg = oracle.huffman_bits(idx, lo, n_levels)
+    assert np.array_equal(got_counts, counts) and np.array_equal(r_counts, counts)
+    assert total == int(r_total)
+    assert abs(avg - r_avg) <= 1e-6 + 1e-5 * r_avg
+    if shape == "equal":
+        assert total == 8 * idx.size             # 256 equal counts: every code has 8 bits
+    if shape == "two_symbols_of_256":
+        assert total == idx.size                 # one bit each
