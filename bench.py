@@ -489,6 +489,19 @@ def main():
     out["roofline"] = roofline
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, st)
+    if wl.has_gemm:
+        # limb counts of the two backward products (diagnostic words at the start of the workspace): the int8 work
+        # actually issued is that many times the product's own 2*M*N*K
+        w_, x_ = wl.w_spec, wl.x_spec
+        cdl.cdl_qgemm_bwd(st.G, st.Xi, st.Wi, wl.M, wl.N, wl.K, x_.delta, w_.delta, st.dXh, st.dWh, st.ws)   # (untimed: the words are overwritten by the calls that follow it in a step)
+        torch.cuda.synchronize()
+        limbs = st.ws[:8].view(torch.int32).cpu().tolist()
+        for r in kernels:
+            which = {"limb_gemm_kernel(d_a_hat)": 0, "limb_gemm_kernel(d_b_hat)": 1}.get(r["kernel"])
+            if which is not None and "algorithmic_TOPS" in r:
+                r["limbs"] = limbs[which]
+                r["issued_TOPS"] = r["algorithmic_TOPS"] * limbs[which]
+                r["issued_frac_of_int8_peak"] = r["issued_TOPS"] / INT8_PEAK_TOPS
     out["kernels"] = kernels
     q_us = sum(r["avg_us"] for r in kernels if r["kernel"] in ("quantize_fwd_kernel", "quantize_bwd_kernel",
                                                                  "marginal_finalize_kernel", "scalar_finalize_kernel"))

@@ -185,6 +185,9 @@ int cdl_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N
  * At least one output non-NULL.  CDL_ERR_RANGE if d_a_hat is requested and N > 131071 (int32
  * accumulators over the contraction; the contraction over M is cut into pieces internally), or if
  * d_b_hat is requested and M > 11 000 000 (32-bit offsets into the transposed copy of a_idx).
+ * Diagnostic: once the call has run, the first two int32 of ws hold the limb counts the device
+ * chose for d_a_hat and for d_b_hat (meaningful for a product that was requested; d_a_hat with
+ * N <= 32 is formed directly in double, without limbs).
  */
 int cdl_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
                   int32_t M, int32_t N, int32_t K, float delta_a, float delta_b,
