@@ -233,3 +233,29 @@ def test_qgemm_all_three_products_on_seeded_random_shapes(oracle, M, N, K):
     r_a, r_b = oracle.qgemm_bwd(g, a, b, da, db)
     gu.assert_close(d_a, r_a, "d_a_hat")
     gu.assert_close(d_b, r_b, "d_b_hat")
+
+
+def test_qgemm_bwd_leaves_the_limb_counts_in_the_workspace():
+    """The header documents two diagnostic words at the start of the workspace: the limb counts (3..6) the device
+    chose; a gradient a million times larger cannot need fewer, coarser indices cannot need more."""
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    M, N, K = 640, 256, 384
+    rng = np.random.default_rng(3)
+    g = rng.standard_normal((M, N)).astype(np.float32)
+    a_d = gu.dev(cdl_inputs.draw_indices((M, K), -127, 127, seed=1))
+    b_d = gu.dev(cdl_inputs.draw_indices((N, K), -127, 127, seed=2))
+    da, db = gu.empty((M, K), torch.float32), gu.empty((N, K), torch.float32)
+    ws = gu.workspace(cdl.qgemm_bwd_workspace_bytes(M, N, K))
+
+    def limbs(gh, ad, bd):
+        cdl.cdl_qgemm_bwd(gu.dev(gh), ad, bd, M, N, K, 0.15, 0.15, da, db, ws)
+        torch.cuda.synchronize()
+        return ws[:8].view(torch.int32).cpu().tolist()
+
+    base = limbs(g, a_d, b_d)
+    assert all(3 <= v <= 6 for v in base), base
+    big = limbs(g * np.float32(2.0 ** 20), a_d, b_d)          # the absolute error bound is fixed: a larger g needs more digits
+    assert all(3 <= v <= 6 for v in big) and all(v >= w for v, w in zip(big, base)), (big, base)
+    small = limbs(g, gu.dev(cdl_inputs.draw_indices((M, K), 0, 3, seed=1)), gu.dev(cdl_inputs.draw_indices((N, K), -1, 1, seed=2)))
+    assert all(s <= v for s, v in zip(small, base)), (small, base)
