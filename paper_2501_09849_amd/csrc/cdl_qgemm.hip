@@ -819,7 +819,9 @@ void limb_reduce_kernel(const double *__restrict__ partial, int splits, int64_t 
 // at least three quarters padding there; here a block takes 64 rows of g (kept in LDS as doubles), a thread
 // one output column, whose N index values it keeps in registers as doubles, and every output is a chain of N
 // fused multiply-adds in double: products of a float and an int8 are exact in double and N <= 32 additions
-// round at 2^-53 relative.  Bound by the fp32 output it writes.
+// round at 2^-53 relative.  The shader clock inside the kernel (workload 2: M = 131072, N = 16, K = 144) shows a
+// block spending 9 k cycles on its loads and conversions, 36 k on its 64 rows (560 per row: six to eight waves
+// per SIMD take turns at 16 double-precision multiply-adds and 8 LDS reads each) and 3 k waiting for its stores.
 constexpr int kDirectMaxN = 32;
 constexpr int kDirectRows = 64;
 
