@@ -42,8 +42,8 @@ extern "C" {
  * sharpness alpha (the paper's alpha_l / beta_l).  The paper's signed b-bit set is
  * lo = -2^(b-1), n_levels = 2^b; its unsigned set is lo = 0, n_levels = 2^b; any contiguous set
  * inside [-128, 127] is accepted, so indices always fit an int8.
- * top_k = 0: the CPMF of eq. CPMF over all levels.  top_k = 1, 3, 5, 7 or 9: the CPMF "concentrated
- * proportionally on the top" top_k values (Sec. V-B, where the paper uses five for activations):
+ * top_k = 0: the CPMF of eq. CPMF over all levels.  top_k = 1, 3, 5, 7 or 9: the CPMF truncated to its
+ * top_k most probable values (Sec. V-B, where the paper uses five for activations):
  * the top_k most probable levels - the nearest ones, lower index first on a tie - keep their
  * probabilities renormalised to sum 1, all others get 0; every entry point then works with that
  * truncated CPMF.  A top_k of n_levels or more is the full CPMF.
@@ -98,8 +98,8 @@ int cdl_quantize_fwd(const float *theta, int64_t n, const cdl_qparams *p,
  *   dtheta[e] = g[e] * 2 alpha Var{Q_p | theta[e]}                              (fp32[n], nullable)
  *   d_delta   = sum_e g[e] * (E + 2 alpha theta Var - 2 alpha Skew_u) / delta  (fp32[1], nullable)
  *   d_alpha   = sum_e g[e] * (2 theta Var - Skew_u)                           (fp32[1], nullable)
- * The last formula is the derivative the paper says "can be computed analytically" without
- * printing it: dQ_d/dalpha = -Cov(Q_p, (theta - Q_p)^2).  At least one output must be non-NULL.
+ * The last formula is not printed in the paper (Sec. IV-B only notes that it has an analytic form):
+ * dQ_d/dalpha = -Cov(Q_p, (theta - Q_p)^2).  At least one output must be non-NULL.
  * The two sums are reproducible: same inputs, same bits.
  */
 int cdl_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl_qparams *p,
@@ -134,8 +134,8 @@ int cdl_quantize_draw(const float *theta, const float *u, int64_t n, const cdl_q
  *   d_delta   = scale * dH/d delta,  d_alpha = scale * dH/d alpha   (DEVICE fp32[1], nullable)
  * marg: DEVICE fp32[n_levels], the marginal PMF the forward pass produced for this tensor and
  * these parameters (levels with marg = 0 contribute nothing).  scale: e.g. lambda * n for the
- * total-bits term lambda * n * H added to a loss whose gradient is g_in.  The paper says these
- * partials "can be computed analytically" without printing them; they follow from
+ * total-bits term lambda * n * H added to a loss whose gradient is g_in.  The paper does not print
+ * these partials (Sec. IV-D only notes that they have an analytic form); they follow from
  * dH = -sum_k log2(m_k) dm_k and the CPMF derivatives of Appendix B.  Workspace as for
  * cdl_quantize_bwd when a scalar output is requested.  At least one output non-NULL.
  */

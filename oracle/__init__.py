@@ -63,7 +63,10 @@ def lib():
                                                   ctypes.c_float, ctypes.c_float, _f64p, _f64p]
         L.cdl_oracle_quantize_bwd.restype = None
         L.cdl_oracle_quantize_bwd.argtypes = [_f32p, _f32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
-                                              ctypes.c_float, ctypes.c_float, _f64p, _f64p, _f64p, _f64p, _f64p]
+                                              ctypes.c_float, ctypes.c_float, _f64p, _f64p, _f64p]
+        L.cdl_oracle_moments_k.restype = None
+        L.cdl_oracle_moments_k.argtypes = [_f32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                           ctypes.c_float, ctypes.c_float, ctypes.c_int, _f64p, _f64p, _f64p]
         L.cdl_oracle_cpmf_k.restype = ctypes.c_int
         L.cdl_oracle_cpmf_k.argtypes = [ctypes.c_double, ctypes.c_int, ctypes.c_int, ctypes.c_double,
                                         ctypes.c_double, ctypes.c_int, _f64p, _f64p]
@@ -79,7 +82,7 @@ def lib():
         L.cdl_oracle_quantize_bwd_k.restype = None
         L.cdl_oracle_quantize_bwd_k.argtypes = [_f32p, _f32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
                                                 ctypes.c_float, ctypes.c_float, ctypes.c_int,
-                                                _f64p, _f64p, _f64p, _f64p, _f64p]
+                                                _f64p, _f64p, _f64p]
         L.cdl_oracle_quantize_draw.restype = None
         L.cdl_oracle_quantize_draw.argtypes = [_f32p, _f32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
                                                ctypes.c_float, ctypes.c_float, ctypes.c_int, _i32p, _f64p]
@@ -170,17 +173,25 @@ def marginal_entropy(theta: np.ndarray, lo: int, n_levels: int, delta: float, al
 
 def quantize_bwd(theta: np.ndarray, g: np.ndarray, lo: int, n_levels: int, delta: float, alpha: float,
                  want_dtheta: bool = True, top_k: int = 0) -> dict:
-    """dtheta float64[n], d_delta, d_alpha and the sums of |term| behind the two scalars."""
+    """dtheta float64[n] (None if not wanted), d_delta, d_alpha."""
     th = _c(theta, np.float32).reshape(-1)
     gg = _c(g, np.float32).reshape(-1)
     assert th.size == gg.size
     dth = np.empty(th.size, dtype=np.float64) if want_dtheta else None
-    s = [ctypes.c_double() for _ in range(4)]
+    s = [ctypes.c_double() for _ in range(2)]
     lib().cdl_oracle_quantize_bwd_k(_ptr(th, _f32p), _ptr(gg, _f32p), th.size, lo, n_levels,
                                     float(delta), float(alpha), int(top_k), _ptr(dth, _f64p),
                                     *[ctypes.byref(x) for x in s])
-    return dict(dtheta=dth, d_delta=s[0].value, d_alpha=s[1].value,
-                abs_sum_delta=s[2].value, abs_sum_alpha=s[3].value)
+    return dict(dtheta=dth, d_delta=s[0].value, d_alpha=s[1].value)
+
+
+def moments(theta: np.ndarray, lo: int, n_levels: int, delta: float, alpha: float, top_k: int = 0):
+    """Per entry, the three quantities of Lemma 1: (E{Q_p}, Var{Q_p}, Skew_u{Q_p}), float64[n] each."""
+    th = _c(theta, np.float32).reshape(-1)
+    out = [np.empty(th.size, dtype=np.float64) for _ in range(3)]
+    lib().cdl_oracle_moments_k(_ptr(th, _f32p), th.size, lo, n_levels, float(delta), float(alpha), int(top_k),
+                               *[_ptr(o, _f64p) for o in out])
+    return tuple(out)
 
 
 def quantize_draw(theta: np.ndarray, u: np.ndarray, lo: int, n_levels: int, delta: float, alpha: float,
@@ -197,17 +208,20 @@ def quantize_draw(theta: np.ndarray, u: np.ndarray, lo: int, n_levels: int, delt
 
 
 def entropy_bwd(theta: np.ndarray, marg: np.ndarray, lo: int, n_levels: int, delta: float, alpha: float,
-                scale: float = 1.0, want_dtheta: bool = True, top_k: int = 0) -> dict:
-    """scale * dH/d(theta, delta, alpha) of the entropy of the marginal PMF `marg` (float64[n_levels])."""
+                scale: float = 1.0, want_dtheta: bool = True, top_k: int = 0, want_terms: bool = False) -> dict:
+    """scale * dH/d(theta, delta, alpha) of the entropy of the marginal PMF `marg` (float64[n_levels]);
+    want_terms: also the contribution of every entry to d_delta and d_alpha (float64[n] each)."""
     th = _c(theta, np.float32).reshape(-1)
     mm = _c(marg, np.float64).reshape(-1)
     assert mm.size == n_levels
     dth = np.empty(th.size, dtype=np.float64) if want_dtheta else None
-    s = [ctypes.c_double() for _ in range(4)]
+    td = np.empty(th.size, dtype=np.float64) if want_terms else None
+    ta = np.empty(th.size, dtype=np.float64) if want_terms else None
+    s = [ctypes.c_double() for _ in range(2)]
     lib().cdl_oracle_entropy_bwd(_ptr(th, _f32p), th.size, lo, n_levels, float(delta), float(alpha), int(top_k),
-                                 _ptr(mm, _f64p), float(scale), _ptr(dth, _f64p), *[ctypes.byref(x) for x in s])
-    return dict(dtheta=dth, d_delta=s[0].value, d_alpha=s[1].value,
-                abs_sum_delta=s[2].value, abs_sum_alpha=s[3].value)
+                                 _ptr(mm, _f64p), float(scale), _ptr(dth, _f64p), ctypes.byref(s[0]), ctypes.byref(s[1]),
+                                 _ptr(td, _f64p), _ptr(ta, _f64p))
+    return dict(dtheta=dth, d_delta=s[0].value, d_alpha=s[1].value, term_delta=td, term_alpha=ta)
 
 
 def huffman_bits(idx: np.ndarray, lo: int, n_levels: int):

@@ -65,8 +65,8 @@ static int cpmf_core(double theta, int lo, int n_levels, double delta, double al
     }
     if (top_k > 0 && top_k < n_levels) {
         /*
-         * Truncated CPMF (Sec. V-B, "Quantization operations in a mini-batch"): the CPMF is
-         * "concentrated proportionally on the top five values", the other probabilities are 0.
+         * Truncated CPMF (Sec. V-B, the paragraph on quantizing within a mini-batch): only the
+         * most probable values keep probability mass, in proportion; all others get 0.
          * Reading: keep the top_k levels of largest probability (= largest score; on equal
          * scores the lower index is kept first), renormalise over them.  The paper uses 5.
          */
@@ -147,8 +147,8 @@ static moments_t moments(const double *P, double theta, int lo, int n_levels, do
  *   dQd/dtheta = 2 alpha Var                                   (Lemma 1, eq. partialW)
  *   dQd/dq     = (E + 2 alpha theta Var - 2 alpha Skew_u) / q  (Lemma 1, eq. partialQ)
  *   dQd/dalpha = -Cov(X, (theta - X)^2)
- * The paper only says the last one "can be computed analytically"
- * (Sec. IV-B, after eq. Jgrad_alpha_q).  Differentiating eq. CPMF gives
+ * The paper does not print the last one (Sec. IV-B, after eq. Jgrad_alpha_q, only notes that it
+ * has an analytic form).  Differentiating eq. CPMF gives
  * dP_i/dalpha = -P_i (d_i^2 - sum_j P_j d_j^2) with d_i = theta - i q, and
  * summing i q dP_i/dalpha gives the covariance above.
  */
@@ -282,27 +282,15 @@ void cdl_oracle_marginal_entropy(const float *theta, int64_t n, int lo, int n_le
  *   dtheta[e] = g[e] * dQd/dtheta                    (eq. partialX3 / partialW3)
  *   d_delta   = sum_e g[e] * dQd/dq                  (eq. Jgradqw / Jgradqx)
  *   d_alpha   = sum_e g[e] * dQd/dalpha              (eq. Jgradq_alpha_w / Jgrad_alpha_q)
- * Also returns, for the two scalar sums, the size of what has to be added up:
- * sum_e |g[e]| times the magnitudes of the pieces of each partial taken about
- * the mean,
- *   dQd/dq     = (E + 2 alpha (theta - 2 E) Var - 2 alpha C3) / q     (eq. partialQ with Skew_u = C3 + 2 E Var)
- *   dQd/dalpha = 2 (theta - E) Var - C3                               (C3: third central moment)
- * so that a caller can judge a difference against it; theta - E counts as the two distances |theta - c q|
- * and |E - c q| from the nearest level c q, which is how far apart theta and E can be told at all when
- * theta sits next to a midpoint in the sharp regime (both about q/2 from c q, their difference far smaller).  In the soft regime Q_d
- * tends to theta, which does not depend on q: the pieces of dQd/dq, each of
- * the size of E/q, cancel almost completely, and an evaluation in single
- * precision is as good as the pieces are large, not as the result is.
  * ---------------------------------------------------------------------- */
 void cdl_oracle_quantize_bwd_k(const float *theta, const float *g, int64_t n, int lo, int n_levels,
                                float delta_f, float alpha_f, int top_k,
                                double *dtheta /* n, nullable */,
-                               double *d_delta, double *d_alpha,
-                               double *abs_sum_delta /* nullable */, double *abs_sum_alpha /* nullable */)
+                               double *d_delta, double *d_alpha)
 {
     const double delta = (double)delta_f, alpha = (double)alpha_f;
-    double sd = 0.0, sa = 0.0, ad = 0.0, aa = 0.0;
-#pragma omp parallel reduction(+ : sd, sa, ad, aa)
+    double sd = 0.0, sa = 0.0;
+#pragma omp parallel reduction(+ : sd, sa)
     {
         double *P = (double *)malloc(sizeof(double) * (size_t)n_levels);
 #pragma omp for schedule(static)
@@ -314,30 +302,46 @@ void cdl_oracle_quantize_bwd_k(const float *theta, const float *g, int64_t n, in
             double d_q = (m.mean + 2.0 * alpha * th * m.var - 2.0 * alpha * m.skew_u) / delta;
             double d_al = -m.cov_x_d2;
             if (dtheta) dtheta[e] = ge * d_th;
-            double c3 = m.skew_u - 2.0 * m.mean * m.var;
             sd += ge * d_q;
-            ad += fabs(ge) * (fabs(m.mean) + 2.0 * alpha * fabs(th - 2.0 * m.mean) * m.var + 2.0 * alpha * fabs(c3)) / delta;
             sa += ge * d_al;
-            double cl = nearbyint(th / delta);
-            if (cl < (double)lo) cl = (double)lo;
-            if (cl > (double)(lo + n_levels - 1)) cl = (double)(lo + n_levels - 1);
-            aa += fabs(ge) * (2.0 * (fabs(th - cl * delta) + fabs(m.mean - cl * delta)) * m.var + fabs(c3));
         }
         free(P);
     }
     *d_delta = sd;
     *d_alpha = sa;
-    if (abs_sum_delta) *abs_sum_delta = ad;
-    if (abs_sum_alpha) *abs_sum_alpha = aa;
 }
 
 void cdl_oracle_quantize_bwd(const float *theta, const float *g, int64_t n, int lo, int n_levels,
                              float delta_f, float alpha_f,
                              double *dtheta /* n, nullable */,
-                             double *d_delta, double *d_alpha,
-                             double *abs_sum_delta /* nullable */, double *abs_sum_alpha /* nullable */)
+                             double *d_delta, double *d_alpha)
 {
-    cdl_oracle_quantize_bwd_k(theta, g, n, lo, n_levels, delta_f, alpha_f, 0, dtheta, d_delta, d_alpha, abs_sum_delta, abs_sum_alpha);
+    cdl_oracle_quantize_bwd_k(theta, g, n, lo, n_levels, delta_f, alpha_f, 0, dtheta, d_delta, d_alpha);
+}
+
+/*
+ * The three quantities Lemma 1 is written in, for every entry of a tensor: E{Q_p}, Var{Q_p} and
+ * Skew_u{Q_p} under the (possibly truncated) CPMF of that entry.
+ */
+void cdl_oracle_moments_k(const float *theta, int64_t n, int lo, int n_levels,
+                          float delta_f, float alpha_f, int top_k,
+                          double *mean /* n */, double *var /* n */, double *skew_u /* n */)
+{
+    const double delta = (double)delta_f, alpha = (double)alpha_f;
+#pragma omp parallel
+    {
+        double *P = (double *)malloc(sizeof(double) * (size_t)n_levels);
+#pragma omp for schedule(static)
+        for (int64_t e = 0; e < n; ++e) {
+            double th = (double)theta[e];
+            cpmf_core(th, lo, n_levels, delta, alpha, top_k, P, NULL);
+            moments_t m = moments(P, th, lo, n_levels, delta);
+            mean[e] = m.mean;
+            var[e] = m.var;
+            skew_u[e] = m.skew_u;
+        }
+        free(P);
+    }
 }
 
 /* ------------------------------------------------------------------------
@@ -385,8 +389,8 @@ void cdl_oracle_quantize_draw(const float *theta, const float *u, int64_t n, int
 
 /* ------------------------------------------------------------------------
  * Gradient of the entropy term of the objective (eq. obj / eq. opt4, Sec. IV-D; Algorithm 1, the
- * step that computes the partials of H(w) and H(x)).  The paper states that these partials "can
- * be computed analytically" and prints no formula; this is the derivation used.
+ * step that computes the partials of H(w) and H(x)).  The paper prints no formula for these
+ * partials (it only notes that they have an analytic form); this is the derivation used.
  *
  * H = -sum_k m_k log2 m_k with the marginal PMF m_k = (1/n) sum_e P_k(theta_e)  (eq. approx1/n).
  * For any parameter x:  dH/dx = -sum_k (log2 m_k + 1/ln 2) dm_k/dx = -sum_k log2(m_k) dm_k/dx,
@@ -397,7 +401,8 @@ void cdl_oracle_quantize_draw(const float *theta, const float *u, int64_t n, int
  *   dP_k/dq     =  2 alpha P_k k d_k - 2 alpha P_k sum_j P_j j d_j
  *   dP_k/dalpha = -P_k d_k^2 + P_k sum_j P_j d_j^2
  * Outputs (each multiplied by `scale`, e.g. lambda * n for the total-bits term lambda * n * H):
- *   dtheta[e] = dH/dtheta_e,   d_delta = dH/dq,   d_alpha = dH/dalpha.
+ *   dtheta[e] = dH/dtheta_e,   d_delta = dH/dq,   d_alpha = dH/dalpha,
+ * and, on request, the contribution of every entry to the last two (term_delta, term_alpha).
  * The marginal PMF is an input (the one the forward pass produced); levels with m_k = 0
  * contribute nothing (their P_k vanish wherever they are evaluated to working precision).
  * ---------------------------------------------------------------------- */
@@ -405,14 +410,14 @@ void cdl_oracle_entropy_bwd(const float *theta, int64_t n, int lo, int n_levels,
                             float delta_f, float alpha_f, int top_k,
                             const double *marg /* n_levels */, double scale,
                             double *dtheta /* n, nullable */, double *d_delta, double *d_alpha,
-                            double *abs_sum_delta /* nullable */, double *abs_sum_alpha /* nullable */)
+                            double *term_delta /* n, nullable */, double *term_alpha /* n, nullable */)
 {
     const double delta = (double)delta_f, alpha = (double)alpha_f;
     double *ell = (double *)malloc(sizeof(double) * (size_t)n_levels);
     for (int k = 0; k < n_levels; ++k) ell[k] = marg[k] > 0.0 ? log2(marg[k]) : 0.0;
     const double inv_n = n > 0 ? 1.0 / (double)n : 0.0;
-    double sd = 0.0, sa = 0.0, ad = 0.0, aa = 0.0;
-#pragma omp parallel reduction(+ : sd, sa, ad, aa)
+    double sd = 0.0, sa = 0.0;
+#pragma omp parallel reduction(+ : sd, sa)
     {
         double *P = (double *)malloc(sizeof(double) * (size_t)n_levels);
 #pragma omp for schedule(static)
@@ -436,16 +441,16 @@ void cdl_oracle_entropy_bwd(const float *theta, int64_t n, int lo, int n_levels,
             }
             g_th *= inv_n * scale; g_q *= inv_n * scale; g_al *= inv_n * scale;
             if (dtheta) dtheta[e] = g_th;
-            sd += g_q; ad += fabs(g_q);
-            sa += g_al; aa += fabs(g_al);
+            sd += g_q;
+            sa += g_al;
+            if (term_delta) term_delta[e] = g_q;
+            if (term_alpha) term_alpha[e] = g_al;
         }
         free(P);
     }
     free(ell);
     *d_delta = sd;
     *d_alpha = sa;
-    if (abs_sum_delta) *abs_sum_delta = ad;
-    if (abs_sum_alpha) *abs_sum_alpha = aa;
 }
 
 /* ------------------------------------------------------------------------
@@ -512,8 +517,7 @@ void cdl_oracle_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_i
 
 /* ------------------------------------------------------------------------
  * Bits per entry of a quantized tensor under Huffman coding of its level indices (Sec. V-A,
- * eq. Nofbits: the paper reports the average number of bits per weight / activation "required to
- * represent the layer using Huffman coding").  counts[k] = number of entries equal to level lo+k.
+ * eq. Nofbits: the paper reports the average Huffman code length per weight / activation of a layer).  counts[k] = number of entries equal to level lo+k.
  * A Huffman code is built by repeatedly merging the two least frequent nodes; the total code
  * length in bits is the sum of the weights of all merged nodes, and it is the same for every
  * Huffman tree of the same counts (ties may be broken either way), so only the total is returned

@@ -56,8 +56,8 @@ def test_truncated_cpmf_forward_backward_marginal(oracle, lo, n_levels, delta, k
     gu.assert_close([float(sc[0])], [r_h], "entropy")
     rb = oracle.quantize_bwd(th, g, *a, top_k=top_k)
     gu.assert_close(dth.cpu().numpy(), rb["dtheta"], "dtheta")
-    assert abs(float(sc[1]) - rb["d_delta"]) <= 1e-6 + 1e-5 * abs(rb["d_delta"]) + 2e-7 * rb["abs_sum_delta"]
-    assert abs(float(sc[2]) - rb["d_alpha"]) <= 1e-6 + 1e-5 * abs(rb["d_alpha"]) + 2e-7 * rb["abs_sum_alpha"]
+    gu.check_quantizer_scalars(oracle, "top-%d levels %d..%d delta %g kappa %g" % (top_k, lo, lo + n_levels - 1, delta, kappa),
+                               th, g, a, float(sc[1]), float(sc[2]), rb, top_k=top_k)
     # marginal-only entry point
     m2, h2 = gu.empty((n_levels,), torch.float32), gu.empty((1,), torch.float32)
     _call(cdl.cdl_marginal_entropy, th_d, n, *a, m2, h2, ws, top_k=top_k)
@@ -140,11 +140,12 @@ def test_entropy_gradient_matches_oracle(oracle, lo, n_levels, delta, kappa, top
     dth, dth_add, sc = gu.empty((n,), torch.float32), gu.empty((n,), torch.float32), gu.empty((2,), torch.float32)
     _call(cdl.cdl_entropy_bwd, th_d, marg, n, *a, scale, None, dth, sc[0:1], sc[1:2], ws, top_k=top_k)
     _call(cdl.cdl_entropy_bwd, th_d, marg, n, *a, scale, g_d, dth_add, None, None, None, top_k=top_k)
-    r = oracle.entropy_bwd(th, marg.cpu().numpy().astype(np.float64), *a, scale=scale, top_k=top_k)
+    r = oracle.entropy_bwd(th, marg.cpu().numpy().astype(np.float64), *a, scale=scale, top_k=top_k, want_terms=True)
     gu.assert_close(dth.cpu().numpy(), r["dtheta"], "dH/dtheta")
     gu.assert_close(dth_add.cpu().numpy(), g.astype(np.float64) + r["dtheta"], "g + dH/dtheta")
-    assert abs(float(sc[0]) - r["d_delta"]) <= 1e-6 + 1e-5 * abs(r["d_delta"]) + 2e-7 * r["abs_sum_delta"], (float(sc[0]), r["d_delta"])
-    assert abs(float(sc[1]) - r["d_alpha"]) <= 1e-6 + 1e-5 * abs(r["d_alpha"]) + 2e-7 * r["abs_sum_alpha"], (float(sc[1]), r["d_alpha"])
+    label = "dH levels %d..%d delta %g kappa %g top_k %d" % (lo, lo + n_levels - 1, delta, kappa, top_k)
+    gu.check_scalar_sum(label, "d_delta", float(sc[0]), r["d_delta"], lambda: np.abs(r["term_delta"]).sum())
+    gu.check_scalar_sum(label, "d_alpha", float(sc[1]), r["d_alpha"], lambda: np.abs(r["term_alpha"]).sum())
     # scalars only
     sc2 = gu.empty((2,), torch.float32)
     _call(cdl.cdl_entropy_bwd, th_d, marg, n, *a, scale, None, None, sc2[0:1], sc2[1:2], ws, top_k=top_k)
@@ -278,8 +279,8 @@ def test_extensions_on_seeded_random_parameters(oracle, lo, n_levels, delta, kap
     gu.assert_close([float(sc[0])], [r_h], "entropy")
     rb = oracle.quantize_bwd(th, g, *a, top_k=top_k)
     gu.assert_close(dth.cpu().numpy(), rb["dtheta"], "dtheta")
-    assert abs(float(sc[1]) - rb["d_delta"]) <= 1e-6 + 1e-5 * abs(rb["d_delta"]) + 2e-7 * rb["abs_sum_delta"], ("d_delta", float(sc[1]), rb["d_delta"])
-    assert abs(float(sc[2]) - rb["d_alpha"]) <= 1e-6 + 1e-5 * abs(rb["d_alpha"]) + 2e-7 * rb["abs_sum_alpha"], ("d_alpha", float(sc[2]), rb["d_alpha"])
+    label = "ext sweep levels %d..%d delta %.3g kappa %.3g top_k %d n %d" % (lo, lo + n_levels - 1, spec.delta, spec.alpha * spec.delta ** 2, top_k, n)
+    gu.check_quantizer_scalars(oracle, label, th, g, a, float(sc[1]), float(sc[2]), rb, top_k=top_k)
     # the draw
     didx = gu.empty((n,), torch.int8)
     _call(cdl.cdl_quantize_draw, th_d, gu.dev(u), n, *a, didx, top_k=top_k)
@@ -292,10 +293,10 @@ def test_extensions_on_seeded_random_parameters(oracle, lo, n_levels, delta, kap
     scale = n / (2.0 * spec.alpha * spec.delta)
     eth = gu.empty((n,), torch.float32)
     _call(cdl.cdl_entropy_bwd, th_d, marg, n, *a, scale, None, eth, sc[3:4], sc[4:5], ws, top_k=top_k)
-    r = oracle.entropy_bwd(th, marg.cpu().numpy().astype(np.float64), *a, scale=scale, top_k=top_k)
+    r = oracle.entropy_bwd(th, marg.cpu().numpy().astype(np.float64), *a, scale=scale, top_k=top_k, want_terms=True)
     gu.assert_close(eth.cpu().numpy(), r["dtheta"], "dH/dtheta")
-    assert abs(float(sc[3]) - r["d_delta"]) <= 1e-6 + 1e-5 * abs(r["d_delta"]) + 2e-7 * r["abs_sum_delta"], ("dH/d_delta", float(sc[3]), r["d_delta"])
-    assert abs(float(sc[4]) - r["d_alpha"]) <= 1e-6 + 1e-5 * abs(r["d_alpha"]) + 2e-7 * r["abs_sum_alpha"], ("dH/d_alpha", float(sc[4]), r["d_alpha"])
+    gu.check_scalar_sum(label + " dH", "d_delta", float(sc[3]), r["d_delta"], lambda: np.abs(r["term_delta"]).sum())
+    gu.check_scalar_sum(label + " dH", "d_alpha", float(sc[4]), r["d_alpha"], lambda: np.abs(r["term_alpha"]).sum())
 
 
 def _indices_with_counts(counts, lo, seed):

@@ -62,13 +62,7 @@ def test_quantize_bwd_matches_oracle(oracle, lo, L, kappa):
     dth, dd, da = q.bwd(gu.dev(theta), gu.dev(g))
     ref = oracle.quantize_bwd(theta, g, *q.args)
     gu.assert_close(dth, ref["dtheta"], "dtheta")
-    # the two scalars are sums with cancellation: judged against 1e-6 + 1e-5|ref| and, where that is below
-    # what fp32 terms can carry, against 2e-7 of the sum of |terms| (reported by the oracle)
-    for name, got, want, mass in (("d_delta", dd, ref["d_delta"], ref["abs_sum_delta"]),
-                                  ("d_alpha", da, ref["d_alpha"], ref["abs_sum_alpha"])):
-        tol = max(gu.ABS_TOL + gu.REL_TOL * abs(want), 2e-7 * mass)
-        assert abs(got - want) <= tol, "%s: gpu %.9g ref %.9g (|diff| %.3g, tol %.3g, sum|terms| %.3g)" % (
-            name, got, want, abs(got - want), tol, mass)
+    gu.check_quantizer_scalars(oracle, "bwd levels %d..%d kappa %g" % (lo, lo + L - 1, kappa), theta, g, q.args, dd, da, ref)
 
 
 @pytest.mark.parametrize("lo,L", [(0, 2), (-1, 3), (-128, 256), (100, 28), (-128, 9)])
@@ -90,10 +84,7 @@ def test_smallest_widest_and_off_centre_level_sets(oracle, lo, L, kappa):
     dth, dd, da = q.bwd(gu.dev(theta), gu.dev(g))
     ref = oracle.quantize_bwd(theta, g, *q.args)
     gu.assert_close(dth, ref["dtheta"], "dtheta")
-    for name, got, want, mass in (("d_delta", dd, ref["d_delta"], ref["abs_sum_delta"]),
-                                  ("d_alpha", da, ref["d_alpha"], ref["abs_sum_alpha"])):
-        tol = max(gu.ABS_TOL + gu.REL_TOL * abs(want), 2e-7 * mass)
-        assert abs(got - want) <= tol, (name, got, want, tol)
+    gu.check_quantizer_scalars(oracle, "edge sets levels %d..%d kappa %g" % (lo, lo + L - 1, kappa), theta, g, q.args, dd, da, ref)
 
 
 @pytest.mark.parametrize("lo,L,kappa", [(-7, 15, 4.0), (0, 16, 31.25), (-15, 31, 0.008), (-127, 255, 4.0)])
@@ -223,7 +214,5 @@ def test_forward_and_backward_on_seeded_random_parameters(oracle, lo, L, delta, 
     dth, dd, da = q.bwd(gu.dev(theta), gu.dev(g))
     ref = oracle.quantize_bwd(theta, g, *q.args)
     gu.assert_close(dth, ref["dtheta"], "dtheta")
-    for name, got, want, mass in (("d_delta", dd, ref["d_delta"], ref["abs_sum_delta"]),
-                                  ("d_alpha", da, ref["d_alpha"], ref["abs_sum_alpha"])):
-        tol = max(gu.ABS_TOL + gu.REL_TOL * abs(want), 2e-7 * mass)
-        assert abs(got - want) <= tol, (name, got, want, tol)
+    gu.check_quantizer_scalars(oracle, "sweep levels %d..%d delta %.3g kappa %.3g n %d" % (lo, lo + L - 1, delta, kappa, n),
+                               theta, g, q.args, dd, da, ref)

@@ -277,36 +277,87 @@ def test_tensor_backward_is_elementwise_product_and_sum_of_element_partials(orac
             t = th64.copy(); t[j] = x
             return F(t, delta, alpha)
         assert out["dtheta"][j] == pytest.approx(_fd(Fj, th64[j], 1e-6 * delta), rel=1e-6, abs=1e-9)
-    assert out["abs_sum_delta"] >= abs(out["d_delta"]) and out["abs_sum_alpha"] >= abs(out["d_alpha"])
 
 
-def test_size_of_the_scalar_sums_in_two_closed_form_cases(oracle):
-    """What the oracle reports as the size of the two scalar sums, where it has a closed form.
+def test_per_entry_moments_of_lemma_1(oracle):
+    """oracle.moments returns E, Var, Skew_u per entry.  Pinned by: the raw-power definitions of Lemma 1 written out
+    with numpy on the CPMF (small indices, where raw powers are well conditioned); the two-level closed form
+    (Bernoulli: E = q s, Var = q^2 s (1 - s), Skew_u = E X^3 - E X E X^2 = q^3 s (1 - s)); and Lemma 1 itself,
+    which turns them into the partials that finite differences pin elsewhere in this file."""
+    rng = np.random.default_rng(21)
+    lo, L, delta, alpha = -4, 8, 0.1, 300.0
+    theta = rng.uniform(-0.5, 0.45, 40).astype(np.float32)
+    E, V, S = oracle.moments(theta, lo, L, delta, alpha)
+    v = (lo + np.arange(L)) * np.float64(np.float32(delta))
+    for e, t in enumerate(theta):
+        P, _, _ = oracle.cpmf(float(t), lo, L, float(np.float32(delta)), float(np.float32(alpha)))
+        e1, e2, e3 = np.sum(P * v), np.sum(P * v ** 2), np.sum(P * v ** 3)
+        assert E[e] == pytest.approx(e1, rel=1e-12, abs=1e-15)
+        assert V[e] == pytest.approx(e2 - e1 ** 2, rel=1e-9, abs=1e-15)
+        assert S[e] == pytest.approx(e3 - e1 * e2, rel=1e-9, abs=1e-15)
+        el = oracle.element(float(t), lo, L, float(np.float32(delta)), float(np.float32(alpha)))
+        a64, d64 = float(np.float32(alpha)), float(np.float32(delta))
+        assert el["dtheta"] == pytest.approx(2.0 * a64 * V[e], rel=1e-12)
+        assert el["ddelta"] == pytest.approx((E[e] + 2.0 * a64 * float(t) * V[e] - 2.0 * a64 * S[e]) / d64, rel=1e-9, abs=1e-12)
+    # two levels {0, q}
+    q, al = float(np.float32(0.3)), float(np.float32(25.0))
+    th = np.array([0.05, 0.15, 0.2, -0.4, 0.9], np.float32)
+    E, V, S = oracle.moments(th, 0, 2, q, al)
+    s = expit(al * q * (2.0 * th.astype(np.float64) - q))
+    np.testing.assert_allclose(E, q * s, rtol=1e-12)
+    np.testing.assert_allclose(V, q * q * s * (1 - s), rtol=1e-10, atol=1e-18)
+    np.testing.assert_allclose(S, q ** 3 * s * (1 - s), rtol=1e-10, atol=1e-18)
+
+
+def test_size_measure_of_the_scalar_sums_in_closed_form_cases(oracle):
+    """The size of what the two scalar sums add up, as the GPU tests form it from the oracle's per-entry moments
+    (tests/gpu_util.py), where it has a closed form.
     Sharp regime, theta on a level: the CPMF is one-hot, variance and third moment vanish, dQd/dq is the index
     itself, so the size is sum |g| |index| and that of the alpha sum is 0.  Soft regime, level set far from
     zero: E is about theta and 2 alpha Var about 1, so the three pieces of dQd/dq are E/q, -E/q and ~0 and the
     size is about 2 sum |g theta| / q while the sum itself is far smaller."""
+    import gpu_util as gu
     delta = float(np.float32(0.25))
     idx = np.array([3, -5, 0, 7], dtype=np.float64)
     theta = (idx * delta).astype(np.float32)
     g = np.array([1.5, -2.0, 4.0, 0.5], dtype=np.float32)
-    out = oracle.quantize_bwd(theta, g, -8, 16, delta, float(np.float32(1e4 / delta ** 2)))
-    assert out["abs_sum_delta"] == pytest.approx(float(np.sum(np.abs(g) * np.abs(idx))), rel=1e-12)
-    assert out["abs_sum_alpha"] == pytest.approx(0.0, abs=1e-12)
+    args = (-8, 16, delta, float(np.float32(1e4 / delta ** 2)))
+    out = oracle.quantize_bwd(theta, g, *args)
+    size_d, size_a = gu.scalar_sum_sizes(oracle, theta, g, *args)
+    assert size_d == pytest.approx(float(np.sum(np.abs(g) * np.abs(idx))), rel=1e-12)
+    assert size_a == pytest.approx(0.0, abs=1e-12)
     assert out["d_delta"] == pytest.approx(float(np.sum(g * idx)), rel=1e-12)
 
     # sharp regime, theta on a midpoint: P = (1/2, 1/2), Var = q^2 / 4, C3 = 0, E = theta: the term vanishes, and
     # its size is 2 (q/2 + q/2) q^2/4 = q^3 / 2 per unit of |g|
     mid = np.array([2.5 * delta], dtype=np.float32)
-    out = oracle.quantize_bwd(mid, np.array([3.0], np.float32), -8, 16, delta, float(np.float32(1e4 / delta ** 2)))
-    assert out["abs_sum_alpha"] == pytest.approx(3.0 * delta ** 3 / 2.0, rel=1e-9)
+    g1 = np.array([3.0], np.float32)
+    out = oracle.quantize_bwd(mid, g1, *args)
+    assert gu.scalar_sum_sizes(oracle, mid, g1, *args)[1] == pytest.approx(3.0 * delta ** 3 / 2.0, rel=1e-9)
     assert abs(out["d_alpha"]) < 1e-12
 
     rng = np.random.default_rng(4)
     lo, L = 60, 60                                             # levels 60 .. 119
     theta = (rng.uniform(80.0, 100.0, 500) * delta).astype(np.float32)
     g = rng.normal(0, 1, 500).astype(np.float32)
-    out = oracle.quantize_bwd(theta, g, lo, L, delta, float(np.float32(0.3 / delta ** 2)))
+    args = (lo, L, delta, float(np.float32(0.3 / delta ** 2)))
+    out = oracle.quantize_bwd(theta, g, *args)
     size = 2.0 * float(np.sum(np.abs(g.astype(np.float64) * theta.astype(np.float64)))) / delta
-    assert out["abs_sum_delta"] == pytest.approx(size, rel=1e-3)
-    assert abs(out["d_delta"]) < 1e-6 * out["abs_sum_delta"]
+    size_d, _ = gu.scalar_sum_sizes(oracle, theta, g, *args)
+    assert size_d == pytest.approx(size, rel=1e-3)
+    assert abs(out["d_delta"]) < 1e-6 * size_d
+
+
+def test_scalar_sum_check_takes_the_stated_tolerance_first():
+    """The helper of the GPU tests: inside 1e-6 + 1e-5|ref| passes; outside it fails unless the sum has cancelled
+    to under a thousandth of its size and the error is under 2e-7 of that size."""
+    import gpu_util as gu
+    assert gu.check_scalar_sum("t", "x", 1.0 + 5e-6, 1.0) <= 1.0
+    with pytest.raises(AssertionError):
+        gu.check_scalar_sum("t", "x", 1.0 + 5e-5, 1.0, lambda: 100.0)            # not cancelled: 1 > 1e-3 * 100
+    with pytest.raises(AssertionError):
+        gu.check_scalar_sum("t", "x", 1.0 + 5e-5, 1.0, lambda: 1e6, strict_only=True)
+    assert gu.check_scalar_sum("t", "x", 1.0 + 5e-5, 1.0, lambda: 1e4) > 1.0     # cancelled, 5e-5 < 2e-7 * 1e4
+    with pytest.raises(AssertionError):
+        gu.check_scalar_sum("t", "x", 1.0 + 5e-2, 1.0, lambda: 1e4)              # cancelled, but beyond 2e-7 of the size
+    del gu.SCALAR_LOG[:]
