@@ -63,7 +63,8 @@ typedef enum cdl_status {
     CDL_ERR_RANGE     = -3,   /* level set leaves [-128,127], or an int32 accumulator could overflow */
     CDL_ERR_ALIGN     = -4,   /* pointer alignment, see above */
     CDL_ERR_WORKSPACE = -5,   /* ws is NULL or smaller than the query says */
-    CDL_ERR_HIP       = -6    /* a HIP call failed; see cdl_last_hip_error() */
+    CDL_ERR_HIP       = -6,   /* a HIP call failed; see cdl_last_hip_error() */
+    CDL_ERR_TOO_LARGE = -7    /* cdl_quantize_fwd_static: the tensor needs more scratch than the built-in buffer holds */
 } cdl_status;
 
 /* Scratch needed by cdl_quantize_fwd / cdl_quantize_bwd / cdl_marginal_entropy for n elements. */
@@ -90,6 +91,24 @@ size_t cdl_qgemm_bwd_workspace_bytes(int32_t M, int32_t N, int32_t K);
 int cdl_quantize_fwd(const float *theta, int64_t n, const cdl_qparams *p,
                      int8_t *idx, float *soft, float *marg, float *entropy_bits,
                      void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * cdl_quantize_fwd for callers that cannot allocate device memory or have no workspace to hand over: code
+ * running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * outputs and kernels as cdl_quantize_fwd, minus `ws`: the per-block histograms, the second-level sums and the
+ * ticket word of the marginal PMF live in a buffer that is part of the library's device code
+ * (cdl_static_scratch_bytes() = 8 MiB on every GPU the library runs on, held until the process ends).  The call
+ * allocates and frees nothing, on the host or on the device, as long as cdl_profile_enable is off.
+ * CDL_ERR_TOO_LARGE when marg or entropy_bits is requested and cdl_quantize_workspace_bytes(n, n_levels)
+ * exceeds cdl_static_scratch_bytes() (with 255 levels: beyond about 10^8 entries); nothing is launched then.
+ * Without marg and entropy_bits no scratch is used and any n is accepted.
+ * All calls on one GPU share that GPU's buffer, which keeps the last call's contents (every call overwrites
+ * what it reads): two calls that overlap in time on one GPU - different streams, different host threads -
+ * race.  Calls ordered on one stream are safe.
+ */
+size_t cdl_static_scratch_bytes(void);
+int cdl_quantize_fwd_static(const float *theta, int64_t n, const cdl_qparams *p,
+                            int8_t *idx, float *soft, float *marg, float *entropy_bits, void *hip_stream);
 
 /*
  * Backward of the quantizer through its soft proxy Q_d (Lemma 1; chain rule of Sec. IV-B,

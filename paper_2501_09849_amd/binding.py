@@ -16,7 +16,7 @@ _LIB = None
 
 EXPORTS = (
     "cdl_quantize_workspace_bytes", "cdl_qgemm_fwd_workspace_bytes", "cdl_qgemm_bwd_workspace_bytes",
-    "cdl_quantize_fwd", "cdl_quantize_bwd", "cdl_marginal_entropy", "cdl_qgemm_fwd", "cdl_qgemm_bwd",
+    "cdl_quantize_fwd", "cdl_quantize_fwd_static", "cdl_static_scratch_bytes", "cdl_quantize_bwd", "cdl_marginal_entropy", "cdl_qgemm_fwd", "cdl_qgemm_bwd",
     "cdl_quantize_draw", "cdl_entropy_bwd", "cdl_huffman_workspace_bytes", "cdl_huffman_bits",
     "cdl_profile_enable", "cdl_profile_collect", "cdl_probe_mfma_int8",
     "cdl_status_string", "cdl_last_hip_error", "cdl_version",
@@ -72,6 +72,10 @@ def load():
         L.cdl_qgemm_bwd_workspace_bytes.argtypes = [i32, i32, i32]
         L.cdl_quantize_fwd.restype = ctypes.c_int
         L.cdl_quantize_fwd.argtypes = [vp, i64, qp, vp, vp, vp, vp, vp, sz, vp]
+        L.cdl_quantize_fwd_static.restype = ctypes.c_int
+        L.cdl_quantize_fwd_static.argtypes = [vp, i64, qp, vp, vp, vp, vp, vp]
+        L.cdl_static_scratch_bytes.restype = sz
+        L.cdl_static_scratch_bytes.argtypes = []
         L.cdl_quantize_bwd.restype = ctypes.c_int
         L.cdl_quantize_bwd.argtypes = [vp, vp, i64, qp, vp, vp, vp, vp, sz, vp]
         L.cdl_marginal_entropy.restype = ctypes.c_int
@@ -153,6 +157,17 @@ def cdl_quantize_fwd(theta, n, lo, n_levels, delta, alpha, idx, soft=None, marg=
     q = _qp(lo, n_levels, delta, alpha, top_k)
     _check(load().cdl_quantize_fwd(_ptr(theta), n, ctypes.byref(q), _ptr(idx), _ptr(soft), _ptr(marg),
                                    _ptr(entropy_bits), wp, wb, _stream(stream)), "cdl_quantize_fwd")
+
+
+def static_scratch_bytes() -> int:
+    return int(load().cdl_static_scratch_bytes())
+
+
+def cdl_quantize_fwd_static(theta, n, lo, n_levels, delta, alpha, idx, soft=None, marg=None, entropy_bits=None,
+                            stream=None, top_k=0):
+    q = _qp(lo, n_levels, delta, alpha, top_k)
+    _check(load().cdl_quantize_fwd_static(_ptr(theta), n, ctypes.byref(q), _ptr(idx), _ptr(soft), _ptr(marg),
+                                          _ptr(entropy_bits), _stream(stream)), "cdl_quantize_fwd_static")
 
 
 def cdl_quantize_bwd(theta, g, n, lo, n_levels, delta, alpha, dtheta=None, d_delta=None, d_alpha=None,

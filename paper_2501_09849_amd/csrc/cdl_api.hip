@@ -137,6 +137,26 @@ int cdl_quantize_fwd(const float *theta, int64_t n, const cdl_qparams *p,
     return launch_quantize_fwd(theta, n, *p, idx, soft, marg, entropy_bits, ws, (hipStream_t)hip_stream);
 }
 
+size_t cdl_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int cdl_quantize_fwd_static(const float *theta, int64_t n, const cdl_qparams *p,
+                            int8_t *idx, float *soft, float *marg, float *entropy_bits, void *hip_stream)
+{
+    int rc = check_qparams(p);
+    if (rc != CDL_OK) return rc;
+    if (n < 0) return CDL_ERR_PARAM;
+    if (n > 0 && (!theta || !idx)) return CDL_ERR_NULL;
+    if (!aligned(theta, 16) || !aligned(soft, 16) || !aligned(idx, 4) || !aligned(marg, 4) || !aligned(entropy_bits, 4))
+        return CDL_ERR_ALIGN;
+    void *ws = nullptr;
+    if (marg || entropy_bits) {
+        if (quantize_workspace_bytes(n, p->n_levels) > kStaticScratchBytes) return CDL_ERR_TOO_LARGE;
+        rc = quantizer_static_scratch(&ws);
+        if (rc != CDL_OK) return rc;
+    }
+    return launch_quantize_fwd(theta, n, *p, idx, soft, marg, entropy_bits, ws, (hipStream_t)hip_stream);
+}
+
 int cdl_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl_qparams *p,
                      float *dtheta, float *d_delta, float *d_alpha,
                      void *ws, size_t ws_bytes, void *hip_stream)
@@ -304,6 +324,7 @@ const char *cdl_status_string(int status)
         case CDL_ERR_ALIGN: return "pointer not sufficiently aligned";
         case CDL_ERR_WORKSPACE: return "workspace missing or too small";
         case CDL_ERR_HIP: return "a HIP call failed (see cdl_last_hip_error)";
+        case CDL_ERR_TOO_LARGE: return "tensor needs more scratch than the library's built-in buffer holds (see cdl_static_scratch_bytes)";
         default: return "unknown status";
     }
 }

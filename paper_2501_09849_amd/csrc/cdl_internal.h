@@ -85,6 +85,11 @@ int launch_quantize_draw(const float *theta, const float *u, int64_t n, const cd
 int launch_entropy_bwd(const float *theta, const float *marg, const float *g_in, int64_t n, const cdl_qparams &p,
                        float scale, float *dtheta, float *d_delta, float *d_alpha, void *ws, hipStream_t stream);
 
+// Scratch that lives inside the library (one file-scope device array per GPU) for the entry point that takes
+// no workspace: its size, and its device address on the current device (looked up on first use).
+constexpr size_t kStaticScratchBytes = 8u << 20;
+int quantizer_static_scratch(void **ptr);
+
 // Half-width of the band of levels around the nearest one that the kernels visit for a given
 // kappa = alpha*delta^2 (levels further out carry less than fp32 resolution of the result).
 int quantizer_window(double kappa, int n_levels);

@@ -28,6 +28,8 @@
 
 #include <math.h>
 
+#include <mutex>
+
 namespace cdl {
 
 namespace {
@@ -806,6 +808,36 @@ int quantizer_window(double kappa, int n_levels)
 size_t quantize_workspace_bytes(int64_t n, int32_t n_levels)
 {
     return hist_bytes(n, n_levels) + aux_bytes() + scalar_bytes();
+}
+
+// ---- built-in scratch for callers that cannot allocate ---------------------------------------
+// One array per GPU the library runs on, held until the process ends.  In host code the array's name is only a
+// stand-in: the device address comes from hipGetSymbolAddress, looked up once per device (with that device
+// current) and kept; kernels and copies are always handed that address.
+namespace {
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+int quantizer_static_scratch(void **ptr)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_failed(e);
+    if (dev < 0 || dev >= kMaxDevices) return CDL_ERR_PARAM;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_failed(e);
+        if (!p) return hip_failed(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return CDL_OK;
 }
 
 int launch_quantize_fwd(const float *theta, int64_t n, const cdl_qparams &p,
