@@ -10,7 +10,10 @@ sampled entries the oracle computes one by one, or through a property that holds
   the pieces are compared with the oracle;
 * forward product: sampled rows of y, and of the int32 accumulators (bit-exact);
 * backward products: sampled rows of dL/dQ(x) (each needs one row of g), sampled rows of dL/dQ(w)
-  (each needs one column of g and the whole contraction over the batch).
+  (each needs one column of g and the whole contraction over the batch);
+* every entry of all four product outputs: contractions of the whole matrix with an all-ones and with a
+  random-sign vector from either side, against the same contraction of the operands evaluated on the host in
+  O(M K + M N) - exact for the int32 accumulators, within the summed entry tolerances for the fp32 outputs.
 
 Tolerances as everywhere: |gpu - oracle| <= 1e-6 + 1e-5 |oracle|, hard indices exact except where the
 oracle's two best level scores differ by less than 1e-6.
@@ -86,6 +89,88 @@ def _quantizer_full(oracle, spec, theta_h, g_h, label, strict_scalars=True):
     return idx, exempt
 
 
+def _signs(n, seed):
+    return np.random.default_rng(seed).integers(0, 2, n).astype(np.float64) * 2.0 - 1.0
+
+
+def _gpu_times_vector(t, v, left=False, chunk=4096):
+    """t @ v (or v @ t) in double on the device, a block of rows at a time (plumbing: the values come back to the host)."""
+    torch = gu.torch_mod()
+    v_d = torch.from_numpy(np.ascontiguousarray(v, dtype=np.float64)).cuda()
+    rows = t.shape[0]
+    if not left:
+        out = torch.empty(rows, dtype=torch.float64, device="cuda")
+        for r0 in range(0, rows, chunk):
+            out[r0:r0 + chunk] = t[r0:r0 + chunk].double() @ v_d
+        return out.cpu().numpy()
+    out = torch.zeros(t.shape[1], dtype=torch.float64, device="cuda")
+    for r0 in range(0, rows, chunk):
+        out += v_d[r0:r0 + chunk] @ t[r0:r0 + chunk].double()
+    return out.cpu().numpy()
+
+
+def _gpu_abs_times_ones(t, left=False, chunk=4096):
+    torch = gu.torch_mod()
+    rows = t.shape[0]
+    if not left:
+        out = torch.empty(rows, dtype=torch.float64, device="cuda")
+        for r0 in range(0, rows, chunk):
+            out[r0:r0 + chunk] = t[r0:r0 + chunk].double().abs().sum(dim=1)
+        return out.cpu().numpy()
+    out = torch.zeros(t.shape[1], dtype=torch.float64, device="cuda")
+    for r0 in range(0, rows, chunk):
+        out += t[r0:r0 + chunk].double().abs().sum(dim=0)
+    return out.cpu().numpy()
+
+
+def _host_mat_vec(a, v, left=False, chunk=8192):
+    """a @ v (or v @ a) in double on the host, a block of rows at a time (a may be int8 or fp32)."""
+    v = np.asarray(v, dtype=np.float64)
+    if not left:
+        return np.concatenate([a[r0:r0 + chunk].astype(np.float64) @ v for r0 in range(0, a.shape[0], chunk)])
+    out = np.zeros(a.shape[1])
+    for r0 in range(0, a.shape[0], chunk):
+        out += v[r0:r0 + chunk] @ a[r0:r0 + chunk].astype(np.float64)
+    return out
+
+
+def _whole_matrix_checks(xi, wi, G, delta_x, delta_w, acc_d, Y_d, dXh_d, dWh_d):
+    """Every entry of every product enters two identities that the host can evaluate in O(M K + M N):
+    for any vectors u, v:  acc v = Xi (Wi^T v)  and  u^T acc = (u^T Xi) Wi^T, exact in integers (held in doubles
+    below 2^53); the same for y, dL/dQ(x) = delta_w G Wi and dL/dQ(w) = delta_x G^T Xi in double, where each GPU
+    entry may be off by its own tolerance 1e-6 + 1e-5 |entry|, so a contraction with a +-1 vector may be off by the
+    sum of those.  u, v: all ones (plain row and column sums) and seeded random signs (errors that cancel in
+    a plain sum do not cancel in both)."""
+    M, K = xi.shape
+    N = wi.shape[0]
+    scale = float(delta_x) * float(delta_w)
+    for tag, v_n, u_m, v_k, u_n in (("ones", np.ones(N), np.ones(M), np.ones(K), np.ones(N)),
+                                    ("signs", _signs(N, 1), _signs(M, 2), _signs(K, 3), _signs(N, 4))):
+        # ---- forward: acc [M, N] exact, y = scale * acc ----
+        right = _host_mat_vec(xi, _host_mat_vec(wi, v_n, left=True))            # Xi (Wi^T v): [M]
+        left = _host_mat_vec(wi, _host_mat_vec(xi, u_m, left=True))             # Wi (Xi^T u): [N]
+        assert np.array_equal(_gpu_times_vector(acc_d, v_n), right), "acc: row identity (%s)" % tag
+        assert np.array_equal(_gpu_times_vector(acc_d, u_m, left=True), left), "acc: column identity (%s)" % tag
+        tol_r = 1e-6 * N + 1e-5 * _gpu_abs_times_ones(Y_d)
+        tol_c = 1e-6 * M + 1e-5 * _gpu_abs_times_ones(Y_d, left=True)
+        assert np.all(np.abs(_gpu_times_vector(Y_d, v_n) - scale * right) <= tol_r), "y: row identity (%s)" % tag
+        assert np.all(np.abs(_gpu_times_vector(Y_d, u_m, left=True) - scale * left) <= tol_c), "y: column identity (%s)" % tag
+        # ---- dL/dQ(x) [M, K] = delta_w G Wi ----
+        ref_r = float(delta_w) * _host_mat_vec(G, _host_mat_vec(wi, v_k))       # G (Wi v): [M]
+        ref_c = float(delta_w) * _host_mat_vec(wi, _host_mat_vec(G, u_m, left=True), left=True)   # (u^T G) Wi: [K]
+        tol_r = 1e-6 * K + 1e-5 * _gpu_abs_times_ones(dXh_d)
+        tol_c = 1e-6 * M + 1e-5 * _gpu_abs_times_ones(dXh_d, left=True)
+        assert np.all(np.abs(_gpu_times_vector(dXh_d, v_k) - ref_r) <= tol_r), "dL/dQ(x): row identity (%s)" % tag
+        assert np.all(np.abs(_gpu_times_vector(dXh_d, u_m, left=True) - ref_c) <= tol_c), "dL/dQ(x): column identity (%s)" % tag
+        # ---- dL/dQ(w) [N, K] = delta_x G^T Xi ----
+        ref_r = float(delta_x) * _host_mat_vec(G, _host_mat_vec(xi, v_k), left=True)               # G^T (Xi v): [N]
+        ref_c = float(delta_x) * _host_mat_vec(xi, _host_mat_vec(G, u_n), left=True)               # (G u)^T Xi: [K]
+        tol_r = 1e-6 * K + 1e-5 * _gpu_abs_times_ones(dWh_d)
+        tol_c = 1e-6 * N + 1e-5 * _gpu_abs_times_ones(dWh_d, left=True)
+        assert np.all(np.abs(_gpu_times_vector(dWh_d, v_k) - ref_r) <= tol_r), "dL/dQ(w): row identity (%s)" % tag
+        assert np.all(np.abs(_gpu_times_vector(dWh_d, u_n, left=True) - ref_c) <= tol_c), "dL/dQ(w): column identity (%s)" % tag
+
+
 @pytest.mark.parametrize("number", [2, 3, 5])
 def test_layer_step_at_full_size(oracle, number):
     import paper_2501_09849_amd as cdl
@@ -120,13 +205,13 @@ def test_layer_step_at_full_size(oracle, number):
     cols = np.unique(np.concatenate([rng.choice(N, size=min(N, 6), replace=False), [0, N - 1]]))
     _, r_db = oracle.qgemm_bwd(np.ascontiguousarray(G[:, cols]), xi, np.ascontiguousarray(wi[cols]), x.delta, w.delta, want_da=False)
     gu.assert_close(dWh[torch.from_numpy(cols).cuda()].cpu().numpy(), r_db, "dL/dQ(w) rows")
-    del Y
-    torch.cuda.empty_cache()
     acc = gu.empty((M, N), torch.int32)
     cdl.cdl_qgemm_fwd(Xi_d, Wi_d, M, N, K, x.delta, w.delta, acc, None, ws)
     torch.cuda.synchronize()
     assert np.array_equal(acc[rows_d].cpu().numpy(), r_acc), "int32 accumulators differ on the sampled rows"
-    del acc
+    # ---- every entry of the four outputs, through identities the host can afford ----
+    _whole_matrix_checks(xi, wi, G, x.delta, w.delta, acc, Y, dXh, dWh)
+    del acc, Y
     torch.cuda.empty_cache()
 
     # ---- quantizer forward and backward on W and X, the backward fed with the GPU's own fp32 product gradients ----
