@@ -61,8 +61,8 @@ __device__ __forceinline__ void store_stream4(float *p, float a, float b, float 
     const cdl_v4f v = {a, b, c, d};
     __builtin_nontemporal_store(v, reinterpret_cast<cdl_v4f *>(p));
 }
-// entries from which a tensor counts as large (128 MiB of fp32)
-constexpr long long kStreamFrom = 1ll << 25;
+// entries from which a tensor counts as large (32 MiB of fp32)
+constexpr long long kStreamFrom = 1ll << 23;
 __device__ __forceinline__ void store_stream_u32(void *p, unsigned int v)
 {
     __builtin_nontemporal_store(v, reinterpret_cast<unsigned int *>(p));

@@ -474,6 +474,289 @@ void quantize_bwd_kernel(const float *__restrict__ theta, const float *__restric
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Soft regime on a small level set (at most 33 levels, kappa small enough that every level carries weight:
+// the paper starts training at alpha = 500, Sec. V-B, where kappa is 0.01 - 0.5 for 2 - 5 bit weights).
+// Here the band is the whole set for every entry, so nothing is gained by anchoring at the nearest level, and
+// a common centre makes the loop over the levels the same for every lane.  With c0 the centre of the set
+// (a level for an odd number of levels, a midpoint for an even one), r = theta / delta - c0 and offsets
+// o_j = j - eps (eps = 0 or 1/2), the weight of the level at c0 +- o_j is
+//     exp(-kappa o_j^2) T^(+-o_j),      T = exp(2 kappa r),
+// a launch constant times a power of one exponential per entry.  The even and odd parts
+//     s_j = T^o_j + T^-o_j,   d_j = T^o_j - T^-o_j
+// obey s_(j+1) = (T + 1/T) s_j - s_(j-1) (the same for d): one fused multiply-add each per pair of levels,
+// and the power sums take one more each (Z += E_j s_j, S1 += o_j E_j d_j, S2 += o_j^2 E_j s_j, S3 += o_j^3 E_j d_j)
+// against an exponential and five instructions per single level in the generic loop.
+// Everything is in double: an error of T is raised to the power o_j and hits all levels alike (it acts like a
+// shift of theta by var_j * eps * delta, 5e-6 delta for fp32 with 31 live levels - too much next to the
+// tolerance), moments about a centre that may be 16 levels away from the mean would cancel in fp32, and with
+// packed fp32 arithmetic switched off a double fused multiply-add issues at the same rate as a single one.
+// theta far outside the set: r is held at +-r_safe = JH + 15 / kappa, beyond which the CPMF is one level to
+// 1e-13, so that T^JH stays finite.  The host uses these kernels when kappa * JH^2 <= 72.
+// Marginal PMF: sum_e P = sum_e (E_j / 2Z_e)(s_j +- d_j): every thread keeps sum_e s_j / Z_e and sum_e d_j / Z_e
+// for all j in registers (the loop is unrolled, JH is a template parameter, level sets in between are padded
+// with E_j = 0), the block adds them up in a fixed order through LDS and writes one fixed-point row like the
+// histogram kernels do - no atomics at all, where the generic kernel issues one per entry and level.
+// ------------------------------------------------------------------------------------------
+constexpr int kUniMaxJH = 16;
+constexpr int kUniThreads = 256;
+
+struct UniConst {
+    double delta, c0;          // step; centre of the level set in units of the step
+    double inv_delta;
+    double x_per_r;            // log2(e) * kappa: T^(1/2) = exp2(x_per_r * r)
+    double two_kappa;
+    double r_safe;
+    double e[kUniMaxJH][4];    // E_j, o_j E_j, o_j^2 E_j, o_j^3 E_j (zero for offsets beyond the set)
+    int odd;                   // number of levels is odd: offsets are integers and the centre is a level
+    int pairs;                 // pairs of levels: n_levels / 2
+};
+
+template <int JH>
+struct UniSums {
+    double Z, S1, S2, S3, r;
+};
+
+// NMOM: how many of S1, S2, S3 are needed.  HIST: also adds s_j / Z and d_j / Z (and 1 / Z for the centre) to acc.
+template <int JH, int NMOM, bool HIST>
+__device__ __forceinline__ void uni_sums(float th, const UniConst &u, UniSums<JH> &o, double (&acc_s)[JH], double (&acc_d)[JH], double &acc_0)
+{
+    double r = fma((double)th, u.inv_delta, -u.c0);
+    r = fmin(fmax(r, -u.r_safe), u.r_safe);
+    o.r = r;
+    const double half = exp2(u.x_per_r * r);      // T^(1/2)
+    const double half_inv = 1.0 / half;
+    const double T = half * half, Tinv = half_inv * half_inv;
+    const double c = T + Tinv;
+    const double a = u.odd ? T : half, b = u.odd ? Tinv : half_inv;
+    const double s1 = a + b, d1 = a - b;
+    double s_prev = u.odd ? 2.0 : s1, d_prev = u.odd ? 0.0 : -d1;
+    double s = s1, d = d1;
+    double Z = u.odd ? 1.0 : 0.0, S1 = 0.0, S2 = 0.0, S3 = 0.0;
+#pragma unroll
+    for (int j = 0; j < JH; ++j) {
+        Z = fma(u.e[j][0], s, Z);
+        S1 = fma(u.e[j][1], d, S1);
+        if (NMOM >= 2) S2 = fma(u.e[j][2], s, S2);
+        if (NMOM >= 3) S3 = fma(u.e[j][3], d, S3);
+        const double s_next = fma(c, s, -s_prev), d_next = fma(c, d, -d_prev);
+        s_prev = s; d_prev = d; s = s_next; d = d_next;
+    }
+    o.Z = Z; o.S1 = S1; o.S2 = S2; o.S3 = S3;
+    if (HIST) {
+        const double inv = 1.0 / Z;
+        acc_0 += inv;
+        s_prev = u.odd ? 2.0 : s1; d_prev = u.odd ? 0.0 : -d1;
+        s = s1 * inv; d = d1 * inv;
+        s_prev *= inv; d_prev *= inv;
+#pragma unroll
+        for (int j = 0; j < JH; ++j) {
+            acc_s[j] += s;
+            acc_d[j] += d;
+            const double s_next = fma(c, s, -s_prev), d_next = fma(c, d, -d_prev);
+            s_prev = s; d_prev = d; s = s_next; d = d_next;
+        }
+    }
+}
+
+// The same sums for the backward pass, which needs all four.  Four launch constants per offset would be 128
+// scalar registers at JH = 16, more than a wave has (the compiler then parks them in vector registers and
+// fetches each with two extra instructions: measured twice the time).  So only E_j comes from the table and the
+// powers of o_j = j - eps are literals, which costs two more multiplications per pair of levels; ODD (the
+// number of levels is odd, eps = 0) is a template parameter for that reason.
+template <int JH, int NMOM, bool ODD>
+__device__ __forceinline__ void uni_sums_literal(float th, const UniConst &u, UniSums<JH> &o)
+{
+    double r = fma((double)th, u.inv_delta, -u.c0);
+    r = fmin(fmax(r, -u.r_safe), u.r_safe);
+    o.r = r;
+    const double half = exp2(u.x_per_r * r);      // T^(1/2)
+    const double half_inv = 1.0 / half;
+    const double T = half * half, Tinv = half_inv * half_inv;
+    const double c = T + Tinv;
+    const double a = ODD ? T : half, b = ODD ? Tinv : half_inv;
+    const double s1 = a + b, d1 = a - b;
+    double s_prev = ODD ? 2.0 : s1, d_prev = ODD ? 0.0 : -d1;
+    double s = s1, d = d1;
+    double Z = ODD ? 1.0 : 0.0, S1 = 0.0, S2 = 0.0, S3 = 0.0;
+#pragma unroll
+    for (int j = 0; j < JH; ++j) {
+        constexpr double kEps = ODD ? 0.0 : 0.5;
+        const double off = (double)(j + 1) - kEps;
+        const double es = u.e[j][0] * s, ed = u.e[j][0] * d;
+        Z += es;
+        S1 = fma(off, ed, S1);
+        if (NMOM >= 2) S2 = fma(off * off, es, S2);
+        if (NMOM >= 3) S3 = fma(off * off * off, ed, S3);
+        const double s_next = fma(c, s, -s_prev), d_next = fma(c, d, -d_prev);
+        s_prev = s; d_prev = d; s = s_next; d = d_next;
+    }
+    o.Z = Z; o.S1 = S1; o.S2 = S2; o.S3 = S3;
+}
+
+template <int JH, bool IDX, bool SOFT, bool MARG>
+__global__ __launch_bounds__(kUniThreads)
+void quantize_fwd_uniform_kernel(const float *__restrict__ theta, int64_t n, QConst k, UniConst u,
+                                 int8_t *__restrict__ idx, float *__restrict__ soft,
+                                 unsigned long long *__restrict__ partial /* [gridDim.x][n_levels] */,
+                                 unsigned int *__restrict__ ticket)
+{
+    extern __shared__ double uni_lds[];   // [kUniThreads][2 JH + 1] when MARG
+    double acc_s[JH], acc_d[JH], acc_0 = 0.0;
+#pragma unroll
+    for (int j = 0; j < JH; ++j) { acc_s[j] = 0.0; acc_d[j] = 0.0; }
+    if (MARG && blockIdx.x == 0 && threadIdx.x == 0) *ticket = 0u;
+
+    const int64_t n4 = n >> 2;
+    const int64_t stride = (int64_t)gridDim.x * kUniThreads;
+    const int tail = (int)(n - (n4 << 2));
+    for (int64_t v = (int64_t)blockIdx.x * kUniThreads + threadIdx.x; v < n4 + (tail ? 1 : 0); v += stride) {
+        float th[4];
+        int cnt = 4;
+        if (v < n4) {
+            const float4 t = load_stream4(theta + 4 * v, k.stream);
+            th[0] = t.x; th[1] = t.y; th[2] = t.z; th[3] = t.w;
+        } else {
+            cnt = tail;
+            for (int e = 0; e < 4; ++e) th[e] = (e < cnt) ? theta[(n4 << 2) + e] : 0.0f;
+        }
+        float sv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        int ci[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (IDX) ci[e] = (int)anchor_level<true>(th[e], k);
+        if (MARG) {
+            // (one entry after the other in a loop that stays a loop, see the backward kernel; entries past the end
+            // of the tensor are not visited)
+#pragma unroll 1
+            for (int e = 0; e < cnt; ++e) {
+                const float th_e = e == 0 ? th[0] : (e == 1 ? th[1] : (e == 2 ? th[2] : th[3]));
+                UniSums<JH> q;
+                uni_sums<JH, 1, true>(th_e, u, q, acc_s, acc_d, acc_0);
+                const float sv_e = (float)(u.delta * (u.c0 + q.S1 / q.Z));
+                sv[0] = e == 0 ? sv_e : sv[0]; sv[1] = e == 1 ? sv_e : sv[1];
+                sv[2] = e == 2 ? sv_e : sv[2]; sv[3] = e == 3 ? sv_e : sv[3];
+            }
+        } else if (SOFT) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                UniSums<JH> q;
+                uni_sums<JH, 1, false>(th[e], u, q, acc_s, acc_d, acc_0);
+                sv[e] = (float)(u.delta * (u.c0 + q.S1 / q.Z));
+            }
+        }
+        if (v < n4) {
+            if (SOFT) store_stream4(soft + 4 * v, sv[0], sv[1], sv[2], sv[3], k.stream);
+            if (IDX) reinterpret_cast<uint32_t *>(idx)[v] = (uint32_t)(ci[0] & 0xff) | ((uint32_t)(ci[1] & 0xff) << 8) |
+                                                            ((uint32_t)(ci[2] & 0xff) << 16) | ((uint32_t)(ci[3] & 0xff) << 24);
+        } else {
+            for (int e = 0; e < cnt; ++e) {
+                if (SOFT) soft[(n4 << 2) + e] = sv[e];
+                if (IDX) idx[(n4 << 2) + e] = (int8_t)ci[e];
+            }
+        }
+    }
+
+    if (MARG) {
+        // per thread: the sums over its entries of P(level) for every level; row stride 2 JH + 1 doubles
+        constexpr int LS = 2 * JH + 1;
+        double *mine = uni_lds + (size_t)threadIdx.x * LS;
+        // level index (from the lowest level) of the offsets +o_j and -o_j: odd sets pairs + j and pairs - j around the
+        // centre level `pairs`; even sets pairs - 1 + j and pairs - j
+        if (u.odd) mine[u.pairs] = acc_0;
+#pragma unroll
+        for (int j = 1; j <= JH; ++j) {
+            if (j <= u.pairs) {
+                const double up = 0.5 * u.e[j - 1][0] * (acc_s[j - 1] + acc_d[j - 1]);
+                const double dn = 0.5 * u.e[j - 1][0] * (acc_s[j - 1] - acc_d[j - 1]);
+                mine[u.odd ? u.pairs + j : u.pairs - 1 + j] = up;
+                mine[u.pairs - j] = dn;
+            }
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < k.n_levels) {
+            double tot = 0.0;
+            for (int t = 0; t < kUniThreads; ++t) tot += uni_lds[(size_t)t * LS + threadIdx.x];
+            partial[(size_t)blockIdx.x * k.n_levels + threadIdx.x] =
+                (unsigned long long)__double2ll_rn(tot * (double)(1u << kHistScaleBits));
+        }
+    }
+}
+
+template <int JH, bool ODD, bool DTHETA, bool SCALARS>
+__global__ __launch_bounds__(kUniThreads)
+void quantize_bwd_uniform_kernel(const float *__restrict__ theta, const float *__restrict__ g, int64_t n, QConst k, UniConst u,
+                                 float *__restrict__ dtheta, double *__restrict__ partial /* [gridDim.x][2] */)
+{
+    double acc_d = 0.0, acc_a = 0.0;
+    const int64_t n4 = n >> 2;
+    const int64_t stride = (int64_t)gridDim.x * kUniThreads;
+    const int tail = (int)(n - (n4 << 2));
+    for (int64_t v = (int64_t)blockIdx.x * kUniThreads + threadIdx.x; v < n4 + (tail ? 1 : 0); v += stride) {
+        float th[4], ge[4];
+        int cnt = 4;
+        if (v < n4) {
+            const float4 t = load_stream4(theta + 4 * v, k.stream);
+            const float4 q = load_stream4(g + 4 * v, k.stream);
+            th[0] = t.x; th[1] = t.y; th[2] = t.z; th[3] = t.w;
+            ge[0] = q.x; ge[1] = q.y; ge[2] = q.z; ge[3] = q.w;
+        } else {
+            cnt = tail;
+            for (int e = 0; e < 4; ++e) {
+                th[e] = (e < cnt) ? theta[(n4 << 2) + e] : 0.0f;
+                ge[e] = (e < cnt) ? g[(n4 << 2) + e] : 0.0f;
+            }
+        }
+        float dv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        // One entry after the other, in a loop that stays a loop: four interleaved entries of this much double
+        // arithmetic need more registers than four waves per SIMD leave (the compiler took 234, or spilled).
+        // th_e, g_e and the outputs move through selects on the loop counter, which is uniform.
+#pragma unroll 1
+        for (int e = 0; e < 4; ++e) {
+            const float th_e = e == 0 ? th[0] : (e == 1 ? th[1] : (e == 2 ? th[2] : th[3]));
+            const float g_e = e == 0 ? ge[0] : (e == 1 ? ge[1] : (e == 2 ? ge[2] : ge[3]));
+            UniSums<JH> q;
+            uni_sums_literal<JH, SCALARS ? 3 : 2, ODD>(th_e, u, q);
+            const double inv = 1.0 / q.Z;
+            const double mu = q.S1 * inv, m2 = q.S2 * inv;
+            const double var = fma(-mu, mu, m2);
+            const double gd = (double)g_e;
+            const float dv_e = (float)(gd * (u.two_kappa * var));
+            dv[0] = e == 0 ? dv_e : dv[0]; dv[1] = e == 1 ? dv_e : dv[1];
+            dv[2] = e == 2 ? dv_e : dv[2]; dv[3] = e == 3 ? dv_e : dv[3];
+            if (SCALARS) {
+                const double m3 = q.S3 * inv;
+                const double c3 = fma(-mu, fma(-2.0 * mu, mu, 3.0 * m2), m3);   // m3 - 3 mu m2 + 2 mu^3
+                // Lemma 1 in offsets from the centre c0 (the derivation holds for any origin of the level index)
+                const double t_d = (u.c0 + mu) + u.two_kappa * fma(q.r - u.c0 - 2.0 * mu, var, -c3);
+                const double t_a = fma(2.0 * (q.r - mu), var, -c3);
+                acc_d = fma(gd, t_d, acc_d);
+                acc_a = fma(gd, t_a, acc_a);
+            }
+        }
+        if (DTHETA) {
+            if (v < n4) store_stream4(dtheta + 4 * v, dv[0], dv[1], dv[2], dv[3], k.stream);
+            else for (int e = 0; e < cnt; ++e) dtheta[(n4 << 2) + e] = dv[e];
+        }
+    }
+    if (SCALARS) {
+        __shared__ double red_d[kUniThreads / 64], red_a[kUniThreads / 64];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            acc_d += __shfl_down(acc_d, off, 64);
+            acc_a += __shfl_down(acc_a, off, 64);
+        }
+        if ((threadIdx.x & 63) == 0) { red_d[threadIdx.x >> 6] = acc_d; red_a[threadIdx.x >> 6] = acc_a; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double sd = 0.0, sa = 0.0;
+            for (int w = 0; w < kUniThreads / 64; ++w) { sd += red_d[w]; sa += red_a[w]; }
+            partial[2 * (size_t)blockIdx.x] = sd;
+            partial[2 * (size_t)blockIdx.x + 1] = sa;
+        }
+    }
+}
+
 // d_delta = mul_d * sum of partials; d_alpha = mul_a * sum of partials.  Fixed summation order.
 __global__ __launch_bounds__(256)
 void scalar_finalize_kernel(const double *__restrict__ partial, int nblocks, double mul_d, double mul_a,
@@ -777,6 +1060,87 @@ void launch_fwd(bool want_idx, bool want_soft, bool want_marg, int grid, hipStre
     launch_fwd_w<W>(want_idx, want_soft, want_marg, grid, s, theta, n, k, idx, soft, partial, ticket);
 }
 
+// The soft-regime kernels on a common centre serve: the full CPMF, 6 to 33 levels (smaller sets always fall to
+// the unrolled band kernels), and kappa * JH^2 <= 72 with JH the padded half-width, so that T^JH stays finite
+// at +-r_safe.  Returns the padded half-width (4, 8 or 16), or 0 when the other kernels serve.
+int uniform_half_width(const cdl_qparams &p, const QConst &k)
+{
+    if (k.slide || band_template(k) != 0) return 0;
+    if (p.n_levels < 6 || p.n_levels > 2 * kUniMaxJH + 1) return 0;
+    const int pairs = p.n_levels / 2;
+    const int jh = pairs <= 4 ? 4 : (pairs <= 8 ? 8 : 16);
+    const double kappa = (double)p.alpha * (double)p.delta * (double)p.delta;
+    // only where (nearly) every level is live anyway: a band much narrower than the set is cheaper in the generic loop
+    if (2 * k.wgen + 1 < p.n_levels - 2) return 0;
+    if (kappa * jh * jh > 72.0) return 0;
+    return jh;
+}
+
+UniConst make_uniform(const cdl_qparams &p, int jh)
+{
+    UniConst u{};
+    const double delta = (double)p.delta, alpha = (double)p.alpha;
+    const double kappa = alpha * delta * delta;
+    u.delta = delta;
+    u.inv_delta = 1.0 / delta;
+    u.odd = p.n_levels & 1;
+    u.pairs = p.n_levels / 2;
+    u.c0 = (double)p.lo + 0.5 * (double)(p.n_levels - 1);
+    u.x_per_r = kappa * 1.4426950408889634;
+    u.two_kappa = 2.0 * kappa;
+    u.r_safe = (double)jh + 15.0 / kappa;
+    for (int j = 1; j <= kUniMaxJH; ++j) {
+        const double o = u.odd ? (double)j : (double)j - 0.5;
+        const double E = j <= u.pairs ? exp(-kappa * o * o) : 0.0;
+        u.e[j - 1][0] = E;
+        u.e[j - 1][1] = o * E;
+        u.e[j - 1][2] = o * o * E;
+        u.e[j - 1][3] = o * o * o * E;
+    }
+    return u;
+}
+
+template <int JH>
+int launch_fwd_uniform(bool want_idx, bool want_soft, bool want_marg, int grid, hipStream_t s, const float *theta, int64_t n,
+                       const QConst &k, const UniConst &u, int8_t *idx, float *soft, unsigned long long *partial, unsigned int *ticket)
+{
+    const size_t lds = want_marg ? (size_t)kUniThreads * (2 * JH + 1) * sizeof(double) : 0;
+#define CDL_UNI(I, S, M)                                                                                        \
+    do {                                                                                                        \
+        if (lds > 65536) {                                                                                      \
+            const hipError_t e_ = hipFuncSetAttribute((const void *)quantize_fwd_uniform_kernel<JH, I, S, M>,   \
+                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);    \
+            if (e_ != hipSuccess) return hip_failed(e_);                                                        \
+        }                                                                                                       \
+        CDL_LAUNCH((I) ? "quantize_fwd_kernel" : "quantize_fwd_kernel(marginal only)", s,                       \
+                   (quantize_fwd_uniform_kernel<JH, I, S, M>), dim3(grid), dim3(kUniThreads), lds,              \
+                   theta, n, k, u, idx, soft, partial, ticket);                                                 \
+    } while (0)
+    if (want_idx && want_soft && want_marg) CDL_UNI(true, true, true);
+    else if (want_idx && want_soft) CDL_UNI(true, true, false);
+    else if (want_idx && want_marg) CDL_UNI(true, false, true);
+    else CDL_UNI(false, false, true);
+#undef CDL_UNI
+    return CDL_OK;
+}
+
+template <int JH>
+void launch_bwd_uniform(bool want_dtheta, bool want_scalars, int grid, hipStream_t s, const float *theta, const float *g,
+                        int64_t n, const QConst &k, const UniConst &u, float *dtheta, double *partial)
+{
+#define CDL_UNIB(D, S)                                                                                                          \
+    do {                                                                                                                        \
+        if (u.odd) CDL_LAUNCH("quantize_bwd_kernel", s, (quantize_bwd_uniform_kernel<JH, true, D, S>), dim3(grid), dim3(kUniThreads), 0, \
+                              theta, g, n, k, u, dtheta, partial);                                                              \
+        else CDL_LAUNCH("quantize_bwd_kernel", s, (quantize_bwd_uniform_kernel<JH, false, D, S>), dim3(grid), dim3(kUniThreads), 0,      \
+                        theta, g, n, k, u, dtheta, partial);                                                                    \
+    } while (0)
+    if (want_dtheta && want_scalars) CDL_UNIB(true, true);
+    else if (want_dtheta) CDL_UNIB(true, false);
+    else CDL_UNIB(false, true);
+#undef CDL_UNIB
+}
+
 template <int W>
 void launch_bwd_w(bool want_dtheta, bool want_scalars, int grid, hipStream_t s, const float *theta,
                   const float *g, int64_t n, const QConst &k, float *dtheta, double *partial)
@@ -857,12 +1221,23 @@ int launch_quantize_fwd(const float *theta, int64_t n, const cdl_qparams &p,
     k.stream = n >= kStreamFrom;
     const int64_t grid64 = want_marg ? hist_grid_for(n) : grid_for(n);
     if (grid64 > 2147483647LL) return CDL_ERR_PARAM;
-    const int grid = (int)grid64;
+    int grid = (int)grid64;
     unsigned long long *partial = reinterpret_cast<unsigned long long *>(ws);
     unsigned long long *second = want_marg
         ? reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(ws) + hist_bytes(n, p.n_levels)) : nullptr;
     unsigned int *ticket = want_marg ? reinterpret_cast<unsigned int *>(second + kFinChunks * 256) : nullptr;
     const bool want_idx = idx != nullptr, want_soft = soft != nullptr;
+    const int jh = (want_soft || want_marg) ? uniform_half_width(p, k) : 0;
+    if (jh) {
+        const UniConst u = make_uniform(p, jh);
+        const int ugrid = grid < kMaxQuantBlocks ? grid : kMaxQuantBlocks;   // (any grid serves: the loop strides over the tensor)
+        int rcu = CDL_OK;
+        if (jh == 4) rcu = launch_fwd_uniform<4>(want_idx, want_soft, want_marg, ugrid, stream, theta, n, k, u, idx, soft, partial, ticket);
+        else if (jh == 8) rcu = launch_fwd_uniform<8>(want_idx, want_soft, want_marg, ugrid, stream, theta, n, k, u, idx, soft, partial, ticket);
+        else rcu = launch_fwd_uniform<16>(want_idx, want_soft, want_marg, ugrid, stream, theta, n, k, u, idx, soft, partial, ticket);
+        if (rcu != CDL_OK) return rcu;
+        grid = ugrid;
+    } else
     switch (band_template(k)) {
         case 1: launch_fwd<1>(want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
         case 2: launch_fwd<2>(want_idx, want_soft, want_marg, grid, stream, theta, n, k, idx, soft, partial, ticket); break;
@@ -901,6 +1276,13 @@ int launch_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl
     double *partial = want_scalars
         ? reinterpret_cast<double *>(reinterpret_cast<char *>(ws) + hist_bytes(n, p.n_levels) + aux_bytes()) : nullptr;
     const bool want_dtheta = dtheta != nullptr;
+    const int jh = uniform_half_width(p, k);
+    if (jh) {
+        const UniConst u = make_uniform(p, jh);
+        if (jh == 4) launch_bwd_uniform<4>(want_dtheta, want_scalars, grid, stream, theta, g, n, k, u, dtheta, partial);
+        else if (jh == 8) launch_bwd_uniform<8>(want_dtheta, want_scalars, grid, stream, theta, g, n, k, u, dtheta, partial);
+        else launch_bwd_uniform<16>(want_dtheta, want_scalars, grid, stream, theta, g, n, k, u, dtheta, partial);
+    } else
     switch (band_template(k)) {
         case 1: launch_bwd_w<1>(want_dtheta, want_scalars, grid, stream, theta, g, n, k, dtheta, partial); break;
         case 2: launch_bwd_w<2>(want_dtheta, want_scalars, grid, stream, theta, g, n, k, dtheta, partial); break;

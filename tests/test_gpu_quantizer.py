@@ -87,6 +87,41 @@ def test_smallest_widest_and_off_centre_level_sets(oracle, lo, L, kappa):
     gu.check_quantizer_scalars(oracle, "edge sets levels %d..%d kappa %g" % (lo, lo + L - 1, kappa), theta, g, q.args, dd, da, ref)
 
 
+@pytest.mark.parametrize("lo,L", [(0, 6), (-3, 7), (-4, 8), (100, 9), (-128, 10), (-8, 17), (0, 18), (95, 32), (-16, 33), (-128, 33)])
+@pytest.mark.parametrize("kappa,delta", [(0.004, 0.9), (0.05, 0.0731), (0.25, 0.011)])
+def test_soft_regime_on_small_level_sets(oracle, lo, L, kappa, delta):
+    """At most 33 levels, all of them live (the regime of the paper's initial sharpness, Sec. V-B): the kernels
+    that evaluate every entry about the centre of the level set.  Even and odd level counts, every padded loop
+    length, sets at either end of the int8 range, a large step (where a soft value next to zero has only the absolute
+    tolerance), values far outside the set, exact levels and midpoints, a ragged tail."""
+    n = 9001 + L
+    spec = _spec(lo, L, delta, kappa)
+    theta = _theta(lo, L, spec.delta, n, seed=L * 31 + abs(lo))
+    g = np.random.default_rng(L).standard_normal(n).astype(np.float32)
+    q = gu.Quantizer(spec)
+    th_d, g_d = gu.dev(theta), gu.dev(g)
+    idx, soft, marg, H = q.fwd(th_d)
+    r_idx, r_soft, r_gap = oracle.quantize_fwd(theta, *q.args)
+    r_marg, r_H = oracle.marginal_entropy(theta, *q.args)
+    gu.assert_indices(idx, r_idx, r_gap, "idx")
+    gu.assert_close(soft, r_soft, "soft")
+    gu.assert_close(marg, r_marg, "marg")
+    gu.assert_close([H], [r_H], "entropy")
+    marg2, H2 = q.marginal(th_d)
+    assert np.array_equal(marg2, marg) and H2 == H
+    _, soft_only, _, _ = q.fwd(th_d, marg=False)
+    assert np.array_equal(soft_only, soft)
+    dth, dd, da = q.bwd(th_d, g_d)
+    ref = oracle.quantize_bwd(theta, g, *q.args)
+    gu.assert_close(dth, ref["dtheta"], "dtheta")
+    gu.check_quantizer_scalars(oracle, "soft regime levels %d..%d kappa %g delta %g" % (lo, lo + L - 1, kappa, delta),
+                               theta, g, q.args, dd, da, ref)
+    dth_only, _, _ = q.bwd(th_d, g_d, scalars=False)
+    assert np.array_equal(dth_only, dth)
+    _, dd2, da2 = q.bwd(th_d, g_d, dtheta=False)
+    assert dd2 == dd and da2 == da
+
+
 @pytest.mark.parametrize("lo,L,kappa", [(-7, 15, 4.0), (0, 16, 31.25), (-15, 31, 0.008), (-127, 255, 4.0)])
 def test_marginal_entropy_entry_point_matches_oracle(oracle, lo, L, kappa):
     spec = _spec(lo, L, 0.02, kappa)
