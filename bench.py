@@ -10,11 +10,18 @@ seeded synthetic input, in the order of Algorithm 1 of the paper:
     backward products                           dL/dQ(X), dL/dQ(W)   (fp32 upstream gradient)
     quantizer backward for X and for W          dX, dW, d(step), d(sharpness)
 
-All inputs are resident in HBM before the timed region.  The default workload is
-the largest of the five (transformer-MLP-shaped, 8-bit levels).  One JSON line is
-printed; `value` is quantized tensor entries pushed through the whole step per
-second.  Per-kernel times come from HIP events the library records around each
-of its kernels on the launch stream during the timed steps.
+All inputs are resident in HBM before the timed region.  The timed step runs on the
+largest of the five workloads (transformer-MLP-shaped, 8-bit levels).  One JSON line
+is printed.  Its metric has two halves, and the line carries both:
+  value                the quantizer's forward + backward rate in Gelem/s on the flat 25.6 M-entry weight
+                       tensor (workload 4), from a cold cache, with its fraction of the 8 TB/s HBM peak beside it;
+  index_gemm_fwd_TOPS  the forward index product on the timed workload, with its fractions of the int8 peak
+                       and of its own roofline beside it.
+ms_per_step is the whole step on the timed workload (step_gelem_per_s: entries of W and X per second of it).
+Per-kernel times come from HIP events the library records around each of its kernels on the launch stream.
+Cache state of every figure: "cold" = a 1 GiB scrub buffer is written right before the timed call (the chip's
+last-level cache holds 256 MB); "warm" = calls back to back.  A step of workload 5 moves about 3.8 GB and is
+cold by its size.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload {1,2,3,4,5}]
 """
@@ -44,10 +51,12 @@ def log(*a):
 
 
 def ensure_built():
+    """The library must have been built from the sources in the tree: a missing or stale binary ends the run."""
     import paper_2501_09849_amd.build as b
-    if not os.path.exists(b.LIB_PATH):
-        log("[bench] libcdl.so missing: building")
-        b.build_lib()
+    if b.is_stale():
+        log("bench.py: %s is missing or was not built from the sources now in the tree; "
+            "run `python -m paper_2501_09849_amd.build` (or __graft_entry__.build()) first" % b.LIB_PATH)
+        sys.exit(4)
     import oracle
     oracle.build(force=False)
 
@@ -139,70 +148,128 @@ def kernel_model(wl, name, occurrence):
 
 
 def cpu_baseline(wl, step):
-    """Times the oracle, as it is, on a bounded sample of the same workload and scales to one step."""
+    """Times the oracle, as it is, on a bounded sample of the same workload and scales to one step.  The hard
+    indices the oracle produces on the way are compared with the GPU's on the same entries: the count of entries
+    that differ where the oracle's two best level scores are closer than 1e-6 (exempt near-ties), and of any
+    other difference (must be 0)."""
     import oracle
     parts = []
     t_all = time.time()
 
     def timed(f):
         t = time.perf_counter()
-        f()
-        return time.perf_counter() - t
+        r = f()
+        return time.perf_counter() - t, r
 
     est = 0.0
     w, x = wl.w_spec, wl.x_spec
-    for name, host, spec, n_full in (("W", step.W_host, w, step.nW),) + ((("X", step.X_host, x, step.nX),) if wl.has_gemm else ()):
+    index_check = {"sampled": 0, "exempt_near_ties": 0, "other_differences": 0}
+    for name, host, spec, n_full, idx_dev in ((("W", step.W_host, w, step.nW, step.Wi),)
+                                              + ((("X", step.X_host, x, step.nX, step.Xi),) if wl.has_gemm else ())):
         flat = host.reshape(-1)
         n_s = int(min(n_full, max(4096, 400_000_000 // spec.n_levels)))
         th = flat[:n_s]
         g = step.G_host.reshape(-1)[:n_s]
         a = (spec.lo, spec.n_levels, spec.delta, spec.alpha)
-        dt = timed(lambda: oracle.quantize_fwd(th, *a)) + timed(lambda: oracle.marginal_entropy(th, *a)) \
-            + timed(lambda: oracle.quantize_bwd(th, g, *a))
+        dt_f, (r_idx, _, gap) = timed(lambda: oracle.quantize_fwd(th, *a))
+        dt_m, _ = timed(lambda: oracle.marginal_entropy(th, *a))
+        dt_b, _ = timed(lambda: oracle.quantize_bwd(th, g, *a))
+        dt = dt_f + dt_m + dt_b
         est += dt * n_full / n_s
         parts.append("quantizer %s: %d of %d entries %.2fs" % (name, n_s, n_full, dt))
+        diff = idx_dev[:n_s].cpu().numpy().astype(np.int64) != r_idx
+        index_check["sampled"] += n_s
+        index_check["exempt_near_ties"] += int((diff & (gap < 1e-6)).sum())
+        index_check["other_differences"] += int((diff & (gap >= 1e-6)).sum())
     if wl.has_gemm:
         M, N, K = wl.M, wl.N, wl.K
         rows = int(max(1, min(M, 6.0e9 // (3.0 * N * K))))
         xi = cdl_inputs.draw_indices((rows, K), x.lo, x.hi, seed=1)   # timing does not depend on the index values
         wi = cdl_inputs.draw_indices((N, K), w.lo, w.hi, seed=2)
         g = step.G_host[:rows]
-        dt = timed(lambda: oracle.qgemm_fwd(xi, wi, x.delta, w.delta)) + timed(lambda: oracle.qgemm_bwd(g, xi, wi, x.delta, w.delta))
+        dt = timed(lambda: oracle.qgemm_fwd(xi, wi, x.delta, w.delta))[0] + timed(lambda: oracle.qgemm_bwd(g, xi, wi, x.delta, w.delta))[0]
         est += dt * M / rows
         parts.append("GEMM fwd+bwd: %d of %d rows %.2fs" % (rows, M, dt))
     n_total = step.nW + step.nX
     return {
-        "value": n_total / est / 1e9, "unit": "Gelem/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "value": n_total / est / 1e9, "unit": "Gelem/s (entries of W and X per second of one whole step)",
+        "cores": oracle.num_threads(), "kind": "oracle",
         "sample": "; ".join(parts) + "; scaled linearly to one full step (%.0fs estimated), measured in %.1fs"
                   % (est, time.time() - t_all),
-    }
+    }, index_check
 
 
-def quantizer_only(seed=0, iters=10):
-    """Quantizer fwd+bwd on the 25.6 M-entry flat weight tensor (31 levels): Gelem/s and fraction of HBM peak."""
-    import paper_2501_09849_amd as cdl
+SCRUB_BYTES = 1 << 30
+
+
+class Scrub:
+    """The cold-cache protocol: a 1 GiB buffer written right before a timed call, outside the library's events."""
+
+    def __init__(self):
+        import torch
+        self.buf = torch.empty(SCRUB_BYTES // 4, dtype=torch.float32, device="cuda:0")
+        self.n = 0
+
+    def __call__(self):
+        self.n += 1
+        self.buf.fill_(float(self.n))
+
+
+def timed_calls(calls, iters, scrub=None):
+    """Runs every call of `calls` (name -> function that enqueues library kernels) `iters` times with the library's
+    per-kernel events on; `scrub`, if given, runs before every call.  Returns name -> list of per-call kernel
+    time sums in us (one per iteration)."""
     import torch
+    import paper_2501_09849_amd as cdl
+    out = {k: [] for k in calls}
+    for k, f in calls.items():
+        for _ in range(2):
+            f()
+        torch.cuda.synchronize()
+        for _ in range(iters):
+            if scrub is not None:
+                scrub()
+            cdl.cdl_profile_enable(True)
+            f()
+            torch.cuda.synchronize()
+            recs = cdl.cdl_profile_collect()
+            cdl.cdl_profile_enable(False)
+            out[k].append(sum(ms for _, ms in recs) * 1e3)
+    return out
+
+
+def med_min(v):
+    return {"median_us": float(np.median(v)), "min_us": float(np.min(v))}
+
+
+def quantizer_only(scrub, seed=0, iters=10):
+    """Quantizer forward (index, soft value, marginal PMF, entropy) + backward (dtheta, d step, d sharpness) on the
+    25.6 M-entry flat weight tensor (31 levels), cold and warm, at kappa = 4 and at the paper's alpha = 500."""
+    import torch
+    import paper_2501_09849_amd as cdl
     wl = cdl_inputs.workload(4)
     st = Step(wl, seed)
-    for _ in range(3):
-        st.run()
-    torch.cuda.synchronize()
-    cdl.cdl_profile_enable(True)
-    for _ in range(iters):
-        st.run()
-    torch.cuda.synchronize()
-    recs = cdl.cdl_profile_collect()
-    cdl.cdl_profile_enable(False)
-    t = {}
-    for k, ms in recs:
-        t.setdefault(k, []).append(ms)
-    fwd = float(np.mean(t["quantize_fwd_kernel"])) + float(np.mean(t["marginal_finalize_kernel"]))
-    bwd = float(np.mean(t["quantize_bwd_kernel"])) + float(np.mean(t["scalar_finalize_kernel"]))
     n = wl.flat_n
-    gbs = 21.0 * n / ((fwd + bwd) * 1e-3) / 1e9
-    return {"workload": wl.name, "n": n, "levels": wl.w_spec.n_levels, "fwd_us": fwd * 1e3, "bwd_us": bwd * 1e3,
-            "gelem_per_s": n / ((fwd + bwd) * 1e-3) / 1e9, "algorithmic_GBps": gbs, "hbm_frac": gbs / HBM_PEAK_GBS,
-            "kappa": wl.w_spec.alpha * wl.w_spec.delta ** 2}
+    out = {"workload": "%d:%s" % (wl.number, wl.name), "n": n, "levels": wl.w_spec.n_levels,
+           "algorithmic_bytes_per_entry": {"fwd": 9, "bwd": 12}}
+    for tag, spec in (("kappa_4", wl.w_spec), ("alpha_500", wl.w_spec.with_alpha(cdl_inputs.ALPHA_PAPER))):
+        a = (spec.lo, spec.n_levels, spec.delta, spec.alpha)
+        calls = {
+            "fwd": lambda: cdl.cdl_quantize_fwd(st.W, n, *a, st.Wi, st.Wsoft, st.margW, st.scal[0:1], st.ws),
+            "bwd": lambda: cdl.cdl_quantize_bwd(st.W, st.G, n, *a, st.dW, st.scal[2:3], st.scal[3:4], st.ws),
+        }
+        row = {"kappa": spec.alpha * spec.delta ** 2}
+        for state, sc in (("cold", scrub), ("warm", None)):
+            t = timed_calls(calls, iters, sc)
+            tot = np.asarray(t["fwd"]) + np.asarray(t["bwd"])
+            med = float(np.median(tot))
+            row[state] = {"fwd": med_min(t["fwd"]), "bwd": med_min(t["bwd"]), "fwd_plus_bwd": med_min(tot),
+                          "gelem_per_s": n / med / 1e3, "algorithmic_GBps": 21.0 * n / med / 1e3,
+                          "hbm_frac": 21.0 * n / med / 1e3 / HBM_PEAK_GBS}
+        out[tag] = row
+    del st
+    torch.cuda.empty_cache()
+    return out
 
 
 def load_traffic(wl_number):
@@ -344,8 +411,8 @@ def extensions_bench(seed=0, iters=5):
     return out
 
 
-def gemm_only(number, seed=0, iters=5):
-    """The three index products on another workload's shape (workload 3: the ImageNet conv layer)."""
+def gemm_only(number, scrub, seed=0, iters=5):
+    """The three index products alone on another workload's shape, cold and warm, uniform random indices."""
     import torch
     import paper_2501_09849_amd as cdl
     wl = cdl_inputs.workload(number)
@@ -360,29 +427,51 @@ def gemm_only(number, seed=0, iters=5):
     dWh = torch.empty((N, K), dtype=torch.float32, device=dev)
     ws = torch.empty(max(256, cdl.qgemm_fwd_workspace_bytes(M, N, K), cdl.qgemm_bwd_workspace_bytes(M, N, K)),
                      dtype=torch.uint8, device=dev)
-
-    def run():
-        cdl.cdl_qgemm_fwd(Xi, Wi, M, N, K, x.delta, w.delta, None, Y, ws)
-        cdl.cdl_qgemm_bwd(G, Xi, Wi, M, N, K, x.delta, w.delta, dXh, dWh, ws)
-    for _ in range(2):
-        run()
-    torch.cuda.synchronize()
-    cdl.cdl_profile_enable(True)
-    for _ in range(iters):
-        run()
-    torch.cuda.synchronize()
-    recs = cdl.cdl_profile_collect()
-    cdl.cdl_profile_enable(False)
-    t = {}
-    for k, ms in recs:
-        t.setdefault(k, []).append(ms)
+    calls = {
+        "fwd": lambda: cdl.cdl_qgemm_fwd(Xi, Wi, M, N, K, x.delta, w.delta, None, Y, ws),
+        "d_a_hat": lambda: cdl.cdl_qgemm_bwd(G, Xi, Wi, M, N, K, x.delta, w.delta, dXh, None, ws),
+        "d_b_hat": lambda: cdl.cdl_qgemm_bwd(G, Xi, Wi, M, N, K, x.delta, w.delta, None, dWh, ws),
+    }
     ops = 2.0 * M * N * K
-    out = {"workload": "%d:%s" % (wl.number, wl.name), "M": M, "N": N, "K": K, "index_values": "uniform over the level sets"}
-    for key, name in (("fwd", "qgemm_kernel(fwd)"), ("d_a_hat", "limb_gemm_kernel(d_a_hat)"), ("d_b_hat", "limb_gemm_kernel(d_b_hat)")):
-        us = float(np.mean(t[name])) * 1e3
-        out[key + "_us"] = us
-        out[key + "_TOPS"] = ops / us / 1e6
-    out["bwd_total_us"] = sum(float(np.mean(v)) for k, v in t.items() if k != "qgemm_kernel(fwd)") * 1e3
+    t_hbm = (4.0 * M * N + 1.0 * (M + N) * K) / (HBM_PEAK_GBS * 1e9)
+    t_mfma = ops / (INT8_PEAK_TOPS * 1e12)
+    out = {"workload": "%d:%s" % (wl.number, wl.name), "M": M, "N": N, "K": K, "index_values": "uniform over the level sets",
+           "note": "d_a_hat / d_b_hat: one backward call each, helper kernels (max|g|, transposition, plan, reduction) included"}
+    for state, sc in (("cold", scrub), ("warm", None)):
+        t = timed_calls(calls, iters, sc)
+        row = {}
+        for key in calls:
+            mm = med_min(t[key])
+            mm["TOPS"] = ops / mm["median_us"] / 1e6
+            mm["frac_of_int8_peak"] = mm["TOPS"] / INT8_PEAK_TOPS
+            row[key] = mm
+        row["fwd"]["frac_of_roofline"] = max(t_hbm, t_mfma) * 1e6 / row["fwd"]["median_us"]
+        row["fwd"]["roofline_bound"] = "hbm" if t_hbm > t_mfma else "mfma"
+        out[state] = row
+    del Xi, Wi, G, Y, dXh, dWh, ws
+    torch.cuda.empty_cache()
+    return out
+
+
+def small_step(number, steps=20, warmup=3):
+    """One whole layer step on a small workload (1: the tiny linear layer, 2: the CIFAR conv as an im2col GEMM)."""
+    import torch
+    wl = cdl_inputs.workload(number)
+    st = Step(wl)
+    for _ in range(warmup):
+        st.run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        st.run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    t = timed_calls({"step": st.run}, 5)
+    n_total = st.nW + st.nX
+    out = {"workload": "%d:%s" % (wl.number, wl.name), "M": wl.M, "N": wl.N, "K": wl.K, "ms_per_step": ms,
+           "step_gelem_per_s": n_total / (ms * 1e-3) / 1e9, "sum_of_kernel_times": med_min(t["step"]), "cache": "warm (steps back to back)"}
+    del st
+    torch.cuda.empty_cache()
     return out
 
 
@@ -434,7 +523,7 @@ def main():
 
     ms_per_step = elapsed * 1e3 / args.steps
     n_total = st.nW + st.nX
-    value = n_total / (elapsed / args.steps) / 1e9
+    step_rate = n_total / (elapsed / args.steps) / 1e9
 
     # per-kernel table: launches are grouped by (name, position among same-named launches within a step)
     per_step = len(recs) // args.steps
@@ -449,7 +538,8 @@ def main():
     for (name, occ), v in table.items():
         avg = float(np.mean(v))
         bound, amount, n_el = kernel_model(wl, name, occ)
-        row = {"kernel": name, "launch": occ, "avg_us": avg * 1e3, "min_us": float(np.min(v)) * 1e3}
+        row = {"kernel": name, "launch": occ, "avg_us": avg * 1e3, "median_us": float(np.median(v)) * 1e3,
+               "min_us": float(np.min(v)) * 1e3}
         if bound == "hbm":
             row.update(bound="hbm", algorithmic_GBps=amount / (avg * 1e-3) / 1e9,
                        frac=amount / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS)
@@ -459,18 +549,20 @@ def main():
         kernels.append(row)
     dom = max(kernels, key=lambda r: r["avg_us"])
     traffic = traffic_of(load_traffic(wl.number), dom["kernel"], dom["launch"])
+    traffic_source = ("profiles/hbm_traffic_workload%d.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this "
+                      "command, not measured by this run)" % wl.number) if traffic is not None else None
     if dom.get("bound") == "mfma":
         roofline = {"kernel": "%s #%d" % (dom["kernel"], dom["launch"]), "bound": "mfma", "achieved": dom["algorithmic_TOPS"],
                     "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": dom["frac"], "traffic": traffic,
-                    "avg_launch_us": dom["avg_us"]}
+                    "traffic_source": traffic_source, "avg_launch_us": dom["avg_us"]}
     else:
         roofline = {"kernel": "%s #%d" % (dom["kernel"], dom["launch"]), "bound": "hbm", "achieved": dom.get("algorithmic_GBps"),
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom.get("frac"), "traffic": traffic,
-                    "avg_launch_us": dom["avg_us"]}
+                    "traffic_source": traffic_source, "avg_launch_us": dom["avg_us"]}
 
     out = OrderedDict()
     out["metric"] = METRIC
-    out["value"] = value
+    out["value"] = None          # set below: the quantizer's rate on workload 4 from a cold cache
     out["unit"] = "Gelem/s"
     out["n_gpus"] = 1
     out["steps"] = args.steps
@@ -479,16 +571,18 @@ def main():
     out["higher_is_better"] = True
     out["scaling"] = "weak"
     out["vs_baseline"] = None
-    out["dtype"] = "f32 quantizer, int8 x int8 -> int32 products"
+    out["dtype"] = "f32 quantizer (f64 in its soft-regime kernels), int8 x int8 -> int32 products"
     out["data"] = "synthetic"
     cfg = {"workload": "%d:%s" % (wl.number, wl.name), "entries_per_step": n_total,
-           "w_levels": wl.w_spec.n_levels, "kappa": wl.w_spec.alpha * wl.w_spec.delta ** 2}
+           "w_levels": wl.w_spec.n_levels, "kappa": wl.w_spec.alpha * wl.w_spec.delta ** 2,
+           "cache": "cold by size: a step moves about 3.8 GB, the last-level cache holds 256 MB" if wl.number == 5 else "steps back to back"}
     if wl.has_gemm:
         cfg.update(M=wl.M, N=wl.N, K=wl.K, x_levels=wl.x_spec.n_levels)
     out["config"] = cfg
+    out["step_gelem_per_s"] = step_rate
     out["roofline"] = roofline
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, st)
+        out["cpu_baseline"], out["hard_index_check"] = cpu_baseline(wl, st)
     if wl.has_gemm:
         # limb counts of the two backward products (diagnostic words at the start of the workspace): the int8 work
         # actually issued is that many times the product's own 2*M*N*K
@@ -505,7 +599,9 @@ def main():
     out["kernels"] = kernels
     q_us = sum(r["avg_us"] for r in kernels if r["kernel"] in ("quantize_fwd_kernel", "quantize_bwd_kernel",
                                                                  "marginal_finalize_kernel", "scalar_finalize_kernel"))
-    out["quantizer_fwd_bwd_gelem_per_s"] = n_total / (q_us * 1e-6) / 1e9 if q_us else None
+    if q_us:
+        out["quantizer_in_step"] = {"gelem_per_s": n_total / (q_us * 1e-6) / 1e9, "hbm_frac": 21.0 * n_total / (q_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                                    "us": q_us, "cache": "cold by size"}
     gf = [r for r in kernels if r["kernel"] == "qgemm_kernel(fwd)"]
     if gf:
         out["index_gemm_fwd_TOPS"] = gf[0]["algorithmic_TOPS"]
@@ -520,11 +616,26 @@ def main():
         out["step_as_hip_graph"] = graph_replay(st, args.steps)
     del st
     torch.cuda.empty_cache()
+    scrub = Scrub()
+    qo = quantizer_only(scrub)
+    out["quantizer_only_flat_25M"] = qo
+    out["value"] = qo["kappa_4"]["cold"]["gelem_per_s"]
+    out["value_is"] = ("quantizer forward (index, soft value, marginal PMF, entropy) + backward (dtheta, d step, d sharpness) on "
+                       "workload 4 (25.6 M entries, 31 levels, kappa 4), cache cold, median of 10; hbm_frac beside it")
+    out["value_hbm_frac"] = qo["kappa_4"]["cold"]["hbm_frac"]
+    out["targets"] = {
+        "quantizer_fwd_bwd_hbm_frac": {"target": 0.70, "achieved_cold": qo["kappa_4"]["cold"]["hbm_frac"],
+                                       "achieved_warm": qo["kappa_4"]["warm"]["hbm_frac"],
+                                       "met": bool(qo["kappa_4"]["cold"]["hbm_frac"] >= 0.70)},
+    }
+    if gf:
+        out["targets"]["index_gemm_frac_of_int8_peak"] = {"target": 0.60, "achieved": gf[0]["frac"], "met": bool(gf[0]["frac"] >= 0.60),
+                                                          "hbm_limited_ceiling": min(1.0, t_mfma / max(t_hbm, t_mfma))}
     if not args.no_extra:
-        if wl.number != 4:
-            out["quantizer_only_flat_25M"] = quantizer_only()
-        if wl.number != 3:
-            out["index_gemms_conv_layer"] = gemm_only(3)
+        out["small_workloads"] = [small_step(1), small_step(2)]
+        out["index_gemms_alone"] = [gemm_only(n_, scrub) for n_ in (2, 3) if n_ != wl.number]
+        del scrub
+        torch.cuda.empty_cache()
         out["extensions_flat_25M"] = extensions_bench()
         out["machine"] = machine_probes()
     print(json.dumps(out), flush=True)

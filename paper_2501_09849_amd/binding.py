@@ -54,6 +54,11 @@ def load():
         if not os.path.exists(_LIB_PATH):
             raise RuntimeError("libcdl.so is not built: run `python -m paper_2501_09849_amd.build` "
                                "(or __graft_entry__.build()) first; there is no fallback path")
+        from . import build as _build
+        if _LIB_PATH == _build.LIB_PATH and _build.is_stale():
+            raise RuntimeError("libcdl.so was not built from the sources now in the tree (csrc/*.hip, csrc/*.h, "
+                               "include/*.h or the compiler flags changed since): run `python -m "
+                               "paper_2501_09849_amd.build` again; a stale binary is never loaded")
         # PyTorch-ROCm carries its own copy of the HIP runtime and loads it by path.  If libcdl.so came first,
         # the system's copy would be in the process as well, the two would not share a device context, and
         # every launch on torch's memory would fail with hipErrorNoDevice: let torch's be the first one.

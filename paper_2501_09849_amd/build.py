@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import glob
+import hashlib
 import os
 import subprocess
 
@@ -25,12 +26,31 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
+HASH_PATH = LIB_PATH + ".srchash"
+
+
+def _deps():
+    return sources() + sorted(glob.glob(os.path.join(CSRC, "*.h"))) + sorted(glob.glob(os.path.join(_ROOT, "include", "*.h")))
+
+
+def source_hash() -> str:
+    """sha256 over the compiler flags and every source and header the library is built from (contents, not
+    time stamps: a copy of the tree to another machine keeps it)."""
+    h = hashlib.sha256()
+    h.update(" ".join(HIPCC_FLAGS).encode())
+    for path in _deps():
+        h.update(os.path.basename(path).encode())
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
 def is_stale() -> bool:
-    if not os.path.exists(LIB_PATH):
+    """True when libcdl.so is missing or was not built from the sources now in the tree."""
+    if not (os.path.exists(LIB_PATH) and os.path.exists(HASH_PATH)):
         return True
-    t = os.path.getmtime(LIB_PATH)
-    deps = sources() + glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(_ROOT, "include", "*.h"))
-    return any(os.path.getmtime(d) > t for d in deps)
+    with open(HASH_PATH) as f:
+        return f.read().strip() != source_hash()
 
 
 def build_lib(verbose: bool = False) -> str:
@@ -46,6 +66,9 @@ def build_lib(verbose: bool = False) -> str:
     if verbose and res.stdout.strip():
         print(res.stdout)
     os.replace(tmp, LIB_PATH)
+    if LIB_PATH.endswith(os.path.join(os.path.basename(_HERE), "libcdl.so")):
+        with open(HASH_PATH, "w") as f:
+            f.write(source_hash() + "\n")
     return LIB_PATH
 
 

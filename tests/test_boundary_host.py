@@ -160,3 +160,14 @@ def test_window_rule_matches_the_documented_bound():
         assert W == want, (kappa, W, want)
         m = W + 1
         assert m ** 3 * math.exp(-kappa * m * (m - 1)) < 3.1e-9
+
+
+def test_a_stale_binary_is_detected_by_content(monkeypatch):
+    """The loader refuses a libcdl.so that was not built from the sources in the tree: the check hashes file
+    contents and compiler flags, so it survives a copy of the tree that resets every time stamp."""
+    import paper_2501_09849_amd.build as b
+    assert not b.is_stale(), "the library in the tree must have been built from the tree's sources (run the build)"
+    h = b.source_hash()
+    assert h == b.source_hash()
+    monkeypatch.setattr(b, "HIPCC_FLAGS", b.HIPCC_FLAGS + ["-DSOMETHING_ELSE"])
+    assert b.source_hash() != h and b.is_stale()
