@@ -37,7 +37,7 @@ def build(force: bool = True) -> str:
 _f32p = ctypes.POINTER(ctypes.c_float)
 _f64p = ctypes.POINTER(ctypes.c_double)
 _i32p = ctypes.POINTER(ctypes.c_int32)
-_i8p = ctypes.POINTER(ctypes.c_int8)
+_i16p = ctypes.POINTER(ctypes.c_int16)
 
 
 def lib():
@@ -91,13 +91,13 @@ def lib():
                                              ctypes.c_float, ctypes.c_float, ctypes.c_int, _f64p, ctypes.c_double,
                                              _f64p, _f64p, _f64p, _f64p, _f64p]
         L.cdl_oracle_huffman_bits.restype = None
-        L.cdl_oracle_huffman_bits.argtypes = [_i8p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+        L.cdl_oracle_huffman_bits.argtypes = [_i16p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
                                               ctypes.POINTER(ctypes.c_int64), _f64p, _f64p]
         L.cdl_oracle_qgemm_fwd.restype = None
-        L.cdl_oracle_qgemm_fwd.argtypes = [_i8p, _i8p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+        L.cdl_oracle_qgemm_fwd.argtypes = [_i16p, _i16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_float, ctypes.c_float, _i32p, _f64p]
         L.cdl_oracle_qgemm_bwd.restype = None
-        L.cdl_oracle_qgemm_bwd.argtypes = [_f32p, _i8p, _i8p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+        L.cdl_oracle_qgemm_bwd.argtypes = [_f32p, _i16p, _i16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_float, ctypes.c_float, _f64p, _f64p]
         _LIB = L
     return _LIB
@@ -226,25 +226,25 @@ def entropy_bwd(theta: np.ndarray, marg: np.ndarray, lo: int, n_levels: int, del
 
 def huffman_bits(idx: np.ndarray, lo: int, n_levels: int):
     """Huffman-coded size of a tensor of level indices: (counts int64[n_levels], total bits, bits per entry)."""
-    ii = _c(idx, np.int8).reshape(-1)
+    ii = _c(idx, np.int16).reshape(-1)
     counts = np.zeros(n_levels, dtype=np.int64)
     tot, avg = ctypes.c_double(), ctypes.c_double()
-    lib().cdl_oracle_huffman_bits(_ptr(ii, _i8p), ii.size, lo, n_levels,
+    lib().cdl_oracle_huffman_bits(_ptr(ii, _i16p), ii.size, lo, n_levels,
                                   counts.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), ctypes.byref(tot), ctypes.byref(avg))
     return counts, tot.value, avg.value
 
 
 def qgemm_fwd(a_idx: np.ndarray, b_idx: np.ndarray, delta_a: float, delta_b: float,
               want_y: bool = True):
-    """a_idx int8[M,K], b_idx int8[N,K] -> (acc int32[M,N], y float64[M,N] | None)."""
-    a = _c(a_idx, np.int8)
-    b = _c(b_idx, np.int8)
+    """a_idx [M,K], b_idx [N,K] level indices (any integer type, values within int16) -> (acc int32[M,N], y float64[M,N] | None)."""
+    a = _c(a_idx, np.int16)
+    b = _c(b_idx, np.int16)
     M, K = a.shape
     N, K2 = b.shape
     assert K == K2
     acc = np.empty((M, N), dtype=np.int32)
     y = np.empty((M, N), dtype=np.float64) if want_y else None
-    lib().cdl_oracle_qgemm_fwd(_ptr(a, _i8p), _ptr(b, _i8p), M, N, K, float(delta_a), float(delta_b),
+    lib().cdl_oracle_qgemm_fwd(_ptr(a, _i16p), _ptr(b, _i16p), M, N, K, float(delta_a), float(delta_b),
                                _ptr(acc, _i32p), _ptr(y, _f64p))
     return acc, y
 
@@ -253,13 +253,13 @@ def qgemm_bwd(g: np.ndarray, a_idx: np.ndarray, b_idx: np.ndarray, delta_a: floa
               want_da: bool = True, want_db: bool = True):
     """g fp32[M,N] -> (d_a_hat float64[M,K] | None, d_b_hat float64[N,K] | None)."""
     gg = _c(g, np.float32)
-    a = _c(a_idx, np.int8)
-    b = _c(b_idx, np.int8)
+    a = _c(a_idx, np.int16)
+    b = _c(b_idx, np.int16)
     M, K = a.shape
     N, K2 = b.shape
     assert K == K2 and gg.shape == (M, N)
     da = np.empty((M, K), dtype=np.float64) if want_da else None
     db = np.empty((N, K), dtype=np.float64) if want_db else None
-    lib().cdl_oracle_qgemm_bwd(_ptr(gg, _f32p), _ptr(a, _i8p), _ptr(b, _i8p), M, N, K,
+    lib().cdl_oracle_qgemm_bwd(_ptr(gg, _f32p), _ptr(a, _i16p), _ptr(b, _i16p), M, N, K,
                                float(delta_a), float(delta_b), _ptr(da, _f64p), _ptr(db, _f64p))
     return da, db

@@ -461,8 +461,12 @@ void cdl_oracle_entropy_bwd(const float *theta, int64_t n, int lo, int n_levels,
  *   acc[m,n] = sum_k a_idx[m,k] * b_idx[n,k]          (exact integers)
  *   y[m,n]   = delta_a * delta_b * acc[m,n]
  * Both index matrices are row-major with the contraction index contiguous.
+ * The indices are the level indices themselves, whatever the level set (the
+ * paper's unsigned b-bit set {0, ..., 2^b - 1} of eq. repo_alphabet reaches 255
+ * for the 8-bit first and last layers of Sec. V-B), hence 16-bit here; how a
+ * library stores them is its own business.
  * ---------------------------------------------------------------------- */
-void cdl_oracle_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int M, int N, int K,
+void cdl_oracle_qgemm_fwd(const int16_t *a_idx, const int16_t *b_idx, int M, int N, int K,
                           float delta_a, float delta_b,
                           int32_t *acc /* M*N, nullable */, double *y /* M*N, nullable */)
 {
@@ -489,7 +493,7 @@ void cdl_oracle_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int M, int N
  * These are dL/dQ_p(x) and dL/dQ_p(w) of Sec. IV-B, the factors that the
  * quantizer backward multiplies by dQd/dtheta.
  */
-void cdl_oracle_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
+void cdl_oracle_qgemm_bwd(const float *g, const int16_t *a_idx, const int16_t *b_idx,
                           int M, int N, int K, float delta_a, float delta_b,
                           double *d_a_hat /* M*K, nullable */, double *d_b_hat /* N*K, nullable */)
 {
@@ -524,7 +528,7 @@ void cdl_oracle_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_i
  * besides the counts.  Reading for the degenerate case the paper does not mention: a tensor in
  * which a single level occurs costs one bit per entry; an empty tensor costs 0.
  * ---------------------------------------------------------------------- */
-void cdl_oracle_huffman_bits(const int8_t *idx, int64_t n, int lo, int n_levels,
+void cdl_oracle_huffman_bits(const int16_t *idx, int64_t n, int lo, int n_levels,
                              int64_t *counts /* n_levels */, double *total_bits, double *bits_per_entry)
 {
     for (int k = 0; k < n_levels; ++k) counts[k] = 0;

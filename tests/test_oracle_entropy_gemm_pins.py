@@ -86,6 +86,35 @@ def test_qgemm_fwd_matches_numpy_and_dequantised_product(oracle):
     np.testing.assert_allclose(y, deq, rtol=1e-12, atol=1e-15)
 
 
+def test_qgemm_on_the_unsigned_8_bit_alphabet(oracle):
+    """The paper's unsigned b-bit activation alphabet {0, ..., 2^b - 1} (eq. repo_alphabet) with b = 8, the width it
+    keeps for the first and last layers (Sec. V-B): indices up to 255 on either operand.  Brute force with Python
+    integers on a tiny case, numpy int64 / float64 on a larger one, for the forward product and both gradients."""
+    rng = np.random.default_rng(77)
+    a = rng.integers(0, 256, (4, 9)).astype(np.int16)
+    b = rng.integers(0, 256, (3, 9)).astype(np.int16)
+    a[0, :] = 255
+    b[0, :] = 255
+    acc, y = oracle.qgemm_fwd(a, b, 0.5, 0.25)
+    for m in range(4):
+        for n in range(3):
+            s = sum(int(a[m, k]) * int(b[n, k]) for k in range(9))
+            assert acc[m, n] == s and y[m, n] == pytest.approx(0.125 * s, rel=1e-15)
+    assert acc[0, 0] == 9 * 255 * 255
+    M, N, K = 33, 12, 257
+    a = rng.integers(0, 256, (M, K)).astype(np.int16)
+    b = rng.integers(-128, 128, (N, K)).astype(np.int16)
+    g = rng.normal(0, 1, (M, N)).astype(np.float32)
+    da, db = float(np.float32(0.0731)), float(np.float32(0.011))
+    acc, y = oracle.qgemm_fwd(a, b, da, db)
+    assert np.array_equal(acc.astype(np.int64), a.astype(np.int64) @ b.astype(np.int64).T)
+    d_a, d_b = oracle.qgemm_bwd(g, a, b, da, db)
+    g64 = g.astype(np.float64)
+    # (sums of a few hundred terms of size 10 in two different orders: 1e-12 absolute)
+    np.testing.assert_allclose(d_a, g64 @ (b.astype(np.float64) * db), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(d_b, g64.T @ (a.astype(np.float64) * da), rtol=1e-12, atol=1e-12)
+
+
 # ---------------------------------------------------------------- index GEMM backward
 
 def test_qgemm_bwd_matches_numpy_and_directional_derivative(oracle):

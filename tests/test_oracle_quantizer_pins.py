@@ -91,7 +91,7 @@ def _nearest_level_exact(theta: float, delta: float, lo: int, hi: int) -> int:
 
 def test_hard_index_is_nearest_level_with_clamping(oracle):
     rng = np.random.default_rng(3)
-    for lo, L in [(-4, 8), (-7, 15), (0, 16), (-127, 255)]:
+    for lo, L in [(-4, 8), (-7, 15), (0, 16), (-127, 255), (0, 256), (130, 126)]:
         delta = float(np.float32(0.0731))
         alpha = float(np.float32(4.0 / delta ** 2))
         theta = rng.uniform((lo - 3) * delta, (lo + L + 2) * delta, size=300).astype(np.float32)
@@ -102,6 +102,26 @@ def test_hard_index_is_nearest_level_with_clamping(oracle):
     # far outside the range: clamps to the end levels
     idx, _, _ = oracle.quantize_fwd(np.array([-1e3, 1e3, -0.6, 5.0], np.float32), -7, 15, 0.02, 1e4)
     assert idx.tolist() == [-7, 7, -7, 7]
+
+
+def test_unsigned_8_bit_alphabet_end_levels_and_softmax(oracle):
+    """Level set {0, ..., 255} (eq. repo_alphabet with b = 8): clamping at 0 and 255, the CPMF against scipy's softmax,
+    and the two-level logistic closed form shifted to the top pair of levels (254, 255)."""
+    from scipy.special import softmax
+    delta, alpha = float(np.float32(0.05)), float(np.float32(900.0))
+    idx, soft, _ = oracle.quantize_fwd(np.array([-3.0, 0.0, 12.7499, 12.75, 100.0, 6.3751], np.float32), 0, 256, delta, alpha)
+    assert idx.tolist() == [0, 0, 255, 255, 255, 128]
+    theta = 11.93
+    P, mode, _ = oracle.cpmf(theta, 0, 256, delta, alpha)
+    ref = softmax(-alpha * (theta - np.arange(256) * delta) ** 2)
+    np.testing.assert_allclose(P, ref, rtol=1e-12, atol=1e-300)
+    assert mode == int(np.argmax(ref)) == 239
+    # far above the set only the top two levels matter: P(255) = expit(alpha delta (2 theta - (254 + 255) delta))
+    theta = 12.78
+    P, _, _ = oracle.cpmf(theta, 0, 256, delta, alpha)
+    assert P[255] == pytest.approx(expit(alpha * delta * (2 * theta - 509 * delta)), rel=1e-9)
+    el = oracle.element(theta, 0, 256, delta, alpha)
+    assert el["soft"] == pytest.approx(delta * (254 + P[255]), rel=1e-9)
 
 
 def test_hard_index_tie_goes_to_lower_level(oracle):
