@@ -117,11 +117,13 @@ def test_unsigned_8_bit_alphabet_end_levels_and_softmax(oracle):
     np.testing.assert_allclose(P, ref, rtol=1e-12, atol=1e-300)
     assert mode == int(np.argmax(ref)) == 239
     # far above the set only the top two levels matter: P(255) = expit(alpha delta (2 theta - (254 + 255) delta))
-    theta = 12.78
+    # (at theta = 12.9 level 253 carries e^-36 of the top level's weight)
+    theta = 12.9
     P, _, _ = oracle.cpmf(theta, 0, 256, delta, alpha)
-    assert P[255] == pytest.approx(expit(alpha * delta * (2 * theta - 509 * delta)), rel=1e-9)
+    assert P[254] == pytest.approx(expit(-alpha * delta * (2 * theta - 509 * delta)), rel=1e-9)
+    assert P[255] == pytest.approx(expit(alpha * delta * (2 * theta - 509 * delta)), rel=1e-12)
     el = oracle.element(theta, 0, 256, delta, alpha)
-    assert el["soft"] == pytest.approx(delta * (254 + P[255]), rel=1e-9)
+    assert el["soft"] == pytest.approx(delta * (254 + P[255]), rel=1e-12)
 
 
 def test_hard_index_tie_goes_to_lower_level(oracle):
