@@ -40,8 +40,12 @@ extern "C" {
  * A uniform quantizer of the paper (Sec. III-A, Sec. IV-A): index set {lo, ..., lo+n_levels-1},
  * reproduction value of index i is i*delta (the paper's q_l for weights, s_l for activations),
  * sharpness alpha (the paper's alpha_l / beta_l).  The paper's signed b-bit set is
- * lo = -2^(b-1), n_levels = 2^b; its unsigned set is lo = 0, n_levels = 2^b; any contiguous set
- * inside [-128, 127] is accepted, so indices always fit an int8.
+ * lo = -2^(b-1), n_levels = 2^b; its unsigned set (eq. repo_alphabet) is lo = 0, n_levels = 2^b.
+ * Accepted: any contiguous set inside [-128, 127], and any contiguous set inside [0, 255] - which
+ * includes the unsigned 8-bit set the paper keeps for the first and last layer (Sec. V-B).
+ * Level indices are stored as int8: as they are for sets inside [-128, 127], and as index - 128 for
+ * sets that reach beyond 127; cdl_index_offset() returns that offset (0 or 128) for a quantizer, and
+ * the *_offset forms of the layer products take it for each operand.
  * top_k = 0: the CPMF of eq. CPMF over all levels.  top_k = 1, 3, 5, 7 or 9: the CPMF truncated to its
  * top_k most probable values (Sec. V-B, where the paper uses five for activations):
  * the top_k most probable levels - the nearest ones, lower index first on a tie - keep their
@@ -60,7 +64,7 @@ typedef enum cdl_status {
     CDL_OK            =  0,
     CDL_ERR_NULL      = -1,   /* a required pointer is NULL */
     CDL_ERR_PARAM     = -2,   /* negative size, n_levels < 2, delta/alpha not finite and positive, ... */
-    CDL_ERR_RANGE     = -3,   /* level set leaves [-128,127], or an int32 accumulator could overflow */
+    CDL_ERR_RANGE     = -3,   /* level set inside neither [-128,127] nor [0,255], or an int32 accumulator could overflow */
     CDL_ERR_ALIGN     = -4,   /* pointer alignment, see above */
     CDL_ERR_WORKSPACE = -5,   /* ws is NULL or smaller than the query says */
     CDL_ERR_HIP       = -6,   /* a HIP call failed; see cdl_last_hip_error() */
@@ -73,6 +77,16 @@ size_t cdl_quantize_workspace_bytes(int64_t n, int32_t n_levels);
 /* Scratch needed by cdl_qgemm_fwd (staging copies when K is not a multiple of 16). */
 size_t cdl_qgemm_fwd_workspace_bytes(int32_t M, int32_t N, int32_t K);
 
+/* Scratch needed by cdl_qgemm_fwd_offset (the above plus one int32 per output row and column). */
+size_t cdl_qgemm_fwd_offset_workspace_bytes(int32_t M, int32_t N, int32_t K);
+
+/*
+ * What the library subtracts from the level indices of this quantizer before storing them as int8:
+ * 0 for level sets inside [-128, 127], 128 for sets that reach beyond 127 (eq. repo_alphabet with b = 8:
+ * {0, ..., 255} is stored as -128 ... 127).  A negative cdl_status for invalid parameters.
+ */
+int32_t cdl_index_offset(const cdl_qparams *p);
+
 /* Scratch needed by cdl_qgemm_bwd (transposed index copies, partial sums of the split contraction). */
 size_t cdl_qgemm_bwd_workspace_bytes(int32_t M, int32_t N, int32_t K);
 
@@ -81,7 +95,8 @@ size_t cdl_qgemm_bwd_workspace_bytes(int32_t M, int32_t N, int32_t K);
  * eq. softboth).  For each entry theta[e] the conditional PMF over the levels is
  * softmax_i(-alpha (theta[e] - i delta)^2).  Outputs:
  *   idx[e]   the level index at the mode of that PMF, i.e. the nearest level, clamped to the set;
- *            an exact tie between two levels goes to the lower index          (int8[n], required)
+ *            an exact tie between two levels goes to the lower index; stored minus
+ *            cdl_index_offset(p)                                               (int8[n], required)
  *   soft[e]  Q_d(theta[e]) = sum_i P_i * i * delta                            (fp32[n], nullable)
  *   marg[k]  (1/n) sum_e P(level lo+k | theta[e]), the marginal PMF of eq. approx1/n
  *                                                                      (fp32[n_levels], nullable)
@@ -169,8 +184,9 @@ int cdl_entropy_bwd(const float *theta, const float *marg, const float *g_in, in
  *   counts[k]      = number of entries equal to level lo + k       (DEVICE uint64[n_levels], nullable)
  *   total_bits     = total code length of an optimal prefix code   (DEVICE uint64[1], nullable)
  *   bits_per_entry = total_bits / n                                (DEVICE fp32[1], nullable)
- * idx: DEVICE int8[n], 16-byte aligned (the hard indices or the draws of the quantizer); entries
- * outside [lo, lo + n_levels) are ignored.  The total is the same for every Huffman tree of the
+ * idx: DEVICE int8[n], 16-byte aligned (the hard indices or the draws of the quantizer, stored as the
+ * quantizer stores them: minus 128 for a level set that reaches beyond 127); entries outside
+ * [lo, lo + n_levels) are ignored.  The total is the same for every Huffman tree of the
  * counts.  A tensor in which a single level occurs costs one bit per entry (the paper does not
  * treat the case); n = 0 gives zeros.  Scratch: cdl_huffman_workspace_bytes(n), 256-byte aligned.
  */
@@ -190,6 +206,20 @@ int cdl_huffman_bits(const int8_t *idx, int64_t n, int32_t lo, int32_t n_levels,
 int cdl_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
                   float delta_a, float delta_b, int32_t *acc, float *y,
                   void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * The same product for operands stored with an offset (Sec. IV-A on the unsigned 8-bit alphabet of
+ * eq. repo_alphabet; first and last layer in Sec. V-B): a_idx holds level index - a_offset, b_idx holds
+ * level index - b_offset (each offset 0 or 128, as cdl_index_offset reports for the operand's quantizer), and
+ *   acc[m,n] = sum_k (a_idx[m,k] + a_offset) * (b_idx[n,k] + b_offset),
+ * the product of the level indices themselves: the matrix cores multiply the stored int8 values, and the
+ * epilogue adds a_offset * sum_k b_idx[n,k] + b_offset * sum_k a_idx[m,k] + K * a_offset * b_offset from row
+ * sums that a small kernel forms first.  CDL_ERR_RANGE if K products of indices up to 255 (operand with offset)
+ * or 128 could overflow int32; CDL_ERR_PARAM for other offsets.  Scratch: cdl_qgemm_fwd_offset_workspace_bytes.
+ */
+int cdl_qgemm_fwd_offset(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
+                         float delta_a, float delta_b, int32_t a_offset, int32_t b_offset,
+                         int32_t *acc, float *y, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * Backward of that product with respect to the two quantized operands (Algorithm 1, backward
@@ -212,6 +242,19 @@ int cdl_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
                   int32_t M, int32_t N, int32_t K, float delta_a, float delta_b,
                   float *d_a_hat, float *d_b_hat,
                   void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * cdl_qgemm_bwd for operands stored with an offset (see cdl_qgemm_fwd_offset): the gradients with respect to
+ * the quantized operands whose level indices are a_idx + a_offset and b_idx + b_offset,
+ *   d_a_hat[m,k] = delta_b * sum_n g[m,n] * (b_idx[n,k] + b_offset)
+ *   d_b_hat[n,k] = delta_a * sum_m g[m,n] * (a_idx[m,k] + a_offset).
+ * The offset parts, b_offset * delta_b * sum_n g[m,n] and a_offset * delta_a * sum_m g[m,n], are sums of the
+ * unrounded fp32 gradient taken in double by separate passes over g.  Scratch: cdl_qgemm_bwd_workspace_bytes.
+ */
+int cdl_qgemm_bwd_offset(const float *g, const int8_t *a_idx, const int8_t *b_idx,
+                         int32_t M, int32_t N, int32_t K, float delta_a, float delta_b,
+                         int32_t a_offset, int32_t b_offset, float *d_a_hat, float *d_b_hat,
+                         void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * Optional per-kernel timing (a measurement aid, not part of the method).  While enabled, every

@@ -16,6 +16,7 @@ _LIB = None
 
 EXPORTS = (
     "cdl_quantize_workspace_bytes", "cdl_qgemm_fwd_workspace_bytes", "cdl_qgemm_bwd_workspace_bytes",
+    "cdl_qgemm_fwd_offset_workspace_bytes", "cdl_index_offset", "cdl_qgemm_fwd_offset", "cdl_qgemm_bwd_offset",
     "cdl_quantize_fwd", "cdl_quantize_fwd_static", "cdl_static_scratch_bytes", "cdl_quantize_bwd", "cdl_marginal_entropy", "cdl_qgemm_fwd", "cdl_qgemm_bwd",
     "cdl_quantize_draw", "cdl_entropy_bwd", "cdl_huffman_workspace_bytes", "cdl_huffman_bits",
     "cdl_profile_enable", "cdl_profile_collect", "cdl_probe_mfma_int8",
@@ -97,6 +98,14 @@ def load():
         L.cdl_qgemm_fwd.argtypes = [vp, vp, i32, i32, i32, f32, f32, vp, vp, vp, sz, vp]
         L.cdl_qgemm_bwd.restype = ctypes.c_int
         L.cdl_qgemm_bwd.argtypes = [vp, vp, vp, i32, i32, i32, f32, f32, vp, vp, vp, sz, vp]
+        L.cdl_qgemm_fwd_offset_workspace_bytes.restype = sz
+        L.cdl_qgemm_fwd_offset_workspace_bytes.argtypes = [i32, i32, i32]
+        L.cdl_index_offset.restype = i32
+        L.cdl_index_offset.argtypes = [qp]
+        L.cdl_qgemm_fwd_offset.restype = ctypes.c_int
+        L.cdl_qgemm_fwd_offset.argtypes = [vp, vp, i32, i32, i32, f32, f32, i32, i32, vp, vp, vp, sz, vp]
+        L.cdl_qgemm_bwd_offset.restype = ctypes.c_int
+        L.cdl_qgemm_bwd_offset.argtypes = [vp, vp, vp, i32, i32, i32, f32, f32, i32, i32, vp, vp, vp, sz, vp]
         L.cdl_profile_enable.restype = ctypes.c_int
         L.cdl_profile_enable.argtypes = [ctypes.c_int]
         L.cdl_profile_collect.restype = ctypes.c_int
@@ -149,6 +158,18 @@ def qgemm_fwd_workspace_bytes(M: int, N: int, K: int) -> int:
 
 def qgemm_bwd_workspace_bytes(M: int, N: int, K: int) -> int:
     return int(load().cdl_qgemm_bwd_workspace_bytes(M, N, K))
+
+
+def qgemm_fwd_offset_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(load().cdl_qgemm_fwd_offset_workspace_bytes(M, N, K))
+
+
+def cdl_index_offset(lo: int, n_levels: int, delta: float = 1.0, alpha: float = 1.0) -> int:
+    q = _qp(lo, n_levels, delta, alpha)
+    off = int(load().cdl_index_offset(ctypes.byref(q)))
+    if off < 0:
+        raise CdlError(off, "cdl_index_offset")
+    return off
 
 
 def _check(rc: int, where: str):
@@ -220,6 +241,19 @@ def cdl_qgemm_fwd(a_idx, b_idx, M, N, K, delta_a, delta_b, acc=None, y=None, ws=
     wp, wb = _ws(ws)
     _check(load().cdl_qgemm_fwd(_ptr(a_idx), _ptr(b_idx), M, N, K, delta_a, delta_b, _ptr(acc), _ptr(y),
                                 wp, wb, _stream(stream)), "cdl_qgemm_fwd")
+
+
+def cdl_qgemm_fwd_offset(a_idx, b_idx, M, N, K, delta_a, delta_b, a_offset, b_offset, acc=None, y=None, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(load().cdl_qgemm_fwd_offset(_ptr(a_idx), _ptr(b_idx), M, N, K, delta_a, delta_b, int(a_offset), int(b_offset),
+                                       _ptr(acc), _ptr(y), wp, wb, _stream(stream)), "cdl_qgemm_fwd_offset")
+
+
+def cdl_qgemm_bwd_offset(g, a_idx, b_idx, M, N, K, delta_a, delta_b, a_offset, b_offset, d_a_hat=None, d_b_hat=None,
+                         ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(load().cdl_qgemm_bwd_offset(_ptr(g), _ptr(a_idx), _ptr(b_idx), M, N, K, delta_a, delta_b, int(a_offset), int(b_offset),
+                                       _ptr(d_a_hat), _ptr(d_b_hat), wp, wb, _stream(stream)), "cdl_qgemm_bwd_offset")
 
 
 def cdl_qgemm_bwd(g, a_idx, b_idx, M, N, K, delta_a, delta_b, d_a_hat=None, d_b_hat=None, ws=None, stream=None):

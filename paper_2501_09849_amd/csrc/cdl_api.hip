@@ -78,7 +78,8 @@ int check_qparams(const cdl_qparams *p)
     if (!(std::isfinite(p->delta) && p->delta > 0.0f)) return CDL_ERR_PARAM;
     if (!(std::isfinite(p->alpha) && p->alpha > 0.0f)) return CDL_ERR_PARAM;
     const int64_t hi = (int64_t)p->lo + (int64_t)p->n_levels - 1;
-    if (p->lo < -128 || hi > 127) return CDL_ERR_RANGE;
+    // stored as int8: sets inside [-128, 127] as they are, sets that reach beyond 127 (up to 255) minus 128
+    if (p->lo < -128 || hi > 255 || (hi > 127 && p->lo < 0)) return CDL_ERR_RANGE;
     if (!(p->top_k == 0 || (p->top_k >= 1 && p->top_k <= 9 && (p->top_k & 1)))) return CDL_ERR_PARAM;
     // derived constants must stay finite in fp32
     const double kappa = (double)p->alpha * (double)p->delta * (double)p->delta;
@@ -111,7 +112,19 @@ size_t cdl_quantize_workspace_bytes(int64_t n, int32_t n_levels)
 size_t cdl_qgemm_fwd_workspace_bytes(int32_t M, int32_t N, int32_t K)
 {
     if (M < 0 || N < 0 || K < 0) return 0;
-    return qgemm_fwd_workspace_bytes(M, N, K);
+    return qgemm_fwd_workspace_bytes(M, N, K, false);
+}
+
+size_t cdl_qgemm_fwd_offset_workspace_bytes(int32_t M, int32_t N, int32_t K)
+{
+    if (M < 0 || N < 0 || K < 0) return 0;
+    return qgemm_fwd_workspace_bytes(M, N, K, true);
+}
+
+int32_t cdl_index_offset(const cdl_qparams *p)
+{
+    const int rc = check_qparams(p);
+    return rc != CDL_OK ? rc : index_offset(*p);
 }
 
 size_t cdl_qgemm_bwd_workspace_bytes(int32_t M, int32_t N, int32_t K)
@@ -228,7 +241,9 @@ int cdl_huffman_bits(const int8_t *idx, int64_t n, int32_t lo, int32_t n_levels,
                      void *ws, size_t ws_bytes, void *hip_stream)
 {
     if (n < 0 || n_levels < 1) return CDL_ERR_PARAM;
-    if (lo < -128 || (int64_t)lo + n_levels - 1 > 127) return CDL_ERR_RANGE;
+    const int64_t hi = (int64_t)lo + n_levels - 1;
+    if (lo < -128 || hi > 255 || (hi > 127 && lo < 0)) return CDL_ERR_RANGE;
+    if (hi > 127) lo -= 128;      // such sets are stored as index - 128
     if (!counts && !total_bits && !bits_per_entry) return CDL_ERR_NULL;
     if (n > 0 && !idx) return CDL_ERR_NULL;
     if (!aligned(idx, 16) || !aligned(counts, 8) || !aligned(total_bits, 8) || !aligned(bits_per_entry, 4)) return CDL_ERR_ALIGN;
@@ -237,30 +252,42 @@ int cdl_huffman_bits(const int8_t *idx, int64_t n, int32_t lo, int32_t n_levels,
     return launch_huffman_bits(idx, n, lo, n_levels, counts, total_bits, bits_per_entry, ws, (hipStream_t)hip_stream);
 }
 
+namespace {
+bool offset_ok(int32_t o) { return o == 0 || o == 128; }
+}
+
+int cdl_qgemm_fwd_offset(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
+                         float delta_a, float delta_b, int32_t a_offset, int32_t b_offset, int32_t *acc, float *y,
+                         void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (M < 0 || N < 0 || K < 0 || !offset_ok(a_offset) || !offset_ok(b_offset)) return CDL_ERR_PARAM;
+    if (!(std::isfinite(delta_a) && delta_a > 0.0f) || !(std::isfinite(delta_b) && delta_b > 0.0f)) return CDL_ERR_PARAM;
+    if (!acc && !y) return CDL_ERR_NULL;
+    // the int32 result holds K products of level indices of magnitude up to 128, or 255 for an operand stored with an offset
+    if ((int64_t)K * (a_offset ? 255 : 128) * (b_offset ? 255 : 128) > 2147483647LL) return CDL_ERR_RANGE;
+    if ((int64_t)M * N > 0 && K > 0 && (!a_idx || !b_idx)) return CDL_ERR_NULL;
+    if (!aligned(a_idx, 16) || !aligned(b_idx, 16) || !aligned(acc, 16) || !aligned(y, 16)) return CDL_ERR_ALIGN;
+    int rc = check_ws(ws, ws_bytes, qgemm_fwd_workspace_bytes(M, N, K, a_offset != 0 || b_offset != 0));
+    if (rc != CDL_OK) return rc;
+    return launch_qgemm_fwd(a_idx, b_idx, M, N, K, delta_a, delta_b, a_offset, b_offset, acc, y, ws, (hipStream_t)hip_stream);
+}
+
 int cdl_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
                   float delta_a, float delta_b, int32_t *acc, float *y,
                   void *ws, size_t ws_bytes, void *hip_stream)
 {
-    if (M < 0 || N < 0 || K < 0) return CDL_ERR_PARAM;
-    if (!(std::isfinite(delta_a) && delta_a > 0.0f) || !(std::isfinite(delta_b) && delta_b > 0.0f)) return CDL_ERR_PARAM;
-    if (!acc && !y) return CDL_ERR_NULL;
-    if ((int64_t)K * 128 * 128 > 2147483647LL) return CDL_ERR_RANGE;
-    if ((int64_t)M * N > 0 && K > 0 && (!a_idx || !b_idx)) return CDL_ERR_NULL;
-    if (!aligned(a_idx, 16) || !aligned(b_idx, 16) || !aligned(acc, 16) || !aligned(y, 16)) return CDL_ERR_ALIGN;
-    int rc = check_ws(ws, ws_bytes, qgemm_fwd_workspace_bytes(M, N, K));
-    if (rc != CDL_OK) return rc;
-    return launch_qgemm_fwd(a_idx, b_idx, M, N, K, delta_a, delta_b, acc, y, ws, (hipStream_t)hip_stream);
+    return cdl_qgemm_fwd_offset(a_idx, b_idx, M, N, K, delta_a, delta_b, 0, 0, acc, y, ws, ws_bytes, hip_stream);
 }
 
-int cdl_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
-                  int32_t M, int32_t N, int32_t K, float delta_a, float delta_b,
-                  float *d_a_hat, float *d_b_hat,
-                  void *ws, size_t ws_bytes, void *hip_stream)
+int cdl_qgemm_bwd_offset(const float *g, const int8_t *a_idx, const int8_t *b_idx,
+                         int32_t M, int32_t N, int32_t K, float delta_a, float delta_b, int32_t a_offset, int32_t b_offset,
+                         float *d_a_hat, float *d_b_hat,
+                         void *ws, size_t ws_bytes, void *hip_stream)
 {
-    if (M < 0 || N < 0 || K < 0) return CDL_ERR_PARAM;
+    if (M < 0 || N < 0 || K < 0 || !offset_ok(a_offset) || !offset_ok(b_offset)) return CDL_ERR_PARAM;
     if (!(std::isfinite(delta_a) && delta_a > 0.0f) || !(std::isfinite(delta_b) && delta_b > 0.0f)) return CDL_ERR_PARAM;
     if (!d_a_hat && !d_b_hat) return CDL_ERR_NULL;
-    // int32 accumulators hold limb (<= 128) x index (<= 128) products over the contraction length; the
+    // int32 accumulators hold limb (<= 128) x stored index (<= 128) products over the contraction length; the
     // contraction over M is cut into pieces by the library, the one over N is not
     if (d_a_hat && (int64_t)N * 128 * 128 > 2147483647LL) return CDL_ERR_RANGE;
     // the kernels address 384 rows of the transposed copy of a_idx (row length M, padded) with 32-bit offsets
@@ -270,7 +297,15 @@ int cdl_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
         return CDL_ERR_ALIGN;
     int rc = check_ws(ws, ws_bytes, qgemm_bwd_workspace_bytes(M, N, K));
     if (rc != CDL_OK) return rc;
-    return launch_qgemm_bwd(g, a_idx, b_idx, M, N, K, delta_a, delta_b, d_a_hat, d_b_hat, ws, (hipStream_t)hip_stream);
+    return launch_qgemm_bwd(g, a_idx, b_idx, M, N, K, delta_a, delta_b, a_offset, b_offset, d_a_hat, d_b_hat, ws, (hipStream_t)hip_stream);
+}
+
+int cdl_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
+                  int32_t M, int32_t N, int32_t K, float delta_a, float delta_b,
+                  float *d_a_hat, float *d_b_hat,
+                  void *ws, size_t ws_bytes, void *hip_stream)
+{
+    return cdl_qgemm_bwd_offset(g, a_idx, b_idx, M, N, K, delta_a, delta_b, 0, 0, d_a_hat, d_b_hat, ws, ws_bytes, hip_stream);
 }
 
 int cdl_probe_mfma_int8(int32_t iters, int32_t random_operands, int32_t blocks, void *sink, double *ops, void *hip_stream)

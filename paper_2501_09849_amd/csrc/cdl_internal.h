@@ -90,20 +90,24 @@ int launch_entropy_bwd(const float *theta, const float *marg, const float *g_in,
 constexpr size_t kStaticScratchBytes = 8u << 20;
 int quantizer_static_scratch(void **ptr);
 
+// 0, or 128 for level sets that reach beyond 127: what the kernels subtract from a level index before storing it.
+int index_offset(const cdl_qparams &p);
+
 // Half-width of the band of levels around the nearest one that the kernels visit for a given
 // kappa = alpha*delta^2 (levels further out carry less than fp32 resolution of the result).
 int quantizer_window(double kappa, int n_levels);
 
 // ---- index GEMMs (cdl_qgemm.hip) ---------------------------------------------------------
-size_t qgemm_fwd_workspace_bytes(int32_t M, int32_t N, int32_t K);
+size_t qgemm_fwd_workspace_bytes(int32_t M, int32_t N, int32_t K, bool with_offsets);
 size_t qgemm_bwd_workspace_bytes(int32_t M, int32_t N, int32_t K);
 
+// a_offset / b_offset: what was subtracted from the level indices of that operand before they were stored (0 or 128)
 int launch_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
-                     float delta_a, float delta_b, int32_t *acc, float *y,
+                     float delta_a, float delta_b, int32_t a_offset, int32_t b_offset, int32_t *acc, float *y,
                      void *ws, hipStream_t stream);
 
 int launch_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
-                     int32_t M, int32_t N, int32_t K, float delta_a, float delta_b,
+                     int32_t M, int32_t N, int32_t K, float delta_a, float delta_b, int32_t a_offset, int32_t b_offset,
                      float *d_a_hat, float *d_b_hat, void *ws, hipStream_t stream);
 
 // ---- Huffman-coded size (cdl_huffman.hip) --------------------------------------------------

@@ -46,6 +46,11 @@ struct GemmArgs {
     float *y_out;         // [rowsA][ldc] or null
     int64_t ldc;
     float scale;          // delta_a * delta_b
+    // Operands stored as index - offset (level sets that reach beyond 127): what the stored product lacks,
+    //   sum_k (a' + oa)(b' + ob) - sum_k a' b' = oa sum_k b'[s,k] + ob sum_k a'[r,k] + K oa ob,
+    // as one int32 per output column (corr_col, includes the constant) and one per output row (corr_row); null = 0.
+    const int32_t *corr_col;
+    const int32_t *corr_row;
 };
 
 __device__ __forceinline__ int swz(int row, int q) { return q ^ ((row >> 1) & 3); }
@@ -169,13 +174,15 @@ void qgemm_kernel(GemmArgs a)
         for (int j = 0; j < TN; ++j) {
             const int col = tile_n * BN + wn * TN * 32 + j * 32 + (lane & 31);
             if (col >= a.rowsB) continue;
+            const int cc = a.corr_col ? a.corr_col[col] : 0;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = tile_m * BM + wm * TM * 32 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                 if (row >= a.rowsA) continue;
                 const int64_t o = (int64_t)row * a.ldc + col;
-                if (a.acc_out) a.acc_out[o] = acc[i][j][r];
-                if (a.y_out) a.y_out[o] = a.scale * (float)acc[i][j][r];
+                const int v = acc[i][j][r] + cc + (a.corr_row ? a.corr_row[row] : 0);
+                if (a.acc_out) a.acc_out[o] = v;
+                if (a.y_out) a.y_out[o] = a.scale * (float)v;
             }
         }
 }
@@ -208,6 +215,8 @@ struct LimbArgs {
     int which;            // 0 = d_a_hat, 1 = d_b_hat
     float *out;           // [rows][cols] (splits == 1)
     double *partial;      // [splits][rows][cols] (splits > 1)
+    const double *row_corr;   // [rows] or null: added to every entry of an output row (the index operand is stored with an offset:
+                              // the missing part of the product is offset * step * sum of g over the contraction); splits == 1 only
 };
 
 constexpr int kLBK = 128;     // contraction bytes per K-tile
@@ -331,13 +340,15 @@ void qgemm_dma_kernel(GemmArgs a)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int col = tile_n * kFTile + (wn * TN + j) * 32 + (lane & 31);
+            const int cc = (a.corr_col && col < a.rowsB) ? a.corr_col[col] : 0;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = tile_m * kFTile + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                 if (full || (row < a.rowsA && col < a.rowsB)) {
                     const int64_t o = (int64_t)row * a.ldc + col;
-                    if (a.acc_out) a.acc_out[o] = acc[i][j][r];
-                    if (a.y_out) a.y_out[o] = a.scale * (float)acc[i][j][r];
+                    const int v = acc[i][j][r] + cc + (a.corr_row ? a.corr_row[row] : 0);
+                    if (a.acc_out) a.acc_out[o] = v;
+                    if (a.y_out) a.y_out[o] = a.scale * (float)v;
                 }
             }
         }
@@ -638,6 +649,7 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
         // one address per row, the TN column tiles of a wave at fixed distances from it; tiles that do not reach
         // the edge of the matrix (FULL) store without a test
         const int64_t first = (int64_t)erow * a.cols + ecol;
+        const bool corr = a.row_corr != nullptr && a.splits == 1;
         auto emit = [&](auto full_c, auto *base) {
             constexpr bool FULL = decltype(full_c)::value;
             using T = std::remove_pointer_t<decltype(base)>;
@@ -646,10 +658,11 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
                 const int dr = 8 * (rr >> 2) + (rr & 3);
                 T *p = base + (int64_t)dr * a.cols;
                 const bool row_ok = FULL || erow + dr < a.rows;
+                const double rc = (corr && row_ok) ? a.row_corr[erow + dr] : 0.0;
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     if (FULL || (row_ok && ecol + j * 32 < a.cols)) {
-                        if (std::is_same<T, float>::value) p[j * 32] = (T)(combined(j, rr) * out_scale);
+                        if (std::is_same<T, float>::value) p[j * 32] = (T)__builtin_fma(combined(j, rr), out_scale, rc);
                         else p[j * 32] = (T)combined(j, rr);
                     }
                 }
@@ -789,7 +802,8 @@ void limb_gemm_kernel(LimbArgs a)
 // when there are few outputs and many splits, where one lane per output leaves most of the chip idle.
 template <int LANES>
 __global__ __launch_bounds__(256)
-void limb_reduce_kernel(const double *__restrict__ partial, int splits, int64_t n, const BwdPlan *plan, float *__restrict__ out)
+void limb_reduce_kernel(const double *__restrict__ partial, int splits, int64_t n, const BwdPlan *plan, float *__restrict__ out,
+                        const double *__restrict__ row_corr /* [n / cols] or null */, int cols)
 {
     const double out_scale = plan->out_scale_db;
     const int sub = threadIdx.x % LANES;
@@ -810,7 +824,7 @@ void limb_reduce_kernel(const double *__restrict__ partial, int splits, int64_t 
         double s = (s0 + s1) + (s2 + s3);
 #pragma unroll
         for (int off = LANES / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-        if (sub == 0 && i < n) out[i] = (float)(s * out_scale);
+        if (sub == 0 && i < n) out[i] = (float)__builtin_fma(s, out_scale, row_corr ? row_corr[i / cols] : 0.0);
     }
 }
 
@@ -828,7 +842,7 @@ constexpr int kDirectRows = 64;
 template <int NN>
 __global__ __launch_bounds__(256)
 void da_direct_kernel(const float *__restrict__ g, const int8_t *__restrict__ b_idx, int M, int N, int K,
-                      double delta_b, float *__restrict__ out)
+                      double delta_b, double b_offset, float *__restrict__ out)
 {
     __shared__ double gs[kDirectRows][NN];
     const int row0 = blockIdx.x * kDirectRows;
@@ -840,7 +854,7 @@ void da_direct_kernel(const float *__restrict__ g, const int8_t *__restrict__ b_
     }
     double b[NN];
 #pragma unroll
-    for (int n = 0; n < NN; ++n) b[n] = (n < N && k < K) ? (double)b_idx[(int64_t)n * K + k] : 0.0;
+    for (int n = 0; n < NN; ++n) b[n] = (n < N && k < K) ? (double)b_idx[(int64_t)n * K + k] + b_offset : 0.0;   // (the level index itself)
     __syncthreads();
     if (k >= K) return;
     for (int r = 0; r < rows; ++r) {
@@ -849,6 +863,67 @@ void da_direct_kernel(const float *__restrict__ g, const int8_t *__restrict__ b_
         for (int n = 0; n < NN; ++n) acc = fma(gs[r][n], b[n], acc);
         out[(int64_t)(row0 + r) * K + k] = (float)(acc * delta_b);
     }
+}
+
+// out[r] = mult * sum_k idx[r][k] + add for an int8 matrix [rows][K]: the corrections of a product whose
+// other operand is stored with an offset.  One wave per row, 4 bytes per lane and trip.
+__global__ __launch_bounds__(256) void index_rowsum_kernel(const int8_t *__restrict__ idx, int rows, int K, int mult, int add,
+                                                           int32_t *__restrict__ out)
+{
+    const int lane = threadIdx.x & 63;
+    for (int r = blockIdx.x * 4 + (threadIdx.x >> 6); r < rows; r += gridDim.x * 4) {
+        const int8_t *p = idx + (int64_t)r * K;
+        int s = 0;
+        for (int k = lane; k < K; k += 64) s += (int)p[k];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
+        if (lane == 0) out[r] = mult * s + add;
+    }
+}
+
+// Row sums of the fp32 gradient g [M][N] in double, times `mult`: out[m] = mult * sum_n g[m][n].  One wave per row.
+__global__ __launch_bounds__(256) void g_rowsum_kernel(const float *__restrict__ g, int M, int N, double mult, double *__restrict__ out)
+{
+    const int lane = threadIdx.x & 63;
+    for (int m = blockIdx.x * 4 + (threadIdx.x >> 6); m < M; m += gridDim.x * 4) {
+        const float *p = g + (int64_t)m * N;
+        double s = 0.0;
+        for (int n = lane; n < N; n += 64) s += (double)p[n];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
+        if (lane == 0) out[m] = mult * s;
+    }
+}
+
+// Column sums of g [M][N]: block b adds rows b * rows_per .. of every column into partial[b][N] (a thread walks its
+// columns down the rows, neighbouring threads read neighbouring columns); g_colsum_finish adds the blocks in a
+// fixed order and multiplies by `mult`.
+constexpr int kColsumBlocks = 512;
+
+__global__ __launch_bounds__(256) void g_colsum_kernel(const float *__restrict__ g, int M, int N, int rows_per, double *__restrict__ partial)
+{
+    const int m0 = blockIdx.x * rows_per, m1 = min(M, m0 + rows_per);
+    for (int n = threadIdx.x; n < N; n += 256) {
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+        int m = m0;
+        for (; m + 3 < m1; m += 4) {
+            s0 += (double)g[(int64_t)m * N + n];
+            s1 += (double)g[(int64_t)(m + 1) * N + n];
+            s2 += (double)g[(int64_t)(m + 2) * N + n];
+            s3 += (double)g[(int64_t)(m + 3) * N + n];
+        }
+        for (; m < m1; ++m) s0 += (double)g[(int64_t)m * N + n];
+        partial[(int64_t)blockIdx.x * N + n] = (s0 + s1) + (s2 + s3);
+    }
+}
+
+__global__ __launch_bounds__(256) void g_colsum_finish_kernel(const double *__restrict__ partial, int blocks, int N, double mult, double *__restrict__ out)
+{
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    double s = 0.0;
+    for (int b = 0; b < blocks; ++b) s += partial[(int64_t)b * N + n];
+    out[n] = mult * s;
 }
 
 // ---- helpers -------------------------------------------------------------------------------
@@ -1083,7 +1158,7 @@ inline unsigned blocks_for(int64_t n, int per_block, int cap = 65536)
 
 // workspace layout of a backward call
 struct BwdLayout {
-    size_t plan, block_max, ss_a, ss_b, bt, at, partial, total;
+    size_t plan, block_max, ss_a, ss_b, bt, at, partial, corr_da, corr_db, colsum_partial, total;
     int n_max, n_ss_a, n_ss_b;    // per-block partial results of the absmax and the two transpose launches
     int64_t ldn, ldm;             // row strides of the transposed index copies (odd multiples of kLBK)
     int nk_n, nk_m;               // K-tiles of the two contractions
@@ -1121,6 +1196,10 @@ BwdLayout bwd_layout(int32_t M, int32_t N, int32_t K)
     L.bt = off;      off += align_up((size_t)K * (size_t)L.ldn, 256);           // b_idx^T: [K][ldn]
     L.at = off;      off += align_up((size_t)K * (size_t)L.ldm, 256);           // a_idx^T: [K][ldm]
     L.partial = off; off += L.splits > 1 ? align_up((size_t)L.splits * (size_t)N * (size_t)K * sizeof(double), 256) : 0;
+    // operands stored with an offset: one correction per output row of either product, and the per-block column sums of g
+    L.corr_da = off; off += align_up((size_t)M * sizeof(double), 256);
+    L.corr_db = off; off += align_up((size_t)N * sizeof(double), 256);
+    L.colsum_partial = off; off += align_up((size_t)kColsumBlocks * (size_t)N * sizeof(double), 256);
     L.total = off;
     return L;
 }
@@ -1174,11 +1253,16 @@ int launch_mfma_probe(int iters, int random_operands, int blocks, int *sink, hip
     return check_launch();
 }
 
-size_t qgemm_fwd_workspace_bytes(int32_t M, int32_t N, int32_t K)
+// forward workspace: [zero-padded operand copies when K % 16 != 0][with offsets: corrections per output column: int32 N][per output row: int32 M]
+size_t qgemm_fwd_workspace_bytes(int32_t M, int32_t N, int32_t K, bool with_offsets)
 {
-    if (K % 16 == 0) return 0;
-    const int64_t kp = pad_to(K, 16);
-    return align_up((size_t)M * (size_t)kp, 256) + align_up((size_t)N * (size_t)kp, 256);
+    size_t b = 0;
+    if (K % 16 != 0) {
+        const int64_t kp = pad_to(K, 16);
+        b += align_up((size_t)M * (size_t)kp, 256) + align_up((size_t)N * (size_t)kp, 256);
+    }
+    if (with_offsets) b += align_up((size_t)N * sizeof(int32_t), 256) + align_up((size_t)M * sizeof(int32_t), 256);
+    return b;
 }
 
 size_t qgemm_bwd_workspace_bytes(int32_t M, int32_t N, int32_t K)
@@ -1188,7 +1272,8 @@ size_t qgemm_bwd_workspace_bytes(int32_t M, int32_t N, int32_t K)
 }
 
 int launch_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
-                     float delta_a, float delta_b, int32_t *acc, float *y, void *ws, hipStream_t stream)
+                     float delta_a, float delta_b, int32_t a_offset, int32_t b_offset,
+                     int32_t *acc, float *y, void *ws, hipStream_t stream)
 {
     if ((int64_t)M * N == 0) return CDL_OK;
     if (K == 0) {
@@ -1199,6 +1284,21 @@ int launch_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_
     GemmArgs g{};
     g.A = a_idx; g.B = b_idx; g.lda = K; g.ldb = K;
     g.rowsA = M; g.rowsB = N; g.Kc = K;
+    char *corr_base = reinterpret_cast<char *>(ws) + qgemm_fwd_workspace_bytes(M, N, K, false);
+    int32_t *corr_col = reinterpret_cast<int32_t *>(corr_base);
+    int32_t *corr_row = reinterpret_cast<int32_t *>(corr_base + align_up((size_t)N * sizeof(int32_t), 256));
+    if (a_offset != 0) {
+        // per output column s: oa * sum_k b'[s][k] + K oa ob
+        CDL_LAUNCH("index_rowsum_kernel", stream, index_rowsum_kernel, dim3(blocks_for(N, 4, 4096)), dim3(256), 0, b_idx, N, K, a_offset,
+                   K * a_offset * b_offset, corr_col);
+        g.corr_col = corr_col;
+    }
+    if (b_offset != 0) {
+        // per output row r: ob * sum_k a'[r][k] (plus the constant if no column correction carries it)
+        CDL_LAUNCH("index_rowsum_kernel", stream, index_rowsum_kernel, dim3(blocks_for(M, 4, 4096)), dim3(256), 0, a_idx, M, K, b_offset,
+                   a_offset != 0 ? 0 : K * a_offset * b_offset, corr_row);
+        g.corr_row = corr_row;
+    }
     if (K % 16 != 0) {
         // rows would not start on 16-byte boundaries: stage zero-padded copies
         const int kp = (int)pad_to(K, 16);
@@ -1219,7 +1319,7 @@ int launch_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_
 }
 
 int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
-                     int32_t M, int32_t N, int32_t K, float delta_a, float delta_b,
+                     int32_t M, int32_t N, int32_t K, float delta_a, float delta_b, int32_t a_offset, int32_t b_offset,
                      float *d_a_hat, float *d_b_hat, void *ws, hipStream_t stream)
 {
     if (d_a_hat && ((int64_t)M * K > 0) && N == 0)
@@ -1230,8 +1330,8 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
 
     if (d_a_hat && N <= kDirectMaxN) {
         const dim3 grid((M + kDirectRows - 1) / kDirectRows, (K + 255) / 256);
-        if (N <= 16) CDL_LAUNCH("da_direct_kernel", stream, da_direct_kernel<16>, grid, dim3(256), 0, gr, b_idx, M, N, K, (double)delta_b, d_a_hat);
-        else CDL_LAUNCH("da_direct_kernel", stream, da_direct_kernel<32>, grid, dim3(256), 0, gr, b_idx, M, N, K, (double)delta_b, d_a_hat);
+        if (N <= 16) CDL_LAUNCH("da_direct_kernel", stream, da_direct_kernel<16>, grid, dim3(256), 0, gr, b_idx, M, N, K, (double)delta_b, (double)b_offset, d_a_hat);
+        else CDL_LAUNCH("da_direct_kernel", stream, da_direct_kernel<32>, grid, dim3(256), 0, gr, b_idx, M, N, K, (double)delta_b, (double)b_offset, d_a_hat);
         d_a_hat = nullptr;           // done; what follows is for the other product only
         if (!d_b_hat) return check_launch();
     }
@@ -1251,6 +1351,23 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
     if (d_b_hat) launch_transpose(a_idx, M, K, at, L.ldm, ss_a, stream);
     CDL_LAUNCH("plan_kernel", stream, plan_kernel, dim3(1), dim3(1024), 0, plan, block_max, L.n_max,
                ss_a, d_b_hat ? L.n_ss_a : 0, ss_b, d_a_hat ? L.n_ss_b : 0, M, N, K, delta_a, delta_b);
+    // operands stored as index - offset: d_a_hat lacks delta_b * ob * sum_n g[m][n] in row m, d_b_hat lacks
+    // delta_a * oa * sum_m g[m][n] in row n; both sums are taken of the unrounded g, in double
+    double *corr_da = nullptr, *corr_db = nullptr;
+    if (d_a_hat && b_offset != 0) {
+        corr_da = reinterpret_cast<double *>(base + L.corr_da);
+        CDL_LAUNCH("g_rowsum_kernel", stream, g_rowsum_kernel, dim3(blocks_for(M, 4, 8192)), dim3(256), 0, gr, M, N,
+                   (double)delta_b * (double)b_offset, corr_da);
+    }
+    if (d_b_hat && a_offset != 0) {
+        corr_db = reinterpret_cast<double *>(base + L.corr_db);
+        double *cp = reinterpret_cast<double *>(base + L.colsum_partial);
+        const int rows_per = (M + kColsumBlocks - 1) / kColsumBlocks;
+        const int blocks = (M + rows_per - 1) / rows_per;
+        CDL_LAUNCH("g_colsum_kernel", stream, g_colsum_kernel, dim3(blocks), dim3(256), 0, gr, M, N, rows_per, cp);
+        CDL_LAUNCH("g_colsum_finish_kernel", stream, g_colsum_finish_kernel, dim3((N + 255) / 256), dim3(256), 0, cp, blocks, N,
+                   (double)delta_a * (double)a_offset, corr_db);
+    }
     int rc = check_launch();
     if (rc != CDL_OK) return rc;
 
@@ -1263,6 +1380,7 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
         a.tiles_r = (M + kLRows - 1) / kLRows; a.splits = 1; a.kt_per_split = L.nk_n;
         a.plan = plan; a.which = 0;
         a.out = d_a_hat; a.partial = nullptr;
+        a.row_corr = corr_da;
         rc = launch_limb_gemm(a, false, stream);
         if (rc != CDL_OK) return rc;
     }
@@ -1275,15 +1393,16 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
         a.tiles_r = (N + kLRows - 1) / kLRows; a.splits = L.splits; a.kt_per_split = L.kt_per_split;
         a.plan = plan; a.which = 1;
         a.out = d_b_hat; a.partial = partial;
+        a.row_corr = corr_db;
         rc = launch_limb_gemm(a, true, stream);
         if (rc != CDL_OK) return rc;
         if (L.splits > 1) {
             if ((int64_t)N * K <= 65536 && L.splits >= 32)
                 CDL_LAUNCH("limb_reduce_kernel", stream, limb_reduce_kernel<16>, dim3(blocks_for((int64_t)N * K * 16, 256, 4096)), dim3(256), 0,
-                           partial, L.splits, (int64_t)N * K, plan, d_b_hat);
+                           partial, L.splits, (int64_t)N * K, plan, d_b_hat, corr_db, K);
             else
                 CDL_LAUNCH("limb_reduce_kernel", stream, limb_reduce_kernel<1>, dim3(blocks_for((int64_t)N * K, 256, 4096)), dim3(256), 0,
-                           partial, L.splits, (int64_t)N * K, plan, d_b_hat);
+                           partial, L.splits, (int64_t)N * K, plan, d_b_hat, corr_db, K);
             rc = check_launch();
         }
     }

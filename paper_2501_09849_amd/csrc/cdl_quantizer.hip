@@ -55,11 +55,19 @@ struct QConst {
     float hi_f;
     int lo;
     int n_levels;
+    int idx_off;      // what is subtracted from a level index before it is stored as an int8 (0, or 128 for sets that reach beyond 127)
     int wgen;         // band half-width of the generic kernel
     int stream;       // 1: the tensor is large, read and write it with non-temporal accesses
     int slide;        // 1: truncated CPMF - the band of 2 wgen + 1 levels slides at the ends of the level set instead of being cut
     float r_clamp;    // |u / delta| beyond which the W = 2 kernels hold the offset fixed (see band_weights), else infinity
 };
+
+// Four level indices as the four int8 of one word, each stored as index - off
+__device__ __forceinline__ uint32_t pack_indices(int c0, int c1, int c2, int c3, int off)
+{
+    return (uint32_t)((c0 - off) & 0xff) | ((uint32_t)((c1 - off) & 0xff) << 8) |
+           ((uint32_t)((c2 - off) & 0xff) << 16) | ((uint32_t)((c3 - off) & 0xff) << 24);
+}
 
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -302,8 +310,7 @@ void quantize_fwd_kernel(const float *__restrict__ theta, int64_t n, QConst k,
         forward4<W, IDX, MARG>(th, 4, k, my_hist, sv, ci);
         if (SOFT) store_stream4(soft + 4 * v, sv[0], sv[1], sv[2], sv[3], k.stream);
         if (IDX) {
-            const uint32_t packed = (uint32_t)(ci[0] & 0xff) | ((uint32_t)(ci[1] & 0xff) << 8) |
-                                    ((uint32_t)(ci[2] & 0xff) << 16) | ((uint32_t)(ci[3] & 0xff) << 24);
+            const uint32_t packed = pack_indices(ci[0], ci[1], ci[2], ci[3], k.idx_off);
             reinterpret_cast<uint32_t *>(idx)[v] = packed;   // (ordinary store: the products read the indices next)
         }
     }
@@ -315,7 +322,7 @@ void quantize_fwd_kernel(const float *__restrict__ theta, int64_t n, QConst k,
         forward4<W, IDX, MARG>(th, cnt, k, my_hist, sv, ci);
         for (int e = 0; e < cnt; ++e) {
             if (SOFT) soft[(n4 << 2) + e] = sv[e];
-            if (IDX) idx[(n4 << 2) + e] = (int8_t)ci[e];
+            if (IDX) idx[(n4 << 2) + e] = (int8_t)(ci[e] - k.idx_off);
         }
     }
 
@@ -647,12 +654,11 @@ void quantize_fwd_uniform_kernel(const float *__restrict__ theta, int64_t n, QCo
         }
         if (v < n4) {
             if (SOFT) store_stream4(soft + 4 * v, sv[0], sv[1], sv[2], sv[3], k.stream);
-            if (IDX) reinterpret_cast<uint32_t *>(idx)[v] = (uint32_t)(ci[0] & 0xff) | ((uint32_t)(ci[1] & 0xff) << 8) |
-                                                            ((uint32_t)(ci[2] & 0xff) << 16) | ((uint32_t)(ci[3] & 0xff) << 24);
+            if (IDX) reinterpret_cast<uint32_t *>(idx)[v] = pack_indices(ci[0], ci[1], ci[2], ci[3], k.idx_off);
         } else {
             for (int e = 0; e < cnt; ++e) {
                 if (SOFT) soft[(n4 << 2) + e] = sv[e];
-                if (IDX) idx[(n4 << 2) + e] = (int8_t)ci[e];
+                if (IDX) idx[(n4 << 2) + e] = (int8_t)(ci[e] - k.idx_off);
             }
         }
     }
@@ -831,11 +837,10 @@ void quantize_draw_kernel(const float *__restrict__ theta, const float *__restri
         const float4 r = load_stream4(u + 4 * v, k.stream);
         const int c0 = draw_one<W>(t.x, r.x, k), c1 = draw_one<W>(t.y, r.y, k);
         const int c2 = draw_one<W>(t.z, r.z, k), c3 = draw_one<W>(t.w, r.w, k);
-        reinterpret_cast<uint32_t *>(idx)[v] = (uint32_t)(c0 & 0xff) | ((uint32_t)(c1 & 0xff) << 8) |
-                                               ((uint32_t)(c2 & 0xff) << 16) | ((uint32_t)(c3 & 0xff) << 24);
+        reinterpret_cast<uint32_t *>(idx)[v] = pack_indices(c0, c1, c2, c3, k.idx_off);
     }
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0)
-        for (int64_t e = n4 << 2; e < n; ++e) idx[e] = (int8_t)draw_one<W>(theta[e], u[e], k);
+        for (int64_t e = n4 << 2; e < n; ++e) idx[e] = (int8_t)(draw_one<W>(theta[e], u[e], k) - k.idx_off);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -983,6 +988,7 @@ QConst make_const(const cdl_qparams &p)
     k.k4 = (float)exp(-4.0 * kappa);
     k.two_kappa = (float)(2.0 * kappa);
     k.lo = p.lo;
+    k.idx_off = index_offset(p);
     k.n_levels = p.n_levels;
     k.lo_f = (float)p.lo;
     k.hi_f = (float)(p.lo + p.n_levels - 1);
@@ -1155,6 +1161,10 @@ void launch_bwd_w(bool want_dtheta, bool want_scalars, int grid, hipStream_t s, 
 }
 
 }  // namespace
+
+// Level sets that reach beyond 127 (the paper's unsigned 8-bit alphabet {0, ..., 255}, eq. repo_alphabet) are
+// stored as index - 128, which fits an int8 because such sets start at 0 or above.
+int index_offset(const cdl_qparams &p) { return (int64_t)p.lo + p.n_levels - 1 > 127 ? 128 : 0; }
 
 // Smallest W such that every level m > W away from the nearest one has relative weight
 // m^3 exp(-kappa m (m-1)) below 3e-9, i.e. below fp32 resolution of every moment used.

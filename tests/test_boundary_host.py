@@ -66,8 +66,13 @@ def test_quantizer_argument_validation_happens_before_any_gpu_work(cdl):
     assert f(FAKE, 16, _q(-7, 15, 0.02, -1.0), FAKE, None, None, None, None, 0, None) == PARAM
     assert f(FAKE, 16, _q(-7, 15, float("nan"), 1.0), FAKE, None, None, None, None, 0, None) == PARAM
     assert f(FAKE, 16, _q(-7, 15, 0.02, float("inf")), FAKE, None, None, None, None, 0, None) == PARAM
-    assert f(FAKE, 16, _q(0, 256, 0.02, 1e4), FAKE, None, None, None, None, 0, None) == RANGE    # the unsigned 8-bit set
+    assert f(FAKE, 16, _q(0, 257, 0.02, 1e4), FAKE, None, None, None, None, 0, None) == RANGE    # beyond the unsigned 8-bit set
+    assert f(FAKE, 16, _q(-5, 140, 0.02, 1e4), FAKE, None, None, None, None, 0, None) == RANGE   # inside neither [-128,127] nor [0,255]
     assert f(FAKE, 16, _q(-129, 4, 0.02, 1e4), FAKE, None, None, None, None, 0, None) == RANGE
+    # the offset a level set is stored with: 0 inside [-128, 127], 128 for sets that reach beyond 127
+    assert lib.cdl_index_offset(_q(-128, 256, 0.02, 1e4)) == 0 and lib.cdl_index_offset(_q(0, 128, 0.02, 1e4)) == 0
+    assert lib.cdl_index_offset(_q(0, 256, 0.02, 1e4)) == 128 and lib.cdl_index_offset(_q(100, 29, 0.02, 1e4)) == 128
+    assert lib.cdl_index_offset(_q(-1, 130, 0.02, 1e4)) == RANGE and lib.cdl_index_offset(None) == NULL
     assert f(FAKE, -1, good, FAKE, None, None, None, None, 0, None) == PARAM
     assert f(None, 16, good, FAKE, None, None, None, None, 0, None) == NULL
     assert f(FAKE, 16, good, None, None, None, None, None, 0, None) == NULL
