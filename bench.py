@@ -483,6 +483,8 @@ def main():
     ap.add_argument("--workload", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
+    ap.add_argument("--step-only", action="store_true",
+                    help="time the step and nothing else (for profiler runs): no quantizer-only legs, so `value` is null")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known HBM traffic, to calibrate rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -612,10 +614,13 @@ def main():
         t_mfma = 2.0 * wl.M * wl.N * wl.K / (INT8_PEAK_TOPS * 1e12)
         out["index_gemm_fwd_frac_of_roofline"] = max(t_hbm, t_mfma) / (gf[0]["avg_us"] * 1e-6)
         out["index_gemm_fwd_roofline_bound"] = "hbm" if t_hbm > t_mfma else "mfma"
-    if not args.no_extra:
+    if not args.no_extra and not args.step_only:
         out["step_as_hip_graph"] = graph_replay(st, args.steps)
     del st
     torch.cuda.empty_cache()
+    if args.step_only:
+        print(json.dumps(out), flush=True)
+        return
     scrub = Scrub()
     qo = quantizer_only(scrub)
     out["quantizer_only_flat_25M"] = qo
