@@ -229,14 +229,19 @@ int cdl_qgemm_fwd_offset(const int8_t *a_idx, const int8_t *b_idx, int32_t M, in
  * The gradient stays fp32 (the paper quantizes weights and activations only).  Internally every
  * g is rounded to q = rint(g * 2^(8L-1) / sigma) for one power-of-two sigma > max|g|, q is written
  * in L balanced base-256 digits (int8 limbs), each limb product is accumulated exactly in int32 on
- * the int8 matrix cores and the limbs are recombined in double; L (3..6) is chosen on the device
- * so that the rounding of q contributes about 1.7e-7 absolute (one standard deviation) or less.
+ * the int8 matrix cores and the limbs are recombined in double.  Every g is thereby represented to
+ * within sigma * 2^-8L, so an output differs from the exact contraction of the fp32 g by at most
+ *   step * sigma * 2^-8L * (largest sum of |index| over the contraction, one sum per output column)
+ * whatever the values and signs of g; L (3..6) is chosen on the device as the smallest count for
+ * which this bound is at most 9e-7.  (Only if six limbs do not reach that - contractions over many
+ * millions of large indices - is the bound larger; it is reported, see below.)
  * At least one output non-NULL.  CDL_ERR_RANGE if d_a_hat is requested and N > 131071 (int32
  * accumulators over the contraction; the contraction over M is cut into pieces internally), or if
  * d_b_hat is requested and M > 11 000 000 (32-bit offsets into the transposed copy of a_idx).
- * Diagnostic: once the call has run, the first two int32 of ws hold the limb counts the device
- * chose for d_a_hat and for d_b_hat (meaningful for a product that was requested; d_a_hat with
- * N <= 32 is formed directly in double, without limbs).
+ * Diagnostics: once the call has run, the first two int32 of ws hold the limb counts the device
+ * chose for d_a_hat and for d_b_hat, and the two doubles at byte offsets 32 and 40 of ws the bounds
+ * above for the two products (meaningful for a product that was requested; d_a_hat with N <= 32 is
+ * formed directly in double, without limbs).
  */
 int cdl_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
                   int32_t M, int32_t N, int32_t K, float delta_a, float delta_b,

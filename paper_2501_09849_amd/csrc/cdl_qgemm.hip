@@ -34,6 +34,7 @@ struct BwdPlan {
     int limbs_da, limbs_db;          // limbs used for d_a_hat / d_b_hat
     float gscale_da, gscale_db;      // 2^(8L-1) / sigma
     double out_scale_da, out_scale_db;  // delta_b * sigma / 2^(8L-1), delta_a * sigma / 2^(8L-1)
+    double bound_da, bound_db;          // what the rounding of g can change in one entry of d_a_hat / d_b_hat, at most
 };
 
 struct GemmArgs {
@@ -167,24 +168,31 @@ void qgemm_kernel(GemmArgs a)
         __syncthreads();
     }
 
-    // epilogue: lane holds column (lane%32) of each 32x32 tile; register r holds row 8(r/4) + 4(lane/32) + r%4
+    // epilogue: lane holds column (lane%32) of each 32x32 tile; register r holds row 8(r/4) + 4(lane/32) + r%4.
+    // CORR: operands stored with an offset, corrections per column and row (a branch of its own: a test per
+    // element in the common path cost a third of the kernel's time)
+    auto epilogue = [&](auto corr_c) {
+        constexpr bool CORR = decltype(corr_c)::value;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = tile_n * BN + wn * TN * 32 + j * 32 + (lane & 31);
-            if (col >= a.rowsB) continue;
-            const int cc = a.corr_col ? a.corr_col[col] : 0;
+            for (int j = 0; j < TN; ++j) {
+                const int col = tile_n * BN + wn * TN * 32 + j * 32 + (lane & 31);
+                if (col >= a.rowsB) continue;
+                const int cc = (CORR && a.corr_col) ? a.corr_col[col] : 0;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = tile_m * BM + wm * TM * 32 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (row >= a.rowsA) continue;
-                const int64_t o = (int64_t)row * a.ldc + col;
-                const int v = acc[i][j][r] + cc + (a.corr_row ? a.corr_row[row] : 0);
-                if (a.acc_out) a.acc_out[o] = v;
-                if (a.y_out) a.y_out[o] = a.scale * (float)v;
+                for (int r = 0; r < 16; ++r) {
+                    const int row = tile_m * BM + wm * TM * 32 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    if (row >= a.rowsA) continue;
+                    const int64_t o = (int64_t)row * a.ldc + col;
+                    const int v = CORR ? acc[i][j][r] + cc + (a.corr_row ? a.corr_row[row] : 0) : acc[i][j][r];
+                    if (a.acc_out) a.acc_out[o] = v;
+                    if (a.y_out) a.y_out[o] = a.scale * (float)v;
+                }
             }
-        }
+    };
+    if (a.corr_col || a.corr_row) epilogue(std::true_type{});
+    else epilogue(std::false_type{});
 }
 
 template <int TM, int TN>
@@ -335,23 +343,29 @@ void qgemm_dma_kernel(GemmArgs a)
     }
 
     const bool full = (tile_m + 1) * kFTile <= a.rowsA && (tile_n + 1) * kFTile <= a.rowsB;
+    // (CORR: operands stored with an offset; kept out of the common path, see qgemm_kernel)
+    auto epilogue = [&](auto corr_c) {
+        constexpr bool CORR = decltype(corr_c)::value;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = tile_n * kFTile + (wn * TN + j) * 32 + (lane & 31);
-            const int cc = (a.corr_col && col < a.rowsB) ? a.corr_col[col] : 0;
+            for (int j = 0; j < TN; ++j) {
+                const int col = tile_n * kFTile + (wn * TN + j) * 32 + (lane & 31);
+                const int cc = (CORR && a.corr_col && col < a.rowsB) ? a.corr_col[col] : 0;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = tile_m * kFTile + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (full || (row < a.rowsA && col < a.rowsB)) {
-                    const int64_t o = (int64_t)row * a.ldc + col;
-                    const int v = acc[i][j][r] + cc + (a.corr_row ? a.corr_row[row] : 0);
-                    if (a.acc_out) a.acc_out[o] = v;
-                    if (a.y_out) a.y_out[o] = a.scale * (float)v;
+                for (int r = 0; r < 16; ++r) {
+                    const int row = tile_m * kFTile + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    if (full || (row < a.rowsA && col < a.rowsB)) {
+                        const int64_t o = (int64_t)row * a.ldc + col;
+                        const int v = CORR ? acc[i][j][r] + cc + (a.corr_row ? a.corr_row[row] : 0) : acc[i][j][r];
+                        if (a.acc_out) a.acc_out[o] = v;
+                        if (a.y_out) a.y_out[o] = a.scale * (float)v;
+                    }
                 }
             }
-        }
+    };
+    if (a.corr_col || a.corr_row) epilogue(std::true_type{});
+    else epilogue(std::false_type{});
 }
 
 int launch_gemm_dma(GemmArgs a, hipStream_t stream)
@@ -942,8 +956,12 @@ __global__ void pad_rows_kernel(const int8_t *__restrict__ src, int64_t rows, in
 // max |g| per block (as fp32 bits: non-negative floats order like unsigned ints): each block streams
 // contiguous pieces, eight independent 16-byte loads per thread and trip.  One plain store per block -
 // thousands of atomics on one address would take longer than the pass itself.
-__global__ __launch_bounds__(256) void absmax_kernel(const float *__restrict__ g, int64_t n, unsigned int *__restrict__ block_max)
+__global__ __launch_bounds__(256) void absmax_kernel(const float *__restrict__ g, int64_t n, unsigned int *__restrict__ block_max,
+                                                     unsigned int *__restrict__ clear, int n_clear)
 {
+    // (the transposition kernels that follow on the stream add into these words)
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i < n_clear; i += 256) clear[i] = 0u;
     __shared__ unsigned int wave_max[4];
     unsigned int m = 0u;
     const int64_t n4 = n >> 2;
@@ -978,107 +996,118 @@ __global__ __launch_bounds__(256) void absmax_kernel(const float *__restrict__ g
 }
 
 // dst[c][r] = src[r][c] for an int8 matrix [rows][cols]; dst rows are ldd bytes apart and are
-// zero-filled from `rows` up to the next multiple of 128.  Also writes the block's sum(src^2) to
-// block_sumsq[block].  One block moves a tile of 128 rows x
+// zero-filled from `rows` up to the next multiple of 128.  Also adds, for every column c of src, the sum of
+// |src[r][c]| over the block's rows to col_abs[c] (one atomic per column and block; the array is cleared by the
+// max|g| kernel that runs first): the largest of these sums bounds what the rounding of g can do to one output of
+// the product that contracts over r, see plan_kernel.  One block moves a tile of 128 rows x
 // 64 columns: 4-byte loads along the rows into LDS (row stride 17 words), then every thread takes a
 // 4 x 4 byte block, transposes it in registers and stores 4 bytes of four output rows, so that 32
 // lanes write 128 contiguous bytes.  VEC: cols % 4 == 0 (aligned 4-byte loads).
 template <bool VEC>
 __global__ __launch_bounds__(256) void transpose_i8_kernel(const int8_t *__restrict__ src, int rows, int cols,
                                                            int8_t *__restrict__ dst, int64_t ldd,
-                                                           unsigned int *__restrict__ block_sumsq)
+                                                           unsigned int *__restrict__ col_abs, int tiles_per_block)
 {
     __shared__ uint32_t tile[128 * 17];
-    __shared__ unsigned int wave_ss[4];
-    const int r0 = blockIdx.x * 128, c0 = blockIdx.y * 64;   // neighbouring blocks write neighbouring 128-byte pieces
+    __shared__ unsigned int abs_s[64];
+    const int c0 = blockIdx.y * 64;   // neighbouring blocks write neighbouring 128-byte pieces
     const int tid = threadIdx.x;
-    unsigned int ss = 0u;
+    if (tid < 64) abs_s[tid] = 0u;
+    // A block takes `tiles_per_block` consecutive row tiles of its 64 columns and keeps the column sums of |x| in
+    // registers across them: one atomic per column and BLOCK on col_abs (with one per tile the 512 row tiles of
+    // workload 5's activations queued 512 atomics on every address and doubled the kernel's time).
+    unsigned int part[2][4] = {};
+    const int row_tiles = (rows + 127) / 128;
+    const int t_end = min(row_tiles, ((int)blockIdx.x + 1) * tiles_per_block);
+    for (int rt = (int)blockIdx.x * tiles_per_block; rt < t_end; ++rt) {
+        const int r0 = rt * 128;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int i = tid + 256 * j, row = i >> 4, cd = i & 15;
-        uint32_t w = 0u;
-        const int r = r0 + row, c = c0 + 4 * cd;
-        if (r < rows) {
-            const int8_t *p = src + (int64_t)r * cols + c;
-            if (VEC) {
-                if (c < cols) w = *reinterpret_cast<const uint32_t *>(p);
-            } else {
+        for (int j = 0; j < 8; ++j) {
+            const int i = tid + 256 * j, row = i >> 4, cd = i & 15;
+            uint32_t w = 0u;
+            const int r = r0 + row, c = c0 + 4 * cd;
+            if (r < rows) {
+                const int8_t *p = src + (int64_t)r * cols + c;
+                if (VEC) {
+                    if (c < cols) w = *reinterpret_cast<const uint32_t *>(p);
+                } else {
 #pragma unroll
-                for (int b = 0; b < 4; ++b)
-                    if (c + b < cols) w |= (uint32_t)(uint8_t)p[b] << (8 * b);
+                    for (int b = 0; b < 4; ++b)
+                        if (c + b < cols) w |= (uint32_t)(uint8_t)p[b] << (8 * b);
+                }
+            }
+            tile[row * 17 + cd] = w;
+        }
+        __syncthreads();
+        const int rg = tid & 31;
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int cg = (tid >> 5) + 8 * p;
+            const uint32_t d0 = tile[(4 * rg) * 17 + cg], d1 = tile[(4 * rg + 1) * 17 + cg];
+            const uint32_t d2 = tile[(4 * rg + 2) * 17 + cg], d3 = tile[(4 * rg + 3) * 17 + cg];
+            const uint32_t t0 = bperm(d1, d0, 0x05010400u), t2 = bperm(d3, d2, 0x05010400u);
+            const uint32_t t1 = bperm(d1, d0, 0x07030602u), t3 = bperm(d3, d2, 0x07030602u);
+            const uint32_t o[4] = {bperm(t2, t0, 0x05040100u), bperm(t2, t0, 0x07060302u),
+                                   bperm(t3, t1, 0x05040100u), bperm(t3, t1, 0x07060302u)};
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int c = c0 + 4 * cg + b;
+                if (c < cols) *reinterpret_cast<uint32_t *>(dst + (int64_t)c * ldd + r0 + 4 * rg) = o[b];
+                // sum of |x| over the four int8 of the word: |x| = |(x + 128) - 128| on the biased bytes
+                part[p][b] += __builtin_amdgcn_sad_u8(o[b] ^ 0x80808080u, 0x80808080u, 0u);
             }
         }
-        tile[row * 17 + cd] = w;
+        __syncthreads();   // the tile is overwritten by the next trip
+    }
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-            const int v = (int)(int8_t)(w >> (8 * b));
-            ss += (unsigned int)(v * v);
+            // the 32 lanes of a half-wave hold the same column: add them up, one LDS atomic per half-wave
+            unsigned int v = part[p][b];
+#pragma unroll
+            for (int off = 16; off > 0; off >>= 1) v += (unsigned int)__shfl_xor((int)v, off, 32);
+            if ((tid & 31) == 0) atomicAdd(&abs_s[4 * ((tid >> 5) + 8 * p) + b], v);
         }
-    }
     __syncthreads();
-    const int rg = tid & 31;
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-        const int cg = (tid >> 5) + 8 * p;
-        const uint32_t d0 = tile[(4 * rg) * 17 + cg], d1 = tile[(4 * rg + 1) * 17 + cg];
-        const uint32_t d2 = tile[(4 * rg + 2) * 17 + cg], d3 = tile[(4 * rg + 3) * 17 + cg];
-        const uint32_t t0 = bperm(d1, d0, 0x05010400u), t2 = bperm(d3, d2, 0x05010400u);
-        const uint32_t t1 = bperm(d1, d0, 0x07030602u), t3 = bperm(d3, d2, 0x07030602u);
-        const uint32_t o[4] = {bperm(t2, t0, 0x05040100u), bperm(t2, t0, 0x07060302u),
-                               bperm(t3, t1, 0x05040100u), bperm(t3, t1, 0x07060302u)};
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int c = c0 + 4 * cg + b;
-            if (c < cols) *reinterpret_cast<uint32_t *>(dst + (int64_t)c * ldd + r0 + 4 * rg) = o[b];
-        }
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) ss += (unsigned int)__shfl_down((int)ss, off, 64);
-    if ((threadIdx.x & 63) == 0) wave_ss[threadIdx.x >> 6] = ss;
-    __syncthreads();   // (the barrier above separates the tile's writes from its reads; this one the partial sums)
-    if (threadIdx.x == 0)   // at most 128 * 64 * 128^2 = 2^27
-        block_sumsq[(size_t)blockIdx.y * gridDim.x + blockIdx.x] = wave_ss[0] + wave_ss[1] + wave_ss[2] + wave_ss[3];
+    if (tid < 64 && c0 + tid < cols && abs_s[tid] != 0u) atomicAdd(&col_abs[c0 + tid], abs_s[tid]);
 }
 
 // Chooses the power-of-two scale of g and, for each backward product, the number of limbs.  With
-// sigma = 2^e > 1.01 max|g| and L limbs, q = rint(g 2^(8L-1)/sigma) leaves a rounding error uniform
-// in +-sigma 2^-8L per entry, so a contraction over n_c index entries of mean square s has a random
-// error of about delta sigma 2^(1-8L) sqrt(n_c s / 12); L is the smallest count (3..6) that brings
-// this under 1.7e-7, a sixth of the absolute parity tolerance.
+// sigma = 2^e > 1.01 max|g| and L limbs, q = rint(g 2^(8L-1)/sigma) is off by at most half a unit, i.e. every
+// entry of g is represented to within sigma 2^-8L, so one output of a product, delta * sum_c g_c idx_c, is off by
+// at most delta sigma 2^-8L sum_c |idx_c| whatever the signs and values of g: a bound, not an estimate.  The
+// largest sum of |idx| over the contraction (one per output column: col_abs, from the transposition kernels)
+// goes in, and L is the smallest count (3..6) that brings the bound under 9e-7 - the absolute part of the
+// parity tolerance, less a margin for the roundings of the recombination and of the fp32 result, which are
+// relative (1e-7) and covered by its relative part.  If six limbs do not reach it (contractions of many
+// millions of large indices) six are used and the bound, stored in the plan, says what was reached.
+constexpr double kLimbBoundTarget = 9e-7;
+
 __global__ __launch_bounds__(1024)
 void plan_kernel(BwdPlan *plan, const unsigned int *__restrict__ block_max, int n_max,
-                 const unsigned int *__restrict__ ss_a, int n_ss_a, const unsigned int *__restrict__ ss_b, int n_ss_b,
-                 int M, int N, int K, float delta_a, float delta_b)
+                 const unsigned int *__restrict__ col_abs_a, int n_abs_a, const unsigned int *__restrict__ col_abs_b, int n_abs_b,
+                 float delta_a, float delta_b)
 {
-    __shared__ unsigned int red_m[1024];
-    __shared__ unsigned long long red_a[1024], red_b[1024];
-    // one block of 1024 threads, four independent loads per thread and trip (the arrays hold up to a few ten
+    __shared__ unsigned int red_m[1024], red_a[1024], red_b[1024];
+    // one block of 1024 threads, four independent loads per thread and trip (the first array holds up to a few
     // thousand per-block results; a single dependent chain per thread is all latency)
     const int t = threadIdx.x;
-    unsigned int m = 0u;
-    unsigned long long sa = 0ull, sb = 0ull;
+    unsigned int m = 0u, sa = 0u, sb = 0u;
     for (int i = t; i < n_max; i += 4096) {
         const unsigned int v0 = block_max[i], v1 = i + 1024 < n_max ? block_max[i + 1024] : 0u;
         const unsigned int v2 = i + 2048 < n_max ? block_max[i + 2048] : 0u, v3 = i + 3072 < n_max ? block_max[i + 3072] : 0u;
         m = max(max(m, v0), max(max(v1, v2), v3));
     }
-    for (int i = t; i < n_ss_a; i += 4096) {
-        const unsigned int v0 = ss_a[i], v1 = i + 1024 < n_ss_a ? ss_a[i + 1024] : 0u;
-        const unsigned int v2 = i + 2048 < n_ss_a ? ss_a[i + 2048] : 0u, v3 = i + 3072 < n_ss_a ? ss_a[i + 3072] : 0u;
-        sa += ((unsigned long long)v0 + v1) + ((unsigned long long)v2 + v3);
-    }
-    for (int i = t; i < n_ss_b; i += 4096) {
-        const unsigned int v0 = ss_b[i], v1 = i + 1024 < n_ss_b ? ss_b[i + 1024] : 0u;
-        const unsigned int v2 = i + 2048 < n_ss_b ? ss_b[i + 2048] : 0u, v3 = i + 3072 < n_ss_b ? ss_b[i + 3072] : 0u;
-        sb += ((unsigned long long)v0 + v1) + ((unsigned long long)v2 + v3);
-    }
+    for (int i = t; i < n_abs_a; i += 1024) sa = max(sa, col_abs_a[i]);
+    for (int i = t; i < n_abs_b; i += 1024) sb = max(sb, col_abs_b[i]);
     red_m[t] = m; red_a[t] = sa; red_b[t] = sb;
     __syncthreads();
     for (int off = 512; off > 0; off >>= 1) {
         if (t < off) {
             red_m[t] = max(red_m[t], red_m[t + off]);
-            red_a[t] += red_a[t + off];
-            red_b[t] += red_b[t + off];
+            red_a[t] = max(red_a[t], red_a[t + off]);
+            red_b[t] = max(red_b[t], red_b[t + off]);
         }
         __syncthreads();
     }
@@ -1087,12 +1116,13 @@ void plan_kernel(BwdPlan *plan, const unsigned int *__restrict__ block_max, int 
     int e = 0;
     if (amax > 0.0f) frexpf(amax * 1.01f, &e);   // amax * 1.01 = f 2^e with f in [0.5, 1)
     e = max(min(e, 127), -80);                   // keeps 2^(8L-1-e) a normal float for every L
-    const double msq_a = (double)red_a[0] / fmax(1.0, (double)M * (double)K);
-    const double msq_b = (double)red_b[0] / fmax(1.0, (double)N * (double)K);
-    const double target = 1.7e-7;
+    // d_a_hat contracts g with b_idx (step delta_b), d_b_hat with a_idx (step delta_a)
+    const double unit_da = (double)delta_b * (double)red_b[0], unit_db = (double)delta_a * (double)red_a[0];
     int la = kMinLimbs, lb = kMinLimbs;
-    while (la < kMaxLimbs && (double)delta_b * ldexp(1.0, e + 1 - 8 * la) * sqrt((double)N * msq_b / 12.0) > target) ++la;
-    while (lb < kMaxLimbs && (double)delta_a * ldexp(1.0, e + 1 - 8 * lb) * sqrt((double)M * msq_a / 12.0) > target) ++lb;
+    while (la < kMaxLimbs && unit_da * ldexp(1.0, e - 8 * la) > kLimbBoundTarget) ++la;
+    while (lb < kMaxLimbs && unit_db * ldexp(1.0, e - 8 * lb) > kLimbBoundTarget) ++lb;
+    plan->bound_da = unit_da * ldexp(1.0, e - 8 * la);
+    plan->bound_db = unit_db * ldexp(1.0, e - 8 * lb);
     plan->limbs_da = la;
     plan->limbs_db = lb;
     plan->gscale_da = ldexpf(1.0f, 8 * la - 1 - e);
@@ -1159,7 +1189,7 @@ inline unsigned blocks_for(int64_t n, int per_block, int cap = 65536)
 // workspace layout of a backward call
 struct BwdLayout {
     size_t plan, block_max, ss_a, ss_b, bt, at, partial, corr_da, corr_db, colsum_partial, total;
-    int n_max, n_ss_a, n_ss_b;    // per-block partial results of the absmax and the two transpose launches
+    int n_max;                    // per-block partial results of the absmax launch
     int64_t ldn, ldm;             // row strides of the transposed index copies (odd multiples of kLBK)
     int nk_n, nk_m;               // K-tiles of the two contractions
     int splits, kt_per_split;     // d_b_hat: splits of the contraction over M
@@ -1186,13 +1216,11 @@ BwdLayout bwd_layout(int32_t M, int32_t N, int32_t K)
     L.splits = (int)splits;
     L.kt_per_split = (int)per;
     L.n_max = (int)blocks_for(((int64_t)M * N) >> 2, 2048, 2048);
-    L.n_ss_a = (int)(((int64_t)M + 127) / 128 * ((K + 63) / 64));
-    L.n_ss_b = (int)(((int64_t)N + 127) / 128 * ((K + 63) / 64));
     size_t off = 0;
     L.plan = off;    off += align_up(sizeof(BwdPlan), 256);
     L.block_max = off; off += align_up((size_t)L.n_max * sizeof(unsigned int), 256);
-    L.ss_a = off;    off += align_up((size_t)L.n_ss_a * sizeof(unsigned int), 256);
-    L.ss_b = off;    off += align_up((size_t)L.n_ss_b * sizeof(unsigned int), 256);
+    L.ss_a = off;    off += align_up((size_t)K * sizeof(unsigned int), 256);   // sums of |a_idx| per column, directly followed by
+    L.ss_b = off;    off += align_up((size_t)K * sizeof(unsigned int), 256);   // sums of |b_idx| per column (cleared together)
     L.bt = off;      off += align_up((size_t)K * (size_t)L.ldn, 256);           // b_idx^T: [K][ldn]
     L.at = off;      off += align_up((size_t)K * (size_t)L.ldm, 256);           // a_idx^T: [K][ldm]
     L.partial = off; off += L.splits > 1 ? align_up((size_t)L.splits * (size_t)N * (size_t)K * sizeof(double), 256) : 0;
@@ -1238,11 +1266,15 @@ int launch_limb_gemm(LimbArgs a, bool trans, hipStream_t stream)
     return check_launch();
 }
 
-void launch_transpose(const int8_t *src, int rows, int cols, int8_t *dst, int64_t ldd, unsigned int *block_sumsq, hipStream_t stream)
+void launch_transpose(const int8_t *src, int rows, int cols, int8_t *dst, int64_t ldd, unsigned int *col_abs, hipStream_t stream)
 {
-    const dim3 grid((rows + 127) / 128, (cols + 63) / 64);
-    if (cols % 4 == 0) CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel<true>, grid, dim3(256), 0, src, rows, cols, dst, ldd, block_sumsq);
-    else CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel<false>, grid, dim3(256), 0, src, rows, cols, dst, ldd, block_sumsq);
+    // about a thousand blocks where the matrix has that many tiles, each with up to 16 row tiles of its columns
+    const int row_tiles = (rows + 127) / 128, col_tiles = (cols + 63) / 64;
+    int per = (int)(((int64_t)row_tiles * col_tiles + 1023) / 1024);
+    per = per < 1 ? 1 : (per > 16 ? 16 : per);
+    const dim3 grid((row_tiles + per - 1) / per, col_tiles);
+    if (cols % 4 == 0) CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel<true>, grid, dim3(256), 0, src, rows, cols, dst, ldd, col_abs, per);
+    else CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel<false>, grid, dim3(256), 0, src, rows, cols, dst, ldd, col_abs, per);
 }
 
 }  // namespace
@@ -1346,11 +1378,12 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
     unsigned int *block_max = reinterpret_cast<unsigned int *>(base + L.block_max);
     unsigned int *ss_a = reinterpret_cast<unsigned int *>(base + L.ss_a);
     unsigned int *ss_b = reinterpret_cast<unsigned int *>(base + L.ss_b);
-    CDL_LAUNCH("absmax_kernel", stream, absmax_kernel, dim3(L.n_max), dim3(256), 0, gr, (int64_t)M * N, block_max);
+    CDL_LAUNCH("absmax_kernel", stream, absmax_kernel, dim3(L.n_max), dim3(256), 0, gr, (int64_t)M * N, block_max,
+               ss_a, (int)((L.ss_b - L.ss_a) / sizeof(unsigned int)) + K);
     if (d_a_hat) launch_transpose(b_idx, N, K, bt, L.ldn, ss_b, stream);
     if (d_b_hat) launch_transpose(a_idx, M, K, at, L.ldm, ss_a, stream);
     CDL_LAUNCH("plan_kernel", stream, plan_kernel, dim3(1), dim3(1024), 0, plan, block_max, L.n_max,
-               ss_a, d_b_hat ? L.n_ss_a : 0, ss_b, d_a_hat ? L.n_ss_b : 0, M, N, K, delta_a, delta_b);
+               ss_a, d_b_hat ? K : 0, ss_b, d_a_hat ? K : 0, delta_a, delta_b);
     // operands stored as index - offset: d_a_hat lacks delta_b * ob * sum_n g[m][n] in row m, d_b_hat lacks
     // delta_a * oa * sum_m g[m][n] in row n; both sums are taken of the unrounded g, in double
     double *corr_da = nullptr, *corr_db = nullptr;

@@ -259,3 +259,81 @@ def test_qgemm_bwd_leaves_the_limb_counts_in_the_workspace():
     assert all(3 <= v <= 6 for v in big) and all(v >= w for v, w in zip(big, base)), (big, base)
     small = limbs(g, gu.dev(cdl_inputs.draw_indices((M, K), 0, 3, seed=1)), gu.dev(cdl_inputs.draw_indices((N, K), -1, 1, seed=2)))
     assert all(s <= v for s, v in zip(small, base)), (small, base)
+
+
+def _limb_diagnostics(ws):
+    torch = gu.torch_mod()
+    head = ws[:48].cpu().numpy().tobytes()
+    limbs = np.frombuffer(head[:8], dtype=np.int32).tolist()
+    bounds = np.frombuffer(head[32:48], dtype=np.float64).tolist()
+    return limbs, bounds
+
+
+@pytest.mark.parametrize("M,N,K,lo_a,hi_a,lo_b,hi_b,scale", [
+    (640, 256, 384, -127, 127, -127, 127, 1.0), (3000, 96, 200, 0, 15, -7, 7, 1.0), (20000, 48, 130, 0, 15, -7, 7, 37.0),
+    (512, 2048, 256, -128, 127, -128, 127, 1e-3)])
+def test_limb_count_meets_the_worst_case_bound(oracle, M, N, K, lo_a, hi_a, lo_b, hi_b, scale):
+    """The bound the library reports for the rounding of g - step * sigma * 2^-8L * max over output columns of the sum
+    of |index| over the contraction - recomputed on the host from the operands and the limb counts, and at most
+    9e-7 (so that, whatever g looks like, the limbs cost less than the absolute tolerance)."""
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    rng = np.random.default_rng(M + N)
+    a = cdl_inputs.draw_indices((M, K), lo_a, hi_a, seed=M)
+    b = cdl_inputs.draw_indices((N, K), lo_b, hi_b, seed=N)
+    g = (rng.standard_normal((M, N)) * scale).astype(np.float32)
+    da, db = float(np.float32(0.56419)), float(np.float32(0.016623))
+    d_a, d_b = gu.empty((M, K), torch.float32), gu.empty((N, K), torch.float32)
+    ws = gu.workspace(cdl.qgemm_bwd_workspace_bytes(M, N, K))
+    cdl.cdl_qgemm_bwd(gu.dev(g), gu.dev(a), gu.dev(b), M, N, K, da, db, d_a, d_b, ws)
+    torch.cuda.synchronize()
+    (la, lb), (bound_a, bound_b) = _limb_diagnostics(ws)
+    sigma = 2.0 ** np.frexp(np.float32(np.abs(g).max()) * np.float32(1.01))[1]
+    want_a = db * sigma * 2.0 ** (-8 * la) * np.abs(b.astype(np.int64)).sum(axis=0).max()     # d_a_hat contracts over n with b_idx
+    want_b = da * sigma * 2.0 ** (-8 * lb) * np.abs(a.astype(np.int64)).sum(axis=0).max()
+    if N > 32:      # (shorter contractions form d_a_hat directly in double)
+        assert bound_a == pytest.approx(want_a, rel=1e-12) and bound_a <= 9e-7
+        assert la == 3 or db * sigma * 2.0 ** (-8 * (la - 1)) * np.abs(b.astype(np.int64)).sum(axis=0).max() > 9e-7   # and no limb too many
+    assert bound_b == pytest.approx(want_b, rel=1e-12) and bound_b <= 9e-7
+    assert lb == 3 or da * sigma * 2.0 ** (-8 * (lb - 1)) * np.abs(a.astype(np.int64)).sum(axis=0).max() > 9e-7
+    r_a, r_b = oracle.qgemm_bwd(g, a, b, da, db)
+    gu.assert_close(d_a.cpu().numpy(), r_a, "d_a_hat")
+    gu.assert_close(d_b.cpu().numpy(), r_b, "d_b_hat")
+    # the error actually made stays under the bound (plus the fp32 rounding of the result)
+    assert np.max(np.abs(d_b.cpu().numpy() - r_b) - 6e-8 * np.abs(r_b)) <= bound_b
+    if N > 32:
+        assert np.max(np.abs(d_a.cpu().numpy() - r_a) - 6e-8 * np.abs(r_a)) <= bound_a
+
+
+@pytest.mark.parametrize("limbs_if_statistical", [3])
+def test_coherent_rounding_of_a_two_valued_gradient(oracle, limbs_if_statistical):
+    """The case a statistical choice of the limb count gets wrong: indices of one sign, a gradient of two values whose
+    roundings to three limbs err in the same direction, and outputs that nearly cancel - every entry's rounding
+    error then adds up instead of averaging out, and only the relative part of the tolerance could hide it, which a
+    result near zero does not have.  Three limbs would leave an error of about half a unit per entry times the sum of
+    the indices; the library's bound makes it choose more, and the result meets the stated tolerance."""
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    M, N, K = 4096, 64, 256
+    rng = np.random.default_rng(0)
+    a = rng.integers(8, 16, (M, K)).astype(np.int8)            # all positive
+    b = rng.integers(1, 8, (N, K)).astype(np.int8)
+    unit = 2.0 ** -23                                           # three limbs on sigma = 1 resolve 2^-23
+    v_plus = np.float32((3_000_000 + 0.49) * unit)              # rounds down by 0.49 units
+    v_minus = np.float32(-(3_000_000 + 0.51) * unit)            # rounds down (away from zero) by 0.49 units
+    assert abs(float(v_plus)) < 0.5 and abs(float(v_minus)) < 0.5
+    g = np.where(rng.random((M, N)) < 0.5, v_plus, v_minus).astype(np.float32)
+    g[0, 0] = np.float32(0.99)                                  # fixes sigma = 1
+    da, db = float(np.float32(0.25)), float(np.float32(0.02))
+    d_a, d_b = gu.empty((M, K), torch.float32), gu.empty((N, K), torch.float32)
+    ws = gu.workspace(cdl.qgemm_bwd_workspace_bytes(M, N, K))
+    cdl.cdl_qgemm_bwd(gu.dev(g), gu.dev(a), gu.dev(b), M, N, K, da, db, d_a, d_b, ws)
+    torch.cuda.synchronize()
+    (la, lb), (bound_a, bound_b) = _limb_diagnostics(ws)
+    # what three limbs would have cost on d_b_hat: 0.49 units per entry, all in one direction
+    coherent = da * 0.49 * unit * a.astype(np.int64).sum(axis=0).min()
+    assert coherent > 3e-6 and lb > limbs_if_statistical and bound_b <= 9e-7
+    r_a, r_b = oracle.qgemm_bwd(g, a, b, da, db)
+    assert np.median(np.abs(r_b)) < 0.2 * da * float(v_plus) * a.astype(np.int64).sum(axis=0).mean()   # the outputs do cancel
+    gu.assert_close(d_a.cpu().numpy(), r_a, "d_a_hat")
+    gu.assert_close(d_b.cpu().numpy(), r_b, "d_b_hat")
