@@ -64,8 +64,9 @@ def ensure_built():
 class Step:
     """Device buffers and the sequence of library calls of one layer step."""
 
-    def __init__(self, wl, seed=0):
+    def __init__(self, wl, seed=0, fused=False):
         import torch
+        self.fused = fused and wl.has_gemm and wl.N > 32 and wl.K % 4 == 0
         import paper_2501_09849_amd as cdl
         self.torch, self.cdl, self.wl = torch, cdl, wl
         dev = "cuda:0"
@@ -113,8 +114,13 @@ class Step:
         M, N, K = wl.M, wl.N, wl.K
         cdl.cdl_quantize_fwd(self.X, self.nX, *xa, self.Xi, self.Xsoft, self.margX, s[1:2], self.ws)
         cdl.cdl_qgemm_fwd(self.Xi, self.Wi, M, N, K, x.delta, w.delta, None, self.Y, self.ws)
-        cdl.cdl_qgemm_bwd(self.G, self.Xi, self.Wi, M, N, K, x.delta, w.delta, self.dXh, self.dWh, self.ws)
-        cdl.cdl_quantize_bwd(self.X, self.dXh, self.nX, *xa, self.dX, s[4:5], s[5:6], self.ws)
+        if self.fused:
+            # the activation-gradient product applies the quantizer's backward pass in its epilogue: dL/dQ(X) is never written
+            cdl.cdl_qgemm_bwd_quantize_bwd(self.G, self.Xi, self.Wi, M, N, K, self.X, *xa, w.delta, self.dX, s[4:5], s[5:6],
+                                           self.dWh, self.ws)
+        else:
+            cdl.cdl_qgemm_bwd(self.G, self.Xi, self.Wi, M, N, K, x.delta, w.delta, self.dXh, self.dWh, self.ws)
+            cdl.cdl_quantize_bwd(self.X, self.dXh, self.nX, *xa, self.dX, s[4:5], s[5:6], self.ws)
         cdl.cdl_quantize_bwd(self.W, self.dWh, self.nW, *wa, self.dW, s[2:3], s[3:4], self.ws)
 
 
@@ -135,6 +141,8 @@ def kernel_model(wl, name, occurrence):
     if name == "quantize_bwd_kernel":
         n = (nX if occurrence == 0 else nW) if wl.has_gemm else nW
         return "hbm", 12.0 * n, n
+    if name == "limb_gemm_kernel(d_a_hat + quantize_bwd)":
+        return "mfma", 2.0 * wl.M * wl.N * wl.K, 0
     if name.startswith("qgemm_kernel") or name.startswith("limb_gemm_kernel"):
         return "mfma", 2.0 * wl.M * wl.N * wl.K, 0
     if name == "absmax_kernel":
@@ -483,6 +491,10 @@ def main():
     ap.add_argument("--workload", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
+    ap.add_argument("--fused", action="store_true",
+                    help="backward step of the activations through cdl_qgemm_bwd_quantize_bwd (the quantizer's backward pass in the "
+                         "product's epilogue, dL/dQ(X) never written) instead of cdl_qgemm_bwd followed by cdl_quantize_bwd; "
+                         "measured slower by 1-3 %% on workload 5, so the two calls are the default")
     ap.add_argument("--step-only", action="store_true",
                     help="time the step and nothing else (for profiler runs): no quantizer-only legs, so `value` is null")
     ap.add_argument("--copy-probe", action="store_true",
@@ -500,7 +512,7 @@ def main():
         sys.exit(3)
     cdl.load()
     wl = cdl_inputs.workload(args.workload)
-    st = Step(wl)
+    st = Step(wl, fused=args.fused)
 
     if args.copy_probe:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
@@ -577,7 +589,8 @@ def main():
     out["data"] = "synthetic"
     cfg = {"workload": "%d:%s" % (wl.number, wl.name), "entries_per_step": n_total,
            "w_levels": wl.w_spec.n_levels, "kappa": wl.w_spec.alpha * wl.w_spec.delta ** 2,
-           "cache": "cold by size: a step moves about 3.8 GB, the last-level cache holds 256 MB" if wl.number == 5 else "steps back to back"}
+           "cache": "cold by size: a step moves about 3.8 GB, the last-level cache holds 256 MB" if wl.number == 5 else "steps back to back",
+           "backward_of_activations": "cdl_qgemm_bwd_quantize_bwd (fused epilogue)" if st.fused else "cdl_qgemm_bwd + cdl_quantize_bwd"}
     if wl.has_gemm:
         cfg.update(M=wl.M, N=wl.N, K=wl.K, x_levels=wl.x_spec.n_levels)
     out["config"] = cfg
@@ -593,7 +606,7 @@ def main():
         torch.cuda.synchronize()
         limbs = st.ws[:8].view(torch.int32).cpu().tolist()
         for r in kernels:
-            which = {"limb_gemm_kernel(d_a_hat)": 0, "limb_gemm_kernel(d_b_hat)": 1}.get(r["kernel"])
+            which = {"limb_gemm_kernel(d_a_hat)": 0, "limb_gemm_kernel(d_a_hat + quantize_bwd)": 0, "limb_gemm_kernel(d_b_hat)": 1}.get(r["kernel"])
             if which is not None and "algorithmic_TOPS" in r:
                 r["limbs"] = limbs[which]
                 r["issued_TOPS"] = r["algorithmic_TOPS"] * limbs[which]

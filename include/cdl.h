@@ -262,6 +262,26 @@ int cdl_qgemm_bwd_offset(const float *g, const int8_t *a_idx, const int8_t *b_id
                          void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * The backward step of Algorithm 1 for the activation operand in one call: cdl_qgemm_bwd followed by
+ * cdl_quantize_bwd on its d_a_hat, with the quantizer's backward pass (Lemma 1; eq. partialX3, Jgradqx,
+ * Jgrad_alpha_q) applied to each tile of dL/dQ(x) in the epilogue of the product, while the tile is still on the
+ * chip.  dL/dQ(x) itself is never written to memory or read back (on a transformer-sized layer that is a fifth of the
+ * backward pass's traffic).  Arguments as for the two calls it replaces:
+ *   theta_a   fp32[M,K], the activations that were quantized into a_idx with the quantizer *p_a
+ *   a_idx     int8[M,K] as cdl_quantize_fwd stored it (needed for d_b_hat only), b_idx int8[N,K] stored minus b_offset
+ *   d_theta_a fp32[M,K]  = (delta_b * sum_n g[m,n] * level index of b[n,k]) * dQ_d/dtheta(theta_a[m,k])   (required)
+ *   d_delta_a, d_alpha_a  the two scalar gradients of the activation quantizer       (DEVICE fp32[1], nullable)
+ *   d_b_hat   fp32[N,K] as in cdl_qgemm_bwd(_offset), with a_offset = cdl_index_offset(p_a)              (nullable)
+ * Results equal those of the two separate calls (the same arithmetic on the same fp32 intermediate; the scalar
+ * sums are added up in a different, fixed order).  Restrictions: M, N, K > 0, K a multiple of 4 and N > 32, else
+ * CDL_ERR_PARAM - use the two calls there.  Scratch: cdl_qgemm_bwd_workspace_bytes(M, N, K).
+ */
+int cdl_qgemm_bwd_quantize_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
+                               const float *theta_a, const cdl_qparams *p_a, float delta_b, int32_t b_offset,
+                               float *d_theta_a, float *d_delta_a, float *d_alpha_a, float *d_b_hat,
+                               void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * Optional per-kernel timing (a measurement aid, not part of the method).  While enabled, every
  * kernel the library enqueues is bracketed by a pair of HIP events recorded on the caller's
  * stream.  cdl_profile_collect waits for the recorded events, writes up to max_records entries

@@ -17,6 +17,7 @@ _LIB = None
 EXPORTS = (
     "cdl_quantize_workspace_bytes", "cdl_qgemm_fwd_workspace_bytes", "cdl_qgemm_bwd_workspace_bytes",
     "cdl_qgemm_fwd_offset_workspace_bytes", "cdl_index_offset", "cdl_qgemm_fwd_offset", "cdl_qgemm_bwd_offset",
+    "cdl_qgemm_bwd_quantize_bwd",
     "cdl_quantize_fwd", "cdl_quantize_fwd_static", "cdl_static_scratch_bytes", "cdl_quantize_bwd", "cdl_marginal_entropy", "cdl_qgemm_fwd", "cdl_qgemm_bwd",
     "cdl_quantize_draw", "cdl_entropy_bwd", "cdl_huffman_workspace_bytes", "cdl_huffman_bits",
     "cdl_profile_enable", "cdl_profile_collect", "cdl_probe_mfma_int8",
@@ -104,6 +105,8 @@ def load():
         L.cdl_index_offset.argtypes = [qp]
         L.cdl_qgemm_fwd_offset.restype = ctypes.c_int
         L.cdl_qgemm_fwd_offset.argtypes = [vp, vp, i32, i32, i32, f32, f32, i32, i32, vp, vp, vp, sz, vp]
+        L.cdl_qgemm_bwd_quantize_bwd.restype = ctypes.c_int
+        L.cdl_qgemm_bwd_quantize_bwd.argtypes = [vp, vp, vp, i32, i32, i32, vp, qp, f32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.cdl_qgemm_bwd_offset.restype = ctypes.c_int
         L.cdl_qgemm_bwd_offset.argtypes = [vp, vp, vp, i32, i32, i32, f32, f32, i32, i32, vp, vp, vp, sz, vp]
         L.cdl_profile_enable.restype = ctypes.c_int
@@ -254,6 +257,15 @@ def cdl_qgemm_bwd_offset(g, a_idx, b_idx, M, N, K, delta_a, delta_b, a_offset, b
     wp, wb = _ws(ws)
     _check(load().cdl_qgemm_bwd_offset(_ptr(g), _ptr(a_idx), _ptr(b_idx), M, N, K, delta_a, delta_b, int(a_offset), int(b_offset),
                                        _ptr(d_a_hat), _ptr(d_b_hat), wp, wb, _stream(stream)), "cdl_qgemm_bwd_offset")
+
+
+def cdl_qgemm_bwd_quantize_bwd(g, a_idx, b_idx, M, N, K, theta_a, lo_a, n_levels_a, delta_a, alpha_a, delta_b, d_theta_a,
+                               d_delta_a=None, d_alpha_a=None, d_b_hat=None, ws=None, stream=None, b_offset=0, top_k=0):
+    wp, wb = _ws(ws)
+    q = _qp(lo_a, n_levels_a, delta_a, alpha_a, top_k)
+    _check(load().cdl_qgemm_bwd_quantize_bwd(_ptr(g), _ptr(a_idx), _ptr(b_idx), M, N, K, _ptr(theta_a), ctypes.byref(q), delta_b,
+                                             int(b_offset), _ptr(d_theta_a), _ptr(d_delta_a), _ptr(d_alpha_a), _ptr(d_b_hat),
+                                             wp, wb, _stream(stream)), "cdl_qgemm_bwd_quantize_bwd")
 
 
 def cdl_qgemm_bwd(g, a_idx, b_idx, M, N, K, delta_a, delta_b, d_a_hat=None, d_b_hat=None, ws=None, stream=None):

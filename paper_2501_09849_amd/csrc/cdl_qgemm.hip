@@ -12,6 +12,7 @@
 // products are exact in int32 and are recombined in double in the epilogue.  L (3..6) is chosen on
 // the device so that the rounding of q stays well below the parity tolerance.
 #include "cdl_internal.h"
+#include "cdl_quantizer_math.h"
 
 #include <math.h>
 
@@ -223,6 +224,12 @@ struct LimbArgs {
     int which;            // 0 = d_a_hat, 1 = d_b_hat
     float *out;           // [rows][cols] (splits == 1)
     double *partial;      // [splits][rows][cols] (splits > 1)
+    // d_a_hat only: the quantizer's backward pass applied to the tile before it leaves the chip (fq_theta != null):
+    // out receives dL/dtheta instead of dL/dQ(theta), fq_partial one pair of partial scalar gradients per block
+    const float *fq_theta;    // [rows][cols] the tensor that was quantized into the index operand of the forward product
+    double *fq_partial;       // [work items][2]
+    QConst fq_k;
+    int fq_wsel;              // band_template(fq_k)
     const double *row_corr;   // [rows] or null: added to every entry of an output row (the index operand is stored with an offset:
                               // the missing part of the product is offset * step * sum of g over the contraction); splits == 1 only
 };
@@ -455,7 +462,7 @@ __device__ __forceinline__ void limbs_of4(const float (&g)[4], float gscale, uin
 // lets the scheduler put the VALU and LDS work into the shadow of the MFMAs.
 // TRANS: G is read transposed (rows of the product are columns of G).  VEC: 16-byte loads of G
 // (N % 4 == 0).
-template <int L, int TN, bool TRANS, bool VEC, bool LONG_RUNS>
+template <int L, int TN, bool TRANS, bool VEC, bool LONG_RUNS, bool FUSED = false>
 __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, float gscale, double out_scale)
 {
     constexpr int NB = 4 * TN * 32;
@@ -692,6 +699,97 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
         }
     };
 
+
+    // ---- the quantizer's backward pass in the epilogue (eq. partialX3, Jgradqx, Jgrad_alpha_q applied to the
+    // tile of dL/dQ(x) while it is still on the chip): the recombined tile goes to LDS as fp32 (the stages are free
+    // by now), then all threads walk it four entries at a time, load the matching entries of theta, evaluate the
+    // band of the CPMF as the stand-alone kernel does, and store dL/dtheta; dL/dQ(x) itself is never written. ----
+    auto fused_tile = [&]() {
+        constexpr int NBP = NB + 4;           // row pitch in floats: the two half-waves of a store land 16 banks apart
+        float *tile = reinterpret_cast<float *>(lds);
+        const int row0 = tile_r0 * kLRows, col0 = c_begin * NB;
+        constexpr int Q = NB / 4;             // groups of four columns per row
+        const QConst &k = a.fq_k;
+        // every thread takes T groups of four entries; all loads of theta are issued here, before the tile is
+        // recombined and written to LDS (with one wave per SIMD nothing else hides their latency)
+        constexpr int T = kLRows * Q / kLThreads;
+        static_assert(T * kLThreads == kLRows * Q, "whole trips");
+        float4 th4[T];
+        bool ok[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int e4 = tid + t * kLThreads, row = e4 / Q, c4 = e4 - row * Q;
+            const int grow = row0 + row, gcol = col0 + 4 * c4;
+            ok[t] = grow < a.rows && gcol < a.cols;          // (cols % 4 == 0: a group is inside or outside)
+            const int64_t o = (int64_t)min(grow, a.rows - 1) * a.cols + min(gcol, a.cols - 4);
+            th4[t] = load_stream4(a.fq_theta + o, k.stream);
+        }
+        __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
+        barrier();                            // every wave has read its last fragments
+        {
+            const int lrow = 4 * (lane >> 5), lcol = wave * TN * 32 + (lane & 31);
+#pragma unroll
+            for (int rr = 0; rr < 16; ++rr) {
+                const int dr = 8 * (rr >> 2) + (rr & 3);
+                const double rc = (a.row_corr && row0 + lrow + dr < a.rows) ? a.row_corr[row0 + lrow + dr] : 0.0;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    double run = (double)acc[L - 1][j][rr];
+#pragma unroll
+                    for (int l = L - 2; l >= 0; --l) run = __builtin_fma(run, 256.0, (double)acc[l][j][rr]);
+                    tile[(lrow + dr) * NBP + lcol + j * 32] = (float)__builtin_fma(run, out_scale, rc);
+                }
+            }
+        }
+        __syncthreads();
+        double acc_d = 0.0, acc_a = 0.0;
+        auto walk = [&](auto w_c) {
+            constexpr int W = decltype(w_c)::value;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const int e4 = tid + t * kLThreads, row = e4 / Q, c4 = e4 - row * Q;
+                const int grow = row0 + row, gcol = col0 + 4 * c4;
+                const float4 v = *reinterpret_cast<const float4 *>(tile + row * NBP + 4 * c4);
+                const float ge[4] = {v.x, v.y, v.z, v.w}, th[4] = {th4[t].x, th4[t].y, th4[t].z, th4[t].w};
+                float dv[4], sum_d = 0.0f, sum_a = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float d_th, t_d, t_a;
+                    quantizer_bwd_terms<W, true>(th[e], k, d_th, t_d, t_a);
+                    dv[e] = ge[e] * d_th;
+                    sum_d = fmaf(ge[e], t_d, sum_d);
+                    sum_a = fmaf(ge[e], t_a, sum_a);
+                }
+                if (ok[t]) {
+                    acc_d += (double)sum_d;
+                    acc_a += (double)sum_a;
+                    store_stream4(a.out + ((int64_t)grow * a.cols + gcol), dv[0], dv[1], dv[2], dv[3], k.stream);
+                }
+            }
+        };
+        switch (a.fq_wsel) {
+            case 1: walk(std::integral_constant<int, 1>{}); break;
+            case 2: walk(std::integral_constant<int, 2>{}); break;
+            case 3: walk(std::integral_constant<int, 3>{}); break;
+            case 4: walk(std::integral_constant<int, 4>{}); break;
+            default: walk(std::integral_constant<int, 0>{}); break;
+        }
+        // partial sums of the block, in a fixed order
+        __syncthreads();
+        double *red = reinterpret_cast<double *>(lds);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            acc_d += __shfl_down(acc_d, off, 64);
+            acc_a += __shfl_down(acc_a, off, 64);
+        }
+        if (lane == 0) { red[2 * wave] = acc_d; red[2 * wave + 1] = acc_a; }
+        __syncthreads();
+        if (tid == 0) {
+            a.fq_partial[2 * logical] = (red[0] + red[2]) + (red[4] + red[6]);
+            a.fq_partial[2 * logical + 1] = (red[1] + red[3]) + (red[5] + red[7]);
+        }
+    };
+
     // positions of the steps s, s+1, s+2, s+3 in the block's sequence: (row tile, column tile, K-tile), the
     // K-tile running fastest; past the end they stay on the last valid step (such loads go to registers or
     // to an LDS stage nobody reads)
@@ -790,10 +888,13 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
     // the loads issued for steps past the end write LDS: they must be done before this wave ends
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
 #undef CDL_INTERLEAVE
-    if (!RUNS) write_tile(0, 0);
+    if (!RUNS) {
+        if (FUSED) fused_tile();
+        else write_tile(0, 0);
+    }
 }
 
-template <bool TRANS, bool LONG_RUNS>
+template <bool TRANS, bool LONG_RUNS, bool FUSED = false>
 __global__ __launch_bounds__(kLThreads, 1)
 void limb_gemm_kernel(LimbArgs a)
 {
@@ -803,10 +904,10 @@ void limb_gemm_kernel(LimbArgs a)
     const float gscale = a.which == 0 ? a.plan->gscale_da : a.plan->gscale_db;
     const double out_scale = a.which == 0 ? a.plan->out_scale_da : a.plan->out_scale_db;
     switch (limbs) {
-        case 3: if (vec) limb_gemm_body<3, 3, TRANS, true, LONG_RUNS>(a, limb_lds, gscale, out_scale); else limb_gemm_body<3, 3, TRANS, false, LONG_RUNS>(a, limb_lds, gscale, out_scale); break;
-        case 4: if (vec) limb_gemm_body<4, 3, TRANS, true, LONG_RUNS>(a, limb_lds, gscale, out_scale); else limb_gemm_body<4, 3, TRANS, false, LONG_RUNS>(a, limb_lds, gscale, out_scale); break;
-        case 5: if (vec) limb_gemm_body<5, 3, TRANS, true, false>(a, limb_lds, gscale, out_scale); else limb_gemm_body<5, 3, TRANS, false, false>(a, limb_lds, gscale, out_scale); break;
-        default: if (vec) limb_gemm_body<6, 2, TRANS, true, false>(a, limb_lds, gscale, out_scale); else limb_gemm_body<6, 2, TRANS, false, false>(a, limb_lds, gscale, out_scale); break;
+        case 3: if (vec) limb_gemm_body<3, 3, TRANS, true, LONG_RUNS, FUSED>(a, limb_lds, gscale, out_scale); else limb_gemm_body<3, 3, TRANS, false, LONG_RUNS, FUSED>(a, limb_lds, gscale, out_scale); break;
+        case 4: if (vec) limb_gemm_body<4, 3, TRANS, true, LONG_RUNS, FUSED>(a, limb_lds, gscale, out_scale); else limb_gemm_body<4, 3, TRANS, false, LONG_RUNS, FUSED>(a, limb_lds, gscale, out_scale); break;
+        case 5: if (vec) limb_gemm_body<5, 3, TRANS, true, false, FUSED>(a, limb_lds, gscale, out_scale); else limb_gemm_body<5, 3, TRANS, false, false, FUSED>(a, limb_lds, gscale, out_scale); break;
+        default: if (vec) limb_gemm_body<6, 2, TRANS, true, false, FUSED>(a, limb_lds, gscale, out_scale); else limb_gemm_body<6, 2, TRANS, false, false, FUSED>(a, limb_lds, gscale, out_scale); break;
     }
 }
 
@@ -1188,7 +1289,8 @@ inline unsigned blocks_for(int64_t n, int per_block, int cap = 65536)
 
 // workspace layout of a backward call
 struct BwdLayout {
-    size_t plan, block_max, ss_a, ss_b, bt, at, partial, corr_da, corr_db, colsum_partial, total;
+    size_t plan, block_max, ss_a, ss_b, fq_partial, bt, at, partial, corr_da, corr_db, colsum_partial, total;
+    int fq_items;                 // most work items the fused activation-gradient product can have
     int n_max;                    // per-block partial results of the absmax launch
     int64_t ldn, ldm;             // row strides of the transposed index copies (odd multiples of kLBK)
     int nk_n, nk_m;               // K-tiles of the two contractions
@@ -1221,6 +1323,9 @@ BwdLayout bwd_layout(int32_t M, int32_t N, int32_t K)
     L.block_max = off; off += align_up((size_t)L.n_max * sizeof(unsigned int), 256);
     L.ss_a = off;    off += align_up((size_t)K * sizeof(unsigned int), 256);   // sums of |a_idx| per column, directly followed by
     L.ss_b = off;    off += align_up((size_t)K * sizeof(unsigned int), 256);   // sums of |b_idx| per column (cleared together)
+    // fused quantizer backward: one pair of partial scalar gradients per work item of the narrowest column tile (cleared with the above)
+    L.fq_items = (int)((((int64_t)M + kLRows - 1) / kLRows) * ((K + limb_cols(6) - 1) / limb_cols(6)));
+    L.fq_partial = off; off += align_up((size_t)L.fq_items * 2 * sizeof(double), 256);
     L.bt = off;      off += align_up((size_t)K * (size_t)L.ldn, 256);           // b_idx^T: [K][ldn]
     L.at = off;      off += align_up((size_t)K * (size_t)L.ldm, 256);           // a_idx^T: [K][ldm]
     L.partial = off; off += L.splits > 1 ? align_up((size_t)L.splits * (size_t)N * (size_t)K * sizeof(double), 256) : 0;
@@ -1252,14 +1357,17 @@ int launch_limb_gemm(LimbArgs a, bool trans, hipStream_t stream)
     // Runs pay off for short contractions (measured against one tile per block: -12 % at two K-tiles, -20 % at
     // one, +10 % at 24, where the start-up they save is small and the blocks, all in the same phase for the
     // whole launch, ask L2 for the same lines at the same moments).
-    const bool long_runs = a.kt_per_split <= 4;
-    const void *fn = trans ? (long_runs ? (const void *)limb_gemm_kernel<true, true> : (const void *)limb_gemm_kernel<true, false>)
+    const bool fused = a.fq_theta != nullptr;      // (one tile per block: the epilogue needs the LDS of the stages)
+    const bool long_runs = a.kt_per_split <= 4 && !fused;
+    const void *fn = fused ? (const void *)limb_gemm_kernel<false, false, true>
+                   : trans ? (long_runs ? (const void *)limb_gemm_kernel<true, true> : (const void *)limb_gemm_kernel<true, false>)
                            : (long_runs ? (const void *)limb_gemm_kernel<false, true> : (const void *)limb_gemm_kernel<false, false>);
     // more than 64 KiB of dynamic LDS has to be allowed per function (and per device: set it every time)
     const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLimbLdsBytes);
     if (e != hipSuccess) return hip_failed(e);
     const char *name = trans ? "limb_gemm_kernel(d_b_hat)" : "limb_gemm_kernel(d_a_hat)";
-    if (trans && long_runs) CDL_LAUNCH(name, stream, (limb_gemm_kernel<true, true>), dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
+    if (fused) CDL_LAUNCH("limb_gemm_kernel(d_a_hat + quantize_bwd)", stream, (limb_gemm_kernel<false, false, true>), dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
+    else if (trans && long_runs) CDL_LAUNCH(name, stream, (limb_gemm_kernel<true, true>), dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
     else if (trans) CDL_LAUNCH(name, stream, (limb_gemm_kernel<true, false>), dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
     else if (long_runs) CDL_LAUNCH(name, stream, (limb_gemm_kernel<false, true>), dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
     else CDL_LAUNCH(name, stream, (limb_gemm_kernel<false, false>), dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
@@ -1352,7 +1460,7 @@ int launch_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_
 
 int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
                      int32_t M, int32_t N, int32_t K, float delta_a, float delta_b, int32_t a_offset, int32_t b_offset,
-                     float *d_a_hat, float *d_b_hat, void *ws, hipStream_t stream)
+                     float *d_a_hat, float *d_b_hat, void *ws, hipStream_t stream, const FusedQuantBwd *fq)
 {
     if (d_a_hat && ((int64_t)M * K > 0) && N == 0)
         CDL_LAUNCH("zero_f32_kernel", stream, zero_f32_kernel, dim3(blocks_for((int64_t)M * K, 256, 4096)), dim3(256), 0, d_a_hat, (int64_t)M * K);
@@ -1379,7 +1487,8 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
     unsigned int *ss_a = reinterpret_cast<unsigned int *>(base + L.ss_a);
     unsigned int *ss_b = reinterpret_cast<unsigned int *>(base + L.ss_b);
     CDL_LAUNCH("absmax_kernel", stream, absmax_kernel, dim3(L.n_max), dim3(256), 0, gr, (int64_t)M * N, block_max,
-               ss_a, (int)((L.ss_b - L.ss_a) / sizeof(unsigned int)) + K);
+               ss_a, fq ? (int)((L.fq_partial - L.ss_a) / sizeof(unsigned int)) + L.fq_items * 4
+                        : (int)((L.ss_b - L.ss_a) / sizeof(unsigned int)) + K);
     if (d_a_hat) launch_transpose(b_idx, N, K, bt, L.ldn, ss_b, stream);
     if (d_b_hat) launch_transpose(a_idx, M, K, at, L.ldm, ss_a, stream);
     CDL_LAUNCH("plan_kernel", stream, plan_kernel, dim3(1), dim3(1024), 0, plan, block_max, L.n_max,
@@ -1414,8 +1523,20 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
         a.plan = plan; a.which = 0;
         a.out = d_a_hat; a.partial = nullptr;
         a.row_corr = corr_da;
+        if (fq) {
+            a.fq_theta = fq->theta;
+            a.fq_partial = reinterpret_cast<double *>(base + L.fq_partial);
+            a.fq_k = make_const(*fq->p);
+            a.fq_k.stream = (int64_t)M * K >= kStreamFrom;
+            a.fq_wsel = band_template(a.fq_k);
+        }
         rc = launch_limb_gemm(a, false, stream);
         if (rc != CDL_OK) return rc;
+        if (fq && (fq->d_delta || fq->d_alpha)) {
+            const double d = (double)fq->p->delta;
+            rc = launch_scalar_finalize(a.fq_partial, L.fq_items, 1.0, d * d * d, fq->d_delta, fq->d_alpha, stream);
+            if (rc != CDL_OK) return rc;
+        }
     }
     if (d_b_hat) {
         LimbArgs a{};
