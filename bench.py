@@ -363,6 +363,24 @@ def machine_probes():
         recs = cdl.cdl_profile_collect()
         cdl.cdl_profile_enable(False)
         out[key] = ops / (recs[0][1] * 1e-3) / 1e12
+    # For scale only (no part of the path): the vendor library's int8 product, int32 output, on the shapes of the
+    # forward product and of one limb of dL/dQ(x) of workload 5, uniformly random index bytes.
+    try:
+        for key, (m, n, k) in (("library_int8_gemm_TOPS_65536x3072x768", (65536, 3072, 768)),
+                               ("library_int8_gemm_TOPS_65536x768x3072", (65536, 768, 3072))):
+            a = torch.randint(-128, 128, (m, k), dtype=torch.int8, device="cuda:0")
+            b = torch.randint(-128, 128, (k, n), dtype=torch.int8, device="cuda:0")
+            for _ in range(2):
+                torch._int_mm(a, b)
+            e0.record()
+            for _ in range(5):
+                torch._int_mm(a, b)
+            e1.record()
+            torch.cuda.synchronize()
+            out[key] = 2.0 * m * n * k / (e0.elapsed_time(e1) / 5 * 1e-3) / 1e12
+            del a, b
+    except Exception as ex:   # the probe is context, not a requirement
+        out["library_int8_gemm"] = "unavailable: " + repr(ex)[:120]
     return out
 
 
