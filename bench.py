@@ -66,7 +66,7 @@ class Step:
 
     def __init__(self, wl, seed=0, fused=False):
         import torch
-        self.fused = fused and wl.has_gemm and wl.N > 32 and wl.K % 4 == 0
+        self.fused = fused if (fused and wl.has_gemm and wl.N > 32 and wl.K % 4 == 0) else None
         import paper_2501_09849_amd as cdl
         self.torch, self.cdl, self.wl = torch, cdl, wl
         dev = "cuda:0"
@@ -114,6 +114,12 @@ class Step:
         M, N, K = wl.M, wl.N, wl.K
         cdl.cdl_quantize_fwd(self.X, self.nX, *xa, self.Xi, self.Xsoft, self.margX, s[1:2], self.ws)
         cdl.cdl_qgemm_fwd(self.Xi, self.Wi, M, N, K, x.delta, w.delta, None, self.Y, self.ws)
+        if self.fused == "both":
+            # the whole backward step in one call: neither dL/dQ(X) nor dL/dQ(W) is written
+            cdl.cdl_qgemm_bwd_quantize_bwd(self.G, self.Xi, self.Wi, M, N, K, self.X, *xa, w.delta, self.dX, s[4:5], s[5:6],
+                                           None, self.ws, theta_b=self.W, qparams_b=wa, d_theta_b=self.dW, d_delta_b=s[2:3],
+                                           d_alpha_b=s[3:4])
+            return
         if self.fused:
             # the activation-gradient product applies the quantizer's backward pass in its epilogue: dL/dQ(X) is never written
             cdl.cdl_qgemm_bwd_quantize_bwd(self.G, self.Xi, self.Wi, M, N, K, self.X, *xa, w.delta, self.dX, s[4:5], s[5:6],
@@ -509,10 +515,10 @@ def main():
     ap.add_argument("--workload", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
-    ap.add_argument("--fused", action="store_true",
-                    help="backward step of the activations through cdl_qgemm_bwd_quantize_bwd (the quantizer's backward pass in the "
-                         "product's epilogue, dL/dQ(X) never written) instead of cdl_qgemm_bwd followed by cdl_quantize_bwd; "
-                         "measured slower by 1-3 %% on workload 5, so the two calls are the default")
+    ap.add_argument("--fused", nargs="?", const="both", default=None, choices=["activations", "both"],
+                    help="backward step through cdl_qgemm_bwd_quantize_bwd (the quantizer's backward pass applied where the products "
+                         "finish: dL/dQ(X), and with 'both' also dL/dQ(W), never written) instead of cdl_qgemm_bwd followed by "
+                         "cdl_quantize_bwd; measured slower by about 1 %% on workload 5, so the separate calls are the default")
     ap.add_argument("--step-only", action="store_true",
                     help="time the step and nothing else (for profiler runs): no quantizer-only legs, so `value` is null")
     ap.add_argument("--copy-probe", action="store_true",
@@ -608,7 +614,7 @@ def main():
     cfg = {"workload": "%d:%s" % (wl.number, wl.name), "entries_per_step": n_total,
            "w_levels": wl.w_spec.n_levels, "kappa": wl.w_spec.alpha * wl.w_spec.delta ** 2,
            "cache": "cold by size: a step moves about 3.8 GB, the last-level cache holds 256 MB" if wl.number == 5 else "steps back to back",
-           "backward_of_activations": "cdl_qgemm_bwd_quantize_bwd (fused epilogue)" if st.fused else "cdl_qgemm_bwd + cdl_quantize_bwd"}
+           "backward_step": ("cdl_qgemm_bwd_quantize_bwd (%s)" % st.fused) if st.fused else "cdl_qgemm_bwd + cdl_quantize_bwd"}
     if wl.has_gemm:
         cfg.update(M=wl.M, N=wl.N, K=wl.K, x_levels=wl.x_spec.n_levels)
     out["config"] = cfg
@@ -632,7 +638,7 @@ def main():
     out["kernels"] = kernels
     q_us = sum(r["avg_us"] for r in kernels if r["kernel"] in ("quantize_fwd_kernel", "quantize_bwd_kernel",
                                                                  "marginal_finalize_kernel", "scalar_finalize_kernel"))
-    if q_us:
+    if q_us and not st.fused:
         out["quantizer_in_step"] = {"gelem_per_s": n_total / (q_us * 1e-6) / 1e9, "hbm_frac": 21.0 * n_total / (q_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                                     "us": q_us, "cache": "cold by size"}
     gf = [r for r in kernels if r["kernel"] == "qgemm_kernel(fwd)"]
@@ -647,6 +653,27 @@ def main():
         out["index_gemm_fwd_roofline_bound"] = "hbm" if t_hbm > t_mfma else "mfma"
     if not args.no_extra and not args.step_only:
         out["step_as_hip_graph"] = graph_replay(st, args.steps)
+        if wl.has_gemm and wl.N > 32 and wl.K % 4 == 0 and not st.fused:
+            # the same step with the backward pass of both quantizers applied where the backward products finish
+            # (cdl_qgemm_bwd_quantize_bwd), against the separate calls: same buffers, same box, right after the timed
+            # steps, both without the per-kernel events of the timed region
+            def eager(mode):
+                st.fused = mode
+                for _ in range(2):
+                    st.run()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(args.steps):
+                    st.run()
+                torch.cuda.synchronize()
+                st.fused = None
+                return (time.perf_counter() - t0) * 1e3 / args.steps
+            ms_s, ms_f = eager(None), eager("both")
+            out["step_without_kernel_events"] = {
+                "separate_calls": {"ms_per_step": ms_s, "gelem_per_s": n_total / (ms_s * 1e-3) / 1e9},
+                "fused_backward": {"ms_per_step": ms_f, "gelem_per_s": n_total / (ms_f * 1e-3) / 1e9,
+                                   "calls": "cdl_qgemm_bwd_quantize_bwd for both operands instead of cdl_qgemm_bwd + 2 x cdl_quantize_bwd"},
+                "fused_over_separate": ms_f / ms_s}
     del st
     torch.cuda.empty_cache()
     if args.step_only:

@@ -262,8 +262,8 @@ int cdl_qgemm_bwd_offset(const float *g, const int8_t *a_idx, const int8_t *b_id
                          void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
- * The backward step of Algorithm 1 for the activation operand in one call: cdl_qgemm_bwd followed by
- * cdl_quantize_bwd on its d_a_hat, with the quantizer's backward pass (Lemma 1; eq. partialX3, Jgradqx,
+ * The backward step of Algorithm 1 for a layer in one call: cdl_qgemm_bwd followed by cdl_quantize_bwd on its
+ * d_a_hat (and, optionally, on its d_b_hat), with the quantizer's backward pass (Lemma 1; eq. partialX3, Jgradqx,
  * Jgrad_alpha_q) applied to each tile of dL/dQ(x) in the epilogue of the product, while the tile is still on the
  * chip.  dL/dQ(x) itself is never written to memory or read back (on a transformer-sized layer that is a fifth of the
  * backward pass's traffic).  Arguments as for the two calls it replaces:
@@ -272,13 +272,22 @@ int cdl_qgemm_bwd_offset(const float *g, const int8_t *a_idx, const int8_t *b_id
  *   d_theta_a fp32[M,K]  = (delta_b * sum_n g[m,n] * level index of b[n,k]) * dQ_d/dtheta(theta_a[m,k])   (required)
  *   d_delta_a, d_alpha_a  the two scalar gradients of the activation quantizer       (DEVICE fp32[1], nullable)
  *   d_b_hat   fp32[N,K] as in cdl_qgemm_bwd(_offset), with a_offset = cdl_index_offset(p_a)              (nullable)
- * Results equal those of the two separate calls (the same arithmetic on the same fp32 intermediate; the scalar
+ * The weight operand likewise, if theta_b is given (all five of its arguments may be NULL instead): the quantizer's
+ * backward pass on the weights (eq. partialW3, Jgradqw, Jgradq_alpha_w) is applied where the pieces of the
+ * contraction over M are added up, so dL/dQ(w) is not read back either:
+ *   theta_b   fp32[N,K], the weights that were quantized into b_idx with *p_b; p_b->delta must equal delta_b and
+ *             cdl_index_offset(p_b) must equal b_offset, else CDL_ERR_PARAM
+ *   d_theta_b fp32[N,K]  = (delta_a * sum_m g[m,n] * level index of a[m,k]) * dQ_d/dtheta(theta_b[n,k])   (required then)
+ *   d_delta_b, d_alpha_b  the two scalar gradients of the weight quantizer              (DEVICE fp32[1], nullable)
+ *   d_b_hat   may still be requested and is written by the same kernel.
+ * Results equal those of the separate calls (the same arithmetic on the same fp32 intermediate; the scalar
  * sums are added up in a different, fixed order).  Restrictions: M, N, K > 0, K a multiple of 4 and N > 32, else
- * CDL_ERR_PARAM - use the two calls there.  Scratch: cdl_qgemm_bwd_workspace_bytes(M, N, K).
+ * CDL_ERR_PARAM - use the separate calls there.  Scratch: cdl_qgemm_bwd_workspace_bytes(M, N, K).
  */
 int cdl_qgemm_bwd_quantize_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
                                const float *theta_a, const cdl_qparams *p_a, float delta_b, int32_t b_offset,
                                float *d_theta_a, float *d_delta_a, float *d_alpha_a, float *d_b_hat,
+                               const float *theta_b, const cdl_qparams *p_b, float *d_theta_b, float *d_delta_b, float *d_alpha_b,
                                void *ws, size_t ws_bytes, void *hip_stream);
 
 /*

@@ -106,7 +106,7 @@ def load():
         L.cdl_qgemm_fwd_offset.restype = ctypes.c_int
         L.cdl_qgemm_fwd_offset.argtypes = [vp, vp, i32, i32, i32, f32, f32, i32, i32, vp, vp, vp, sz, vp]
         L.cdl_qgemm_bwd_quantize_bwd.restype = ctypes.c_int
-        L.cdl_qgemm_bwd_quantize_bwd.argtypes = [vp, vp, vp, i32, i32, i32, vp, qp, f32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.cdl_qgemm_bwd_quantize_bwd.argtypes = [vp, vp, vp, i32, i32, i32, vp, qp, f32, i32, vp, vp, vp, vp, vp, qp, vp, vp, vp, vp, sz, vp]
         L.cdl_qgemm_bwd_offset.restype = ctypes.c_int
         L.cdl_qgemm_bwd_offset.argtypes = [vp, vp, vp, i32, i32, i32, f32, f32, i32, i32, vp, vp, vp, sz, vp]
         L.cdl_profile_enable.restype = ctypes.c_int
@@ -260,12 +260,16 @@ def cdl_qgemm_bwd_offset(g, a_idx, b_idx, M, N, K, delta_a, delta_b, a_offset, b
 
 
 def cdl_qgemm_bwd_quantize_bwd(g, a_idx, b_idx, M, N, K, theta_a, lo_a, n_levels_a, delta_a, alpha_a, delta_b, d_theta_a,
-                               d_delta_a=None, d_alpha_a=None, d_b_hat=None, ws=None, stream=None, b_offset=0, top_k=0):
+                               d_delta_a=None, d_alpha_a=None, d_b_hat=None, ws=None, stream=None, b_offset=0, top_k=0,
+                               theta_b=None, qparams_b=None, d_theta_b=None, d_delta_b=None, d_alpha_b=None):
+    """qparams_b: (lo, n_levels, delta, alpha[, top_k]) of the weight quantizer, with theta_b and d_theta_b."""
     wp, wb = _ws(ws)
     q = _qp(lo_a, n_levels_a, delta_a, alpha_a, top_k)
+    qb = _qp(*qparams_b) if qparams_b is not None else None
     _check(load().cdl_qgemm_bwd_quantize_bwd(_ptr(g), _ptr(a_idx), _ptr(b_idx), M, N, K, _ptr(theta_a), ctypes.byref(q), delta_b,
                                              int(b_offset), _ptr(d_theta_a), _ptr(d_delta_a), _ptr(d_alpha_a), _ptr(d_b_hat),
-                                             wp, wb, _stream(stream)), "cdl_qgemm_bwd_quantize_bwd")
+                                             _ptr(theta_b), ctypes.byref(qb) if qb is not None else None, _ptr(d_theta_b),
+                                             _ptr(d_delta_b), _ptr(d_alpha_b), wp, wb, _stream(stream)), "cdl_qgemm_bwd_quantize_bwd")
 
 
 def cdl_qgemm_bwd(g, a_idx, b_idx, M, N, K, delta_a, delta_b, d_a_hat=None, d_b_hat=None, ws=None, stream=None):

@@ -303,6 +303,7 @@ int cdl_qgemm_bwd_offset(const float *g, const int8_t *a_idx, const int8_t *b_id
 int cdl_qgemm_bwd_quantize_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
                                const float *theta_a, const cdl_qparams *p_a, float delta_b, int32_t b_offset,
                                float *d_theta_a, float *d_delta_a, float *d_alpha_a, float *d_b_hat,
+                               const float *theta_b, const cdl_qparams *p_b, float *d_theta_b, float *d_delta_b, float *d_alpha_b,
                                void *ws, size_t ws_bytes, void *hip_stream)
 {
     int rc = check_qparams(p_a);
@@ -312,17 +313,28 @@ int cdl_qgemm_bwd_quantize_bwd(const float *g, const int8_t *a_idx, const int8_t
     // the fused epilogue walks the tile four columns at a time, and very short contractions take a kernel without it
     if (K % 4 != 0 || N <= 32) return CDL_ERR_PARAM;
     if (!d_theta_a) return CDL_ERR_NULL;
+    const bool weights = theta_b || p_b || d_theta_b || d_delta_b || d_alpha_b;
+    if (weights) {
+        rc = check_qparams(p_b);
+        if (rc != CDL_OK) return rc;
+        if (!theta_b || !d_theta_b) return CDL_ERR_NULL;
+        // the weight quantizer is the one b_idx was stored with
+        if (p_b->delta != delta_b || index_offset(*p_b) != b_offset) return CDL_ERR_PARAM;
+    }
+    const bool want_db = d_b_hat || weights;
     if ((int64_t)N * 128 * 128 > 2147483647LL) return CDL_ERR_RANGE;
-    if (d_b_hat && (int64_t)M > 11000000LL) return CDL_ERR_RANGE;
-    if ((int64_t)M * K > 0 && (!g || !b_idx || !theta_a || (d_b_hat && !a_idx))) return CDL_ERR_NULL;
+    if (want_db && (int64_t)M > 11000000LL) return CDL_ERR_RANGE;
+    if (!g || !b_idx || !theta_a || (want_db && !a_idx)) return CDL_ERR_NULL;
     if (!aligned(g, 16) || !aligned(a_idx, 16) || !aligned(b_idx, 16) || !aligned(theta_a, 16) || !aligned(d_theta_a, 16) ||
-        !aligned(d_b_hat, 16) || !aligned(d_delta_a, 4) || !aligned(d_alpha_a, 4))
+        !aligned(d_b_hat, 16) || !aligned(d_delta_a, 4) || !aligned(d_alpha_a, 4) || !aligned(theta_b, 16) || !aligned(d_theta_b, 16) ||
+        !aligned(d_delta_b, 4) || !aligned(d_alpha_b, 4))
         return CDL_ERR_ALIGN;
     rc = check_ws(ws, ws_bytes, qgemm_bwd_workspace_bytes(M, N, K));
     if (rc != CDL_OK) return rc;
-    const FusedQuantBwd fq{theta_a, p_a, d_delta_a, d_alpha_a};
+    const FusedQuantBwd fq{theta_a, p_a, d_delta_a, d_alpha_a, nullptr};
+    const FusedQuantBwd fqb{theta_b, p_b, d_delta_b, d_alpha_b, d_theta_b};
     return launch_qgemm_bwd(g, a_idx, b_idx, M, N, K, p_a->delta, delta_b, index_offset(*p_a), b_offset, d_theta_a, d_b_hat, ws,
-                            (hipStream_t)hip_stream, &fq);
+                            (hipStream_t)hip_stream, &fq, weights ? &fqb : nullptr);
 }
 
 int cdl_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,

@@ -108,15 +108,19 @@ int launch_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_
 
 // fq != null: d_a_hat receives dL/dtheta of the activations (the quantizer's backward pass applied in the epilogue
 // of the product) and the two scalar gradients go to fq->d_delta / fq->d_alpha.
+// fqb != null: the same for the weights, applied where the splits of the weight-gradient product are added up:
+// fqb->d_theta receives dL/dtheta of the weights; d_b_hat (nullable then) still receives dL/dQ(w) when given.
 struct FusedQuantBwd {
-    const float *theta;       // [M][K] the tensor the a operand was quantized from
+    const float *theta;       // the tensor the operand was quantized from, in the operand's layout
     const cdl_qparams *p;     // its quantizer
     float *d_delta, *d_alpha; // DEVICE fp32[1], nullable
+    float *d_theta;           // weight side only: where dL/dtheta goes
 };
 
 int launch_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
                      int32_t M, int32_t N, int32_t K, float delta_a, float delta_b, int32_t a_offset, int32_t b_offset,
-                     float *d_a_hat, float *d_b_hat, void *ws, hipStream_t stream, const FusedQuantBwd *fq = nullptr);
+                     float *d_a_hat, float *d_b_hat, void *ws, hipStream_t stream, const FusedQuantBwd *fq = nullptr,
+                     const FusedQuantBwd *fqb = nullptr);
 
 // d_delta = mul_d * sum of partial[2 i], d_alpha = mul_a * sum of partial[2 i + 1], i < n, in a fixed order.
 int launch_scalar_finalize(const double *partial, int n, double mul_d, double mul_a, float *d_delta, float *d_alpha, hipStream_t stream);

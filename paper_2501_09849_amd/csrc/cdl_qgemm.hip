@@ -223,7 +223,8 @@ struct LimbArgs {
     const BwdPlan *plan;
     int which;            // 0 = d_a_hat, 1 = d_b_hat
     float *out;           // [rows][cols] (splits == 1)
-    double *partial;      // [splits][rows][cols] (splits > 1)
+    double *partial;      // [splits][rows][cols] (splits > 1, or to_partial)
+    int to_partial;       // 1: the unscaled sums go to `partial` as doubles even with one split (a reduction kernel follows)
     // d_a_hat only: the quantizer's backward pass applied to the tile before it leaves the chip (fq_theta != null):
     // out receives dL/dtheta instead of dL/dQ(theta), fq_partial one pair of partial scalar gradients per block
     const float *fq_theta;    // [rows][cols] the tensor that was quantized into the index operand of the forward product
@@ -670,7 +671,8 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
         // one address per row, the TN column tiles of a wave at fixed distances from it; tiles that do not reach
         // the edge of the matrix (FULL) store without a test
         const int64_t first = (int64_t)erow * a.cols + ecol;
-        const bool corr = a.row_corr != nullptr && a.splits == 1;
+        const bool direct = a.splits == 1 && !a.to_partial;      // the block writes the finished fp32 output itself
+        const bool corr = a.row_corr != nullptr && direct;
         auto emit = [&](auto full_c, auto *base) {
             constexpr bool FULL = decltype(full_c)::value;
             using T = std::remove_pointer_t<decltype(base)>;
@@ -689,7 +691,7 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
                 }
             }
         };
-        if (a.splits == 1) {
+        if (direct) {
             if (full) emit(std::true_type{}, a.out + first);
             else emit(std::false_type{}, a.out + first);
         } else {
@@ -940,6 +942,52 @@ void limb_reduce_kernel(const double *__restrict__ partial, int splits, int64_t 
 #pragma unroll
         for (int off = LANES / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
         if (sub == 0 && i < n) out[i] = (float)__builtin_fma(s, out_scale, row_corr ? row_corr[i / cols] : 0.0);
+    }
+}
+
+// limb_reduce_kernel<1> followed by the quantizer's backward pass on its output (Lemma 1; eq. partialW3, Jgradqw,
+// Jgradq_alpha_w): an entry of dL/dQ(w) is formed exactly as above, rounded to fp32 as above, optionally stored, and
+// multiplied by the partials of the quantizer at the matching entry of theta - the arithmetic of the stand-alone
+// backward kernel, on the same fp32 value it would have read back.  Partial scalar gradients: one pair per block.
+template <int W>
+__global__ __launch_bounds__(256)
+void limb_reduce_quantize_bwd_kernel(const double *__restrict__ partial, int splits, int64_t n, const BwdPlan *plan,
+                                     float *__restrict__ d_hat /* nullable */, const double *__restrict__ row_corr, int cols,
+                                     const float *__restrict__ theta, QConst k, float *__restrict__ d_theta,
+                                     double *__restrict__ fq_partial /* [gridDim.x][2] */)
+{
+    const double out_scale = plan->out_scale_db;
+    double acc_d = 0.0, acc_a = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+        int p = 0;
+        for (; p + 3 < splits; p += 4) {
+            s0 += partial[(int64_t)p * n + i];
+            s1 += partial[(int64_t)(p + 1) * n + i];
+            s2 += partial[(int64_t)(p + 2) * n + i];
+            s3 += partial[(int64_t)(p + 3) * n + i];
+        }
+        for (; p < splits; ++p) s0 += partial[(int64_t)p * n + i];
+        const double s = (s0 + s1) + (s2 + s3);
+        const float ge = (float)__builtin_fma(s, out_scale, row_corr ? row_corr[i / cols] : 0.0);
+        if (d_hat) d_hat[i] = ge;
+        float d_th, t_d, t_a;
+        quantizer_bwd_terms<W, true>(theta[i], k, d_th, t_d, t_a);
+        d_theta[i] = ge * d_th;
+        acc_d += (double)(ge * t_d);
+        acc_a += (double)(ge * t_a);
+    }
+    __shared__ double red[8];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        acc_d += __shfl_down(acc_d, off, 64);
+        acc_a += __shfl_down(acc_a, off, 64);
+    }
+    if ((threadIdx.x & 63) == 0) { red[2 * (threadIdx.x >> 6)] = acc_d; red[2 * (threadIdx.x >> 6) + 1] = acc_a; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        fq_partial[2 * (size_t)blockIdx.x] = (red[0] + red[2]) + (red[4] + red[6]);
+        fq_partial[2 * (size_t)blockIdx.x + 1] = (red[1] + red[3]) + (red[5] + red[7]);
     }
 }
 
@@ -1288,8 +1336,10 @@ inline unsigned blocks_for(int64_t n, int per_block, int cap = 65536)
 }
 
 // workspace layout of a backward call
+constexpr int kFusedReduceBlocks = 2048;   // most blocks of limb_reduce_quantize_bwd_kernel
+
 struct BwdLayout {
-    size_t plan, block_max, ss_a, ss_b, fq_partial, bt, at, partial, corr_da, corr_db, colsum_partial, total;
+    size_t plan, block_max, ss_a, ss_b, fq_partial, fqb_partial, bt, at, partial, corr_da, corr_db, colsum_partial, total;
     int fq_items;                 // most work items the fused activation-gradient product can have
     int n_max;                    // per-block partial results of the absmax launch
     int64_t ldn, ldm;             // row strides of the transposed index copies (odd multiples of kLBK)
@@ -1326,9 +1376,11 @@ BwdLayout bwd_layout(int32_t M, int32_t N, int32_t K)
     // fused quantizer backward: one pair of partial scalar gradients per work item of the narrowest column tile (cleared with the above)
     L.fq_items = (int)((((int64_t)M + kLRows - 1) / kLRows) * ((K + limb_cols(6) - 1) / limb_cols(6)));
     L.fq_partial = off; off += align_up((size_t)L.fq_items * 2 * sizeof(double), 256);
+    L.fqb_partial = off; off += align_up((size_t)kFusedReduceBlocks * 2 * sizeof(double), 256);   // same for the weight-gradient side: one pair per block
     L.bt = off;      off += align_up((size_t)K * (size_t)L.ldn, 256);           // b_idx^T: [K][ldn]
     L.at = off;      off += align_up((size_t)K * (size_t)L.ldm, 256);           // a_idx^T: [K][ldm]
-    L.partial = off; off += L.splits > 1 ? align_up((size_t)L.splits * (size_t)N * (size_t)K * sizeof(double), 256) : 0;
+    // (one split: used only when a reduction kernel with the quantizer's backward pass follows)
+    L.partial = off; off += align_up((size_t)L.splits * (size_t)N * (size_t)K * sizeof(double), 256);
     // operands stored with an offset: one correction per output row of either product, and the per-block column sums of g
     L.corr_da = off; off += align_up((size_t)M * sizeof(double), 256);
     L.corr_db = off; off += align_up((size_t)N * sizeof(double), 256);
@@ -1460,8 +1512,9 @@ int launch_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_
 
 int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
                      int32_t M, int32_t N, int32_t K, float delta_a, float delta_b, int32_t a_offset, int32_t b_offset,
-                     float *d_a_hat, float *d_b_hat, void *ws, hipStream_t stream, const FusedQuantBwd *fq)
+                     float *d_a_hat, float *d_b_hat, void *ws, hipStream_t stream, const FusedQuantBwd *fq, const FusedQuantBwd *fqb)
 {
+    const bool want_db = d_b_hat != nullptr || fqb != nullptr;     // the weight-gradient product runs
     if (d_a_hat && ((int64_t)M * K > 0) && N == 0)
         CDL_LAUNCH("zero_f32_kernel", stream, zero_f32_kernel, dim3(blocks_for((int64_t)M * K, 256, 4096)), dim3(256), 0, d_a_hat, (int64_t)M * K);
     if (d_b_hat && ((int64_t)N * K > 0) && M == 0)
@@ -1473,7 +1526,7 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
         if (N <= 16) CDL_LAUNCH("da_direct_kernel", stream, da_direct_kernel<16>, grid, dim3(256), 0, gr, b_idx, M, N, K, (double)delta_b, (double)b_offset, d_a_hat);
         else CDL_LAUNCH("da_direct_kernel", stream, da_direct_kernel<32>, grid, dim3(256), 0, gr, b_idx, M, N, K, (double)delta_b, (double)b_offset, d_a_hat);
         d_a_hat = nullptr;           // done; what follows is for the other product only
-        if (!d_b_hat) return check_launch();
+        if (!want_db) return check_launch();
     }
 
     const BwdLayout L = bwd_layout(M, N, K);
@@ -1490,9 +1543,9 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
                ss_a, fq ? (int)((L.fq_partial - L.ss_a) / sizeof(unsigned int)) + L.fq_items * 4
                         : (int)((L.ss_b - L.ss_a) / sizeof(unsigned int)) + K);
     if (d_a_hat) launch_transpose(b_idx, N, K, bt, L.ldn, ss_b, stream);
-    if (d_b_hat) launch_transpose(a_idx, M, K, at, L.ldm, ss_a, stream);
+    if (want_db) launch_transpose(a_idx, M, K, at, L.ldm, ss_a, stream);
     CDL_LAUNCH("plan_kernel", stream, plan_kernel, dim3(1), dim3(1024), 0, plan, block_max, L.n_max,
-               ss_a, d_b_hat ? K : 0, ss_b, d_a_hat ? K : 0, delta_a, delta_b);
+               ss_a, want_db ? K : 0, ss_b, d_a_hat ? K : 0, delta_a, delta_b);
     // operands stored as index - offset: d_a_hat lacks delta_b * ob * sum_n g[m][n] in row m, d_b_hat lacks
     // delta_a * oa * sum_m g[m][n] in row n; both sums are taken of the unrounded g, in double
     double *corr_da = nullptr, *corr_db = nullptr;
@@ -1501,7 +1554,7 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
         CDL_LAUNCH("g_rowsum_kernel", stream, g_rowsum_kernel, dim3(blocks_for(M, 4, 8192)), dim3(256), 0, gr, M, N,
                    (double)delta_b * (double)b_offset, corr_da);
     }
-    if (d_b_hat && a_offset != 0) {
+    if (want_db && a_offset != 0) {
         corr_db = reinterpret_cast<double *>(base + L.corr_db);
         double *cp = reinterpret_cast<double *>(base + L.colsum_partial);
         const int rows_per = (M + kColsumBlocks - 1) / kColsumBlocks;
@@ -1538,7 +1591,7 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
             if (rc != CDL_OK) return rc;
         }
     }
-    if (d_b_hat) {
+    if (want_db) {
         LimbArgs a{};
         a.G = gr; a.M = M; a.N = N;
         a.Bt = at; a.ldb = L.ldm;
@@ -1547,10 +1600,33 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
         a.tiles_r = (N + kLRows - 1) / kLRows; a.splits = L.splits; a.kt_per_split = L.kt_per_split;
         a.plan = plan; a.which = 1;
         a.out = d_b_hat; a.partial = partial;
+        a.to_partial = fqb ? 1 : 0;
         a.row_corr = corr_db;
         rc = launch_limb_gemm(a, true, stream);
         if (rc != CDL_OK) return rc;
-        if (L.splits > 1) {
+        if (fqb) {
+            // the sum over the splits (one or more) and the quantizer's backward pass on the weights in one kernel
+            QConst k = make_const(*fqb->p);
+            k.stream = 0;
+            double *fp = reinterpret_cast<double *>(base + L.fqb_partial);
+            const int blocks = (int)blocks_for((int64_t)N * K, 256, kFusedReduceBlocks);
+#define CDL_RQ(WW) CDL_LAUNCH("limb_reduce_kernel(+ quantize_bwd)", stream, (limb_reduce_quantize_bwd_kernel<WW>), dim3(blocks), dim3(256), 0, \
+                              partial, L.splits, (int64_t)N * K, plan, d_b_hat, corr_db, K, fqb->theta, k, fqb->d_theta, fp)
+            switch (band_template(k)) {
+                case 1: CDL_RQ(1); break;
+                case 2: CDL_RQ(2); break;
+                case 3: CDL_RQ(3); break;
+                case 4: CDL_RQ(4); break;
+                default: CDL_RQ(0); break;
+            }
+#undef CDL_RQ
+            rc = check_launch();
+            if (rc != CDL_OK) return rc;
+            if (fqb->d_delta || fqb->d_alpha) {
+                const double d = (double)fqb->p->delta;
+                rc = launch_scalar_finalize(fp, blocks, 1.0, d * d * d, fqb->d_delta, fqb->d_alpha, stream);
+            }
+        } else if (L.splits > 1) {
             if ((int64_t)N * K <= 65536 && L.splits >= 32)
                 CDL_LAUNCH("limb_reduce_kernel", stream, limb_reduce_kernel<16>, dim3(blocks_for((int64_t)N * K * 16, 256, 4096)), dim3(256), 0,
                            partial, L.splits, (int64_t)N * K, plan, d_b_hat, corr_db, K);

@@ -571,17 +571,29 @@ void quantize_bwd_uniform_kernel(const float *__restrict__ theta, const float *_
     }
 }
 
-// d_delta = mul_d * sum of partials; d_alpha = mul_a * sum of partials.  Fixed summation order.
-__global__ __launch_bounds__(256)
+// d_delta = mul_d * sum of partials; d_alpha = mul_a * sum of partials.  Fixed summation order: thread t adds the
+// pairs t, t + T, t + 2T, ... (four independent chains, so that four loads are in flight: with a few thousand pairs
+// one chain per thread is nothing but memory latency), then the threads are added up by halving.
+constexpr int kScalarFinThreads = 1024;
+
+__global__ __launch_bounds__(kScalarFinThreads)
 void scalar_finalize_kernel(const double *__restrict__ partial, int nblocks, double mul_d, double mul_a,
                             float *__restrict__ d_delta, float *__restrict__ d_alpha)
 {
-    __shared__ double sd[256], sa[256];
-    double a = 0.0, b = 0.0;
-    for (int i = threadIdx.x; i < nblocks; i += 256) { a += partial[2 * (size_t)i]; b += partial[2 * (size_t)i + 1]; }
-    sd[threadIdx.x] = a; sa[threadIdx.x] = b;
+    constexpr int T = kScalarFinThreads;
+    __shared__ double sd[T], sa[T];
+    const double2 *pairs = reinterpret_cast<const double2 *>(partial);
+    double a[4] = {0.0, 0.0, 0.0, 0.0}, b[4] = {0.0, 0.0, 0.0, 0.0};
+    int i = threadIdx.x;
+    for (; i + 3 * T < nblocks; i += 4 * T) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { const double2 v = pairs[i + u * T]; a[u] += v.x; b[u] += v.y; }
+    }
+    for (int u = 0; i < nblocks; i += T, ++u) { const double2 v = pairs[i]; a[u] += v.x; b[u] += v.y; }
+    sd[threadIdx.x] = (a[0] + a[1]) + (a[2] + a[3]);
+    sa[threadIdx.x] = (b[0] + b[1]) + (b[2] + b[3]);
     __syncthreads();
-    for (int off = 128; off > 0; off >>= 1) {
+    for (int off = T / 2; off > 0; off >>= 1) {
         if ((int)threadIdx.x < off) { sd[threadIdx.x] += sd[threadIdx.x + off]; sa[threadIdx.x] += sa[threadIdx.x + off]; }
         __syncthreads();
     }
@@ -1116,7 +1128,7 @@ int launch_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl
     if (rc != CDL_OK) return rc;
     if (want_scalars) {
         const double d = (double)p.delta;
-        CDL_LAUNCH("scalar_finalize_kernel", stream, scalar_finalize_kernel, dim3(1), dim3(256), 0, partial, grid, 1.0, d * d * d,
+        CDL_LAUNCH("scalar_finalize_kernel", stream, scalar_finalize_kernel, dim3(1), dim3(kScalarFinThreads), 0, partial, grid, 1.0, d * d * d,
                    d_delta, d_alpha);
         rc = check_launch();
     }
@@ -1125,7 +1137,7 @@ int launch_quantize_bwd(const float *theta, const float *g, int64_t n, const cdl
 
 int launch_scalar_finalize(const double *partial, int n, double mul_d, double mul_a, float *d_delta, float *d_alpha, hipStream_t stream)
 {
-    CDL_LAUNCH("scalar_finalize_kernel", stream, scalar_finalize_kernel, dim3(1), dim3(256), 0, partial, n, mul_d, mul_a, d_delta, d_alpha);
+    CDL_LAUNCH("scalar_finalize_kernel", stream, scalar_finalize_kernel, dim3(1), dim3(kScalarFinThreads), 0, partial, n, mul_d, mul_a, d_delta, d_alpha);
     return check_launch();
 }
 
@@ -1195,7 +1207,7 @@ int launch_entropy_bwd(const float *theta, const float *marg, const float *g_in,
     int rc = check_launch();
     if (rc != CDL_OK) return rc;
     if (want_scalars) {
-        CDL_LAUNCH("scalar_finalize_kernel", stream, scalar_finalize_kernel, dim3(1), dim3(256), 0, partial, grid,
+        CDL_LAUNCH("scalar_finalize_kernel", stream, scalar_finalize_kernel, dim3(1), dim3(kScalarFinThreads), 0, partial, grid,
                    mul_theta, (double)scale * delta * delta / (double)n, d_delta, d_alpha);
         rc = check_launch();
     }
