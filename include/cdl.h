@@ -316,6 +316,12 @@ int cdl_probe_mfma_int8(int32_t iters, int32_t random_operands, int32_t blocks, 
 
 int cdl_profile_enable(int enable);
 int cdl_profile_collect(cdl_profile_record *out, int max_records);
+/*
+ * Restricts the timing to launches recorded under exactly this kernel name (as cdl_profile_collect reports it);
+ * NULL or "" = every launch again.  An event pair costs a few microseconds of stream time per launch, so a
+ * caller that times a whole step and wants one kernel's duration from inside it brackets that kernel only.
+ */
+int cdl_profile_only(const char *kernel);
 
 /* Text for a cdl_status. */
 const char *cdl_status_string(int status);

@@ -20,7 +20,7 @@ EXPORTS = (
     "cdl_qgemm_bwd_quantize_bwd",
     "cdl_quantize_fwd", "cdl_quantize_fwd_static", "cdl_static_scratch_bytes", "cdl_quantize_bwd", "cdl_marginal_entropy", "cdl_qgemm_fwd", "cdl_qgemm_bwd",
     "cdl_quantize_draw", "cdl_entropy_bwd", "cdl_huffman_workspace_bytes", "cdl_huffman_bits",
-    "cdl_profile_enable", "cdl_profile_collect", "cdl_probe_mfma_int8",
+    "cdl_profile_enable", "cdl_profile_collect", "cdl_profile_only", "cdl_probe_mfma_int8",
     "cdl_status_string", "cdl_last_hip_error", "cdl_version",
 )
 
@@ -111,6 +111,8 @@ def load():
         L.cdl_qgemm_bwd_offset.argtypes = [vp, vp, vp, i32, i32, i32, f32, f32, i32, i32, vp, vp, vp, sz, vp]
         L.cdl_profile_enable.restype = ctypes.c_int
         L.cdl_profile_enable.argtypes = [ctypes.c_int]
+        L.cdl_profile_only.restype = ctypes.c_int
+        L.cdl_profile_only.argtypes = [ctypes.c_char_p]
         L.cdl_profile_collect.restype = ctypes.c_int
         L.cdl_profile_collect.argtypes = [ctypes.POINTER(ProfileRecord), ctypes.c_int]
         L.cdl_status_string.restype = ctypes.c_char_p
@@ -290,6 +292,11 @@ def cdl_probe_mfma_int8(iters: int, random_operands: bool, blocks: int, sink, st
 
 def cdl_profile_enable(enable: bool) -> None:
     _check(load().cdl_profile_enable(1 if enable else 0), "cdl_profile_enable")
+
+
+def cdl_profile_only(kernel: Optional[str]) -> None:
+    """Time only launches recorded under this kernel name; None = all launches."""
+    _check(load().cdl_profile_only(kernel.encode() if kernel else None), "cdl_profile_only")
 
 
 def cdl_profile_collect(max_records: int = 65536):

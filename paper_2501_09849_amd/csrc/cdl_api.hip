@@ -33,6 +33,7 @@ struct ProfileRec {
 };
 std::atomic<bool> g_profile_on{false};
 std::mutex g_profile_mutex;
+char g_profile_only[56] = "";                // when not empty: only launches recorded under this name are bracketed
 std::vector<ProfileRec> g_profile_recs;      // recorded, not yet collected
 std::vector<hipEvent_t> g_profile_free;      // events ready for reuse
 
@@ -53,6 +54,7 @@ ProfileScope::ProfileScope(const char *name, hipStream_t stream) : slot_(-1), st
 {
     if (!g_profile_on.load(std::memory_order_relaxed)) return;
     std::lock_guard<std::mutex> lock(g_profile_mutex);
+    if (g_profile_only[0] != '\0' && std::strcmp(g_profile_only, name) != 0) return;
     ProfileRec r{name, profile_event(), profile_event()};
     if (!r.start || !r.stop) return;
     (void)hipEventRecord(r.start, stream);
@@ -357,6 +359,14 @@ int cdl_probe_mfma_int8(int32_t iters, int32_t random_operands, int32_t blocks, 
 int cdl_profile_enable(int enable)
 {
     cdl::g_profile_on.store(enable != 0);
+    return CDL_OK;
+}
+
+int cdl_profile_only(const char *kernel)
+{
+    std::lock_guard<std::mutex> lock(cdl::g_profile_mutex);
+    std::memset(cdl::g_profile_only, 0, sizeof(cdl::g_profile_only));
+    if (kernel) std::strncpy(cdl::g_profile_only, kernel, sizeof(cdl::g_profile_only) - 1);
     return CDL_OK;
 }
 
