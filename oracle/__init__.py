@@ -96,6 +96,8 @@ def lib():
         L.cdl_oracle_qgemm_fwd.restype = None
         L.cdl_oracle_qgemm_fwd.argtypes = [_i16p, _i16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_float, ctypes.c_float, _i32p, _f64p]
+        L.cdl_oracle_qconv_fwd.restype = None
+        L.cdl_oracle_qconv_fwd.argtypes = [_i16p, _i16p] + [ctypes.c_int] * 9 + [ctypes.c_float, ctypes.c_float, _i32p, _f64p]
         L.cdl_oracle_qgemm_bwd.restype = None
         L.cdl_oracle_qgemm_bwd.argtypes = [_f32p, _i16p, _i16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_float, ctypes.c_float, _f64p, _f64p]
@@ -246,6 +248,23 @@ def qgemm_fwd(a_idx: np.ndarray, b_idx: np.ndarray, delta_a: float, delta_b: flo
     y = np.empty((M, N), dtype=np.float64) if want_y else None
     lib().cdl_oracle_qgemm_fwd(_ptr(a, _i16p), _ptr(b, _i16p), M, N, K, float(delta_a), float(delta_b),
                                _ptr(acc, _i32p), _ptr(y, _f64p))
+    return acc, y
+
+
+def qconv_fwd(x_idx: np.ndarray, w_idx: np.ndarray, stride: int, pad: int, delta_x: float, delta_w: float,
+              want_y: bool = True):
+    """x_idx [B,H,W,C], w_idx [N,R,S,C] level indices -> (acc int32[B,P,Q,N], y float64[B,P,Q,N] | None)."""
+    x = _c(x_idx, np.int16)
+    w = _c(w_idx, np.int16)
+    B, H, W, C = x.shape
+    N, R, S, C2 = w.shape
+    assert C == C2 and stride >= 1 and pad >= 0
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    assert P >= 1 and Q >= 1
+    acc = np.empty((B, P, Q, N), dtype=np.int32)
+    y = np.empty((B, P, Q, N), dtype=np.float64) if want_y else None
+    lib().cdl_oracle_qconv_fwd(_ptr(x, _i16p), _ptr(w, _i16p), B, H, W, C, N, R, S, int(stride), int(pad),
+                               float(delta_x), float(delta_w), _ptr(acc, _i32p), _ptr(y, _f64p))
     return acc, y
 
 

@@ -484,6 +484,48 @@ void cdl_oracle_qgemm_fwd(const int16_t *a_idx, const int16_t *b_idx, int M, int
 }
 
 /*
+ * The same layer compute for a convolutional layer (Sec. II: fully-connected and convolutional layers are
+ * treated alike; Sec. IV-A: the forward pass runs on the quantized weights and activations; the ResNets of
+ * Sec. V are stacks of such layers), written out as the definition of a 2-D cross-correlation with zero
+ * padding - no im2col matrix is formed:
+ *   acc[b,p,q,n] = sum_{r,s,c} x_idx[b, p*stride + r - pad, q*stride + s - pad, c] * w_idx[n,r,s,c]
+ * over the taps whose input pixel lies inside the image (pixels outside count as level index 0, i.e. the
+ * quantized value 0), y = delta_x * delta_w * acc.  Layouts: x [B][H][W][C], w [N][R][S][C], outputs
+ * [B][P][Q][N] with P = (H + 2 pad - R) / stride + 1, Q = (W + 2 pad - S) / stride + 1.
+ */
+void cdl_oracle_qconv_fwd(const int16_t *x_idx, const int16_t *w_idx, int B, int H, int W, int C,
+                          int N, int R, int S, int stride, int pad, float delta_x, float delta_w,
+                          int32_t *acc /* B*P*Q*N, nullable */, double *y /* B*P*Q*N, nullable */)
+{
+    const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
+    const double scale = (double)delta_x * (double)delta_w;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int b = 0; b < B; ++b) {
+        for (int p = 0; p < P; ++p) {
+            for (int q = 0; q < Q; ++q) {
+                for (int n = 0; n < N; ++n) {
+                    int64_t sum = 0;
+                    for (int r = 0; r < R; ++r) {
+                        const int h = p * stride + r - pad;
+                        if (h < 0 || h >= H) continue;
+                        for (int s = 0; s < S; ++s) {
+                            const int w = q * stride + s - pad;
+                            if (w < 0 || w >= W) continue;
+                            const int16_t *xp = x_idx + (((size_t)b * H + h) * W + w) * C;
+                            const int16_t *wp = w_idx + (((size_t)n * R + r) * S + s) * C;
+                            for (int c = 0; c < C; ++c) sum += (int64_t)xp[c] * (int64_t)wp[c];
+                        }
+                    }
+                    const size_t o = (((size_t)b * P + p) * Q + q) * N + n;
+                    if (acc) acc[o] = (int32_t)sum;
+                    if (y) y[o] = scale * (double)sum;
+                }
+            }
+        }
+    }
+}
+
+/*
  * Backward of the same product with respect to the two quantized operands.
  * With Yhat = Ahat . Bhat^T, Ahat = delta_a*a_idx, Bhat = delta_b*b_idx and
  * g = dL/dYhat (kept in fp32: the paper quantizes weights and activations,
