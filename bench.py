@@ -485,6 +485,58 @@ def gemm_only(number, scrub, seed=0, iters=5):
     return out
 
 
+def conv_forward(scrub, seed=0, iters=5):
+    """The forward product of the convolution that workload 3 stands for (ResNet-18 layer 3: 256 images of 14 x 14 x 256,
+    256 kernels of 3 x 3, padding 1), read where the activations lie (cdl_qconv_fwd), against the index product on the
+    matrix of input windows, which somebody has to write first (9 times the activations)."""
+    import torch
+    import paper_2501_09849_amd as cdl
+    wl = cdl_inputs.workload(3)
+    w, x = wl.w_spec, wl.x_spec
+    B, H, W, C, N, R, S, stride, pad = 256, 14, 14, 256, 256, 3, 3, 1, 1
+    dev = "cuda:0"
+    Xi = torch.from_numpy(cdl_inputs.draw_indices((B, H, W, C), x.lo, x.hi, seed=seed + 1)).to(dev)
+    Wi = torch.from_numpy(cdl_inputs.draw_indices((N, R, S, C), w.lo, w.hi, seed=seed + 2)).to(dev)
+    M, K = B * H * W, R * S * C
+    assert (M, N, K) == (wl.M, wl.N, wl.K)
+    Y = torch.empty((M, N), dtype=torch.float32, device=dev)
+    Y2 = torch.empty((M, N), dtype=torch.float32, device=dev)
+    # the matrix of windows, for the comparison only (torch is plumbing here; its time is reported, not counted)
+    xp = torch.zeros((B, H + 2 * pad, W + 2 * pad, C), dtype=torch.int8, device=dev)
+    xp[:, pad:pad + H, pad:pad + W, :] = Xi
+    st_b, st_h, st_w, st_c = xp.stride()
+    cols = torch.empty((M, K), dtype=torch.int8, device=dev)
+    def expand():
+        cols.view(B, H, W, R, S, C).copy_(torch.as_strided(xp, (B, H, W, R, S, C), (st_b, st_h * stride, st_w * stride, st_h, st_w, st_c)))
+    expand()
+    ws = torch.empty(max(256, cdl.qgemm_fwd_workspace_bytes(M, N, K)), dtype=torch.uint8, device=dev)
+    calls = {"conv": lambda: cdl.cdl_qconv_fwd(Xi, Wi, B, H, W, C, N, R, S, stride, pad, x.delta, w.delta, None, Y, None),
+             "product_on_windows": lambda: cdl.cdl_qgemm_fwd(cols, Wi.view(N, K), M, N, K, x.delta, w.delta, None, Y2, ws)}
+    out = {"layer": "B=256, 14x14x256 -> 256, 3x3, stride 1, padding 1 (M=%d, N=%d, K=%d)" % (M, N, K),
+           "activation_bytes": int(Xi.numel()), "window_matrix_bytes": int(cols.numel())}
+    ops = 2.0 * M * N * K
+    for state, sc in (("cold", scrub), ("warm", None)):
+        t = timed_calls(calls, iters, sc)
+        row = {}
+        for key in calls:
+            mm = med_min(t[key])
+            mm["TOPS"] = ops / mm["median_us"] / 1e6
+            row[key] = mm
+        out[state] = row
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        expand()
+    e1.record()
+    torch.cuda.synchronize()
+    out["forming_the_window_matrix_us (a strided device copy, not a kernel of this library)"] = e0.elapsed_time(e1) / iters * 1e3
+    out["outputs_equal"] = bool(torch.equal(Y, Y2))
+    del Xi, Wi, Y, Y2, xp, cols, ws
+    torch.cuda.empty_cache()
+    return out
+
+
 def small_step(number, steps=20, warmup=3):
     """One whole layer step on a small workload (1: the tiny linear layer, 2: the CIFAR conv as an im2col GEMM)."""
     import torch
@@ -731,6 +783,7 @@ def main():
     if not args.no_extra:
         out["small_workloads"] = [small_step(1), small_step(2)]
         out["index_gemms_alone"] = [gemm_only(n_, scrub) for n_ in (2, 3) if n_ != wl.number]
+        out["conv_forward_without_window_matrix"] = conv_forward(scrub)
         del scrub
         torch.cuda.empty_cache()
         out["extensions_flat_25M"] = extensions_bench()

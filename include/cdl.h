@@ -262,6 +262,27 @@ int cdl_qgemm_bwd_offset(const float *g, const int8_t *a_idx, const int8_t *b_id
                          void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * The forward product of a convolutional layer over level indices (Sec. IV-A, the forward pass over quantized
+ * weights and activations, for the convolutional layers of Sec. II), without forming the matrix of input windows:
+ *   acc[b,p,q,n] = sum_{r,s,c} X[b, p*stride + r - pad, q*stride + s - pad, c] * w_idx[n,r,s,c],
+ *   y = delta_x * delta_w * acc,          P = (H + 2 pad - R) / stride + 1, Q = (W + 2 pad - S) / stride + 1,
+ * where X is the level index of the activation, x_idx + x_offset, inside the image and 0 (the quantized value 0)
+ * outside it.
+ *   x_idx  DEVICE int8[B,H,W,C] (channels contiguous), stored minus x_offset (0, or 128 for the unsigned 8-bit
+ *          alphabet: cdl_index_offset); w_idx DEVICE int8[N,R,S,C], level indices as they are
+ *   acc    DEVICE int32[B,P,Q,N] (nullable), y DEVICE fp32[B,P,Q,N] (nullable), at least one of them
+ * The result is bit for bit what cdl_qgemm_fwd(_offset) gives on the [B*P*Q, R*S*C] matrix of windows; the
+ * activations are read where they lie, each about R*S/stride^2 times from cache instead of once from a matrix
+ * R*S/stride^2 times their size.  Restrictions: C a multiple of 16, pad < R and pad < S, R*S*C <= 32768
+ * (CDL_ERR_PARAM / CDL_ERR_RANGE otherwise: form the matrix and call cdl_qgemm_fwd there).  Both pointers 16-byte
+ * aligned.  Scratch: cdl_qconv_fwd_workspace_bytes(N, x_offset), which is 0 when x_offset is 0.
+ */
+size_t cdl_qconv_fwd_workspace_bytes(int32_t N, int32_t x_offset);
+int cdl_qconv_fwd(const int8_t *x_idx, const int8_t *w_idx, int32_t B, int32_t H, int32_t W, int32_t C, int32_t N,
+                  int32_t R, int32_t S, int32_t stride, int32_t pad, float delta_x, float delta_w, int32_t x_offset,
+                  int32_t *acc, float *y, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * The backward step of Algorithm 1 for a layer in one call: cdl_qgemm_bwd followed by cdl_quantize_bwd on its
  * d_a_hat (and, optionally, on its d_b_hat), with the quantizer's backward pass (Lemma 1; eq. partialX3, Jgradqx,
  * Jgrad_alpha_q) applied to each tile of dL/dQ(x) in the epilogue of the product, while the tile is still on the

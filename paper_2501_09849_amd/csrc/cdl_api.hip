@@ -302,6 +302,34 @@ int cdl_qgemm_bwd_offset(const float *g, const int8_t *a_idx, const int8_t *b_id
     return launch_qgemm_bwd(g, a_idx, b_idx, M, N, K, delta_a, delta_b, a_offset, b_offset, d_a_hat, d_b_hat, ws, (hipStream_t)hip_stream);
 }
 
+size_t cdl_qconv_fwd_workspace_bytes(int32_t N, int32_t x_offset)
+{
+    if (N < 0 || !offset_ok(x_offset)) return 0;
+    return qconv_fwd_workspace_bytes(N, x_offset);
+}
+
+int cdl_qconv_fwd(const int8_t *x_idx, const int8_t *w_idx, int32_t B, int32_t H, int32_t W, int32_t C, int32_t N,
+                  int32_t R, int32_t S, int32_t stride, int32_t pad, float delta_x, float delta_w, int32_t x_offset,
+                  int32_t *acc, float *y, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (B < 0 || H <= 0 || W <= 0 || C <= 0 || N < 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0 || !offset_ok(x_offset)) return CDL_ERR_PARAM;
+    if (!(std::isfinite(delta_x) && delta_x > 0.0f && std::isfinite(delta_w) && delta_w > 0.0f)) return CDL_ERR_PARAM;
+    // a 16-byte chunk of the window matrix must lie inside one tap; padding wider than the kernel makes no sense
+    if (C % 16 != 0 || pad >= R || pad >= S) return CDL_ERR_PARAM;
+    if (H + 2 * pad < R || W + 2 * pad < S) return CDL_ERR_PARAM;
+    if (!acc && !y) return CDL_ERR_NULL;
+    const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
+    const int64_t M = (int64_t)B * P * Q, K = (int64_t)R * S * C;
+    // int32 row index and offsets inside one image, the tap table, and accumulators of products up to 2^14 (2^15 with an offset)
+    if (M > 2147483647LL - 256 || (int64_t)H * W * C > 2147483647LL || K / 16 > qconv_max_chunks()) return CDL_ERR_RANGE;
+    if (K * (x_offset ? 32768 : 16384) > 2147483647LL) return CDL_ERR_RANGE;
+    if (M * N > 0 && (!x_idx || !w_idx)) return CDL_ERR_NULL;
+    if (!aligned(x_idx, 16) || !aligned(w_idx, 16) || !aligned(acc, 4) || !aligned(y, 4)) return CDL_ERR_ALIGN;
+    const int rc = check_ws(ws, ws_bytes, qconv_fwd_workspace_bytes(N, x_offset));
+    if (rc != CDL_OK) return rc;
+    return launch_qconv_fwd(x_idx, w_idx, B, H, W, C, N, R, S, stride, pad, delta_x, delta_w, x_offset, acc, y, ws, (hipStream_t)hip_stream);
+}
+
 int cdl_qgemm_bwd_quantize_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
                                const float *theta_a, const cdl_qparams *p_a, float delta_b, int32_t b_offset,
                                float *d_theta_a, float *d_delta_a, float *d_alpha_a, float *d_b_hat,

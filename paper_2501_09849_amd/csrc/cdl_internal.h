@@ -122,6 +122,13 @@ int launch_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
                      float *d_a_hat, float *d_b_hat, void *ws, hipStream_t stream, const FusedQuantBwd *fq = nullptr,
                      const FusedQuantBwd *fqb = nullptr);
 
+// Forward product of a convolutional layer over level indices, without an im2col matrix (C % 16 == 0).
+size_t qconv_fwd_workspace_bytes(int32_t N, int32_t x_offset);
+int qconv_max_chunks();   // most 16-byte chunks of the contraction R*S*C the kernels index
+int launch_qconv_fwd(const int8_t *x_idx, const int8_t *w_idx, int32_t B, int32_t H, int32_t W, int32_t C, int32_t N,
+                     int32_t R, int32_t S, int32_t stride, int32_t pad, float delta_x, float delta_w, int32_t x_offset,
+                     int32_t *acc, float *y, void *ws, hipStream_t stream);
+
 // d_delta = mul_d * sum of partial[2 i], d_alpha = mul_a * sum of partial[2 i + 1], i < n, in a fixed order.
 int launch_scalar_finalize(const double *partial, int n, double mul_d, double mul_a, float *d_delta, float *d_alpha, hipStream_t stream);
 

@@ -12,6 +12,8 @@
 // products are exact in int32 and are recombined in double in the epilogue.  L (3..6) is chosen on
 // the device so that the rounding of q stays well below the parity tolerance.
 #include "cdl_internal.h"
+
+#include <mutex>
 #include "cdl_quantizer_math.h"
 
 #include <math.h>
@@ -388,6 +390,320 @@ int launch_gemm_dma(GemmArgs a, hipStream_t stream)
     CDL_LAUNCH("qgemm_kernel(fwd)", stream, qgemm_dma_kernel, dim3((unsigned)grid), dim3(kFThreads), kFLdsBytes, a);
     return check_launch();
 }
+
+// ---- forward product of a convolutional layer, without an im2col matrix ---------------------------------
+//
+// acc[b,p,q,n] = sum_{r,s,c} x[b, p*stride + r - pad, q*stride + s - pad, c] * w[n,r,s,c]  (Sec. IV-A for a
+// convolutional layer): the product of the [B*P*Q, R*S*C] matrix of input windows with w^T, where row m of that
+// matrix is never stored - its 16-byte chunks are read from the NHWC tensor where they lie (C is a multiple of
+// 16, so a chunk lies inside one tap), and chunks of taps that fall outside the image come from a page of
+// padding bytes (the stored value of level index 0).
+struct ConvArgs {
+    const int8_t *X;       // [B][H][W][C]
+    const int8_t *Wt;      // [N][R*S*C]
+    const int8_t *pad_page;   // 128 bytes of the padding value (direct-load kernel)
+    int pad_word;          // the padding value in all four bytes (register-staged kernel)
+    int B, H, W, C, N, R, S, stride, pad, P, Q;
+    int M, Kc;             // B*P*Q, R*S*C
+    int tiles_m, tiles_n;
+    int32_t *acc_out;      // [M][N] or null
+    float *y_out;          // [M][N] or null
+    float scale;
+    const int32_t *corr_col;   // [N] or null: x stored with an offset, x_offset * sum over the window of w[n]
+};
+
+// where output pixel m looks: first input row and column of its window, and the offset of that (possibly
+// virtual) pixel in X
+struct ConvRow { int h0, w0; int64_t off; };
+__device__ __forceinline__ ConvRow conv_row(const ConvArgs &a, int m)
+{
+    const int pq = a.P * a.Q;
+    const int b = m / pq, rem = m - b * pq, p = rem / a.Q, q = rem - p * a.Q;
+    ConvRow r;
+    r.h0 = p * a.stride - a.pad;
+    r.w0 = q * a.stride - a.pad;
+    r.off = (((int64_t)b * a.H + r.h0) * a.W + r.w0) * a.C;
+    return r;
+}
+
+__device__ __forceinline__ void conv_store(const ConvArgs &a, int row, int col, int v)
+{
+    const int64_t o = (int64_t)row * a.N + col;
+    if (a.acc_out) a.acc_out[o] = v;
+    if (a.y_out) a.y_out[o] = a.scale * (float)v;
+}
+
+// C a multiple of 128: the structure of qgemm_dma_kernel (256 x 256 tile, K-tiles of 128 bytes by direct
+// global->LDS loads, two stages), a K-tile being 128 channels of one tap.
+__global__ __launch_bounds__(kFThreads, 1)
+void qconv_dma_kernel(ConvArgs a)
+{
+    constexpr int WN = 4, TM = 4, TN = 2, CH = kFBK / 16, KS = kFBK / 32;
+    constexpr int WL = kFTile * CH / 64 / 8;
+    extern __shared__ __attribute__((aligned(16))) int8_t flds[];
+
+    const int total = a.tiles_m * a.tiles_n;
+    const int per_xcd = (int)gridDim.x >> 3;
+    const int logical = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+    if (logical >= total) return;
+    const int tile_m = logical / a.tiles_n, tile_n = logical % a.tiles_n;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+
+    ConvRow xr[WL];
+    const int8_t *gb[WL];
+#pragma unroll
+    for (int i = 0; i < WL; ++i) {
+        const int sidx = (wave * WL + i) * 64 + lane, row = sidx / CH;
+        const int q = (sidx % CH) ^ lswz(row);
+        xr[i] = conv_row(a, min(tile_m * kFTile + row, a.M - 1));
+        xr[i].off += q * 16;
+        gb[i] = a.Wt + (int64_t)min(tile_n * kFTile + row, a.N - 1) * a.Kc + q * 16;
+    }
+    int ra[TM], rb[TN], sa[TM], sb[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int row = (wm * TM + i) * 32 + (lane & 31);
+        ra[i] = row * kFBK;
+        sa[i] = lswz(row);
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int row = (wn * TN + j) * 32 + (lane & 31);
+        rb[j] = kFTile * kFBK + row * kFBK;
+        sb[j] = lswz(row);
+    }
+
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    const int nk = a.Kc / kFBK;
+    // tap (tr, ts) and first channel tc of the K-tile that `issue` is called with next (called with 0, 1, 2, ...)
+    int tr = 0, ts = 0, tc = 0;
+    auto issue = [&](int kt) {
+        int8_t *base = flds + (kt & 1) * kFStage;
+        const int64_t tap_off = ((int64_t)tr * a.W + ts) * a.C + tc;
+#pragma unroll
+        for (int i = 0; i < WL; ++i) {
+            const bool inside = (unsigned)(xr[i].h0 + tr) < (unsigned)a.H && (unsigned)(xr[i].w0 + ts) < (unsigned)a.W;
+            const int8_t *src = inside ? a.X + (xr[i].off + tap_off) : a.pad_page;
+            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(base + (wave * WL + i) * 1024), 16, 0, 0);
+        }
+        const int64_t off = (int64_t)kt * kFBK;
+#pragma unroll
+        for (int i = 0; i < WL; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)(gb[i] + off), (lptr_t)(base + kFTile * kFBK + (wave * WL + i) * 1024), 16, 0, 0);
+        tc += kFBK;
+        if (tc == a.C) { tc = 0; if (++ts == a.S) { ts = 0; ++tr; } }
+    };
+
+    issue(0);
+    for (int kt = 0; kt < nk; ++kt) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (kt + 1 < nk) issue(kt + 1);
+        const int8_t *base = flds + (kt & 1) * kFStage;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            v4i fa[TM], fb[TN];
+            const int q = 2 * ks + (lane >> 5);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const v4i *>(base + ra[i] + ((q ^ sa[i]) << 4));
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const v4i *>(base + rb[j] + ((q ^ sb[j]) << 4));
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    const bool full = (tile_m + 1) * kFTile <= a.M && (tile_n + 1) * kFTile <= a.N;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = tile_n * kFTile + (wn * TN + j) * 32 + (lane & 31);
+            const int cc = (a.corr_col && col < a.N) ? a.corr_col[col] : 0;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = tile_m * kFTile + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (full || (row < a.M && col < a.N)) conv_store(a, row, col, acc[i][j][r] + cc);
+            }
+        }
+}
+
+// Any C that is a multiple of 16: the structure of qgemm_kernel (256 x 128 tile, 64-byte K steps staged through
+// registers), every 16-byte chunk of the window matrix looked up on its own: a table in LDS gives, per chunk of the
+// contraction, its tap and its offset from the window's first pixel.
+constexpr int kConvMaxChunks = 2048;     // contraction lengths up to 32768
+
+template <int TM, int TN>
+__global__ __launch_bounds__(kGemmThreads, 2)
+void qconv_kernel(ConvArgs a)
+{
+    constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
+    constexpr int LA = BM / 64, LB = BN / 64;
+    __shared__ __attribute__((aligned(16))) int8_t lds[2][(BM + BN) * kKT];
+    __shared__ int2 taps[kConvMaxChunks];    // .x: offset of the chunk from the window's first pixel, .y: tap row << 16 | tap column
+
+    const int total = a.tiles_m * a.tiles_n;
+    const int per_xcd = (int)gridDim.x >> 3;
+    const int logical = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+    if (logical >= total) return;
+    const int tile_m = logical / a.tiles_n, tile_n = logical % a.tiles_n;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    for (int c16 = tid; c16 < a.Kc / 16; c16 += kGemmThreads) {
+        const int k = c16 * 16, tap = k / a.C, c = k - tap * a.C, r = tap / a.S, s = tap - r * a.S;
+        taps[c16] = make_int2((r * a.W + s) * a.C + c, (r << 16) | s);
+    }
+
+    ConvRow xr[LA];
+    const int8_t *gb[LB];
+    int qa[LA], qb[LB];
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+        const int s = tid + kGemmThreads * i, row = s >> 2;
+        qa[i] = swz(row, s & 3);
+        xr[i] = conv_row(a, min(tile_m * BM + row, a.M - 1));
+    }
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+        const int s = tid + kGemmThreads * i, row = s >> 2;
+        qb[i] = swz(row, s & 3) * 16;
+        const int grow = min(tile_n * BN + row, a.N - 1);
+        gb[i] = a.Wt + (int64_t)grow * a.Kc + qb[i];
+    }
+
+    int ra[TM][2], rb[TN][2];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const int row = wm * TM * 32 + i * 32 + (lane & 31);
+            ra[i][ks] = row * kKT + swz(row, 2 * ks + (lane >> 5)) * 16;
+        }
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const int row = wn * TN * 32 + j * 32 + (lane & 31);
+            rb[j][ks] = BM * kKT + row * kKT + swz(row, 2 * ks + (lane >> 5)) * 16;
+        }
+
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    const int steps = (a.Kc + kKT - 1) / kKT;
+    const int chunks = a.Kc / 16;
+    const v4i zero4 = {0, 0, 0, 0};
+    const v4i pad4 = {a.pad_word, a.pad_word, a.pad_word, a.pad_word};
+    __syncthreads();        // the tap table is complete
+
+    v4i pa[LA], pb[LB];
+    auto fetch = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            const int c16 = kt * (kKT / 16) + qa[i];
+            v4i v = zero4;                       // beyond the contraction: multiplies zeros of the other operand as well
+            if (c16 < chunks) {
+                const int2 t = taps[c16];
+                const bool inside = (unsigned)(xr[i].h0 + (t.y >> 16)) < (unsigned)a.H && (unsigned)(xr[i].w0 + (t.y & 0xffff)) < (unsigned)a.W;
+                v = inside ? *reinterpret_cast<const v4i *>(a.X + (xr[i].off + t.x)) : pad4;
+            }
+            pa[i] = v;
+        }
+        const int64_t off = (int64_t)kt * kKT;
+#pragma unroll
+        for (int i = 0; i < LB; ++i)
+            pb[i] = (kt * kKT + qb[i] < a.Kc) ? *reinterpret_cast<const v4i *>(gb[i] + off) : zero4;
+    };
+    auto stash = [&](int stage) {
+#pragma unroll
+        for (int i = 0; i < LA; ++i)
+            *reinterpret_cast<v4i *>(&lds[stage][(tid + kGemmThreads * i) * 16]) = pa[i];
+#pragma unroll
+        for (int i = 0; i < LB; ++i)
+            *reinterpret_cast<v4i *>(&lds[stage][BM * kKT + (tid + kGemmThreads * i) * 16]) = pb[i];
+    };
+
+    if (steps > 0) {
+        fetch(0);
+        stash(0);
+    }
+    __syncthreads();
+
+    for (int step = 0; step < steps; ++step) {
+        const int stage = step & 1;
+        if (step + 1 < steps) fetch(step + 1);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            v4i fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const v4i *>(&lds[stage][ra[i][ks]]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const v4i *>(&lds[stage][rb[j][ks]]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        if (step + 1 < steps) stash(stage ^ 1);
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = tile_n * BN + wn * TN * 32 + j * 32 + (lane & 31);
+            if (col >= a.N) continue;
+            const int cc = a.corr_col ? a.corr_col[col] : 0;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = tile_m * BM + wm * TM * 32 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (row < a.M) conv_store(a, row, col, acc[i][j][r] + cc);
+            }
+        }
+}
+
+// 128 bytes that read as level index 0 of an operand stored with offset `off`, and (with an offset) the
+// correction per output channel: off * sum of w[n] over the whole window (a padded tap holds -off + off = 0)
+__global__ __launch_bounds__(256)
+void conv_prep_kernel(int8_t *page, int off, const int8_t *w, int N, int Kc, int32_t *corr)
+{
+    if (blockIdx.x == 0 && threadIdx.x < 128) page[threadIdx.x] = (int8_t)(-off);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int n = blockIdx.x * 4 + wave; n < N; n += gridDim.x * 4) {
+        int s = 0;
+        for (int k = lane; k < Kc; k += 64) s += (int)w[(int64_t)n * Kc + k];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) s += __shfl_down(s, o, 64);
+        if (lane == 0) corr[n] = off * s;
+    }
+}
+
+// a page of zeros that belongs to the library's device code (one copy per GPU): the padding of operands stored
+// without an offset, so that such calls need no workspace
+static __device__ __align__(256) int8_t conv_zero_page[256];
 
 // Digits of four values: out[l] holds digit l (a signed byte, l = 0 least significant) of g[0..3] in
 // its bytes 0..3.  x = g * gscale is exact (gscale is a power of two) and |x| < 0.99 * 2^(8L-1);
@@ -1509,6 +1825,82 @@ int launch_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_
     if (g.Kc % kFBK == 0 && (int64_t)M * N >= (int64_t)kFTile * kFTile * 64) return launch_gemm_dma(g, stream);
     return launch_gemm<4, 2>(g, stream);
 }
+
+size_t qconv_fwd_workspace_bytes(int32_t N, int32_t x_offset)
+{
+    return x_offset != 0 ? 256 + align_up((size_t)N * sizeof(int32_t), 256) : 0;
+}
+
+namespace {
+// address of conv_zero_page on the current device (taken once per device)
+int conv_zero_page_ptr(const int8_t **ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static const int8_t *cached[kMaxDevices];
+    static std::mutex mu;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_failed(e);
+    if (dev < 0 || dev >= kMaxDevices) return CDL_ERR_PARAM;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!cached[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(conv_zero_page));
+        if (e != hipSuccess) return hip_failed(e);
+        if (!p) return hip_failed(hipErrorInvalidSymbol);
+        cached[dev] = reinterpret_cast<const int8_t *>(p);
+    }
+    *ptr = cached[dev];
+    return CDL_OK;
+}
+}  // namespace
+
+int launch_qconv_fwd(const int8_t *x_idx, const int8_t *w_idx, int32_t B, int32_t H, int32_t W, int32_t C, int32_t N,
+                     int32_t R, int32_t S, int32_t stride, int32_t pad, float delta_x, float delta_w, int32_t x_offset,
+                     int32_t *acc, float *y, void *ws, hipStream_t stream)
+{
+    ConvArgs a{};
+    a.X = x_idx; a.Wt = w_idx;
+    a.B = B; a.H = H; a.W = W; a.C = C; a.N = N; a.R = R; a.S = S; a.stride = stride; a.pad = pad;
+    a.P = (H + 2 * pad - R) / stride + 1;
+    a.Q = (W + 2 * pad - S) / stride + 1;
+    a.M = B * a.P * a.Q;
+    a.Kc = R * S * C;
+    a.acc_out = acc; a.y_out = y;
+    a.scale = delta_x * delta_w;
+    if ((int64_t)a.M * N == 0) return CDL_OK;
+    if (x_offset != 0) {
+        int8_t *page = reinterpret_cast<int8_t *>(ws);
+        int32_t *corr = reinterpret_cast<int32_t *>(page + 256);
+        CDL_LAUNCH("conv_prep_kernel", stream, conv_prep_kernel, dim3((unsigned)blocks_for(N, 4, 1024)), dim3(256), 0, page, x_offset, w_idx, N, a.Kc, corr);
+        int rc = check_launch();
+        if (rc != CDL_OK) return rc;
+        a.pad_page = page;
+        a.corr_col = corr;
+    } else {
+        int rc = conv_zero_page_ptr(&a.pad_page);
+        if (rc != CDL_OK) return rc;
+    }
+    const uint32_t pb = (uint32_t)(uint8_t)(int8_t)(-x_offset);
+    a.pad_word = (int)(pb | (pb << 8) | (pb << 16) | (pb << 24));
+    if (C % kFBK == 0 && (int64_t)a.M * N >= (int64_t)kFTile * kFTile * 64) {
+        a.tiles_m = (a.M + kFTile - 1) / kFTile;
+        a.tiles_n = (N + kFTile - 1) / kFTile;
+        const int64_t grid = ((int64_t)a.tiles_m * a.tiles_n + 7) / 8 * 8;
+        const hipError_t e = hipFuncSetAttribute((const void *)qconv_dma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kFLdsBytes);
+        if (e != hipSuccess) return hip_failed(e);
+        CDL_LAUNCH("qconv_kernel(fwd)", stream, qconv_dma_kernel, dim3((unsigned)grid), dim3(kFThreads), kFLdsBytes, a);
+        return check_launch();
+    }
+    constexpr int BM = 256, BN = 128;
+    a.tiles_m = (a.M + BM - 1) / BM;
+    a.tiles_n = (N + BN - 1) / BN;
+    const int64_t grid = ((int64_t)a.tiles_m * a.tiles_n + 7) / 8 * 8;
+    CDL_LAUNCH("qconv_kernel(fwd)", stream, (qconv_kernel<4, 2>), dim3((unsigned)grid), dim3(kGemmThreads), 0, a);
+    return check_launch();
+}
+
+int qconv_max_chunks() { return kConvMaxChunks; }
 
 int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
                      int32_t M, int32_t N, int32_t K, float delta_a, float delta_b, int32_t a_offset, int32_t b_offset,

@@ -1,0 +1,140 @@
+"""cdl_qconv_fwd: the forward product of a convolutional layer over level indices without a matrix of input windows.
+Every int32 accumulator must equal the oracle's cross-correlation (small cases: everywhere; large cases: on whole
+images of the batch) and, bit for bit, what cdl_qgemm_fwd gives on the matrix of windows built on the host; y within
+the stated tolerance.  Both kernels are covered: the register-staged one (any C that is a multiple of 16) and the
+direct-load one (C a multiple of 128, enough output tiles)."""
+import numpy as np
+import pytest
+
+import cdl_inputs
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _windows(x, R, S, stride, pad, fill=0):
+    """[B,H,W,C] -> [B*P*Q, R*S*C], taps outside the image filled with `fill` (host-side, for the comparison only)."""
+    B, H, W, C = x.shape
+    xp = np.full((B, H + 2 * pad, W + 2 * pad, C), fill, dtype=x.dtype)
+    xp[:, pad:pad + H, pad:pad + W, :] = x
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    sb, sh, sw, sc = xp.strides
+    win = np.lib.stride_tricks.as_strided(xp, shape=(B, P, Q, R, S, C), strides=(sb, sh * stride, sw * stride, sh, sw, sc))
+    return np.ascontiguousarray(win.reshape(B * P * Q, R * S * C)), P, Q
+
+
+def _run(cdl, torch, x, w, stride, pad, dx, dw, x_offset=0):
+    B, H, W, C = x.shape
+    N, R, S, _ = w.shape
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    acc = gu.empty((B, P, Q, N), torch.int32)
+    y = gu.empty((B, P, Q, N), torch.float32)
+    acc.fill_(-7)
+    y.fill_(float("nan"))
+    ws = gu.workspace(cdl.qconv_fwd_workspace_bytes(N, x_offset))
+    cdl.cdl_qconv_fwd(gu.dev(x), gu.dev(w), B, H, W, C, N, R, S, stride, pad, dx, dw, acc, None, ws, x_offset=x_offset)
+    cdl.cdl_qconv_fwd(gu.dev(x), gu.dev(w), B, H, W, C, N, R, S, stride, pad, dx, dw, None, y, ws, x_offset=x_offset)
+    torch.cuda.synchronize()
+    return acc.cpu().numpy(), y.cpu().numpy()
+
+
+# (B, H, W, C, N, R, S, stride, pad): the register-staged kernel - ragged tiles in both directions, strides, paddings, kernel
+# shapes, one image smaller than the kernel's reach, more than one tile of rows and of columns, contraction not a multiple of 64
+SMALL = [(2, 7, 9, 16, 20, 3, 3, 1, 1), (1, 8, 8, 32, 130, 3, 3, 2, 1), (3, 6, 5, 48, 33, 1, 1, 1, 0), (1, 9, 7, 16, 5, 5, 3, 1, 2),
+         (5, 12, 12, 16, 16, 3, 3, 1, 1), (1, 10, 11, 64, 40, 3, 5, 2, 0), (2, 4, 4, 80, 3, 1, 1, 2, 0), (1, 3, 3, 16, 8, 3, 3, 1, 1),
+         (4, 17, 13, 32, 140, 3, 3, 1, 1), (1, 2, 2, 128, 7, 3, 3, 1, 1), (2, 32, 32, 16, 16, 3, 3, 1, 1)]
+
+
+@pytest.mark.parametrize("B,H,W,C,N,R,S,stride,pad", SMALL)
+def test_convolution_matches_the_oracle_everywhere(oracle, B, H, W, C, N, R, S, stride, pad):
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    x = cdl_inputs.draw_indices((B, H, W, C), -128, 127, seed=H * W + C)
+    w = cdl_inputs.draw_indices((N, R, S, C), -128, 127, seed=N + R)
+    x[0, 0, 0, :], w[0, :, :, :] = -128, -128          # the largest products
+    dx, dw = float(np.float32(0.15092)), float(np.float32(0.0028209))
+    acc, y = _run(cdl, torch, x, w, stride, pad, dx, dw)
+    ref_acc, ref_y = oracle.qconv_fwd(x, w, stride, pad, dx, dw)
+    assert np.array_equal(acc, ref_acc), "%d accumulators differ" % int((acc != ref_acc).sum())
+    gu.assert_close(y, ref_y, "y")
+    # and what the index product gives on the matrix of windows, bit for bit
+    cols, P, Q = _windows(x, R, S, stride, pad)
+    M, K = cols.shape
+    acc2, y2 = gu.empty((M, N), torch.int32), gu.empty((M, N), torch.float32)
+    ws = gu.workspace(cdl.qgemm_fwd_workspace_bytes(M, N, K))
+    cdl.cdl_qgemm_fwd(gu.dev(cols), gu.dev(w.reshape(N, K)), M, N, K, dx, dw, acc2, y2, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.reshape(M, N), acc2.cpu().numpy())
+    assert np.array_equal(y.reshape(M, N), y2.cpu().numpy())
+
+
+# the direct-load kernel: C a multiple of 128 and at least 64 tiles of 256 x 256 outputs
+LARGE = [(32, 14, 14, 128, 1024, 3, 3, 1, 1), (64, 14, 14, 256, 512, 3, 3, 1, 1), (80, 28, 28, 128, 300, 3, 3, 2, 1),
+         (16, 33, 31, 128, 512, 1, 1, 1, 0), (24, 20, 20, 256, 700, 3, 3, 1, 0), (64, 15, 15, 128, 520, 5, 5, 1, 2)]
+
+
+@pytest.mark.parametrize("B,H,W,C,N,R,S,stride,pad", LARGE)
+def test_convolution_with_direct_loads(oracle, B, H, W, C, N, R, S, stride, pad):
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    x = cdl_inputs.draw_indices((B, H, W, C), -128, 127, seed=B + C)
+    w = cdl_inputs.draw_indices((N, R, S, C), -128, 127, seed=N)
+    dx, dw = float(np.float32(0.0731)), float(np.float32(0.011))
+    acc, y = _run(cdl, torch, x, w, stride, pad, dx, dw)
+    # the oracle on the first, a middle and the last image of the batch
+    for b in (0, B // 2, B - 1):
+        ref_acc, ref_y = oracle.qconv_fwd(x[b:b + 1], w, stride, pad, dx, dw)
+        assert np.array_equal(acc[b:b + 1], ref_acc), "image %d: %d accumulators differ" % (b, int((acc[b:b + 1] != ref_acc).sum()))
+        gu.assert_close(y[b:b + 1], ref_y, "y of image %d" % b)
+    # every accumulator against the index product on the matrix of windows
+    cols, P, Q = _windows(x, R, S, stride, pad)
+    M, K = cols.shape
+    acc2 = gu.empty((M, N), torch.int32)
+    ws = gu.workspace(cdl.qgemm_fwd_workspace_bytes(M, N, K))
+    cdl.cdl_qgemm_fwd(gu.dev(cols), gu.dev(w.reshape(N, K)), M, N, K, dx, dw, acc2, None, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.reshape(M, N), acc2.cpu().numpy())
+    assert np.array_equal(y, (np.float32(np.float32(dx) * np.float32(dw)) * acc.astype(np.float32)))
+
+
+@pytest.mark.parametrize("B,H,W,C,N,R,S,stride,pad", [(2, 7, 9, 16, 20, 3, 3, 1, 1), (3, 9, 9, 32, 130, 3, 3, 2, 1),
+                                                        (32, 14, 14, 128, 1024, 3, 3, 1, 1), (1, 5, 5, 64, 9, 5, 5, 1, 2)])
+def test_convolution_of_activations_from_the_unsigned_alphabet(oracle, B, H, W, C, N, R, S, stride, pad):
+    """Level indices 0..255 stored minus 128: the padding must read as index 0, i.e. as the stored byte -128."""
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    rng = np.random.default_rng(B * 7 + C)
+    x_true = rng.integers(0, 256, size=(B, H, W, C)).astype(np.int16)
+    x_true[0, 0, 0, :] = 255
+    x_true[-1, -1, -1, :] = 0
+    w = cdl_inputs.draw_indices((N, R, S, C), -127, 127, seed=N + 1)
+    x_stored = (x_true - 128).astype(np.int8)
+    dx, dw = float(np.float32(0.02)), float(np.float32(0.011))
+    acc, y = _run(cdl, torch, x_stored, w, stride, pad, dx, dw, x_offset=128)
+    images = range(B) if B <= 3 else (0, B - 1)
+    for b in images:
+        ref_acc, ref_y = oracle.qconv_fwd(x_true[b:b + 1], w, stride, pad, dx, dw)
+        assert np.array_equal(acc[b:b + 1], ref_acc), "image %d" % b
+        gu.assert_close(y[b:b + 1], ref_y, "y of image %d" % b)
+
+
+def test_convolution_rejects_what_it_does_not_serve():
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    t8 = gu.empty((1 << 16,), torch.int8)
+    out = gu.empty((1 << 16,), torch.int32)
+    # C not a multiple of 16; padding as wide as the kernel; kernel larger than the padded image; contraction too long; bad offset
+    for (B, H, W, C, N, R, S, stride, pad, off), status in (((1, 8, 8, 3, 4, 3, 3, 1, 1, 0), -2), ((1, 8, 8, 16, 4, 3, 3, 1, 3, 0), -2),
+                                                            ((1, 2, 2, 16, 4, 5, 5, 1, 1, 0), -2), ((1, 8, 8, 4096, 4, 3, 3, 1, 1, 0), -3),
+                                                            ((1, 8, 8, 16, 4, 3, 3, 1, 1, 64), -2), ((1, 8, 8, 16, 4, 3, 3, 0, 1, 0), -2)):
+        with pytest.raises(cdl.CdlError) as e:
+            cdl.cdl_qconv_fwd(t8, t8, B, H, W, C, N, R, S, stride, pad, 0.1, 0.1, out, None, None, x_offset=off)
+        assert e.value.status == status, (B, H, W, C, N, R, S, stride, pad, off)
+    with pytest.raises(cdl.CdlError) as e:          # an offset needs the workspace
+        cdl.cdl_qconv_fwd(t8, t8, 1, 8, 8, 16, 4, 3, 3, 1, 1, 0.1, 0.1, out, None, None, x_offset=128)
+    assert e.value.status == -5
+    # an empty batch is no error and touches nothing
+    out.fill_(5)
+    cdl.cdl_qconv_fwd(t8, t8, 0, 8, 8, 16, 4, 3, 3, 1, 1, 0.1, 0.1, out, None, None)
+    torch.cuda.synchronize()
+    assert int(out.sum()) == 5 * (1 << 16)
