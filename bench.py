@@ -760,6 +760,15 @@ def main():
                 "fused_backward": {"ms_per_step": ms_f, "gelem_per_s": n_total / (ms_f * 1e-3) / 1e9,
                                    "calls": "cdl_qgemm_bwd_quantize_bwd for both operands instead of cdl_qgemm_bwd + 2 x cdl_quantize_bwd"},
                 "fused_over_separate": ms_f / ms_s}
+    if not args.no_extra and not args.step_only and wl.has_gemm and wl.K % 128 == 0 and wl.x_spec.hi <= 127:
+        # the forward product with the activation quantizer in its prologue (the indices of X are never written),
+        # against the hard-index quantizer followed by the forward product; same buffers
+        x_, w_ = wl.x_spec, wl.w_spec
+        xa_ = (x_.lo, x_.n_levels, x_.delta, x_.alpha)
+        t = timed_calls({"quantizer_in_prologue": lambda: cdl.cdl_qgemm_fwd_quantize(st.X, *xa_, st.Wi, wl.M, wl.N, wl.K, w_.delta, st.Y),
+                         "index_only_quantizer_then_product": lambda: (cdl.cdl_quantize_fwd(st.X, st.nX, *xa_, st.Xi),
+                                                                       cdl.cdl_qgemm_fwd(st.Xi, st.Wi, wl.M, wl.N, wl.K, x_.delta, w_.delta, None, st.Y, st.ws))}, 5)
+        out["forward_with_quantizer_in_prologue"] = {k: med_min(v) for k, v in t.items()}
     del st
     torch.cuda.empty_cache()
     if args.step_only:

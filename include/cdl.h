@@ -262,6 +262,20 @@ int cdl_qgemm_bwd_offset(const float *g, const int8_t *a_idx, const int8_t *b_id
                          void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * cdl_quantize_fwd (hard index only) and cdl_qgemm_fwd in one kernel: y = delta_a * delta_b * (Q_idx(x) . b_idx^T),
+ * where Q_idx(x)[m,k], the level index nearest to x[m,k] (ties: the lower one) under the quantizer *p_a, is formed
+ * tile by tile on the chip and never written to memory (Sec. III-A, the mode of the CPMF; Sec. IV-A).
+ *   x DEVICE fp32[M,K], b_idx DEVICE int8[N,K], y DEVICE fp32[M,N] (all required when M*N > 0)
+ * y is bit for bit what the two calls give.  The fp32 activations are read once per 512 output columns instead of
+ * their int8 indices once per 256: for wide layers this moves more data and costs the nearest-level rule N / 512
+ * times per entry - it pays where the indices are not needed again (inference), not inside a training step, whose
+ * backward products read them.  Restrictions: K a multiple of 128, K <= 131071, a level set stored without an
+ * offset (cdl_index_offset(p_a) == 0), else CDL_ERR_PARAM / CDL_ERR_RANGE.  No scratch.
+ */
+int cdl_qgemm_fwd_quantize(const float *x, const cdl_qparams *p_a, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
+                           float delta_b, float *y, void *hip_stream);
+
+/*
  * The forward product of a convolutional layer over level indices (Sec. IV-A, the forward pass over quantized
  * weights and activations, for the convolutional layers of Sec. II), without forming the matrix of input windows:
  *   acc[b,p,q,n] = sum_{r,s,c} X[b, p*stride + r - pad, q*stride + s - pad, c] * w_idx[n,r,s,c],

@@ -302,6 +302,21 @@ int cdl_qgemm_bwd_offset(const float *g, const int8_t *a_idx, const int8_t *b_id
     return launch_qgemm_bwd(g, a_idx, b_idx, M, N, K, delta_a, delta_b, a_offset, b_offset, d_a_hat, d_b_hat, ws, (hipStream_t)hip_stream);
 }
 
+int cdl_qgemm_fwd_quantize(const float *x, const cdl_qparams *p_a, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
+                           float delta_b, float *y, void *hip_stream)
+{
+    const int rc = check_qparams(p_a);
+    if (rc != CDL_OK) return rc;
+    if (M < 0 || N < 0 || K <= 0) return CDL_ERR_PARAM;
+    if (!(std::isfinite(delta_b) && delta_b > 0.0f)) return CDL_ERR_PARAM;
+    // whole K-tiles of 128 entries; activations whose indices are stored as they are
+    if (K % 128 != 0 || index_offset(*p_a) != 0) return CDL_ERR_PARAM;
+    if ((int64_t)K * 128 * 128 > 2147483647LL) return CDL_ERR_RANGE;
+    if ((int64_t)M * N > 0 && (!x || !b_idx || !y)) return CDL_ERR_NULL;
+    if (!aligned(x, 16) || !aligned(b_idx, 16) || !aligned(y, 4)) return CDL_ERR_ALIGN;
+    return launch_qgemm_quantize_fwd(x, *p_a, b_idx, M, N, K, delta_b, y, (hipStream_t)hip_stream);
+}
+
 size_t cdl_qconv_fwd_workspace_bytes(int32_t N, int32_t x_offset)
 {
     if (N < 0 || !offset_ok(x_offset)) return 0;

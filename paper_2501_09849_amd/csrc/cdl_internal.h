@@ -122,6 +122,10 @@ int launch_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
                      float *d_a_hat, float *d_b_hat, void *ws, hipStream_t stream, const FusedQuantBwd *fq = nullptr,
                      const FusedQuantBwd *fqb = nullptr);
 
+// Forward product with the quantizer of the activations in its prologue (K % 128 == 0, indices stored without an offset).
+int launch_qgemm_quantize_fwd(const float *x, const cdl_qparams &p, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
+                              float delta_b, float *y, hipStream_t stream);
+
 // Forward product of a convolutional layer over level indices, without an im2col matrix (C % 16 == 0).
 size_t qconv_fwd_workspace_bytes(int32_t N, int32_t x_offset);
 int qconv_max_chunks();   // most 16-byte chunks of the contraction R*S*C the kernels index

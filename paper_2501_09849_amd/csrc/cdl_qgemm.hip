@@ -233,6 +233,7 @@ struct LimbArgs {
     double *fq_partial;       // [work items][2]
     QConst fq_k;
     int fq_wsel;              // band_template(fq_k)
+    float fq_scale;           // forward product with the quantizer in its prologue: delta_a * delta_b
     const double *row_corr;   // [rows] or null: added to every entry of an output row (the index operand is stored with an offset:
                               // the missing part of the product is offset * step * sum of g over the contraction); splits == 1 only
 };
@@ -779,7 +780,7 @@ __device__ __forceinline__ void limbs_of4(const float (&g)[4], float gscale, uin
 // lets the scheduler put the VALU and LDS work into the shadow of the MFMAs.
 // TRANS: G is read transposed (rows of the product are columns of G).  VEC: 16-byte loads of G
 // (N % 4 == 0).
-template <int L, int TN, bool TRANS, bool VEC, bool LONG_RUNS, bool FUSED = false>
+template <int L, int TN, bool TRANS, bool VEC, bool LONG_RUNS, bool FUSED = false, bool QUANT = false>
 __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, float gscale, double out_scale)
 {
     constexpr int NB = 4 * TN * 32;
@@ -867,7 +868,13 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
     auto convert_half = [&](const float (&g)[16], int h) {
 #pragma unroll
         for (int q = 2 * h; q < 2 * h + 2; ++q) {
-            if (!TRANS) {
+            if constexpr (QUANT) {
+                // the "digits" are the level indices of the quantizer (one plane): the forward product with the
+                // quantizer in its prologue
+                w[q][0] = pack_indices((int)anchor_level<true>(g[4 * q], a.fq_k), (int)anchor_level<true>(g[4 * q + 1], a.fq_k),
+                                       (int)anchor_level<true>(g[4 * q + 2], a.fq_k), (int)anchor_level<true>(g[4 * q + 3], a.fq_k),
+                                       a.fq_k.idx_off);
+            } else if constexpr (!TRANS) {
                 const float g4[4] = {g[4 * q], g[4 * q + 1], g[4 * q + 2], g[4 * q + 3]};
                 limbs_of4<L>(g4, gscale, w[q]);
             } else {
@@ -1001,7 +1008,8 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     if (FULL || (row_ok && ecol + j * 32 < a.cols)) {
-                        if (std::is_same<T, float>::value) p[j * 32] = (T)__builtin_fma(combined(j, rr), out_scale, rc);
+                        if (QUANT) p[j * 32] = (T)(a.fq_scale * (float)acc[0][j][rr]);      // as the forward product rounds
+                        else if (std::is_same<T, float>::value) p[j * 32] = (T)__builtin_fma(combined(j, rr), out_scale, rc);
                         else p[j * 32] = (T)combined(j, rr);
                     }
                 }
@@ -1227,6 +1235,20 @@ void limb_gemm_kernel(LimbArgs a)
         case 5: if (vec) limb_gemm_body<5, 3, TRANS, true, false, FUSED>(a, limb_lds, gscale, out_scale); else limb_gemm_body<5, 3, TRANS, false, false, FUSED>(a, limb_lds, gscale, out_scale); break;
         default: if (vec) limb_gemm_body<6, 2, TRANS, true, false, FUSED>(a, limb_lds, gscale, out_scale); else limb_gemm_body<6, 2, TRANS, false, false, FUSED>(a, limb_lds, gscale, out_scale); break;
     }
+}
+
+// The forward product with the quantizer of the activations in its prologue: y = delta_a delta_b (Q_idx(X) . Wi^T)
+// where Q_idx(X) - the level indices cdl_quantize_fwd would store - exists only as one int8 plane per K-tile in LDS.
+// The limb kernel's loop with the conversion to digits replaced by the nearest-level rule, one plane, four column
+// tiles per wave (512 columns per block), runs of row tiles per block.
+constexpr int kQuantFwdTN = 4;
+static_assert(2 * (kLPlane + 4 * kQuantFwdTN * 32 * kLBK) <= kLimbLdsBytes, "LDS of the limb kernels serves");
+
+__global__ __launch_bounds__(kLThreads, 1)
+void qgemm_quantize_fwd_kernel(LimbArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) int8_t limb_lds[];
+    limb_gemm_body<1, kQuantFwdTN, false, true, true, false, true>(a, limb_lds, 0.0f, 0.0);
 }
 
 // out = out_scale * sum over the contraction splits.  Four partial sums per lane, combined in a fixed order,
@@ -1824,6 +1846,33 @@ int launch_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_
     // needs enough rows to be worth it)
     if (g.Kc % kFBK == 0 && (int64_t)M * N >= (int64_t)kFTile * kFTile * 64) return launch_gemm_dma(g, stream);
     return launch_gemm<4, 2>(g, stream);
+}
+
+int launch_qgemm_quantize_fwd(const float *x, const cdl_qparams &p, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
+                              float delta_b, float *y, hipStream_t stream)
+{
+    if ((int64_t)M * N == 0) return CDL_OK;
+    LimbArgs a{};
+    a.G = x; a.M = M; a.N = K;            // the fp32 operand: [M][K], contraction along its rows
+    a.Bt = b_idx; a.ldb = K;              // [N][K]: the contraction index is contiguous as it is
+    a.rows = M; a.cols = N; a.kc = K;
+    a.nk = K / kLBK;
+    a.tiles_r = (M + kLRows - 1) / kLRows; a.splits = 1; a.kt_per_split = a.nk;
+    a.out = y;
+    a.fq_k = make_const(p);
+    a.fq_scale = p.delta * delta_b;
+    constexpr int NB = 4 * kQuantFwdTN * 32;
+    if ((int64_t)NB * a.ldb > 0xffffffffLL) return CDL_ERR_RANGE;
+    int dev = 0, n_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
+        n_cu = 256;
+    a.units_per_block = (a.tiles_r + n_cu - 1) / n_cu;
+    const int64_t items = (a.tiles_r + a.units_per_block - 1) / a.units_per_block;      // runs; each takes every column tile
+    const unsigned grid = (unsigned)((items + 7) / 8 * 8);
+    const hipError_t e = hipFuncSetAttribute((const void *)qgemm_quantize_fwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLimbLdsBytes);
+    if (e != hipSuccess) return hip_failed(e);
+    CDL_LAUNCH("qgemm_kernel(quantize + fwd)", stream, qgemm_quantize_fwd_kernel, dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
+    return check_launch();
 }
 
 size_t qconv_fwd_workspace_bytes(int32_t N, int32_t x_offset)
