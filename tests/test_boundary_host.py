@@ -144,6 +144,46 @@ def test_gemm_argument_validation_happens_before_any_gpu_work(cdl):
     assert lib.cdl_profile_collect(None, 4) == PARAM
 
 
+def test_layer_entry_points_validate_before_any_gpu_work(cdl):
+    lib = cdl.load()
+    good = _q(0, 16, 0.25, 64.0)
+    # the convolution: geometry, channel multiple, offsets, contraction length, pointers, workspace with an offset
+    c = lib.cdl_qconv_fwd
+    ok = dict(B=1, H=8, W=8, C=16, N=4, R=3, S=3, stride=1, pad=1)
+    def conv(x=FAKE, w=FAKE, acc=FAKE, y=None, off=0, ws=None, ws_bytes=0, **kw):
+        g = dict(ok, **kw)
+        return c(x, w, g["B"], g["H"], g["W"], g["C"], g["N"], g["R"], g["S"], g["stride"], g["pad"], 0.1, 0.1, off, acc, y, ws, ws_bytes, None)
+    assert conv(C=3) == PARAM and conv(C=24) == PARAM
+    assert conv(pad=3) == PARAM and conv(stride=0) == PARAM and conv(H=1, W=1, R=5, S=5, pad=1) == PARAM
+    assert conv(off=64) == PARAM
+    assert conv(C=4096) == RANGE                              # contraction beyond the tap table
+    assert conv(acc=None) == NULL and conv(x=None) == NULL
+    assert conv(x=FAKE + 8) == ALIGN
+    assert conv(off=128) == WS
+    assert lib.cdl_qconv_fwd_workspace_bytes(64, 0) == 0 and lib.cdl_qconv_fwd_workspace_bytes(64, 128) >= 256 + 64 * 4
+    # the forward product with the quantizer in its prologue
+    f = lib.cdl_qgemm_fwd_quantize
+    assert f(FAKE, None, FAKE, 4, 4, 128, 0.1, FAKE, None) == NULL
+    assert f(FAKE, good, FAKE, 4, 4, 100, 0.1, FAKE, None) == PARAM            # whole K-tiles only
+    assert f(FAKE, _q(0, 256, 0.25, 64.0), FAKE, 4, 4, 128, 0.1, FAKE, None) == PARAM   # indices stored with an offset
+    assert f(FAKE, good, FAKE, 4, 4, 131072, 0.1, FAKE, None) == RANGE
+    assert f(FAKE, good, None, 4, 4, 128, 0.1, FAKE, None) == NULL
+    assert f(FAKE + 4, good, FAKE, 4, 4, 128, 0.1, FAKE, None) == ALIGN
+    # the backward step in one call
+    b = lib.cdl_qgemm_bwd_quantize_bwd
+    def bwd(M=64, N=64, K=64, theta_a=FAKE, d_theta_a=FAKE, delta_b=0.25, b_off=0, theta_b=None, p_b=None, d_theta_b=None, ws=None, ws_bytes=0):
+        return b(FAKE, FAKE, FAKE, M, N, K, theta_a, good, delta_b, b_off, d_theta_a, None, None, None, theta_b, p_b, d_theta_b, None, None,
+                 ws, ws_bytes, None)
+    assert bwd(K=62) == PARAM and bwd(N=32) == PARAM and bwd(M=0) == PARAM
+    assert bwd(d_theta_a=None) == NULL
+    assert bwd(theta_b=FAKE, p_b=good) == NULL                                   # no place for dL/dtheta of the weights
+    assert bwd(theta_b=FAKE, p_b=_q(0, 16, 0.3, 64.0), d_theta_b=FAKE) == PARAM  # not the step the product was told
+    assert bwd(theta_b=FAKE, p_b=good, d_theta_b=FAKE, b_off=128) == PARAM       # not the storage offset of that quantizer
+    assert bwd(theta_b=FAKE, p_b=good, d_theta_b=FAKE) == WS
+    assert bwd() == WS
+    assert lib.cdl_profile_only(None) == OK and lib.cdl_profile_only(b"limb_gemm_kernel(d_b_hat)") == OK and lib.cdl_profile_only(b"") == OK
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch):
     import paper_2501_09849_amd.binding as binding
     monkeypatch.setattr(binding, "_LIB", None)
