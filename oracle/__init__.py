@@ -98,6 +98,8 @@ def lib():
                                            ctypes.c_float, ctypes.c_float, _i32p, _f64p]
         L.cdl_oracle_qconv_fwd.restype = None
         L.cdl_oracle_qconv_fwd.argtypes = [_i16p, _i16p] + [ctypes.c_int] * 9 + [ctypes.c_float, ctypes.c_float, _i32p, _f64p]
+        L.cdl_oracle_qconv_bwd.restype = None
+        L.cdl_oracle_qconv_bwd.argtypes = [_f32p, _i16p, _i16p] + [ctypes.c_int] * 9 + [ctypes.c_float, ctypes.c_float, _f64p, _f64p]
         L.cdl_oracle_qgemm_bwd.restype = None
         L.cdl_oracle_qgemm_bwd.argtypes = [_f32p, _i16p, _i16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_float, ctypes.c_float, _f64p, _f64p]
@@ -266,6 +268,23 @@ def qconv_fwd(x_idx: np.ndarray, w_idx: np.ndarray, stride: int, pad: int, delta
     lib().cdl_oracle_qconv_fwd(_ptr(x, _i16p), _ptr(w, _i16p), B, H, W, C, N, R, S, int(stride), int(pad),
                                float(delta_x), float(delta_w), _ptr(acc, _i32p), _ptr(y, _f64p))
     return acc, y
+
+
+def qconv_bwd(g: np.ndarray, x_idx: np.ndarray, w_idx: np.ndarray, stride: int, pad: int, delta_x: float, delta_w: float,
+              want_dx: bool = True, want_dw: bool = True):
+    """g fp32[B,P,Q,N] -> (d_x_hat float64[B,H,W,C] | None, d_w_hat float64[N,R,S,C] | None)."""
+    gg = _c(g, np.float32)
+    x = _c(x_idx, np.int16)
+    w = _c(w_idx, np.int16)
+    B, H, W, C = x.shape
+    N, R, S, C2 = w.shape
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    assert C == C2 and gg.shape == (B, P, Q, N)
+    dx = np.empty((B, H, W, C), dtype=np.float64) if want_dx else None
+    dw = np.empty((N, R, S, C), dtype=np.float64) if want_dw else None
+    lib().cdl_oracle_qconv_bwd(_ptr(gg, _f32p), _ptr(x, _i16p), _ptr(w, _i16p), B, H, W, C, N, R, S, int(stride), int(pad),
+                               float(delta_x), float(delta_w), _ptr(dx, _f64p), _ptr(dw, _f64p))
+    return dx, dw
 
 
 def qgemm_bwd(g: np.ndarray, a_idx: np.ndarray, b_idx: np.ndarray, delta_a: float, delta_b: float,

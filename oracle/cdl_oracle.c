@@ -526,6 +526,64 @@ void cdl_oracle_qconv_fwd(const int16_t *x_idx, const int16_t *w_idx, int B, int
 }
 
 /*
+ * Backward of the convolution above with respect to its two quantized operands (Algorithm 1, backward step, for
+ * a convolutional layer): with g = dL/dy, fp32 [B][P][Q][N], xhat = delta_x * x_idx and what = delta_w * w_idx,
+ *   d_x_hat[b,h,w,c] = sum over (p,q,r,s,n) with p*stride + r - pad = h and q*stride + s - pad = w of
+ *                      g[b,p,q,n] * what[n,r,s,c]
+ *   d_w_hat[n,r,s,c] = sum over (b,p,q) whose tap (r,s) lies inside the image of
+ *                      g[b,p,q,n] * xhat[b, p*stride + r - pad, q*stride + s - pad, c]
+ * i.e. every product x*w that enters y[b,p,q,n] hands g[b,p,q,n] times the other factor to each of its factors.
+ */
+void cdl_oracle_qconv_bwd(const float *g, const int16_t *x_idx, const int16_t *w_idx, int B, int H, int W, int C,
+                          int N, int R, int S, int stride, int pad, float delta_x, float delta_w,
+                          double *d_x_hat /* B*H*W*C, nullable */, double *d_w_hat /* N*R*S*C, nullable */)
+{
+    const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
+    if (d_x_hat) {
+#pragma omp parallel for schedule(static) collapse(2)
+        for (int b = 0; b < B; ++b)
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w)
+                    for (int c = 0; c < C; ++c) {
+                        double sum = 0.0;
+                        for (int p = 0; p < P; ++p) {
+                            const int r = h - p * stride + pad;
+                            if (r < 0 || r >= R) continue;
+                            for (int q = 0; q < Q; ++q) {
+                                const int s = w - q * stride + pad;
+                                if (s < 0 || s >= S) continue;
+                                const float *gp = g + (((size_t)b * P + p) * Q + q) * N;
+                                for (int n = 0; n < N; ++n)
+                                    sum += (double)gp[n] * (double)w_idx[(((size_t)n * R + r) * S + s) * C + c];
+                            }
+                        }
+                        d_x_hat[(((size_t)b * H + h) * W + w) * C + c] = (double)delta_w * sum;
+                    }
+    }
+    if (d_w_hat) {
+#pragma omp parallel for schedule(static) collapse(2)
+        for (int n = 0; n < N; ++n)
+            for (int r = 0; r < R; ++r)
+                for (int s = 0; s < S; ++s)
+                    for (int c = 0; c < C; ++c) {
+                        double sum = 0.0;
+                        for (int b = 0; b < B; ++b)
+                            for (int p = 0; p < P; ++p) {
+                                const int h = p * stride + r - pad;
+                                if (h < 0 || h >= H) continue;
+                                for (int q = 0; q < Q; ++q) {
+                                    const int w = q * stride + s - pad;
+                                    if (w < 0 || w >= W) continue;
+                                    sum += (double)g[(((size_t)b * P + p) * Q + q) * N + n] *
+                                           (double)x_idx[(((size_t)b * H + h) * W + w) * C + c];
+                                }
+                            }
+                        d_w_hat[(((size_t)n * R + r) * S + s) * C + c] = (double)delta_x * sum;
+                    }
+    }
+}
+
+/*
  * Backward of the same product with respect to the two quantized operands.
  * With Yhat = Ahat . Bhat^T, Ahat = delta_a*a_idx, Bhat = delta_b*b_idx and
  * g = dL/dYhat (kept in fp32: the paper quantizes weights and activations,

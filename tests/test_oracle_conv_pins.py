@@ -86,3 +86,53 @@ def test_unsigned_eight_bit_indices_and_the_largest_accumulator(oracle):
     acc, _ = oracle.qconv_fwd(x, w, 1, 1, 1.0, 1.0, want_y=False)
     assert acc[0, 1, 1, 0] == 9 * 64 * 255 * 127          # the centre sees all nine taps
     assert acc[0, 0, 0, 0] == 4 * 64 * 255 * 127          # a corner sees four
+
+
+@pytest.mark.parametrize("B,H,W,C,N,R,S,stride,pad", [
+    (2, 7, 9, 3, 4, 3, 3, 1, 1), (1, 8, 8, 5, 2, 3, 3, 2, 1), (2, 6, 5, 4, 3, 1, 1, 1, 0), (1, 9, 7, 2, 3, 5, 3, 1, 2),
+    (1, 10, 11, 3, 2, 3, 5, 2, 0), (2, 5, 5, 2, 3, 3, 3, 2, 0)])
+def test_convolution_backward_equals_the_index_product_backward_on_windows(oracle, B, H, W, C, N, R, S, stride, pad):
+    """dL/dQ(w) is the weight gradient of the product on the window matrix; dL/dQ(x) is its activation gradient with
+    every window entry added back to the pixel it came from (numpy add.at), padding entries dropped."""
+    rng = np.random.default_rng(B * 100 + H * 10 + W + C + stride)
+    x, w = _draw(rng, (B, H, W, C)), _draw(rng, (N, R, S, C))
+    cols, P, Q = _im2col(x, R, S, stride, pad)
+    g = rng.standard_normal((B, P, Q, N)).astype(np.float32)
+    dx, dw = oracle.qconv_bwd(g, x, w, stride, pad, 0.25, 0.5)
+    da, db = oracle.qgemm_bwd(g.reshape(-1, N), cols, w.reshape(N, -1), 0.25, 0.5)
+    assert np.allclose(dw.reshape(N, -1), db, rtol=1e-13, atol=1e-13)
+    want = np.zeros((B, H + 2 * pad, W + 2 * pad, C))
+    da = da.reshape(B, P, Q, R, S, C)
+    for r in range(R):
+        for s in range(S):
+            bb, pp, qq = np.meshgrid(np.arange(B), np.arange(P), np.arange(Q), indexing="ij")
+            np.add.at(want, (bb, pp * stride + r, qq * stride + s), da[:, :, :, r, s, :])
+    assert np.allclose(dx, want[:, pad:pad + H, pad:pad + W, :], rtol=1e-13, atol=1e-13)
+
+
+def test_convolution_backward_is_the_derivative_of_the_forward(oracle):
+    """L = sum g * y is bilinear in the two index tensors: moving x by integers u changes L by exactly
+    sum d_x_hat * delta_x * u, and likewise for w - with no window matrix anywhere in the check."""
+    rng = np.random.default_rng(3)
+    B, H, W, C, N, R, S, stride, pad = 2, 7, 6, 3, 4, 3, 3, 2, 1
+    x, w = _draw(rng, (B, H, W, C)), _draw(rng, (N, R, S, C))
+    dxs, dws = 0.25, 0.5
+    _, y = oracle.qconv_fwd(x, w, stride, pad, dxs, dws)
+    g = rng.standard_normal(y.shape).astype(np.float32)
+    dx, dw = oracle.qconv_bwd(g, x, w, stride, pad, dxs, dws)
+    L0 = float((g.astype(np.float64) * y).sum())
+    u = _draw(rng, x.shape, -3, 3)
+    _, y1 = oracle.qconv_fwd(x + u, w, stride, pad, dxs, dws)
+    assert abs(float((g.astype(np.float64) * y1).sum()) - L0 - float((dx * dxs * u).sum())) < 1e-9
+    v = _draw(rng, w.shape, -3, 3)
+    _, y2 = oracle.qconv_fwd(x, w + v, stride, pad, dxs, dws)
+    assert abs(float((g.astype(np.float64) * y2).sum()) - L0 - float((dw * dws * v).sum())) < 1e-9
+
+
+def test_one_by_one_convolution_backward_is_the_index_product_backward(oracle):
+    rng = np.random.default_rng(8)
+    x, w = _draw(rng, (2, 5, 6, 8)), _draw(rng, (7, 1, 1, 8))
+    g = rng.standard_normal((2, 5, 6, 7)).astype(np.float32)
+    dx, dw = oracle.qconv_bwd(g, x, w, 1, 0, 0.3, 0.7)
+    da, db = oracle.qgemm_bwd(g.reshape(-1, 7), x.reshape(-1, 8), w.reshape(7, 8), 0.3, 0.7)
+    assert np.array_equal(dx.reshape(-1, 8), da) and np.array_equal(dw.reshape(7, 8), db)
