@@ -297,6 +297,24 @@ int cdl_qconv_fwd(const int8_t *x_idx, const int8_t *w_idx, int32_t B, int32_t H
                   int32_t *acc, float *y, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * The weight gradient of that convolutional layer (Algorithm 1, backward step), again without the caller forming
+ * the matrix of input windows:
+ *   d_w_hat[n,r,s,c] = delta_x * sum over (b,p,q) of g[b,p,q,n] * X[b, p*stride + r - pad, q*stride + s - pad, c]
+ * with X as in cdl_qconv_fwd (level index x_idx + x_offset inside the image, 0 outside).  It is cdl_qgemm_bwd's
+ * d_b_hat on the window matrix - same limbs, same exactness - whose transposed copy (which that product needs
+ * anyway) is gathered straight from the activations.
+ *   g DEVICE fp32[B,P,Q,N], x_idx DEVICE int8[B,H,W,C], d_w_hat DEVICE fp32[N,R,S,C]
+ * Restrictions as for cdl_qconv_fwd, and B*P*Q <= 11 000 000.  Scratch: cdl_qconv_bwd_weights_workspace_bytes
+ * (it holds the transposed window matrix: R*S*C * B*P*Q bytes).  The gradient with respect to the activations of a
+ * convolution is not served: form g's window matrix or use cdl_qgemm_bwd on explicit windows.
+ */
+size_t cdl_qconv_bwd_weights_workspace_bytes(int32_t B, int32_t H, int32_t W, int32_t C, int32_t N, int32_t R, int32_t S,
+                                             int32_t stride, int32_t pad);
+int cdl_qconv_bwd_weights(const float *g, const int8_t *x_idx, int32_t B, int32_t H, int32_t W, int32_t C, int32_t N,
+                          int32_t R, int32_t S, int32_t stride, int32_t pad, float delta_x, int32_t x_offset,
+                          float *d_w_hat, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * The backward step of Algorithm 1 for a layer in one call: cdl_qgemm_bwd followed by cdl_quantize_bwd on its
  * d_a_hat (and, optionally, on its d_b_hat), with the quantizer's backward pass (Lemma 1; eq. partialX3, Jgradqx,
  * Jgrad_alpha_q) applied to each tile of dL/dQ(x) in the epilogue of the product, while the tile is still on the

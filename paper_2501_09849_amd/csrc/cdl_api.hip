@@ -345,6 +345,38 @@ int cdl_qconv_fwd(const int8_t *x_idx, const int8_t *w_idx, int32_t B, int32_t H
     return launch_qconv_fwd(x_idx, w_idx, B, H, W, C, N, R, S, stride, pad, delta_x, delta_w, x_offset, acc, y, ws, (hipStream_t)hip_stream);
 }
 
+size_t cdl_qconv_bwd_weights_workspace_bytes(int32_t B, int32_t H, int32_t W, int32_t C, int32_t N, int32_t R, int32_t S,
+                                             int32_t stride, int32_t pad)
+{
+    if (B <= 0 || H <= 0 || W <= 0 || C <= 0 || N <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0) return 0;
+    if (H + 2 * pad < R || W + 2 * pad < S) return 0;
+    const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
+    const int64_t M = (int64_t)B * P * Q, K = (int64_t)R * S * C;
+    if (M > 11000000LL || K > 2147483647LL) return 0;
+    return qgemm_bwd_workspace_bytes((int32_t)M, N, (int32_t)K);
+}
+
+int cdl_qconv_bwd_weights(const float *g, const int8_t *x_idx, int32_t B, int32_t H, int32_t W, int32_t C, int32_t N,
+                          int32_t R, int32_t S, int32_t stride, int32_t pad, float delta_x, int32_t x_offset,
+                          float *d_w_hat, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (B <= 0 || H <= 0 || W <= 0 || C <= 0 || N <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0 || !offset_ok(x_offset)) return CDL_ERR_PARAM;
+    if (!(std::isfinite(delta_x) && delta_x > 0.0f)) return CDL_ERR_PARAM;
+    if (C % 16 != 0 || pad >= R || pad >= S) return CDL_ERR_PARAM;
+    if (H + 2 * pad < R || W + 2 * pad < S) return CDL_ERR_PARAM;
+    if (!g || !x_idx || !d_w_hat) return CDL_ERR_NULL;
+    const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
+    const int64_t M = (int64_t)B * P * Q, K = (int64_t)R * S * C;
+    // 32-bit offsets into the activations and into the transposed window matrix
+    if ((int64_t)B * H * W * C > 2147483647LL || M > 11000000LL || K > 2147483647LL / 2) return CDL_ERR_RANGE;
+    if (!aligned(g, 16) || !aligned(x_idx, 16) || !aligned(d_w_hat, 16)) return CDL_ERR_ALIGN;
+    const int rc = check_ws(ws, ws_bytes, qgemm_bwd_workspace_bytes((int32_t)M, N, (int32_t)K));
+    if (rc != CDL_OK) return rc;
+    const ConvWindows cw{B, H, W, C, R, S, stride, pad, (int)P, (int)Q};
+    return launch_qgemm_bwd(g, x_idx, nullptr, (int32_t)M, N, (int32_t)K, delta_x, 1.0f, x_offset, 0, nullptr, d_w_hat, ws,
+                            (hipStream_t)hip_stream, nullptr, nullptr, &cw);
+}
+
 int cdl_qgemm_bwd_quantize_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
                                const float *theta_a, const cdl_qparams *p_a, float delta_b, int32_t b_offset,
                                float *d_theta_a, float *d_delta_a, float *d_alpha_a, float *d_b_hat,

@@ -117,10 +117,16 @@ struct FusedQuantBwd {
     float *d_theta;           // weight side only: where dL/dtheta goes
 };
 
+// cw != null: a_idx is not an [M][K] matrix but the activations [B][H][W][C] of a convolutional layer, whose matrix of
+// input windows (M = B*P*Q rows, K = R*S*C columns) is the operand; only d_b_hat (the weight gradient) is served.
+struct ConvWindows {
+    int B, H, W, C, R, S, stride, pad, P, Q;
+};
+
 int launch_qgemm_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx,
                      int32_t M, int32_t N, int32_t K, float delta_a, float delta_b, int32_t a_offset, int32_t b_offset,
                      float *d_a_hat, float *d_b_hat, void *ws, hipStream_t stream, const FusedQuantBwd *fq = nullptr,
-                     const FusedQuantBwd *fqb = nullptr);
+                     const FusedQuantBwd *fqb = nullptr, const ConvWindows *cw = nullptr);
 
 // Forward product with the quantizer of the activations in its prologue (K % 128 == 0, indices stored without an offset).
 int launch_qgemm_quantize_fwd(const float *x, const cdl_qparams &p, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,

@@ -1490,13 +1490,23 @@ __global__ __launch_bounds__(256) void absmax_kernel(const float *__restrict__ g
 // 64 columns: 4-byte loads along the rows into LDS (row stride 17 words), then every thread takes a
 // 4 x 4 byte block, transposes it in registers and stores 4 bytes of four output rows, so that 32
 // lanes write 128 contiguous bytes.  VEC: cols % 4 == 0 (aligned 4-byte loads).
-template <bool VEC>
+// CONV: src is not a matrix but the activations of a convolutional layer, [B][H][W][C] with C a multiple of 16, and
+// "src[r][c]" is entry c = (tap row, tap column, channel) of the window of output pixel r = (b, p, q) - the matrix of
+// input windows, which is never stored the right way round: only its transpose is written, as the product that
+// contracts over the pixels needs it.  Taps outside the image read as geom.pad_word (the stored byte of level index 0).
+struct ConvGeom {
+    int B, H, W, C, R, S, stride, pad, P, Q;
+    int pad_word;
+};
+
+template <bool VEC, bool CONV = false>
 __global__ __launch_bounds__(256) void transpose_i8_kernel(const int8_t *__restrict__ src, int rows, int cols,
                                                            int8_t *__restrict__ dst, int64_t ldd,
-                                                           unsigned int *__restrict__ col_abs, int tiles_per_block)
+                                                           unsigned int *__restrict__ col_abs, int tiles_per_block, ConvGeom geom)
 {
     __shared__ uint32_t tile[128 * 17];
     __shared__ unsigned int abs_s[64];
+    __shared__ int row_h0[128], row_w0[128], row_off[128];     // CONV: window origin of the tile's rows
     const int c0 = blockIdx.y * 64;   // neighbouring blocks write neighbouring 128-byte pieces
     const int tid = threadIdx.x;
     if (tid < 64) abs_s[tid] = 0u;
@@ -1506,14 +1516,39 @@ __global__ __launch_bounds__(256) void transpose_i8_kernel(const int8_t *__restr
     unsigned int part[2][4] = {};
     const int row_tiles = (rows + 127) / 128;
     const int t_end = min(row_tiles, ((int)blockIdx.x + 1) * tiles_per_block);
+    // CONV: the thread's column (the same in all its loads) as a tap and an offset from the window's origin
+    int tap_r = 0, tap_s = 0, tap_off = 0;
+    if (CONV) {
+        const int c = min(c0 + 4 * (tid & 15), cols - 4);
+        const int tap = c / geom.C;
+        tap_r = tap / geom.S;
+        tap_s = tap - tap_r * geom.S;
+        tap_off = (tap_r * geom.W + tap_s) * geom.C + (c - tap * geom.C);
+    }
     for (int rt = (int)blockIdx.x * tiles_per_block; rt < t_end; ++rt) {
         const int r0 = rt * 128;
+        if (CONV) {
+            if (tid < 128) {
+                const int m = min(r0 + tid, rows - 1), pq = geom.P * geom.Q;
+                const int b = m / pq, rem = m - b * pq, p = rem / geom.Q, q = rem - p * geom.Q;
+                const int h0 = p * geom.stride - geom.pad, w0 = q * geom.stride - geom.pad;
+                row_h0[tid] = h0;
+                row_w0[tid] = w0;
+                row_off[tid] = ((b * geom.H + h0) * geom.W + w0) * geom.C;      // (host: B*H*W*C < 2^31)
+            }
+            __syncthreads();
+        }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int i = tid + 256 * j, row = i >> 4, cd = i & 15;
             uint32_t w = 0u;
             const int r = r0 + row, c = c0 + 4 * cd;
-            if (r < rows) {
+            if (CONV) {
+                if (r < rows && c < cols) {
+                    const bool inside = (unsigned)(row_h0[row] + tap_r) < (unsigned)geom.H && (unsigned)(row_w0[row] + tap_s) < (unsigned)geom.W;
+                    w = inside ? *reinterpret_cast<const uint32_t *>(src + ((int64_t)row_off[row] + tap_off)) : (uint32_t)geom.pad_word;
+                }
+            } else if (r < rows) {
                 const int8_t *p = src + (int64_t)r * cols + c;
                 if (VEC) {
                     if (c < cols) w = *reinterpret_cast<const uint32_t *>(p);
@@ -1771,8 +1806,19 @@ void launch_transpose(const int8_t *src, int rows, int cols, int8_t *dst, int64_
     int per = (int)(((int64_t)row_tiles * col_tiles + 1023) / 1024);
     per = per < 1 ? 1 : (per > 16 ? 16 : per);
     const dim3 grid((row_tiles + per - 1) / per, col_tiles);
-    if (cols % 4 == 0) CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel<true>, grid, dim3(256), 0, src, rows, cols, dst, ldd, col_abs, per);
-    else CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel<false>, grid, dim3(256), 0, src, rows, cols, dst, ldd, col_abs, per);
+    if (cols % 4 == 0) CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel<true>, grid, dim3(256), 0, src, rows, cols, dst, ldd, col_abs, per, ConvGeom{});
+    else CDL_LAUNCH("transpose_i8_kernel", stream, transpose_i8_kernel<false>, grid, dim3(256), 0, src, rows, cols, dst, ldd, col_abs, per, ConvGeom{});
+}
+
+// the transposed matrix of input windows of a convolution, straight from the activations (rows = B*P*Q, cols = R*S*C)
+void launch_transpose_windows(const int8_t *x, const ConvGeom &g, int8_t *dst, int64_t ldd, unsigned int *col_abs, hipStream_t stream)
+{
+    const int rows = g.B * g.P * g.Q, cols = g.R * g.S * g.C;
+    const int row_tiles = (rows + 127) / 128, col_tiles = (cols + 63) / 64;
+    int per = (int)(((int64_t)row_tiles * col_tiles + 1023) / 1024);
+    per = per < 1 ? 1 : (per > 16 ? 16 : per);
+    const dim3 grid((row_tiles + per - 1) / per, col_tiles);
+    CDL_LAUNCH("transpose_i8_kernel(windows)", stream, (transpose_i8_kernel<true, true>), grid, dim3(256), 0, x, rows, cols, dst, ldd, col_abs, per, g);
 }
 
 }  // namespace
@@ -1953,9 +1999,11 @@ int qconv_max_chunks() { return kConvMaxChunks; }
 
 int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
                      int32_t M, int32_t N, int32_t K, float delta_a, float delta_b, int32_t a_offset, int32_t b_offset,
-                     float *d_a_hat, float *d_b_hat, void *ws, hipStream_t stream, const FusedQuantBwd *fq, const FusedQuantBwd *fqb)
+                     float *d_a_hat, float *d_b_hat, void *ws, hipStream_t stream, const FusedQuantBwd *fq, const FusedQuantBwd *fqb,
+                     const ConvWindows *cw)
 {
     const bool want_db = d_b_hat != nullptr || fqb != nullptr;     // the weight-gradient product runs
+    if (cw && d_a_hat) return CDL_ERR_PARAM;                       // (windows: a_idx is not a matrix; only the product over its rows is served)
     if (d_a_hat && ((int64_t)M * K > 0) && N == 0)
         CDL_LAUNCH("zero_f32_kernel", stream, zero_f32_kernel, dim3(blocks_for((int64_t)M * K, 256, 4096)), dim3(256), 0, d_a_hat, (int64_t)M * K);
     if (d_b_hat && ((int64_t)N * K > 0) && M == 0)
@@ -1984,7 +2032,12 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
                ss_a, fq ? (int)((L.fq_partial - L.ss_a) / sizeof(unsigned int)) + L.fq_items * 4
                         : (int)((L.ss_b - L.ss_a) / sizeof(unsigned int)) + K);
     if (d_a_hat) launch_transpose(b_idx, N, K, bt, L.ldn, ss_b, stream);
-    if (want_db) launch_transpose(a_idx, M, K, at, L.ldm, ss_a, stream);
+    if (want_db && cw) {
+        ConvGeom g{cw->B, cw->H, cw->W, cw->C, cw->R, cw->S, cw->stride, cw->pad, cw->P, cw->Q, 0};
+        const uint32_t pb = (uint32_t)(uint8_t)(int8_t)(-a_offset);
+        g.pad_word = (int)(pb | (pb << 8) | (pb << 16) | (pb << 24));
+        launch_transpose_windows(a_idx, g, at, L.ldm, ss_a, stream);
+    } else if (want_db) launch_transpose(a_idx, M, K, at, L.ldm, ss_a, stream);
     CDL_LAUNCH("plan_kernel", stream, plan_kernel, dim3(1), dim3(1024), 0, plan, block_max, L.n_max,
                ss_a, want_db ? K : 0, ss_b, d_a_hat ? K : 0, delta_a, delta_b);
     // operands stored as index - offset: d_a_hat lacks delta_b * ob * sum_n g[m][n] in row m, d_b_hat lacks

@@ -138,3 +138,41 @@ def test_convolution_rejects_what_it_does_not_serve():
     cdl.cdl_qconv_fwd(t8, t8, 0, 8, 8, 16, 4, 3, 3, 1, 1, 0.1, 0.1, out, None, None)
     torch.cuda.synchronize()
     assert int(out.sum()) == 5 * (1 << 16)
+
+
+# (B, H, W, C, N, R, S, stride, pad): the weight gradient - one and several pieces of the contraction over the pixels,
+# ragged everything, both strides, channel counts that are and are not whole 64-column tiles of the transposition
+WGRAD = [(2, 7, 9, 16, 20, 3, 3, 1, 1), (3, 8, 8, 32, 130, 3, 3, 2, 1), (5, 12, 12, 16, 16, 3, 3, 1, 1), (1, 9, 7, 48, 40, 5, 3, 1, 2),
+         (64, 14, 14, 64, 96, 3, 3, 1, 1), (16, 33, 31, 128, 64, 1, 1, 1, 0), (40, 28, 28, 16, 33, 3, 3, 2, 1), (1, 3, 3, 16, 8, 3, 3, 1, 1)]
+
+
+@pytest.mark.parametrize("B,H,W,C,N,R,S,stride,pad", WGRAD)
+@pytest.mark.parametrize("x_offset", [0, 128])
+def test_convolution_weight_gradient(oracle, B, H, W, C, N, R, S, stride, pad, x_offset):
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    rng = np.random.default_rng(B + H * W + C + x_offset)
+    if x_offset:
+        x_true = rng.integers(0, 256, size=(B, H, W, C)).astype(np.int16)
+    else:
+        x_true = rng.integers(-128, 128, size=(B, H, W, C)).astype(np.int16)
+    x_stored = (x_true - x_offset).astype(np.int8)
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    g = rng.standard_normal((B, P, Q, N)).astype(np.float32)
+    dx = float(np.float32(0.0731))
+    dW = gu.empty((N, R, S, C), torch.float32)
+    dW.fill_(float("nan"))
+    ws = gu.workspace(cdl.qconv_bwd_weights_workspace_bytes(B, H, W, C, N, R, S, stride, pad))
+    cdl.cdl_qconv_bwd_weights(gu.dev(g), gu.dev(x_stored), B, H, W, C, N, R, S, stride, pad, dx, dW, ws, x_offset=x_offset)
+    torch.cuda.synchronize()
+    _, ref = oracle.qconv_bwd(g, x_true, np.zeros((N, R, S, C), dtype=np.int16), stride, pad, dx, 1.0, want_dx=False)
+    gu.assert_close(dW.cpu().numpy(), ref, "d_w_hat")
+    # bit for bit the weight-gradient product on the window matrix (padding taps hold the stored byte of index 0)
+    cols, _, _ = _windows(x_stored, R, S, stride, pad, fill=-x_offset)
+    M, K = cols.shape
+    dWh = gu.empty((N, K), torch.float32)
+    ws2 = gu.workspace(cdl.qgemm_bwd_workspace_bytes(M, N, K))
+    cdl.cdl_qgemm_bwd_offset(gu.dev(g.reshape(M, N)), gu.dev(cols), gu.dev(np.zeros((N, K), dtype=np.int8)), M, N, K, dx, 1.0, x_offset, 0,
+                             None, dWh, ws2)
+    torch.cuda.synchronize()
+    assert torch.equal(dW.reshape(N, K), dWh)
