@@ -510,8 +510,18 @@ def conv_forward(scrub, seed=0, iters=5):
         cols.view(B, H, W, R, S, C).copy_(torch.as_strided(xp, (B, H, W, R, S, C), (st_b, st_h * stride, st_w * stride, st_h, st_w, st_c)))
     expand()
     ws = torch.empty(max(256, cdl.qgemm_fwd_workspace_bytes(M, N, K)), dtype=torch.uint8, device=dev)
+    G = torch.from_numpy(cdl_inputs.draw_g(wl, seed)).to(dev)           # [M, N] = [B, P, Q, N]
+    dW, dW2 = torch.empty((N, K), dtype=torch.float32, device=dev), torch.empty((N, K), dtype=torch.float32, device=dev)
+    dX = torch.empty((B, H, W, C), dtype=torch.float32, device=dev)
+    dcols = torch.empty((M, K), dtype=torch.float32, device=dev)
+    wsb = torch.empty(max(256, cdl.qgemm_bwd_workspace_bytes(M, N, K), cdl.qconv_bwd_weights_workspace_bytes(B, H, W, C, N, R, S, stride, pad),
+                          cdl.qconv_bwd_activations_workspace_bytes(B, H, W, C, N, R, S, stride, pad)), dtype=torch.uint8, device=dev)
     calls = {"conv": lambda: cdl.cdl_qconv_fwd(Xi, Wi, B, H, W, C, N, R, S, stride, pad, x.delta, w.delta, None, Y, None),
-             "product_on_windows": lambda: cdl.cdl_qgemm_fwd(cols, Wi.view(N, K), M, N, K, x.delta, w.delta, None, Y2, ws)}
+             "product_on_windows": lambda: cdl.cdl_qgemm_fwd(cols, Wi.view(N, K), M, N, K, x.delta, w.delta, None, Y2, ws),
+             "conv_weight_gradient": lambda: cdl.cdl_qconv_bwd_weights(G, Xi, B, H, W, C, N, R, S, stride, pad, x.delta, dW, wsb),
+             "weight_gradient_on_windows": lambda: cdl.cdl_qgemm_bwd(G, cols, Wi.view(N, K), M, N, K, x.delta, w.delta, None, dW2, wsb),
+             "conv_activation_gradient": lambda: cdl.cdl_qconv_bwd_activations(G, Wi, B, H, W, C, N, R, S, stride, pad, w.delta, dX, wsb),
+             "activation_gradient_on_windows (before the sum over windows)": lambda: cdl.cdl_qgemm_bwd(G, cols, Wi.view(N, K), M, N, K, x.delta, w.delta, dcols, None, wsb)}
     out = {"layer": "B=256, 14x14x256 -> 256, 3x3, stride 1, padding 1 (M=%d, N=%d, K=%d)" % (M, N, K),
            "activation_bytes": int(Xi.numel()), "window_matrix_bytes": int(cols.numel())}
     ops = 2.0 * M * N * K
@@ -531,8 +541,8 @@ def conv_forward(scrub, seed=0, iters=5):
     e1.record()
     torch.cuda.synchronize()
     out["forming_the_window_matrix_us (a strided device copy, not a kernel of this library)"] = e0.elapsed_time(e1) / iters * 1e3
-    out["outputs_equal"] = bool(torch.equal(Y, Y2))
-    del Xi, Wi, Y, Y2, xp, cols, ws
+    out["outputs_equal"] = bool(torch.equal(Y, Y2) and torch.equal(dW, dW2))
+    del Xi, Wi, Y, Y2, xp, cols, ws, G, dW, dW2, dX, dcols, wsb
     torch.cuda.empty_cache()
     return out
 
@@ -792,7 +802,7 @@ def main():
     if not args.no_extra:
         out["small_workloads"] = [small_step(1), small_step(2)]
         out["index_gemms_alone"] = [gemm_only(n_, scrub) for n_ in (2, 3) if n_ != wl.number]
-        out["conv_forward_without_window_matrix"] = conv_forward(scrub)
+        out["conv_layer_without_window_matrix"] = conv_forward(scrub)
         del scrub
         torch.cuda.empty_cache()
         out["extensions_flat_25M"] = extensions_bench()

@@ -305,14 +305,30 @@ int cdl_qconv_fwd(const int8_t *x_idx, const int8_t *w_idx, int32_t B, int32_t H
  * anyway) is gathered straight from the activations.
  *   g DEVICE fp32[B,P,Q,N], x_idx DEVICE int8[B,H,W,C], d_w_hat DEVICE fp32[N,R,S,C]
  * Restrictions as for cdl_qconv_fwd, and B*P*Q <= 11 000 000.  Scratch: cdl_qconv_bwd_weights_workspace_bytes
- * (it holds the transposed window matrix: R*S*C * B*P*Q bytes).  The gradient with respect to the activations of a
- * convolution is not served: form g's window matrix or use cdl_qgemm_bwd on explicit windows.
+ * (it holds the transposed window matrix: R*S*C * B*P*Q bytes).
  */
 size_t cdl_qconv_bwd_weights_workspace_bytes(int32_t B, int32_t H, int32_t W, int32_t C, int32_t N, int32_t R, int32_t S,
                                              int32_t stride, int32_t pad);
 int cdl_qconv_bwd_weights(const float *g, const int8_t *x_idx, int32_t B, int32_t H, int32_t W, int32_t C, int32_t N,
                           int32_t R, int32_t S, int32_t stride, int32_t pad, float delta_x, int32_t x_offset,
                           float *d_w_hat, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * The gradient with respect to the quantized activations of that convolutional layer (Algorithm 1, backward step):
+ *   d_x_hat[b,h,w,c] = delta_w * sum over (p,q,r,s,n) with p*stride + r - pad = h, q*stride + s - pad = w of
+ *                      g[b,p,q,n] * w_idx[n,r,s,c],
+ * an exact real contraction over (r,s,n) rounded once, as cdl_qgemm_bwd's d_a_hat is: the same limb product, whose
+ * fp32 operand is gathered from g tap by tap (a transposed convolution) instead of read row by row.
+ *   g DEVICE fp32[B,P,Q,N], w_idx DEVICE int8[N,R,S,C] (level indices as they are), d_x_hat DEVICE fp32[B,H,W,C]
+ * Restrictions: N a multiple of 128, C a multiple of 4, stride 1 or 2, pad < R and pad < S, R*S*N <= 131071
+ * (CDL_ERR_PARAM / CDL_ERR_RANGE otherwise).  Pointers 16-byte aligned.  Scratch:
+ * cdl_qconv_bwd_activations_workspace_bytes (a rearranged copy of the weights and small tables).
+ */
+size_t cdl_qconv_bwd_activations_workspace_bytes(int32_t B, int32_t H, int32_t W, int32_t C, int32_t N, int32_t R, int32_t S,
+                                                 int32_t stride, int32_t pad);
+int cdl_qconv_bwd_activations(const float *g, const int8_t *w_idx, int32_t B, int32_t H, int32_t W, int32_t C, int32_t N,
+                              int32_t R, int32_t S, int32_t stride, int32_t pad, float delta_w,
+                              float *d_x_hat, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * The backward step of Algorithm 1 for a layer in one call: cdl_qgemm_bwd followed by cdl_quantize_bwd on its

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     cdl_quantize_fwd, cdl_quantize_fwd_static, static_scratch_bytes, cdl_quantize_bwd, cdl_marginal_entropy, cdl_qgemm_fwd, cdl_qgemm_bwd,
     qgemm_fwd_offset_workspace_bytes, cdl_index_offset, cdl_qgemm_fwd_offset, cdl_qgemm_bwd_offset, cdl_qgemm_bwd_quantize_bwd,
     qconv_fwd_workspace_bytes, cdl_qconv_fwd, cdl_qgemm_fwd_quantize, qconv_bwd_weights_workspace_bytes, cdl_qconv_bwd_weights,
+    qconv_bwd_activations_workspace_bytes, cdl_qconv_bwd_activations,
     cdl_quantize_draw, cdl_entropy_bwd, huffman_workspace_bytes, cdl_huffman_bits,
     cdl_profile_enable, cdl_profile_collect, cdl_profile_only, cdl_probe_mfma_int8, EXPORTS,
 )

@@ -19,6 +19,7 @@ EXPORTS = (
     "cdl_qgemm_fwd_offset_workspace_bytes", "cdl_index_offset", "cdl_qgemm_fwd_offset", "cdl_qgemm_bwd_offset",
     "cdl_qgemm_bwd_quantize_bwd", "cdl_qconv_fwd_workspace_bytes", "cdl_qconv_fwd", "cdl_qgemm_fwd_quantize",
     "cdl_qconv_bwd_weights_workspace_bytes", "cdl_qconv_bwd_weights",
+    "cdl_qconv_bwd_activations_workspace_bytes", "cdl_qconv_bwd_activations",
     "cdl_quantize_fwd", "cdl_quantize_fwd_static", "cdl_static_scratch_bytes", "cdl_quantize_bwd", "cdl_marginal_entropy", "cdl_qgemm_fwd", "cdl_qgemm_bwd",
     "cdl_quantize_draw", "cdl_entropy_bwd", "cdl_huffman_workspace_bytes", "cdl_huffman_bits",
     "cdl_profile_enable", "cdl_profile_collect", "cdl_profile_only", "cdl_probe_mfma_int8",
@@ -110,6 +111,10 @@ def load():
         L.cdl_qconv_bwd_weights_workspace_bytes.argtypes = [i32] * 9
         L.cdl_qconv_bwd_weights.restype = ctypes.c_int
         L.cdl_qconv_bwd_weights.argtypes = [vp, vp] + [i32] * 9 + [f32, i32, vp, vp, sz, vp]
+        L.cdl_qconv_bwd_activations_workspace_bytes.restype = ctypes.c_size_t
+        L.cdl_qconv_bwd_activations_workspace_bytes.argtypes = [i32] * 9
+        L.cdl_qconv_bwd_activations.restype = ctypes.c_int
+        L.cdl_qconv_bwd_activations.argtypes = [vp, vp] + [i32] * 9 + [f32, vp, vp, sz, vp]
         L.cdl_qgemm_fwd_quantize.restype = ctypes.c_int
         L.cdl_qgemm_fwd_quantize.argtypes = [vp, qp, vp, i32, i32, i32, f32, vp, vp]
         L.cdl_qconv_fwd_workspace_bytes.restype = ctypes.c_size_t
@@ -293,6 +298,16 @@ def cdl_qconv_bwd_weights(g, x_idx, B, H, W, C, N, R, S, stride, pad, delta_x, d
     wp, wb = _ws(ws)
     _check(load().cdl_qconv_bwd_weights(_ptr(g), _ptr(x_idx), B, H, W, C, N, R, S, stride, pad, delta_x, int(x_offset),
                                         _ptr(d_w_hat), wp, wb, _stream(stream)), "cdl_qconv_bwd_weights")
+
+
+def qconv_bwd_activations_workspace_bytes(B, H, W, C, N, R, S, stride, pad) -> int:
+    return int(load().cdl_qconv_bwd_activations_workspace_bytes(B, H, W, C, N, R, S, stride, pad))
+
+
+def cdl_qconv_bwd_activations(g, w_idx, B, H, W, C, N, R, S, stride, pad, delta_w, d_x_hat, ws, stream=None):
+    wp, wb = _ws(ws)
+    _check(load().cdl_qconv_bwd_activations(_ptr(g), _ptr(w_idx), B, H, W, C, N, R, S, stride, pad, delta_w,
+                                            _ptr(d_x_hat), wp, wb, _stream(stream)), "cdl_qconv_bwd_activations")
 
 
 def cdl_qgemm_fwd_quantize(x, lo_a, n_levels_a, delta_a, alpha_a, b_idx, M, N, K, delta_b, y, stream=None):

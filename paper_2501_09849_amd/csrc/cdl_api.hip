@@ -377,6 +377,44 @@ int cdl_qconv_bwd_weights(const float *g, const int8_t *x_idx, int32_t B, int32_
                             (hipStream_t)hip_stream, nullptr, nullptr, &cw);
 }
 
+namespace {
+// shared checks of the activation gradient of a convolution; M_out = B*P*Q on success
+int conv_dx_geometry(int32_t B, int32_t H, int32_t W, int32_t C, int32_t N, int32_t R, int32_t S, int32_t stride, int32_t pad, int64_t *M_out)
+{
+    if (B <= 0 || H <= 0 || W <= 0 || C <= 0 || N <= 0 || R <= 0 || S <= 0 || pad < 0) return CDL_ERR_PARAM;
+    // a K-tile of the contraction over (tap, output channel) is 128 channels of one tap; strides as the ResNets use them
+    if (N % 128 != 0 || C % 4 != 0 || (stride != 1 && stride != 2) || pad >= R || pad >= S) return CDL_ERR_PARAM;
+    if (H + 2 * pad < R || W + 2 * pad < S) return CDL_ERR_PARAM;
+    const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
+    *M_out = (int64_t)B * P * Q;
+    if ((int64_t)R * S * N > 131071 || *M_out > 2147483647LL / 2 || (int64_t)B * H * W > 2147483647LL / 2) return CDL_ERR_RANGE;
+    return CDL_OK;
+}
+}  // namespace
+
+size_t cdl_qconv_bwd_activations_workspace_bytes(int32_t B, int32_t H, int32_t W, int32_t C, int32_t N, int32_t R, int32_t S,
+                                                 int32_t stride, int32_t pad)
+{
+    int64_t M_out = 0;
+    if (conv_dx_geometry(B, H, W, C, N, R, S, stride, pad, &M_out) != CDL_OK) return 0;
+    return qconv_bwd_activations_workspace_bytes(M_out, N, C, R, S);
+}
+
+int cdl_qconv_bwd_activations(const float *g, const int8_t *w_idx, int32_t B, int32_t H, int32_t W, int32_t C, int32_t N,
+                              int32_t R, int32_t S, int32_t stride, int32_t pad, float delta_w,
+                              float *d_x_hat, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int64_t M_out = 0;
+    int rc = conv_dx_geometry(B, H, W, C, N, R, S, stride, pad, &M_out);
+    if (rc != CDL_OK) return rc;
+    if (!(std::isfinite(delta_w) && delta_w > 0.0f)) return CDL_ERR_PARAM;
+    if (!g || !w_idx || !d_x_hat) return CDL_ERR_NULL;
+    if (!aligned(g, 16) || !aligned(w_idx, 16) || !aligned(d_x_hat, 16)) return CDL_ERR_ALIGN;
+    rc = check_ws(ws, ws_bytes, qconv_bwd_activations_workspace_bytes(M_out, N, C, R, S));
+    if (rc != CDL_OK) return rc;
+    return launch_qconv_bwd_activations(g, w_idx, B, H, W, C, N, R, S, stride, pad, delta_w, d_x_hat, ws, (hipStream_t)hip_stream);
+}
+
 int cdl_qgemm_bwd_quantize_bwd(const float *g, const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
                                const float *theta_a, const cdl_qparams *p_a, float delta_b, int32_t b_offset,
                                float *d_theta_a, float *d_delta_a, float *d_alpha_a, float *d_b_hat,

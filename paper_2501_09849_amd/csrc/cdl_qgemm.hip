@@ -234,6 +234,11 @@ struct LimbArgs {
     QConst fq_k;
     int fq_wsel;              // band_template(fq_k)
     float fq_scale;           // forward product with the quantizer in its prologue: delta_a * delta_b
+    // activation gradient of a convolution (CONVG): the rows of the fp32 operand are gathered.  Output row m is the input
+    // pixel (b, h, w); K-tile kt of the contraction is 128 channels n0.. of tap (r, s), read from G[b, p, q, n0..] with
+    // p = (h + pad - r) / stride, q = (w + pad - s) / stride where those are whole and inside the output image, else 0.
+    const int4 *cg_taps;      // [nk]: {pad - r, pad - s, n0, 0} per K-tile
+    int cg_H, cg_W, cg_P, cg_Q, cg_stride;
     const double *row_corr;   // [rows] or null: added to every entry of an output row (the index operand is stored with an offset:
                               // the missing part of the product is offset * step * sum of g over the contraction); splits == 1 only
 };
@@ -780,7 +785,7 @@ __device__ __forceinline__ void limbs_of4(const float (&g)[4], float gscale, uin
 // lets the scheduler put the VALU and LDS work into the shadow of the MFMAs.
 // TRANS: G is read transposed (rows of the product are columns of G).  VEC: 16-byte loads of G
 // (N % 4 == 0).
-template <int L, int TN, bool TRANS, bool VEC, bool LONG_RUNS, bool FUSED = false, bool QUANT = false>
+template <int L, int TN, bool TRANS, bool VEC, bool LONG_RUNS, bool FUSED = false, bool QUANT = false, bool CONVG = false>
 __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, float gscale, double out_scale)
 {
     constexpr int NB = 4 * TN * 32;
@@ -832,10 +837,34 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
     const int ak = TRANS ? 4 * (tid >> 3) : 4 * (tid & 31);  // first contraction entry inside the K-tile
     // (every address inside a tile is clamped to the matrix)
     // (r, kt): row tile inside the block and K-tile inside the contraction piece, both valid
+    // CONVG (one row tile per block): the input pixel of each of the thread's four rows, as b * P * Q, h, w
+    int cg_base[4] = {0, 0, 0, 0}, cg_h[4] = {0, 0, 0, 0}, cg_w[4] = {0, 0, 0, 0};
+    if (CONVG) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int m = min(tile_r0 * kLRows + ar + 8 * q, a.rows - 1), hw = a.cg_H * a.cg_W;
+            const int b = m / hw, rem = m - b * hw;
+            cg_h[q] = rem / a.cg_W;
+            cg_w[q] = rem - cg_h[q] * a.cg_W;
+            cg_base[q] = b * a.cg_P * a.cg_Q;
+        }
+    }
     auto load_g = [&](float (&g)[16], int r, int kt) {
         const int row0 = (tile_r0 + r) * kLRows;
         const int k0 = (kt0 + kt) * kLBK + ak;
-        if (!TRANS) {
+        if (CONVG) {
+            const int4 tp = a.cg_taps[kt0 + kt];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                int hh = cg_h[q] + tp.x, ww = cg_w[q] + tp.y;
+                bool ok = true;
+                if (a.cg_stride == 2) { ok = ((hh | ww) & 1) == 0; hh >>= 1; ww >>= 1; }
+                ok = ok && (unsigned)hh < (unsigned)a.cg_P && (unsigned)ww < (unsigned)a.cg_Q;
+                const int64_t o = ok ? (int64_t)(cg_base[q] + hh * a.cg_Q + ww) * a.N + (tp.z + ak) : 0;
+                const float4 v = *reinterpret_cast<const float4 *>(a.G + o);
+                g[4 * q] = ok ? v.x : 0.0f; g[4 * q + 1] = ok ? v.y : 0.0f; g[4 * q + 2] = ok ? v.z : 0.0f; g[4 * q + 3] = ok ? v.w : 0.0f;
+            }
+        } else if (!TRANS) {
             // g[4 q + e] = G[row0 + ar + 8 q][k0 + e]
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -1235,6 +1264,54 @@ void limb_gemm_kernel(LimbArgs a)
         case 5: if (vec) limb_gemm_body<5, 3, TRANS, true, false, FUSED>(a, limb_lds, gscale, out_scale); else limb_gemm_body<5, 3, TRANS, false, false, FUSED>(a, limb_lds, gscale, out_scale); break;
         default: if (vec) limb_gemm_body<6, 2, TRANS, true, false, FUSED>(a, limb_lds, gscale, out_scale); else limb_gemm_body<6, 2, TRANS, false, false, FUSED>(a, limb_lds, gscale, out_scale); break;
     }
+}
+
+// dL/dQ(x) of a convolutional layer: the activation-gradient product with the rows of g gathered by taps (CONVG),
+// one row tile of 32 input pixels per block.
+__global__ __launch_bounds__(kLThreads, 1)
+void limb_conv_dx_kernel(LimbArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) int8_t limb_lds[];
+    const int limbs = a.plan->limbs_da;
+    const float gscale = a.plan->gscale_da;
+    const double out_scale = a.plan->out_scale_da;
+    switch (limbs) {
+        case 3: limb_gemm_body<3, 3, false, true, false, false, false, true>(a, limb_lds, gscale, out_scale); break;
+        case 4: limb_gemm_body<4, 3, false, true, false, false, false, true>(a, limb_lds, gscale, out_scale); break;
+        case 5: limb_gemm_body<5, 3, false, true, false, false, false, true>(a, limb_lds, gscale, out_scale); break;
+        default: limb_gemm_body<6, 2, false, true, false, false, false, true>(a, limb_lds, gscale, out_scale); break;
+    }
+}
+
+// For that product: the weights [N][R][S][C] rearranged as its index operand Wr[c][(r, s, n)] (contraction index
+// contiguous, rows ld bytes apart, zero beyond R*S*N), the sum of |w| over the contraction per channel c (the limb
+// rule's column sums) and the tap of every K-tile of 128 output channels.  One wave per input channel.
+__global__ __launch_bounds__(256)
+void conv_dx_prep_kernel(const int8_t *__restrict__ w, int N, int R, int S, int C, int pad, int8_t *__restrict__ wr, int64_t ld,
+                         unsigned int *__restrict__ col_abs, int4 *__restrict__ taps, int nk)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int kc = R * S * N;
+    for (int c = blockIdx.x * 4 + wave; c < C; c += gridDim.x * 4) {
+        unsigned int s_abs = 0u;
+        for (int k = lane; k < (int)ld; k += 64) {
+            int8_t v = 0;
+            if (k < kc) {
+                const int tap = k / N, n = k - tap * N;
+                v = w[((int64_t)n * R * S + tap) * C + c];
+            }
+            wr[(int64_t)c * ld + k] = v;
+            s_abs += (unsigned int)(v < 0 ? -(int)v : (int)v);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) s_abs += (unsigned int)__shfl_down((int)s_abs, o, 64);
+        if (lane == 0) col_abs[c] = s_abs;
+    }
+    if (blockIdx.x == 0)
+        for (int kt = threadIdx.x; kt < nk; kt += 256) {
+            const int k = kt * kLBK, tap = k / N, r = tap / S;
+            taps[kt] = make_int4(pad - r, pad - (tap - r * S), k - tap * N, 0);
+        }
 }
 
 // The forward product with the quantizer of the activations in its prologue: y = delta_a delta_b (Q_idx(X) . Wi^T)
@@ -1918,6 +1995,75 @@ int launch_qgemm_quantize_fwd(const float *x, const cdl_qparams &p, const int8_t
     const hipError_t e = hipFuncSetAttribute((const void *)qgemm_quantize_fwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLimbLdsBytes);
     if (e != hipSuccess) return hip_failed(e);
     CDL_LAUNCH("qgemm_kernel(quantize + fwd)", stream, qgemm_quantize_fwd_kernel, dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
+    return check_launch();
+}
+
+// workspace of the activation gradient of a convolution: [plan][per-block max|g|][col sums][tap table][Wr]
+struct ConvDxLayout {
+    size_t plan, block_max, ss_b, taps, wr, total;
+    int n_max, nk;
+    int64_t ld;
+};
+
+ConvDxLayout conv_dx_layout(int64_t M_out, int32_t N, int32_t C, int32_t R, int32_t S)
+{
+    ConvDxLayout L;
+    const int64_t kc = (int64_t)R * S * N;
+    L.nk = (int)((kc + kLBK - 1) / kLBK);
+    L.ld = (int64_t)(L.nk | 1) * kLBK;
+    L.n_max = (int)blocks_for((M_out * N) >> 2, 2048, 2048);
+    size_t off = 0;
+    L.plan = off;      off += align_up(sizeof(BwdPlan), 256);
+    L.block_max = off; off += align_up((size_t)L.n_max * sizeof(unsigned int), 256);
+    L.ss_b = off;      off += align_up((size_t)C * sizeof(unsigned int), 256);
+    L.taps = off;      off += align_up((size_t)L.nk * sizeof(int4), 256);
+    L.wr = off;        off += align_up((size_t)C * (size_t)L.ld, 256);
+    L.total = off;
+    return L;
+}
+
+size_t qconv_bwd_activations_workspace_bytes(int64_t M_out, int32_t N, int32_t C, int32_t R, int32_t S)
+{
+    return conv_dx_layout(M_out, N, C, R, S).total;
+}
+
+int launch_qconv_bwd_activations(const float *g, const int8_t *w_idx, int32_t B, int32_t H, int32_t W, int32_t C, int32_t N,
+                                 int32_t R, int32_t S, int32_t stride, int32_t pad, float delta_w, float *d_x_hat, void *ws,
+                                 hipStream_t stream)
+{
+    const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
+    const int64_t M_out = (int64_t)B * P * Q;
+    const ConvDxLayout L = conv_dx_layout(M_out, N, C, R, S);
+    char *base = reinterpret_cast<char *>(ws);
+    BwdPlan *plan = reinterpret_cast<BwdPlan *>(base + L.plan);
+    unsigned int *block_max = reinterpret_cast<unsigned int *>(base + L.block_max);
+    unsigned int *ss_b = reinterpret_cast<unsigned int *>(base + L.ss_b);
+    int4 *taps = reinterpret_cast<int4 *>(base + L.taps);
+    int8_t *wr = reinterpret_cast<int8_t *>(base + L.wr);
+    CDL_LAUNCH("absmax_kernel", stream, absmax_kernel, dim3(L.n_max), dim3(256), 0, g, M_out * N, block_max, ss_b, 0);
+    CDL_LAUNCH("conv_dx_prep_kernel", stream, conv_dx_prep_kernel, dim3((unsigned)blocks_for(C, 4, 1024)), dim3(256), 0,
+               w_idx, N, R, S, C, pad, wr, L.ld, ss_b, taps, L.nk);
+    CDL_LAUNCH("plan_kernel", stream, plan_kernel, dim3(1), dim3(1024), 0, plan, block_max, L.n_max,
+               (const unsigned int *)nullptr, 0, ss_b, C, 1.0f, delta_w);
+    int rc = check_launch();
+    if (rc != CDL_OK) return rc;
+    LimbArgs a{};
+    a.G = g; a.M = (int)M_out; a.N = N;
+    a.Bt = wr; a.ldb = L.ld;
+    a.rows = B * H * W; a.cols = C; a.kc = R * S * N;
+    a.nk = L.nk;
+    a.tiles_r = (a.rows + kLRows - 1) / kLRows; a.splits = 1; a.kt_per_split = L.nk;
+    a.units_per_block = 1;
+    a.plan = plan; a.which = 0;
+    a.out = d_x_hat;
+    a.cg_taps = taps; a.cg_H = H; a.cg_W = W; a.cg_P = P; a.cg_Q = Q; a.cg_stride = stride;
+    const int64_t items = (int64_t)a.tiles_r * ((a.cols + limb_cols(6) - 1) / limb_cols(6));
+    if (items > 2147483640LL) return CDL_ERR_PARAM;
+    if ((int64_t)limb_cols(3) * a.ldb > 0xffffffffLL) return CDL_ERR_RANGE;
+    const unsigned grid = (unsigned)((items + 7) / 8 * 8);
+    const hipError_t e = hipFuncSetAttribute((const void *)limb_conv_dx_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLimbLdsBytes);
+    if (e != hipSuccess) return hip_failed(e);
+    CDL_LAUNCH("limb_gemm_kernel(conv d_x_hat)", stream, limb_conv_dx_kernel, dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
     return check_launch();
 }
 

@@ -176,3 +176,47 @@ def test_convolution_weight_gradient(oracle, B, H, W, C, N, R, S, stride, pad, x
                              None, dWh, ws2)
     torch.cuda.synchronize()
     assert torch.equal(dW.reshape(N, K), dWh)
+
+
+# (B, H, W, C, N, R, S, stride, pad): the activation gradient (a transposed convolution inside the limb product) - both
+# strides on even and odd image sizes, kernels that are not square, no padding, more input channels than one column
+# tile of 384, several K-tiles per tap (N = 256), input pixels that no output pixel reaches (stride 2 without padding)
+XGRAD = [(2, 7, 9, 16, 128, 3, 3, 1, 1), (1, 8, 8, 20, 128, 3, 3, 2, 1), (3, 6, 5, 48, 256, 1, 1, 1, 0), (1, 9, 7, 16, 128, 5, 3, 1, 2),
+         (4, 14, 14, 64, 128, 3, 3, 1, 1), (2, 15, 15, 32, 128, 3, 3, 2, 1), (1, 10, 11, 64, 256, 3, 5, 2, 0), (3, 14, 14, 400, 128, 3, 3, 1, 1),
+         (2, 8, 8, 16, 128, 1, 1, 2, 0)]
+
+
+@pytest.mark.parametrize("B,H,W,C,N,R,S,stride,pad", XGRAD)
+@pytest.mark.parametrize("g_scale", [1.0, 3.0e-4])
+def test_convolution_activation_gradient(oracle, B, H, W, C, N, R, S, stride, pad, g_scale):
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    rng = np.random.default_rng(B + H * W + C + N)
+    w = cdl_inputs.draw_indices((N, R, S, C), -127, 127, seed=N + C)
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    g = (rng.standard_normal((B, P, Q, N)) * g_scale).astype(np.float32)
+    dw = float(np.float32(0.011))
+    dX = gu.empty((B, H, W, C), torch.float32)
+    dX.fill_(float("nan"))
+    ws = gu.workspace(cdl.qconv_bwd_activations_workspace_bytes(B, H, W, C, N, R, S, stride, pad))
+    cdl.cdl_qconv_bwd_activations(gu.dev(g), gu.dev(w), B, H, W, C, N, R, S, stride, pad, dw, dX, ws)
+    torch.cuda.synchronize()
+    ref, _ = oracle.qconv_bwd(g, np.zeros((B, H, W, C), dtype=np.int16), w, stride, pad, 1.0, dw, want_dw=False)
+    gu.assert_close(dX.cpu().numpy(), ref, "d_x_hat")
+
+
+def test_convolution_gradients_reject_what_they_do_not_serve():
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    t = gu.empty((1 << 16,), torch.float32)
+    t8 = gu.empty((1 << 16,), torch.int8)
+    ws = gu.workspace(1 << 20)
+    # output channels not whole K-tiles; stride 3; padding as wide as the kernel; contraction beyond the int32 accumulators
+    for (B, H, W, C, N, R, S, stride, pad), status in (((1, 8, 8, 16, 64, 3, 3, 1, 1), -2), ((1, 8, 8, 16, 128, 3, 3, 3, 1), -2),
+                                                       ((1, 8, 8, 16, 128, 3, 3, 1, 3), -2), ((1, 8, 8, 16, 16384, 3, 3, 1, 1), -3)):
+        with pytest.raises(cdl.CdlError) as e:
+            cdl.cdl_qconv_bwd_activations(t, t8, B, H, W, C, N, R, S, stride, pad, 0.1, t, ws)
+        assert e.value.status == status, (B, H, W, C, N, R, S, stride, pad)
+    with pytest.raises(cdl.CdlError) as e:
+        cdl.cdl_qconv_bwd_weights(t, t8, 1, 8, 8, 3, 4, 3, 3, 1, 1, 0.1, t, ws)      # C not a multiple of 16
+    assert e.value.status == -2
