@@ -831,10 +831,14 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
     // one column of a 4 x 4 patch of G^T), laid out so that one load instruction of a wave covers whole
     // 128-byte lines of G:
     // !TRANS: group q is row 8 q + tid / 32, entries 4 (tid % 32) .. +3
-    //  TRANS: the patch is rows 4 (tid % 8) .. +3 by entries 4 (tid / 8) .. +3; group q is its row q
+    //  TRANS: the patch is rows 4 t .. +3 by entries 4 j .. +3 with t = 0..7 and j = 0..7 inside the wave, j + 8 * wave in the
+    //         block; group q is its row q.  t takes tid bits 0, 1 and 5, j bits 2..4: a half-wave then holds four values of
+    //         t (four different swizzles) and all eight j (two chunks x four words), i.e. 32 different LDS banks when the
+    //         digits are stored (with t in bits 0..2 rows t and t + 4 met in every bank: 19 % conflict cycles, measured).
     float gbuf[2][16];
-    const int ar = TRANS ? 4 * (tid & 7) : (tid >> 5);       // row of group 0
-    const int ak = TRANS ? 4 * (tid >> 3) : 4 * (tid & 31);  // first contraction entry inside the K-tile
+    const int tr_t = (tid & 3) | ((tid >> 3) & 4), tr_j = ((tid >> 2) & 7) + 8 * (tid >> 6);
+    const int ar = TRANS ? 4 * tr_t : (tid >> 5);            // row of group 0
+    const int ak = TRANS ? 4 * tr_j : 4 * (tid & 31);        // first contraction entry inside the K-tile
     // (every address inside a tile is clamped to the matrix)
     // (r, kt): row tile inside the block and K-tile inside the contraction piece, both valid
     // CONVG (one row tile per block): the input pixel of each of the thread's four rows, as b * P * Q, h, w
