@@ -119,7 +119,8 @@ int cdl_quantize_fwd(const float *theta, int64_t n, const cdl_qparams *p,
  * Without marg and entropy_bits no scratch is used and any n is accepted.
  * All calls on one GPU share that GPU's buffer, which keeps the last call's contents (every call overwrites
  * what it reads): two calls that overlap in time on one GPU - different streams, different host threads -
- * race.  Calls ordered on one stream are safe.
+ * race.  Calls ordered on one stream are safe.  The first call on a GPU that asks for marg or entropy_bits looks
+ * the buffer's address up (hipGetSymbolAddress, once per GPU): make that call before a capture begins.
  */
 size_t cdl_static_scratch_bytes(void);
 int cdl_quantize_fwd_static(const float *theta, int64_t n, const cdl_qparams *p,
@@ -289,7 +290,9 @@ int cdl_qgemm_fwd_quantize(const float *x, const cdl_qparams *p_a, const int8_t 
  * activations are read where they lie, each about R*S/stride^2 times from cache instead of once from a matrix
  * R*S/stride^2 times their size.  Restrictions: C a multiple of 16, pad < R and pad < S, R*S*C <= 32768
  * (CDL_ERR_PARAM / CDL_ERR_RANGE otherwise: form the matrix and call cdl_qgemm_fwd there).  Both pointers 16-byte
- * aligned.  Scratch: cdl_qconv_fwd_workspace_bytes(N, x_offset), which is 0 when x_offset is 0.
+ * aligned.  Scratch: cdl_qconv_fwd_workspace_bytes(N, x_offset), which is 0 when x_offset is 0 (the padding then
+ * comes from a page of zeros inside the library's device code; the first such call on a GPU looks its address up
+ * with hipGetSymbolAddress, so make one call on each GPU before capturing this entry point into a HIP graph).
  */
 size_t cdl_qconv_fwd_workspace_bytes(int32_t N, int32_t x_offset);
 int cdl_qconv_fwd(const int8_t *x_idx, const int8_t *w_idx, int32_t B, int32_t H, int32_t W, int32_t C, int32_t N,
