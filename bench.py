@@ -807,6 +807,11 @@ def main():
         torch.cuda.empty_cache()
         out["extensions_flat_25M"] = extensions_bench()
         out["machine"] = machine_probes()
+        # the quantizer's traffic against what a plain device copy moves on this machine (half reads, half writes, as the
+        # quantizer's own mix nearly is): the practical ceiling of an HBM-bound kernel here, next to the nameplate one
+        copy = out["machine"].get("copy_1GiB_GBps_read_plus_write")
+        if copy:
+            out["value_frac_of_measured_copy_rate"] = qo["kappa_4"]["cold"]["algorithmic_GBps"] / copy
     print(json.dumps(out), flush=True)
 
 
