@@ -9,6 +9,12 @@
  *   backward over indices   cdl_qgemm_bwd(G, Xi, Wi)       -> dL/dQ(X), dL/dQ(W)
  *   quantizer backward      cdl_quantize_bwd(X, dL/dQ(X))  -> dL/dX, dL/d(step), dL/d(sharpness); same for W
  *
+ * Other forms of the same steps: cdl_qgemm_fwd_offset / cdl_qgemm_bwd_offset (operands of the unsigned 8-bit
+ * alphabet), cdl_qgemm_bwd_quantize_bwd (the last two steps in one call), cdl_qgemm_fwd_quantize (the second and
+ * third), cdl_qconv_fwd / cdl_qconv_bwd_weights / cdl_qconv_bwd_activations (a convolutional layer on [B,H,W,C]
+ * activations), cdl_quantize_fwd_static (no workspace); next to the path: cdl_marginal_entropy, cdl_entropy_bwd,
+ * cdl_quantize_draw, cdl_huffman_bits.
+ *
  * Conventions for every entry point
  *   - All tensor and scalar-output pointers are DEVICE pointers owned by the caller; tensors are
  *     contiguous, row-major.  fp32 tensors must be 16-byte aligned, int8 index tensors 4-byte
