@@ -252,6 +252,27 @@ def timed_calls(calls, iters, scrub=None):
     return out
 
 
+def bracketed_calls(calls, iters, scrub=None):
+    """Stream time of every call of `calls` between one pair of HIP events on the launch stream (the kernels of the
+    call and the gaps between them, no per-kernel events); `scrub`, if given, runs before the first event."""
+    import torch
+    out = {k: [] for k in calls}
+    for k, f in calls.items():
+        for _ in range(2):
+            f()
+        torch.cuda.synchronize()
+        for _ in range(iters):
+            if scrub is not None:
+                scrub()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            f()
+            e1.record()
+            torch.cuda.synchronize()
+            out[k].append(e0.elapsed_time(e1) * 1e3)
+    return out
+
+
 def med_min(v):
     return {"median_us": float(np.median(v)), "min_us": float(np.min(v))}
 
@@ -272,12 +293,16 @@ def quantizer_only(scrub, seed=0, iters=10):
             "fwd": lambda: cdl.cdl_quantize_fwd(st.W, n, *a, st.Wi, st.Wsoft, st.margW, st.scal[0:1], st.ws),
             "bwd": lambda: cdl.cdl_quantize_bwd(st.W, st.G, n, *a, st.dW, st.scal[2:3], st.scal[3:4], st.ws),
         }
+        calls["fwd_then_bwd"] = lambda: (calls["fwd"](), calls["bwd"]())
         row = {"kappa": spec.alpha * spec.delta ** 2}
         for state, sc in (("cold", scrub), ("warm", None)):
-            t = timed_calls(calls, iters, sc)
-            tot = np.asarray(t["fwd"]) + np.asarray(t["bwd"])
-            med = float(np.median(tot))
-            row[state] = {"fwd": med_min(t["fwd"]), "bwd": med_min(t["bwd"]), "fwd_plus_bwd": med_min(tot),
+            # the figure of merit: the two calls one after the other between one pair of events (their four kernels and
+            # the gaps between them); beside it each call alone, and the sums of the kernel times from per-kernel events
+            b = bracketed_calls(calls, iters, sc)
+            t = timed_calls({"fwd": calls["fwd"], "bwd": calls["bwd"]}, iters, sc)
+            med = float(np.median(b["fwd_then_bwd"]))
+            row[state] = {"fwd_plus_bwd": med_min(b["fwd_then_bwd"]), "fwd": med_min(b["fwd"]), "bwd": med_min(b["bwd"]),
+                          "sum_of_kernel_times": {"fwd": med_min(t["fwd"]), "bwd": med_min(t["bwd"])},
                           "gelem_per_s": n / med / 1e3, "algorithmic_GBps": 21.0 * n / med / 1e3,
                           "hbm_frac": 21.0 * n / med / 1e3 / HBM_PEAK_GBS}
         out[tag] = row
@@ -802,7 +827,8 @@ def main():
     out["quantizer_only_flat_25M"] = qo
     out["value"] = qo["kappa_4"]["cold"]["gelem_per_s"]
     out["value_is"] = ("quantizer forward (index, soft value, marginal PMF, entropy) + backward (dtheta, d step, d sharpness) on "
-                       "workload 4 (25.6 M entries, 31 levels, kappa 4), cache cold, median of 10; hbm_frac beside it")
+                       "workload 4 (25.6 M entries, 31 levels, kappa 4), cache cold (1 GiB written before), the two calls between one pair of "
+                       "HIP events on the launch stream, median of 10; hbm_frac beside it")
     out["value_hbm_frac"] = qo["kappa_4"]["cold"]["hbm_frac"]
     out["targets"] = {
         "quantizer_fwd_bwd_hbm_frac": {"target": 0.70, "achieved_cold": qo["kappa_4"]["cold"]["hbm_frac"],
