@@ -329,7 +329,7 @@ int cdl_qconv_bwd_weights(const float *g, const int8_t *x_idx, int32_t B, int32_
  * an exact real contraction over (r,s,n) rounded once, as cdl_qgemm_bwd's d_a_hat is: the same limb product, whose
  * fp32 operand is gathered from g tap by tap (a transposed convolution) instead of read row by row.
  *   g DEVICE fp32[B,P,Q,N], w_idx DEVICE int8[N,R,S,C] (level indices as they are), d_x_hat DEVICE fp32[B,H,W,C]
- * Restrictions: N a multiple of 128, C a multiple of 4, stride 1 or 2, pad < R and pad < S, R*S*N <= 131071
+ * Restrictions: N and C multiples of 4, stride 1 or 2, pad < R and pad < S, R*S*N <= 131071
  * (CDL_ERR_PARAM / CDL_ERR_RANGE otherwise).  Pointers 16-byte aligned.  Scratch:
  * cdl_qconv_bwd_activations_workspace_bytes (a rearranged copy of the weights and small tables).
  */

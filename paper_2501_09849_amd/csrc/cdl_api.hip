@@ -382,8 +382,8 @@ namespace {
 int conv_dx_geometry(int32_t B, int32_t H, int32_t W, int32_t C, int32_t N, int32_t R, int32_t S, int32_t stride, int32_t pad, int64_t *M_out)
 {
     if (B <= 0 || H <= 0 || W <= 0 || C <= 0 || N <= 0 || R <= 0 || S <= 0 || pad < 0) return CDL_ERR_PARAM;
-    // a K-tile of the contraction over (tap, output channel) is 128 channels of one tap; strides as the ResNets use them
-    if (N % 128 != 0 || C % 4 != 0 || (stride != 1 && stride != 2) || pad >= R || pad >= S) return CDL_ERR_PARAM;
+    // four consecutive entries of the contraction over (tap, output channel) share a tap; strides as the ResNets use them
+    if (N % 4 != 0 || C % 4 != 0 || (stride != 1 && stride != 2) || pad >= R || pad >= S) return CDL_ERR_PARAM;
     if (H + 2 * pad < R || W + 2 * pad < S) return CDL_ERR_PARAM;
     const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
     *M_out = (int64_t)B * P * Q;

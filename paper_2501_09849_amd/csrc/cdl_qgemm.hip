@@ -235,10 +235,11 @@ struct LimbArgs {
     int fq_wsel;              // band_template(fq_k)
     float fq_scale;           // forward product with the quantizer in its prologue: delta_a * delta_b
     // activation gradient of a convolution (CONVG): the rows of the fp32 operand are gathered.  Output row m is the input
-    // pixel (b, h, w); K-tile kt of the contraction is 128 channels n0.. of tap (r, s), read from G[b, p, q, n0..] with
+    // pixel (b, h, w); contraction entry k = (tap (r, s), output channel n) is read from G[b, p, q, n] with
     // p = (h + pad - r) / stride, q = (w + pad - s) / stride where those are whole and inside the output image, else 0.
-    const int4 *cg_taps;      // [nk]: {pad - r, pad - s, n0, 0} per K-tile
-    int cg_H, cg_W, cg_P, cg_Q, cg_stride;
+    // A thread's four consecutive entries share a tap (N % 4 == 0).
+    int cg_H, cg_W, cg_P, cg_Q, cg_stride, cg_S, cg_pad;
+    float cg_inv_n, cg_inv_s;     // 1 / N, 1 / S
     const double *row_corr;   // [rows] or null: added to every entry of an output row (the index operand is stored with an offset:
                               // the missing part of the product is offset * step * sum of g over the contraction); splits == 1 only
 };
@@ -857,14 +858,18 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
         const int row0 = (tile_r0 + r) * kLRows;
         const int k0 = (kt0 + kt) * kLBK + ak;
         if (CONVG) {
-            const int4 tp = a.cg_taps[kt0 + kt];
+            // tap and channel of this thread's entries: k0 = tap * N + n0 (k0 < 2^17, so (k0 + 1/2) / N in fp32 is far
+            // from a whole number on either side and truncates to the quotient; likewise tap / S)
+            const int tap = (int)(((float)k0 + 0.5f) * a.cg_inv_n), n0 = k0 - tap * a.N;
+            const int tr = (int)(((float)tap + 0.5f) * a.cg_inv_s), ts = tap - tr * a.cg_S;
+            const int dh = a.cg_pad - tr, dw = a.cg_pad - ts;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                int hh = cg_h[q] + tp.x, ww = cg_w[q] + tp.y;
+                int hh = cg_h[q] + dh, ww = cg_w[q] + dw;
                 bool ok = true;
                 if (a.cg_stride == 2) { ok = ((hh | ww) & 1) == 0; hh >>= 1; ww >>= 1; }
                 ok = ok && (unsigned)hh < (unsigned)a.cg_P && (unsigned)ww < (unsigned)a.cg_Q;
-                const int64_t o = ok ? (int64_t)(cg_base[q] + hh * a.cg_Q + ww) * a.N + (tp.z + ak) : 0;
+                const int64_t o = ok ? (int64_t)(cg_base[q] + hh * a.cg_Q + ww) * a.N + n0 : 0;
                 const float4 v = *reinterpret_cast<const float4 *>(a.G + o);
                 g[4 * q] = ok ? v.x : 0.0f; g[4 * q + 1] = ok ? v.y : 0.0f; g[4 * q + 2] = ok ? v.z : 0.0f; g[4 * q + 3] = ok ? v.w : 0.0f;
             }
@@ -1288,11 +1293,11 @@ void limb_conv_dx_kernel(LimbArgs a)
 }
 
 // For that product: the weights [N][R][S][C] rearranged as its index operand Wr[c][(r, s, n)] (contraction index
-// contiguous, rows ld bytes apart, zero beyond R*S*N), the sum of |w| over the contraction per channel c (the limb
-// rule's column sums) and the tap of every K-tile of 128 output channels.  One wave per input channel.
+// contiguous, rows ld bytes apart, zero beyond R*S*N) and the sum of |w| over the contraction per channel c (the limb
+// rule's column sums).  One wave per input channel.
 __global__ __launch_bounds__(256)
-void conv_dx_prep_kernel(const int8_t *__restrict__ w, int N, int R, int S, int C, int pad, int8_t *__restrict__ wr, int64_t ld,
-                         unsigned int *__restrict__ col_abs, int4 *__restrict__ taps, int nk)
+void conv_dx_prep_kernel(const int8_t *__restrict__ w, int N, int R, int S, int C, int8_t *__restrict__ wr, int64_t ld,
+                         unsigned int *__restrict__ col_abs)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int kc = R * S * N;
@@ -1311,11 +1316,6 @@ void conv_dx_prep_kernel(const int8_t *__restrict__ w, int N, int R, int S, int 
         for (int o = 32; o > 0; o >>= 1) s_abs += (unsigned int)__shfl_down((int)s_abs, o, 64);
         if (lane == 0) col_abs[c] = s_abs;
     }
-    if (blockIdx.x == 0)
-        for (int kt = threadIdx.x; kt < nk; kt += 256) {
-            const int k = kt * kLBK, tap = k / N, r = tap / S;
-            taps[kt] = make_int4(pad - r, pad - (tap - r * S), k - tap * N, 0);
-        }
 }
 
 // The forward product with the quantizer of the activations in its prologue: y = delta_a delta_b (Q_idx(X) . Wi^T)
@@ -2002,9 +2002,9 @@ int launch_qgemm_quantize_fwd(const float *x, const cdl_qparams &p, const int8_t
     return check_launch();
 }
 
-// workspace of the activation gradient of a convolution: [plan][per-block max|g|][col sums][tap table][Wr]
+// workspace of the activation gradient of a convolution: [plan][per-block max|g|][col sums][Wr]
 struct ConvDxLayout {
-    size_t plan, block_max, ss_b, taps, wr, total;
+    size_t plan, block_max, ss_b, wr, total;
     int n_max, nk;
     int64_t ld;
 };
@@ -2020,7 +2020,6 @@ ConvDxLayout conv_dx_layout(int64_t M_out, int32_t N, int32_t C, int32_t R, int3
     L.plan = off;      off += align_up(sizeof(BwdPlan), 256);
     L.block_max = off; off += align_up((size_t)L.n_max * sizeof(unsigned int), 256);
     L.ss_b = off;      off += align_up((size_t)C * sizeof(unsigned int), 256);
-    L.taps = off;      off += align_up((size_t)L.nk * sizeof(int4), 256);
     L.wr = off;        off += align_up((size_t)C * (size_t)L.ld, 256);
     L.total = off;
     return L;
@@ -2042,11 +2041,10 @@ int launch_qconv_bwd_activations(const float *g, const int8_t *w_idx, int32_t B,
     BwdPlan *plan = reinterpret_cast<BwdPlan *>(base + L.plan);
     unsigned int *block_max = reinterpret_cast<unsigned int *>(base + L.block_max);
     unsigned int *ss_b = reinterpret_cast<unsigned int *>(base + L.ss_b);
-    int4 *taps = reinterpret_cast<int4 *>(base + L.taps);
     int8_t *wr = reinterpret_cast<int8_t *>(base + L.wr);
     CDL_LAUNCH("absmax_kernel", stream, absmax_kernel, dim3(L.n_max), dim3(256), 0, g, M_out * N, block_max, ss_b, 0);
     CDL_LAUNCH("conv_dx_prep_kernel", stream, conv_dx_prep_kernel, dim3((unsigned)blocks_for(C, 4, 1024)), dim3(256), 0,
-               w_idx, N, R, S, C, pad, wr, L.ld, ss_b, taps, L.nk);
+               w_idx, N, R, S, C, wr, L.ld, ss_b);
     CDL_LAUNCH("plan_kernel", stream, plan_kernel, dim3(1), dim3(1024), 0, plan, block_max, L.n_max,
                (const unsigned int *)nullptr, 0, ss_b, C, 1.0f, delta_w);
     int rc = check_launch();
@@ -2060,7 +2058,8 @@ int launch_qconv_bwd_activations(const float *g, const int8_t *w_idx, int32_t B,
     a.units_per_block = 1;
     a.plan = plan; a.which = 0;
     a.out = d_x_hat;
-    a.cg_taps = taps; a.cg_H = H; a.cg_W = W; a.cg_P = P; a.cg_Q = Q; a.cg_stride = stride;
+    a.cg_H = H; a.cg_W = W; a.cg_P = P; a.cg_Q = Q; a.cg_stride = stride; a.cg_S = S; a.cg_pad = pad;
+    a.cg_inv_n = 1.0f / (float)N; a.cg_inv_s = 1.0f / (float)S;
     const int64_t items = (int64_t)a.tiles_r * ((a.cols + limb_cols(6) - 1) / limb_cols(6));
     if (items > 2147483640LL) return CDL_ERR_PARAM;
     if ((int64_t)limb_cols(3) * a.ldb > 0xffffffffLL) return CDL_ERR_RANGE;

@@ -183,7 +183,10 @@ def test_convolution_weight_gradient(oracle, B, H, W, C, N, R, S, stride, pad, x
 # tile of 384, several K-tiles per tap (N = 256), input pixels that no output pixel reaches (stride 2 without padding)
 XGRAD = [(2, 7, 9, 16, 128, 3, 3, 1, 1), (1, 8, 8, 20, 128, 3, 3, 2, 1), (3, 6, 5, 48, 256, 1, 1, 1, 0), (1, 9, 7, 16, 128, 5, 3, 1, 2),
          (4, 14, 14, 64, 128, 3, 3, 1, 1), (2, 15, 15, 32, 128, 3, 3, 2, 1), (1, 10, 11, 64, 256, 3, 5, 2, 0), (3, 14, 14, 400, 128, 3, 3, 1, 1),
-         (2, 8, 8, 16, 128, 1, 1, 2, 0)]
+         (2, 8, 8, 16, 128, 1, 1, 2, 0),
+         # output channels that are not whole K-tiles of 128: K-tiles then run across taps (the first stages of a ResNet)
+         (4, 16, 16, 16, 16, 3, 3, 1, 1), (2, 16, 16, 32, 64, 3, 3, 2, 1), (3, 9, 9, 16, 48, 3, 3, 1, 1), (1, 7, 7, 8, 20, 5, 5, 1, 2),
+         (2, 12, 12, 64, 32, 1, 1, 1, 0)]
 
 
 @pytest.mark.parametrize("B,H,W,C,N,R,S,stride,pad", XGRAD)
@@ -211,8 +214,8 @@ def test_convolution_gradients_reject_what_they_do_not_serve():
     t = gu.empty((1 << 16,), torch.float32)
     t8 = gu.empty((1 << 16,), torch.int8)
     ws = gu.workspace(1 << 20)
-    # output channels not whole K-tiles; stride 3; padding as wide as the kernel; contraction beyond the int32 accumulators
-    for (B, H, W, C, N, R, S, stride, pad), status in (((1, 8, 8, 16, 64, 3, 3, 1, 1), -2), ((1, 8, 8, 16, 128, 3, 3, 3, 1), -2),
+    # output channels not a multiple of four; stride 3; padding as wide as the kernel; contraction beyond the int32 accumulators
+    for (B, H, W, C, N, R, S, stride, pad), status in (((1, 8, 8, 16, 6, 3, 3, 1, 1), -2), ((1, 8, 8, 16, 128, 3, 3, 3, 1), -2),
                                                        ((1, 8, 8, 16, 128, 3, 3, 1, 3), -2), ((1, 8, 8, 16, 16384, 3, 3, 1, 1), -3)):
         with pytest.raises(cdl.CdlError) as e:
             cdl.cdl_qconv_bwd_activations(t, t8, B, H, W, C, N, R, S, stride, pad, 0.1, t, ws)
