@@ -223,3 +223,51 @@ def test_convolution_gradients_reject_what_they_do_not_serve():
     with pytest.raises(cdl.CdlError) as e:
         cdl.cdl_qconv_bwd_weights(t, t8, 1, 8, 8, 3, 4, 3, 3, 1, 1, 0.1, t, ws)      # C not a multiple of 16
     assert e.value.status == -2
+
+
+def test_the_convolution_that_workload_3_stands_for(oracle):
+    """ResNet-18 layer 3 at full size (256 images of 14 x 14 x 256, 256 kernels of 3 x 3, padding 1; M = 50176, K = 2304):
+    forward accumulators and weight gradient everywhere against the products on the window matrix (bit for bit), all three
+    outputs against the oracle on the first and the last image (the weight gradient on a batch of those two)."""
+    import paper_2501_09849_amd as cdl
+    torch = gu.torch_mod()
+    wl = cdl_inputs.workload(3)
+    B, H, W, C, N, R, S, stride, pad = 256, 14, 14, 256, 256, 3, 3, 1, 1
+    x_s, w_s = wl.x_spec, wl.w_spec
+    x = cdl_inputs.draw_indices((B, H, W, C), x_s.lo, x_s.hi, seed=31)
+    w = cdl_inputs.draw_indices((N, R, S, C), w_s.lo, w_s.hi, seed=32)
+    g = cdl_inputs.draw_g(wl, 0).reshape(B, H, W, N)
+    acc, y = _run(cdl, torch, x, w, stride, pad, x_s.delta, w_s.delta)
+    x_d, w_d, g_d = gu.dev(x), gu.dev(w), gu.dev(g)
+    dW, dX = gu.empty((N, R, S, C), torch.float32), gu.empty((B, H, W, C), torch.float32)
+    ws = gu.workspace(max(cdl.qconv_bwd_weights_workspace_bytes(B, H, W, C, N, R, S, stride, pad),
+                          cdl.qconv_bwd_activations_workspace_bytes(B, H, W, C, N, R, S, stride, pad)))
+    cdl.cdl_qconv_bwd_weights(g_d, x_d, B, H, W, C, N, R, S, stride, pad, x_s.delta, dW, ws)
+    cdl.cdl_qconv_bwd_activations(g_d, w_d, B, H, W, C, N, R, S, stride, pad, w_s.delta, dX, ws)
+    torch.cuda.synchronize()
+    dX_h = dX.cpu().numpy()
+    for b in (0, B - 1):
+        ref_acc, ref_y = oracle.qconv_fwd(x[b:b + 1], w, stride, pad, x_s.delta, w_s.delta)
+        assert np.array_equal(acc[b:b + 1], ref_acc)
+        gu.assert_close(y[b:b + 1], ref_y, "y of image %d" % b)
+        ref_dx, _ = oracle.qconv_bwd(g[b:b + 1], x[b:b + 1], w, stride, pad, x_s.delta, w_s.delta, want_dw=False)
+        gu.assert_close(dX_h[b:b + 1], ref_dx, "d_x_hat of image %d" % b)
+    # the products on the window matrix: every accumulator and every entry of the weight gradient
+    cols, _, _ = _windows(x, R, S, stride, pad)
+    M, K = cols.shape
+    assert (M, N, K) == (wl.M, wl.N, wl.K)
+    cols_d = gu.dev(cols)
+    acc2, dWh = gu.empty((M, N), torch.int32), gu.empty((N, K), torch.float32)
+    ws2 = gu.workspace(max(cdl.qgemm_fwd_workspace_bytes(M, N, K), cdl.qgemm_bwd_workspace_bytes(M, N, K)))
+    cdl.cdl_qgemm_fwd(cols_d, gu.dev(w.reshape(N, K)), M, N, K, x_s.delta, w_s.delta, acc2, None, ws2)
+    cdl.cdl_qgemm_bwd(g_d, cols_d, gu.dev(w.reshape(N, K)), M, N, K, x_s.delta, w_s.delta, None, dWh, ws2)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.reshape(M, N), acc2.cpu().numpy())
+    assert torch.equal(dW.reshape(N, K), dWh)
+    # the weight gradient against the oracle: linear in the batch, so a batch of two images checks the arithmetic of a slice
+    sel = [0, B - 1]
+    dW2 = gu.empty((N, R, S, C), torch.float32)
+    cdl.cdl_qconv_bwd_weights(gu.dev(g[sel]), gu.dev(x[sel]), 2, H, W, C, N, R, S, stride, pad, x_s.delta, dW2, ws)
+    torch.cuda.synchronize()
+    _, ref_dw = oracle.qconv_bwd(g[sel], x[sel], w, stride, pad, x_s.delta, w_s.delta, want_dx=False)
+    gu.assert_close(dW2.cpu().numpy(), ref_dw, "d_w_hat of two images")
