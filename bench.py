@@ -606,6 +606,69 @@ def small_step(number, steps=20, warmup=3):
     return out
 
 
+def conv_layer_step(steps=10, warmup=3):
+    """The layer that workload 3 stands for as what it is - a convolution on [B,H,W,C] activations (ResNet-18 layer 3: 256
+    images of 14 x 14 x 256, 256 kernels of 3 x 3, padding 1) - against the same layer as an index product on its matrix
+    of input windows (workload 3 as the list gives it: the quantizer then runs on the 9 times larger window matrix).
+    Conv form: quantize W and X (indices, soft values, marginal PMF, entropy), cdl_qconv_fwd, cdl_qconv_bwd_weights,
+    cdl_qconv_bwd_activations, quantizer backward for X and W."""
+    import torch
+    import paper_2501_09849_amd as cdl
+    wl = cdl_inputs.workload(3)
+    w, x = wl.w_spec, wl.x_spec
+    wa, xa = (w.lo, w.n_levels, w.delta, w.alpha), (x.lo, x.n_levels, x.delta, x.alpha)
+    B, H, W, C, N, R, S, stride, pad = 256, 14, 14, 256, 256, 3, 3, 1, 1
+    dev = "cuda:0"
+    f32, i8 = torch.float32, torch.int8
+    nX, nW = B * H * W * C, N * R * S * C
+    X = torch.from_numpy(cdl_inputs.draw_x(wl).reshape(-1)[:nX].copy()).to(dev)     # same distribution, the un-expanded tensor
+    Wt = torch.from_numpy(cdl_inputs.draw_w(wl).reshape(-1)).to(dev)
+    G = torch.from_numpy(cdl_inputs.draw_g(wl)).to(dev)                              # [B*H*W, N]
+    Xi, Wi = torch.empty(nX, dtype=i8, device=dev), torch.empty(nW, dtype=i8, device=dev)
+    Xs, Ws = torch.empty(nX, dtype=f32, device=dev), torch.empty(nW, dtype=f32, device=dev)
+    mX, mW = torch.empty(x.n_levels, dtype=f32, device=dev), torch.empty(w.n_levels, dtype=f32, device=dev)
+    sc = torch.zeros(8, dtype=f32, device=dev)
+    Y = torch.empty((B * H * W, N), dtype=f32, device=dev)
+    dXh, dWh = torch.empty(nX, dtype=f32, device=dev), torch.empty(nW, dtype=f32, device=dev)
+    dX, dW = torch.empty(nX, dtype=f32, device=dev), torch.empty(nW, dtype=f32, device=dev)
+    ws = torch.empty(max(256, cdl.quantize_workspace_bytes(nX, x.n_levels), cdl.quantize_workspace_bytes(nW, w.n_levels),
+                         cdl.qconv_bwd_weights_workspace_bytes(B, H, W, C, N, R, S, stride, pad),
+                         cdl.qconv_bwd_activations_workspace_bytes(B, H, W, C, N, R, S, stride, pad)), dtype=torch.uint8, device=dev)
+
+    def run():
+        cdl.cdl_quantize_fwd(Wt, nW, *wa, Wi, Ws, mW, sc[0:1], ws)
+        cdl.cdl_quantize_fwd(X, nX, *xa, Xi, Xs, mX, sc[1:2], ws)
+        cdl.cdl_qconv_fwd(Xi, Wi, B, H, W, C, N, R, S, stride, pad, x.delta, w.delta, None, Y, None)
+        cdl.cdl_qconv_bwd_weights(G, Xi, B, H, W, C, N, R, S, stride, pad, x.delta, dWh, ws)
+        cdl.cdl_qconv_bwd_activations(G, Wi, B, H, W, C, N, R, S, stride, pad, w.delta, dXh, ws)
+        cdl.cdl_quantize_bwd(X, dXh, nX, *xa, dX, sc[4:5], sc[5:6], ws)
+        cdl.cdl_quantize_bwd(Wt, dWh, nW, *wa, dW, sc[2:3], sc[3:4], ws)
+
+    def eager(f):
+        for _ in range(warmup):
+            f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            f()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    ms_conv = eager(run)
+    del X, Wt, G, Xi, Wi, Xs, Ws, Y, dXh, dWh, dX, dW, ws
+    torch.cuda.empty_cache()
+    st = Step(wl)
+    ms_gemm = eager(st.run)
+    n_gemm = st.nW + st.nX
+    del st
+    torch.cuda.empty_cache()
+    return {"layer": "B=256, 14x14x256 -> 256, 3x3, stride 1, padding 1",
+            "as_convolution": {"ms_per_step": ms_conv, "entries_quantized": nX + nW},
+            "as_index_product_on_windows (workload 3 as listed; forming the window matrix not included)":
+                {"ms_per_step": ms_gemm, "entries_quantized": n_gemm},
+            "cache": "warm (steps back to back)"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -852,6 +915,7 @@ def main():
                                                           "hbm_limited_ceiling": min(1.0, t_mfma / max(t_hbm, t_mfma))}
     if not args.no_extra:
         out["small_workloads"] = [small_step(1), small_step(2)]
+        out["conv_layer_step"] = conv_layer_step()
         out["index_gemms_alone"] = [gemm_only(n_, scrub) for n_ in (2, 3) if n_ != wl.number]
         out["conv_layer_without_window_matrix"] = conv_forward(scrub)
         del scrub
