@@ -606,7 +606,7 @@ def small_step(number, steps=20, warmup=3):
     return out
 
 
-def conv_layer_step(steps=10, warmup=3):
+def conv_layer_step(number=3, geom=(256, 14, 14, 256, 256, 3, 3, 1, 1), steps=10, warmup=3):
     """The layer that workload 3 stands for as what it is - a convolution on [B,H,W,C] activations (ResNet-18 layer 3: 256
     images of 14 x 14 x 256, 256 kernels of 3 x 3, padding 1) - against the same layer as an index product on its matrix
     of input windows (workload 3 as the list gives it: the quantizer then runs on the 9 times larger window matrix).
@@ -614,10 +614,11 @@ def conv_layer_step(steps=10, warmup=3):
     cdl_qconv_bwd_activations, quantizer backward for X and W."""
     import torch
     import paper_2501_09849_amd as cdl
-    wl = cdl_inputs.workload(3)
+    wl = cdl_inputs.workload(number)
     w, x = wl.w_spec, wl.x_spec
     wa, xa = (w.lo, w.n_levels, w.delta, w.alpha), (x.lo, x.n_levels, x.delta, x.alpha)
-    B, H, W, C, N, R, S, stride, pad = 256, 14, 14, 256, 256, 3, 3, 1, 1
+    B, H, W, C, N, R, S, stride, pad = geom
+    assert (B * H * W, N, R * S * C) == (wl.M, wl.N, wl.K) and stride == 1
     dev = "cuda:0"
     f32, i8 = torch.float32, torch.int8
     nX, nW = B * H * W * C, N * R * S * C
@@ -662,9 +663,9 @@ def conv_layer_step(steps=10, warmup=3):
     n_gemm = st.nW + st.nX
     del st
     torch.cuda.empty_cache()
-    return {"layer": "B=256, 14x14x256 -> 256, 3x3, stride 1, padding 1",
+    return {"layer": "workload %d: B=%d, %dx%dx%d -> %d, %dx%d, stride %d, padding %d" % (number, B, H, W, C, N, R, S, stride, pad),
             "as_convolution": {"ms_per_step": ms_conv, "entries_quantized": nX + nW},
-            "as_index_product_on_windows (workload 3 as listed; forming the window matrix not included)":
+            "as_index_product_on_windows (the workload as listed; forming the window matrix not included)":
                 {"ms_per_step": ms_gemm, "entries_quantized": n_gemm},
             "cache": "warm (steps back to back)"}
 
@@ -915,7 +916,7 @@ def main():
                                                           "hbm_limited_ceiling": min(1.0, t_mfma / max(t_hbm, t_mfma))}
     if not args.no_extra:
         out["small_workloads"] = [small_step(1), small_step(2)]
-        out["conv_layer_step"] = conv_layer_step()
+        out["conv_layer_step"] = [conv_layer_step(3, (256, 14, 14, 256, 256, 3, 3, 1, 1)), conv_layer_step(2, (128, 32, 32, 16, 16, 3, 3, 1, 1))]
         out["index_gemms_alone"] = [gemm_only(n_, scrub) for n_ in (2, 3) if n_ != wl.number]
         out["conv_layer_without_window_matrix"] = conv_forward(scrub)
         del scrub

@@ -1292,6 +1292,83 @@ void limb_conv_dx_kernel(LimbArgs a)
     }
 }
 
+// dL/dQ(x) of a convolutional layer with few channels on both sides (the first stages of a small CNN: 16 -> 16 channels,
+// 3 x 3: a contraction of 144 entries and 16 output columns, of which the limb kernel's 32 x 384 tiles would be nine
+// tenths padding): one thread per output entry (input pixel, channel c), the weights as doubles in LDS ([tap][n][c], so
+// that the lanes of a pixel read neighbouring words), every output a chain of at most R*S*N fused multiply-adds in
+// double - products of a float and an int8 are exact there, the additions round at 2^-53 relative.  CC: channels per
+// pixel padded to 16 or 32 lanes.
+template <int CC>
+__global__ __launch_bounds__(256)
+void conv_dx_direct_kernel(const float *__restrict__ g, const int8_t *__restrict__ w, int B, int H, int W, int C, int N,
+                           int R, int S, int stride, int pad, int P, int Q, double delta_w, float *__restrict__ out)
+{
+    extern __shared__ double conv_wl[];      // [R*S*N][CC]
+    const int kc = R * S * N;
+    for (int i = threadIdx.x; i < kc * CC; i += 256) {
+        const int k = i / CC, c = i - k * CC, tap = k / N, n = k - tap * N;
+        conv_wl[i] = c < C ? (double)w[((int64_t)n * R * S + tap) * C + c] : 0.0;
+    }
+    __syncthreads();
+    // a thread takes one channel of kPer consecutive pixels: every weight it reads from LDS serves kPer outputs
+    constexpr int kPer = 4;
+    constexpr int PIX = 256 / CC * kPer;
+    const int c = threadIdx.x % CC, pl = threadIdx.x / CC;
+    const int64_t pixels = (int64_t)B * H * W;
+    const int hw = H * W;
+    for (int64_t pix0 = (int64_t)blockIdx.x * PIX + pl * kPer; pix0 < pixels; pix0 += (int64_t)gridDim.x * PIX) {
+        int pb[kPer], ph[kPer], px[kPer];
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int64_t pix = min(pix0 + i, pixels - 1);
+            pb[i] = (int)(pix / hw);
+            const int rem = (int)(pix - (int64_t)pb[i] * hw);
+            ph[i] = rem / W;
+            px[i] = rem - ph[i] * W;
+        }
+        double acc[kPer] = {0.0, 0.0, 0.0, 0.0};
+        for (int r = 0; r < R; ++r) {
+            for (int t = 0; t < S; ++t) {
+                const float4 *gp[kPer];
+                bool ok[kPer];
+                bool any = false;
+#pragma unroll
+                for (int i = 0; i < kPer; ++i) {
+                    int hh = ph[i] + pad - r, ww = px[i] + pad - t;
+                    ok[i] = hh >= 0 && ww >= 0;
+                    if (stride == 2) { ok[i] = ok[i] && ((hh | ww) & 1) == 0; hh >>= 1; ww >>= 1; }
+                    ok[i] = ok[i] && hh < P && ww < Q;
+                    gp[i] = reinterpret_cast<const float4 *>(g + (ok[i] ? (((int64_t)pb[i] * P + hh) * Q + ww) * N : 0));
+                    any = any || ok[i];
+                }
+                if (!any) continue;
+                const double *wp = conv_wl + (int64_t)((r * S + t) * N) * CC + c;
+                for (int n4 = 0; n4 < N / 4; ++n4) {
+                    float4 v[kPer];
+#pragma unroll
+                    for (int i = 0; i < kPer; ++i) {
+                        v[i] = gp[i][n4];
+                        if (!ok[i]) v[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                    }
+                    const double w0 = wp[(4 * n4) * CC], w1 = wp[(4 * n4 + 1) * CC], w2 = wp[(4 * n4 + 2) * CC], w3 = wp[(4 * n4 + 3) * CC];
+#pragma unroll
+                    for (int i = 0; i < kPer; ++i) {
+                        acc[i] = fma((double)v[i].x, w0, acc[i]);
+                        acc[i] = fma((double)v[i].y, w1, acc[i]);
+                        acc[i] = fma((double)v[i].z, w2, acc[i]);
+                        acc[i] = fma((double)v[i].w, w3, acc[i]);
+                    }
+                }
+            }
+        }
+        if (c < C) {
+#pragma unroll
+            for (int i = 0; i < kPer; ++i)
+                if (pix0 + i < pixels) out[(pix0 + i) * C + c] = (float)(acc[i] * delta_w);
+        }
+    }
+}
+
 // For that product: the weights [N][R][S][C] rearranged as its index operand Wr[c][(r, s, n)] (contraction index
 // contiguous, rows ld bytes apart, zero beyond R*S*N) and the sum of |w| over the contraction per channel c (the limb
 // rule's column sums).  One wave per input channel.
@@ -2002,6 +2079,12 @@ int launch_qgemm_quantize_fwd(const float *x, const cdl_qparams &p, const int8_t
     return check_launch();
 }
 
+// few channels on both sides: the direct kernel (its weights in at most 48 KiB of LDS)
+bool conv_dx_is_direct(int32_t N, int32_t C, int32_t R, int32_t S)
+{
+    return C <= 32 && (int64_t)R * S * N <= 288 && (int64_t)R * S * N * (C <= 16 ? 16 : 32) * 8 <= 49152;
+}
+
 // workspace of the activation gradient of a convolution: [plan][per-block max|g|][col sums][Wr]
 struct ConvDxLayout {
     size_t plan, block_max, ss_b, wr, total;
@@ -2036,6 +2119,14 @@ int launch_qconv_bwd_activations(const float *g, const int8_t *w_idx, int32_t B,
 {
     const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
     const int64_t M_out = (int64_t)B * P * Q;
+    if (conv_dx_is_direct(N, C, R, S)) {
+        const int cc = C <= 16 ? 16 : 32;
+        const size_t lds = (size_t)R * S * N * cc * sizeof(double);
+        const unsigned grid = blocks_for((int64_t)B * H * W, 256 / cc * 4, 16384);
+        if (cc == 16) CDL_LAUNCH("conv_dx_direct_kernel", stream, conv_dx_direct_kernel<16>, dim3(grid), dim3(256), lds, g, w_idx, B, H, W, C, N, R, S, stride, pad, P, Q, (double)delta_w, d_x_hat);
+        else CDL_LAUNCH("conv_dx_direct_kernel", stream, conv_dx_direct_kernel<32>, dim3(grid), dim3(256), lds, g, w_idx, B, H, W, C, N, R, S, stride, pad, P, Q, (double)delta_w, d_x_hat);
+        return check_launch();
+    }
     const ConvDxLayout L = conv_dx_layout(M_out, N, C, R, S);
     char *base = reinterpret_cast<char *>(ws);
     BwdPlan *plan = reinterpret_cast<BwdPlan *>(base + L.plan);

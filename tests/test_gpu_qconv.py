@@ -186,7 +186,10 @@ XGRAD = [(2, 7, 9, 16, 128, 3, 3, 1, 1), (1, 8, 8, 20, 128, 3, 3, 2, 1), (3, 6, 
          (2, 8, 8, 16, 128, 1, 1, 2, 0),
          # output channels that are not whole K-tiles of 128: K-tiles then run across taps (the first stages of a ResNet)
          (4, 16, 16, 16, 16, 3, 3, 1, 1), (2, 16, 16, 32, 64, 3, 3, 2, 1), (3, 9, 9, 16, 48, 3, 3, 1, 1), (1, 7, 7, 8, 20, 5, 5, 1, 2),
-         (2, 12, 12, 64, 32, 1, 1, 1, 0)]
+         (2, 12, 12, 64, 32, 1, 1, 1, 0),
+         # few channels on both sides: the direct kernel (16 and 32 lanes per pixel, both strides, odd sizes, 5 x 5, the workload-2 layer)
+         (3, 9, 11, 20, 16, 3, 3, 1, 1), (2, 15, 15, 16, 32, 3, 3, 2, 1), (1, 7, 7, 4, 8, 5, 5, 1, 2), (2, 10, 9, 32, 4, 3, 3, 2, 0),
+         (128, 32, 32, 16, 16, 3, 3, 1, 1)]
 
 
 @pytest.mark.parametrize("B,H,W,C,N,R,S,stride,pad", XGRAD)
