@@ -1371,28 +1371,35 @@ void conv_dx_direct_kernel(const float *__restrict__ g, const int8_t *__restrict
 
 // For that product: the weights [N][R][S][C] rearranged as its index operand Wr[c][(r, s, n)] (contraction index
 // contiguous, rows ld bytes apart, zero beyond R*S*N) and the sum of |w| over the contraction per channel c (the limb
-// rule's column sums).  One wave per input channel.
+// rule's column sums).
 __global__ __launch_bounds__(256)
 void conv_dx_prep_kernel(const int8_t *__restrict__ w, int N, int R, int S, int C, int8_t *__restrict__ wr, int64_t ld,
                          unsigned int *__restrict__ col_abs)
 {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // one block per input channel c; four entries per thread and trip (one 4-byte store): the byte loads are a stride of C
+    // apart and nothing but latency, so as many of them as possible are in flight
+    __shared__ unsigned int red[4];
     const int kc = R * S * N;
-    for (int c = blockIdx.x * 4 + wave; c < C; c += gridDim.x * 4) {
-        unsigned int s_abs = 0u;
-        for (int k = lane; k < (int)ld; k += 64) {
-            int8_t v = 0;
-            if (k < kc) {
-                const int tap = k / N, n = k - tap * N;
-                v = w[((int64_t)n * R * S + tap) * C + c];
-            }
-            wr[(int64_t)c * ld + k] = v;
-            s_abs += (unsigned int)(v < 0 ? -(int)v : (int)v);
-        }
+    const int c = blockIdx.x;
+    unsigned int s_abs = 0u;
+    for (int k4 = threadIdx.x * 4; k4 < (int)ld; k4 += 1024) {
+        int v[4];
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) s_abs += (unsigned int)__shfl_down((int)s_abs, o, 64);
-        if (lane == 0) col_abs[c] = s_abs;
+        for (int e = 0; e < 4; ++e) {
+            const int k = k4 + e, kk = min(k, kc - 1), tap = kk / N, n = kk - tap * N;
+            const int x = (int)w[((int64_t)n * R * S + tap) * C + c];
+            v[e] = k < kc ? x : 0;
+        }
+        *reinterpret_cast<uint32_t *>(wr + (int64_t)c * ld + k4) =
+            (uint32_t)(v[0] & 0xff) | ((uint32_t)(v[1] & 0xff) << 8) | ((uint32_t)(v[2] & 0xff) << 16) | ((uint32_t)(v[3] & 0xff) << 24);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s_abs += (unsigned int)(v[e] < 0 ? -v[e] : v[e]);
     }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s_abs += (unsigned int)__shfl_down((int)s_abs, o, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s_abs;
+    __syncthreads();
+    if (threadIdx.x == 0) col_abs[c] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
 // The forward product with the quantizer of the activations in its prologue: y = delta_a delta_b (Q_idx(X) . Wi^T)
@@ -2134,7 +2141,7 @@ int launch_qconv_bwd_activations(const float *g, const int8_t *w_idx, int32_t B,
     unsigned int *ss_b = reinterpret_cast<unsigned int *>(base + L.ss_b);
     int8_t *wr = reinterpret_cast<int8_t *>(base + L.wr);
     CDL_LAUNCH("absmax_kernel", stream, absmax_kernel, dim3(L.n_max), dim3(256), 0, g, M_out * N, block_max, ss_b, 0);
-    CDL_LAUNCH("conv_dx_prep_kernel", stream, conv_dx_prep_kernel, dim3((unsigned)blocks_for(C, 4, 1024)), dim3(256), 0,
+    CDL_LAUNCH("conv_dx_prep_kernel", stream, conv_dx_prep_kernel, dim3((unsigned)C), dim3(256), 0,
                w_idx, N, R, S, C, wr, L.ld, ss_b);
     CDL_LAUNCH("plan_kernel", stream, plan_kernel, dim3(1), dim3(1024), 0, plan, block_max, L.n_max,
                (const unsigned int *)nullptr, 0, ss_b, C, 1.0f, delta_w);
