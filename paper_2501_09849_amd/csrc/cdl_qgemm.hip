@@ -493,30 +493,40 @@ void qconv_dma_kernel(ConvArgs a)
     const int nk = a.Kc / kFBK;
     // tap (tr, ts) and first channel tc of the K-tile that `issue` is called with next (called with 0, 1, 2, ...)
     int tr = 0, ts = 0, tc = 0;
-    auto issue = [&](int kt) {
-        int8_t *base = flds + (kt & 1) * kFStage;
+    // where the rows of the next K-tile are read from: worked out while the MFMAs of the current one run, so that the
+    // loads go out right behind the barrier
+    const int8_t *srcA[WL];
+    auto prepare = [&]() {
         const int64_t tap_off = ((int64_t)tr * a.W + ts) * a.C + tc;
 #pragma unroll
         for (int i = 0; i < WL; ++i) {
             const bool inside = (unsigned)(xr[i].h0 + tr) < (unsigned)a.H && (unsigned)(xr[i].w0 + ts) < (unsigned)a.W;
-            const int8_t *src = inside ? a.X + (xr[i].off + tap_off) : a.pad_page;
-            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(base + (wave * WL + i) * 1024), 16, 0, 0);
+            srcA[i] = inside ? a.X + (xr[i].off + tap_off) : a.pad_page;
         }
+        tc += kFBK;
+        if (tc == a.C) { tc = 0; if (++ts == a.S) { ts = 0; ++tr; } }
+    };
+    auto issue = [&](int kt) {
+        int8_t *base = flds + (kt & 1) * kFStage;
+#pragma unroll
+        for (int i = 0; i < WL; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)srcA[i], (lptr_t)(base + (wave * WL + i) * 1024), 16, 0, 0);
         const int64_t off = (int64_t)kt * kFBK;
 #pragma unroll
         for (int i = 0; i < WL; ++i)
             __builtin_amdgcn_global_load_lds((gptr_t)(gb[i] + off), (lptr_t)(base + kFTile * kFBK + (wave * WL + i) * 1024), 16, 0, 0);
-        tc += kFBK;
-        if (tc == a.C) { tc = 0; if (++ts == a.S) { ts = 0; ++tr; } }
     };
 
+    prepare();
     issue(0);
+    if (nk > 1) prepare();
     for (int kt = 0; kt < nk; ++kt) {
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         if (kt + 1 < nk) issue(kt + 1);
+        if (kt + 2 < nk) prepare();
         const int8_t *base = flds + (kt & 1) * kFStage;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
