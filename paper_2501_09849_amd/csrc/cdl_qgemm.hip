@@ -545,18 +545,31 @@ void qconv_dma_kernel(ConvArgs a)
     }
 
     const bool full = (tile_m + 1) * kFTile <= a.M && (tile_n + 1) * kFTile <= a.N;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
+    // (the corrections of an operand stored with an offset are loaded before the first store and live in a copy of the
+    // epilogue of their own: a load between the stores makes every store wait for the one before it - loads and stores
+    // share one counter - which cost 10 us per round of blocks)
+    auto epilogue = [&](auto corr_c) {
+        constexpr bool CORR = decltype(corr_c)::value;
+        int cc[TN];
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int col = tile_n * kFTile + (wn * TN + j) * 32 + (lane & 31);
-            const int cc = (a.corr_col && col < a.N) ? a.corr_col[col] : 0;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = tile_m * kFTile + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (full || (row < a.M && col < a.N)) conv_store(a, row, col, acc[i][j][r] + cc);
-            }
+            cc[j] = (CORR && col < a.N) ? a.corr_col[col] : 0;
         }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = tile_n * kFTile + (wn * TN + j) * 32 + (lane & 31);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = tile_m * kFTile + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    if (full || (row < a.M && col < a.N)) conv_store(a, row, col, CORR ? acc[i][j][r] + cc[j] : acc[i][j][r]);
+                }
+            }
+    };
+    if (a.corr_col) epilogue(std::true_type{});
+    else epilogue(std::false_type{});
 }
 
 // Any C that is a multiple of 16: the structure of qgemm_kernel (256 x 128 tile, 64-byte K steps staged through
@@ -687,19 +700,29 @@ void qconv_kernel(ConvArgs a)
         __syncthreads();
     }
 
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
+    auto epilogue = [&](auto corr_c) {
+        constexpr bool CORR = decltype(corr_c)::value;
+        int cc[TN];
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int col = tile_n * BN + wn * TN * 32 + j * 32 + (lane & 31);
-            if (col >= a.N) continue;
-            const int cc = a.corr_col ? a.corr_col[col] : 0;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = tile_m * BM + wm * TM * 32 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (row < a.M) conv_store(a, row, col, acc[i][j][r] + cc);
-            }
+            cc[j] = (CORR && col < a.N) ? a.corr_col[col] : 0;
         }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = tile_n * BN + wn * TN * 32 + j * 32 + (lane & 31);
+                if (col >= a.N) continue;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = tile_m * BM + wm * TM * 32 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    if (row < a.M) conv_store(a, row, col, CORR ? acc[i][j][r] + cc[j] : acc[i][j][r]);
+                }
+            }
+    };
+    if (a.corr_col) epilogue(std::true_type{});
+    else epilogue(std::false_type{});
 }
 
 // 128 bytes that read as level index 0 of an operand stored with offset `off`, and (with an offset) the
@@ -1044,15 +1067,21 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
         const int64_t first = (int64_t)erow * a.cols + ecol;
         const bool direct = a.splits == 1 && !a.to_partial;      // the block writes the finished fp32 output itself
         const bool corr = a.row_corr != nullptr && direct;
-        auto emit = [&](auto full_c, auto *base) {
+        // CORR: row corrections of an operand stored with an offset, in a copy of the write-out of their own.  A load
+        // between the stores - even one that a branch skips - makes the compiler wait for every earlier store at each
+        // row (loads and stores share one counter) and a store takes microseconds to complete: the common path must
+        // not contain one (it cost dL/dQ(x) 5 %).  The copy with corrections loads one per row and pays for it; holding
+        // all sixteen in registers instead pushed the five-limb kernels into spilling.
+        auto emit = [&](auto full_c, auto corr_c, auto *base) {
             constexpr bool FULL = decltype(full_c)::value;
+            constexpr bool CORR = decltype(corr_c)::value;
             using T = std::remove_pointer_t<decltype(base)>;
 #pragma unroll
             for (int rr = 0; rr < 16; ++rr) {
                 const int dr = 8 * (rr >> 2) + (rr & 3);
                 T *p = base + (int64_t)dr * a.cols;
                 const bool row_ok = FULL || erow + dr < a.rows;
-                const double rc = (corr && row_ok) ? a.row_corr[erow + dr] : 0.0;
+                const double rc = (CORR && row_ok) ? a.row_corr[erow + dr] : 0.0;
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     if (FULL || (row_ok && ecol + j * 32 < a.cols)) {
@@ -1064,12 +1093,17 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
             }
         };
         if (direct) {
-            if (full) emit(std::true_type{}, a.out + first);
-            else emit(std::false_type{}, a.out + first);
+            if (corr) {
+                if (full) emit(std::true_type{}, std::true_type{}, a.out + first);
+                else emit(std::false_type{}, std::true_type{}, a.out + first);
+            } else {
+                if (full) emit(std::true_type{}, std::false_type{}, a.out + first);
+                else emit(std::false_type{}, std::false_type{}, a.out + first);
+            }
         } else {
             double *base = a.partial + (int64_t)split * a.rows * a.cols + first;
-            if (full) emit(std::true_type{}, base);
-            else emit(std::false_type{}, base);
+            if (full) emit(std::true_type{}, std::false_type{}, base);
+            else emit(std::false_type{}, std::false_type{}, base);
         }
     };
 
@@ -1088,6 +1122,19 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
         // recombined and written to LDS (with one wave per SIMD nothing else hides their latency)
         constexpr int T = kLRows * Q / kLThreads;
         static_assert(T * kLThreads == kLRows * Q, "whole trips");
+        // (row corrections of a weight operand stored with an offset: loaded first, in a branch of their own, so that the
+        // common path has no load whose wait would also be a wait for the theta loads below)
+        double rcs[16];
+#pragma unroll
+        for (int rr = 0; rr < 16; ++rr) rcs[rr] = 0.0;
+        if (a.row_corr) {
+            const int lrow0 = tile_r0 * kLRows + 4 * (lane >> 5);
+#pragma unroll
+            for (int rr = 0; rr < 16; ++rr) {
+                const int dr = 8 * (rr >> 2) + (rr & 3);
+                rcs[rr] = lrow0 + dr < a.rows ? a.row_corr[lrow0 + dr] : 0.0;
+            }
+        }
         float4 th4[T];
         bool ok[T];
 #pragma unroll
@@ -1105,7 +1152,7 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
 #pragma unroll
             for (int rr = 0; rr < 16; ++rr) {
                 const int dr = 8 * (rr >> 2) + (rr & 3);
-                const double rc = (a.row_corr && row0 + lrow + dr < a.rows) ? a.row_corr[row0 + lrow + dr] : 0.0;
+                const double rc = rcs[rr];
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     double run = (double)acc[L - 1][j][rr];
