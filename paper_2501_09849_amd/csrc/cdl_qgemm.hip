@@ -240,6 +240,7 @@ struct LimbArgs {
     // A thread's four consecutive entries share a tap (N % 4 == 0).
     int cg_H, cg_W, cg_P, cg_Q, cg_stride, cg_S, cg_pad;
     float cg_inv_n, cg_inv_s;     // 1 / N, 1 / S
+    int tn;                       // 32-column tiles per wave (1..3; with six limbs at most 2)
     const double *row_corr;   // [rows] or null: added to every entry of an output row (the index operand is stored with an offset:
                               // the missing part of the product is offset * step * sum of g over the contraction); splits == 1 only
 };
@@ -1341,12 +1342,32 @@ void limb_conv_dx_kernel(LimbArgs a)
     const int limbs = a.plan->limbs_da;
     const float gscale = a.plan->gscale_da;
     const double out_scale = a.plan->out_scale_da;
-    switch (limbs) {
-        case 3: limb_gemm_body<3, 3, false, true, false, false, false, true>(a, limb_lds, gscale, out_scale); break;
-        case 4: limb_gemm_body<4, 3, false, true, false, false, false, true>(a, limb_lds, gscale, out_scale); break;
-        case 5: limb_gemm_body<5, 3, false, true, false, false, false, true>(a, limb_lds, gscale, out_scale); break;
-        default: limb_gemm_body<6, 2, false, true, false, false, false, true>(a, limb_lds, gscale, out_scale); break;
+    // column tiles per wave (a.tn, chosen by the launcher): channel counts are powers of two, and 256 or 512 output
+    // columns in tiles of 384 would spend a third of the MFMAs on padding
+#define CDL_CONV_DX(L, TN) limb_gemm_body<L, TN, false, true, false, false, false, true>(a, limb_lds, gscale, out_scale)
+    if (a.tn == 1) {
+        switch (limbs) {
+            case 3: CDL_CONV_DX(3, 1); break;
+            case 4: CDL_CONV_DX(4, 1); break;
+            case 5: CDL_CONV_DX(5, 1); break;
+            default: CDL_CONV_DX(6, 1); break;
+        }
+    } else if (a.tn == 2) {
+        switch (limbs) {
+            case 3: CDL_CONV_DX(3, 2); break;
+            case 4: CDL_CONV_DX(4, 2); break;
+            case 5: CDL_CONV_DX(5, 2); break;
+            default: CDL_CONV_DX(6, 2); break;
+        }
+    } else {
+        switch (limbs) {
+            case 3: CDL_CONV_DX(3, 3); break;
+            case 4: CDL_CONV_DX(4, 3); break;
+            case 5: CDL_CONV_DX(5, 3); break;
+            default: CDL_CONV_DX(6, 2); break;
+        }
     }
+#undef CDL_CONV_DX
 }
 
 // dL/dQ(x) of a convolutional layer with few channels on both sides (the first stages of a small CNN: 16 -> 16 channels,
@@ -2215,7 +2236,15 @@ int launch_qconv_bwd_activations(const float *g, const int8_t *w_idx, int32_t B,
     a.out = d_x_hat;
     a.cg_H = H; a.cg_W = W; a.cg_P = P; a.cg_Q = Q; a.cg_stride = stride; a.cg_S = S; a.cg_pad = pad;
     a.cg_inv_n = 1.0f / (float)N; a.cg_inv_s = 1.0f / (float)S;
-    const int64_t items = (int64_t)a.tiles_r * ((a.cols + limb_cols(6) - 1) / limb_cols(6));
+    // the tile width (128, 256 or 384 columns) that pads the channels least; the widest of those that pad equally
+    a.tn = 3;
+    for (int tn = 2; tn >= 1; --tn) {
+        const int w = 128 * tn, wbest = 128 * a.tn;
+        if ((C + w - 1) / w * w < (C + wbest - 1) / wbest * wbest) a.tn = tn;
+    }
+    // (the grid is sized before the limb count is known: six limbs take tiles of at most 256 columns)
+    const int narrow = 128 * (a.tn < 2 ? a.tn : 2);
+    const int64_t items = (int64_t)a.tiles_r * ((a.cols + narrow - 1) / narrow);
     if (items > 2147483640LL) return CDL_ERR_PARAM;
     if ((int64_t)limb_cols(3) * a.ldb > 0xffffffffLL) return CDL_ERR_RANGE;
     const unsigned grid = (unsigned)((items + 7) / 8 * 8);

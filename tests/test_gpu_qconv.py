@@ -184,6 +184,8 @@ def test_convolution_weight_gradient(oracle, B, H, W, C, N, R, S, stride, pad, x
 XGRAD = [(2, 7, 9, 16, 128, 3, 3, 1, 1), (1, 8, 8, 20, 128, 3, 3, 2, 1), (3, 6, 5, 48, 256, 1, 1, 1, 0), (1, 9, 7, 16, 128, 5, 3, 1, 2),
          (4, 14, 14, 64, 128, 3, 3, 1, 1), (2, 15, 15, 32, 128, 3, 3, 2, 1), (1, 10, 11, 64, 256, 3, 5, 2, 0), (3, 14, 14, 400, 128, 3, 3, 1, 1),
          (2, 8, 8, 16, 128, 1, 1, 2, 0),
+         # channel counts served by column tiles of 256 (one and two of them) and of 384 columns (one, and two with a ragged one)
+         (2, 8, 8, 256, 128, 3, 3, 1, 1), (1, 6, 7, 512, 32, 3, 3, 2, 1), (1, 9, 9, 320, 64, 3, 3, 1, 1), (1, 6, 6, 644, 32, 1, 1, 1, 0),
          # output channels that are not whole K-tiles of 128: K-tiles then run across taps (the first stages of a ResNet)
          (4, 16, 16, 16, 16, 3, 3, 1, 1), (2, 16, 16, 32, 64, 3, 3, 2, 1), (3, 9, 9, 16, 48, 3, 3, 1, 1), (1, 7, 7, 8, 20, 5, 5, 1, 2),
          (2, 12, 12, 64, 32, 1, 1, 1, 0),
