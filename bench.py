@@ -532,10 +532,17 @@ def conv_forward(scrub, seed=0, iters=5):
     w, x = wl.w_spec, wl.x_spec
     B, H, W, C, N, R, S, stride, pad = 256, 14, 14, 256, 256, 3, 3, 1, 1
     dev = "cuda:0"
-    Xi = torch.from_numpy(cdl_inputs.draw_indices((B, H, W, C), x.lo, x.hi, seed=seed + 1)).to(dev)
-    Wi = torch.from_numpy(cdl_inputs.draw_indices((N, R, S, C), w.lo, w.hi, seed=seed + 2)).to(dev)
     M, K = B * H * W, R * S * C
     assert (M, N, K) == (wl.M, wl.N, wl.K)
+    # operands as the layer has them: the workload's distributions on the un-expanded tensors, quantized by the library
+    # (uniformly drawn indices would be larger on average and cost the gradient products a limb more)
+    Xf = torch.from_numpy(cdl_inputs.draw_x(wl, seed, rows=(M * C + K - 1) // K).reshape(-1)[:M * C].copy()).to(dev)
+    Wf = torch.from_numpy(cdl_inputs.draw_w(wl, seed).reshape(-1)).to(dev)
+    Xi = torch.empty((B, H, W, C), dtype=torch.int8, device=dev)
+    Wi = torch.empty((N, R, S, C), dtype=torch.int8, device=dev)
+    cdl.cdl_quantize_fwd(Xf, Xf.numel(), x.lo, x.n_levels, x.delta, x.alpha, Xi)
+    cdl.cdl_quantize_fwd(Wf, Wf.numel(), w.lo, w.n_levels, w.delta, w.alpha, Wi)
+    del Xf, Wf
     Y = torch.empty((M, N), dtype=torch.float32, device=dev)
     Y2 = torch.empty((M, N), dtype=torch.float32, device=dev)
     # the matrix of windows, for the comparison only (torch is plumbing here; its time is reported, not counted)
