@@ -591,6 +591,49 @@ def conv_forward(scrub, seed=0, iters=5):
     return out
 
 
+def conv_stage_shapes(batch=128, iters=5):
+    """The three convolution calls on the 3 x 3 layers of a ResNet-18's four stages and its two stride-2 transitions
+    (batch 128; activations |N(0,1)| on 16 unsigned levels, weights N(0, 2/fan-in) on 15 signed levels, the recipe of
+    workload 3; g ~ N(0,1)): sums of kernel times per call, warm, median of `iters`."""
+    import torch
+    import paper_2501_09849_amd as cdl
+    x, w = cdl_inputs.workload(3).x_spec, cdl_inputs.workload(3).w_spec
+    dev = "cuda:0"
+    rows = []
+    for (H, C, N, stride) in ((56, 64, 64, 1), (28, 128, 128, 1), (14, 256, 256, 1), (7, 512, 512, 1), (56, 64, 128, 2), (28, 128, 256, 2)):
+        B, W, R, S, pad = batch, H, 3, 3, 1
+        P = (H + 2 * pad - R) // stride + 1
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(H + C)
+        Xf = torch.randn((B, H, W, C), device=dev, generator=gen).abs_()
+        sigma_w = (2.0 / (R * S * C)) ** 0.5
+        Wf = torch.randn((N, R, S, C), device=dev, generator=gen) * sigma_w
+        delta_w = 2.0 * 0.79788 * sigma_w / 8.0 ** 0.5          # the step rule of Sec. V-B on N(0, sigma_w^2), 4 bits
+        Xi = torch.empty((B, H, W, C), dtype=torch.int8, device=dev)
+        Wi = torch.empty((N, R, S, C), dtype=torch.int8, device=dev)
+        cdl.cdl_quantize_fwd(Xf, Xf.numel(), x.lo, x.n_levels, x.delta, x.alpha, Xi)
+        cdl.cdl_quantize_fwd(Wf, Wf.numel(), w.lo, w.n_levels, delta_w, 4.0 / delta_w ** 2, Wi)
+        G = torch.randn((B, P, P, N), device=dev, generator=gen)
+        Y = torch.empty((B, P, P, N), device=dev)
+        dW = torch.empty((N, R, S, C), device=dev)
+        dX = torch.empty((B, H, W, C), device=dev)
+        ws = torch.empty(max(256, cdl.qconv_bwd_weights_workspace_bytes(B, H, W, C, N, R, S, stride, pad),
+                             cdl.qconv_bwd_activations_workspace_bytes(B, H, W, C, N, R, S, stride, pad)), dtype=torch.uint8, device=dev)
+        calls = {"forward": lambda: cdl.cdl_qconv_fwd(Xi, Wi, B, H, W, C, N, R, S, stride, pad, x.delta, delta_w, None, Y, None),
+                 "weight_gradient": lambda: cdl.cdl_qconv_bwd_weights(G, Xi, B, H, W, C, N, R, S, stride, pad, x.delta, dW, ws),
+                 "activation_gradient": lambda: cdl.cdl_qconv_bwd_activations(G, Wi, B, H, W, C, N, R, S, stride, pad, delta_w, dX, ws)}
+        t = timed_calls(calls, iters)
+        gop = 2.0 * B * P * P * N * R * S * C / 1e9
+        row = {"layer": "%dx%dx%d -> %d, stride %d" % (H, W, C, N, stride), "Gop_per_product": gop}
+        for k in calls:
+            us = float(np.median(t[k]))
+            row[k] = {"us": us, "TOPS": gop / us * 1e3}
+        rows.append(row)
+        del Xf, Wf, Xi, Wi, G, Y, dW, dX, ws
+        torch.cuda.empty_cache()
+    return rows
+
+
 def small_step(number, steps=20, warmup=3):
     """One whole layer step on a small workload (1: the tiny linear layer, 2: the CIFAR conv as an im2col GEMM)."""
     import torch
@@ -926,6 +969,7 @@ def main():
         out["conv_layer_step"] = [conv_layer_step(3, (256, 14, 14, 256, 256, 3, 3, 1, 1)), conv_layer_step(2, (128, 32, 32, 16, 16, 3, 3, 1, 1))]
         out["index_gemms_alone"] = [gemm_only(n_, scrub) for n_ in (2, 3) if n_ != wl.number]
         out["conv_layer_without_window_matrix"] = conv_forward(scrub)
+        out["conv_calls_on_resnet18_stage_shapes_batch128"] = conv_stage_shapes()
         del scrub
         torch.cuda.empty_cache()
         out["extensions_flat_25M"] = extensions_bench()

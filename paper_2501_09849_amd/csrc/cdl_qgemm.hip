@@ -1334,38 +1334,30 @@ void limb_gemm_kernel(LimbArgs a)
 }
 
 // dL/dQ(x) of a convolutional layer: the activation-gradient product with the rows of g gathered by taps (CONVG),
-// one row tile of 32 input pixels per block.
-__global__ __launch_bounds__(kLThreads, 1)
+// one row tile of 32 input pixels per block.  TN = column tiles per wave, chosen by the launcher: channel counts are
+// powers of two, and 256 or 512 output columns in tiles of 384 would spend a third of the MFMAs on padding.  With one
+// column tile per wave (up to 128 channels: the first stages of a network) a K-tile has only 4 L MFMAs per wave, fewer
+// cycles than a load takes to come back, and the loop runs at one memory round trip per K-tile: that kernel is held to
+// 256 registers and asks for 80 KiB of LDS, so that two blocks share a compute unit and fill each other's waits.
+constexpr int conv_dx_lds_bytes(int tn)
+{
+    return tn == 3 ? kLimbLdsBytes : 2 * (kMaxLimbs * kLPlane + 4 * tn * 32 * kLBK);
+}
+
+template <int TN>
+__global__ __launch_bounds__(kLThreads, TN == 1 ? 2 : 1)
 void limb_conv_dx_kernel(LimbArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) int8_t limb_lds[];
     const int limbs = a.plan->limbs_da;
     const float gscale = a.plan->gscale_da;
     const double out_scale = a.plan->out_scale_da;
-    // column tiles per wave (a.tn, chosen by the launcher): channel counts are powers of two, and 256 or 512 output
-    // columns in tiles of 384 would spend a third of the MFMAs on padding
-#define CDL_CONV_DX(L, TN) limb_gemm_body<L, TN, false, true, false, false, false, true>(a, limb_lds, gscale, out_scale)
-    if (a.tn == 1) {
-        switch (limbs) {
-            case 3: CDL_CONV_DX(3, 1); break;
-            case 4: CDL_CONV_DX(4, 1); break;
-            case 5: CDL_CONV_DX(5, 1); break;
-            default: CDL_CONV_DX(6, 1); break;
-        }
-    } else if (a.tn == 2) {
-        switch (limbs) {
-            case 3: CDL_CONV_DX(3, 2); break;
-            case 4: CDL_CONV_DX(4, 2); break;
-            case 5: CDL_CONV_DX(5, 2); break;
-            default: CDL_CONV_DX(6, 2); break;
-        }
-    } else {
-        switch (limbs) {
-            case 3: CDL_CONV_DX(3, 3); break;
-            case 4: CDL_CONV_DX(4, 3); break;
-            case 5: CDL_CONV_DX(5, 3); break;
-            default: CDL_CONV_DX(6, 2); break;
-        }
+#define CDL_CONV_DX(L, T) limb_gemm_body<L, T, false, true, false, false, false, true>(a, limb_lds, gscale, out_scale)
+    switch (limbs) {
+        case 3: CDL_CONV_DX(3, TN); break;
+        case 4: CDL_CONV_DX(4, TN); break;
+        case 5: CDL_CONV_DX(5, TN); break;
+        default: CDL_CONV_DX(6, (TN < 2 ? TN : 2)); break;
     }
 #undef CDL_CONV_DX
 }
@@ -2248,9 +2240,13 @@ int launch_qconv_bwd_activations(const float *g, const int8_t *w_idx, int32_t B,
     if (items > 2147483640LL) return CDL_ERR_PARAM;
     if ((int64_t)limb_cols(3) * a.ldb > 0xffffffffLL) return CDL_ERR_RANGE;
     const unsigned grid = (unsigned)((items + 7) / 8 * 8);
-    const hipError_t e = hipFuncSetAttribute((const void *)limb_conv_dx_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLimbLdsBytes);
+    const void *fn = a.tn == 1 ? (const void *)limb_conv_dx_kernel<1> : a.tn == 2 ? (const void *)limb_conv_dx_kernel<2> : (const void *)limb_conv_dx_kernel<3>;
+    const int lds_bytes = conv_dx_lds_bytes(a.tn);
+    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return hip_failed(e);
-    CDL_LAUNCH("limb_gemm_kernel(conv d_x_hat)", stream, limb_conv_dx_kernel, dim3(grid), dim3(kLThreads), kLimbLdsBytes, a);
+    if (a.tn == 1) CDL_LAUNCH("limb_gemm_kernel(conv d_x_hat)", stream, limb_conv_dx_kernel<1>, dim3(grid), dim3(kLThreads), lds_bytes, a);
+    else if (a.tn == 2) CDL_LAUNCH("limb_gemm_kernel(conv d_x_hat)", stream, limb_conv_dx_kernel<2>, dim3(grid), dim3(kLThreads), lds_bytes, a);
+    else CDL_LAUNCH("limb_gemm_kernel(conv d_x_hat)", stream, limb_conv_dx_kernel<3>, dim3(grid), dim3(kLThreads), lds_bytes, a);
     return check_launch();
 }
 
