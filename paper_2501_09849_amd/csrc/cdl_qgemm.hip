@@ -2125,8 +2125,13 @@ int launch_qgemm_fwd(const int8_t *a_idx, const int8_t *b_idx, int32_t M, int32_
     g.scale = delta_a * delta_b;
     // contraction lengths that are whole 128-byte K-tiles take the direct-load kernel (a tile grid of 256 x 256
     // needs enough rows to be worth it)
-    if (g.Kc % kFBK == 0 && (int64_t)M * N >= (int64_t)kFTile * kFTile * 64) return launch_gemm_dma(g, stream);
-    return launch_gemm<4, 2>(g, stream);
+    // (up to 128 output columns would leave half of its 256-column tile empty)
+    if (g.Kc % kFBK == 0 && (int64_t)M * N >= (int64_t)kFTile * kFTile * 64 && N > 128) return launch_gemm_dma(g, stream);
+    // (up to 64 output columns: tiles 64 columns wide, so that half of a wider one is not padding; fewer tiles of 256
+    // rows than compute units: tiles of 128 rows, twice as many blocks)
+    const bool few = (int64_t)((M + 255) / 256) * ((N + (N <= 64 ? 63 : 127)) / (N <= 64 ? 64 : 128)) < 256 && M > 128;
+    if (N <= 64) return few ? launch_gemm<2, 1>(g, stream) : launch_gemm<4, 1>(g, stream);
+    return few ? launch_gemm<2, 2>(g, stream) : launch_gemm<4, 2>(g, stream);
 }
 
 int launch_qgemm_quantize_fwd(const float *x, const cdl_qparams &p, const int8_t *b_idx, int32_t M, int32_t N, int32_t K,
@@ -2307,7 +2312,7 @@ int launch_qconv_fwd(const int8_t *x_idx, const int8_t *w_idx, int32_t B, int32_
     }
     const uint32_t pb = (uint32_t)(uint8_t)(int8_t)(-x_offset);
     a.pad_word = (int)(pb | (pb << 8) | (pb << 16) | (pb << 24));
-    if (C % kFBK == 0 && (int64_t)a.M * N >= (int64_t)kFTile * kFTile * 64) {
+    if (C % kFBK == 0 && (int64_t)a.M * N >= (int64_t)kFTile * kFTile * 64 && N > 128) {
         a.tiles_m = (a.M + kFTile - 1) / kFTile;
         a.tiles_n = (N + kFTile - 1) / kFTile;
         const int64_t grid = ((int64_t)a.tiles_m * a.tiles_n + 7) / 8 * 8;
@@ -2316,11 +2321,18 @@ int launch_qconv_fwd(const int8_t *x_idx, const int8_t *w_idx, int32_t B, int32_
         CDL_LAUNCH("qconv_kernel(fwd)", stream, qconv_dma_kernel, dim3((unsigned)grid), dim3(kFThreads), kFLdsBytes, a);
         return check_launch();
     }
-    constexpr int BM = 256, BN = 128;
+    // (tiles of 256 x 128, or 256 x 64 for up to 64 output channels)
+    // (fewer such tiles than compute units: 128 rows per tile, twice as many blocks)
+    const int BN = N <= 64 ? 64 : 128;
+    const bool few = (int64_t)((a.M + 255) / 256) * ((N + BN - 1) / BN) < 256 && a.M > 128;
+    const int BM = few ? 128 : 256;
     a.tiles_m = (a.M + BM - 1) / BM;
     a.tiles_n = (N + BN - 1) / BN;
     const int64_t grid = ((int64_t)a.tiles_m * a.tiles_n + 7) / 8 * 8;
-    CDL_LAUNCH("qconv_kernel(fwd)", stream, (qconv_kernel<4, 2>), dim3((unsigned)grid), dim3(kGemmThreads), 0, a);
+    if (N <= 64 && few) CDL_LAUNCH("qconv_kernel(fwd)", stream, (qconv_kernel<2, 1>), dim3((unsigned)grid), dim3(kGemmThreads), 0, a);
+    else if (N <= 64) CDL_LAUNCH("qconv_kernel(fwd)", stream, (qconv_kernel<4, 1>), dim3((unsigned)grid), dim3(kGemmThreads), 0, a);
+    else if (few) CDL_LAUNCH("qconv_kernel(fwd)", stream, (qconv_kernel<2, 2>), dim3((unsigned)grid), dim3(kGemmThreads), 0, a);
+    else CDL_LAUNCH("qconv_kernel(fwd)", stream, (qconv_kernel<4, 2>), dim3((unsigned)grid), dim3(kGemmThreads), 0, a);
     return check_launch();
 }
 
