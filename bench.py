@@ -183,7 +183,7 @@ def cpu_baseline(wl, step):
         flat = host.reshape(-1)
         n_s = int(min(n_full, max(4096, 400_000_000 // spec.n_levels)))
         th = flat[:n_s]
-        g = step.G_host.reshape(-1)[:n_s]
+        g = np.resize(step.G_host.reshape(-1), n_s)       # (repeated where the gradient tensor is the smaller one: timing only)
         a = (spec.lo, spec.n_levels, spec.delta, spec.alpha)
         dt_f, (r_idx, _, gap) = timed(lambda: oracle.quantize_fwd(th, *a))
         dt_m, _ = timed(lambda: oracle.marginal_entropy(th, *a))

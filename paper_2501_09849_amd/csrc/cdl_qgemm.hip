@@ -1566,38 +1566,72 @@ void limb_reduce_quantize_bwd_kernel(const double *__restrict__ partial, int spl
 
 // dL/dQ(a) for a very short contraction (N <= 32: the first stages of a small CNN have 16 or 32 output
 // channels): d_a_hat[m][k] = delta_b * sum_n g[m][n] * b_idx[n][k].  One K-tile of the limb kernel would be
-// at least three quarters padding there; here a block takes 64 rows of g (kept in LDS as doubles), a thread
-// one output column, whose N index values it keeps in registers as doubles, and every output is a chain of N
-// fused multiply-adds in double: products of a float and an int8 are exact in double and N <= 32 additions
-// round at 2^-53 relative.  The shader clock inside the kernel (workload 2: M = 131072, N = 16, K = 144) shows a
-// block spending 9 k cycles on its loads and conversions, 36 k on its 64 rows (560 per row: six to eight waves
-// per SIMD take turns at 16 double-precision multiply-adds and 8 LDS reads each) and 3 k waiting for its stores.
+// at least three quarters padding there; here a block takes 128 or 64 rows of g (kept in LDS as doubles), a thread
+// C neighbouring output columns, whose N index values each it keeps in registers as doubles, and every output
+// is a chain of N fused multiply-adds in double: products of a float and an int8 are exact in double and N <= 32
+// additions round at 2^-53 relative.  The threads of a block are spread over (group of C columns, row group):
+// with one column per thread and 256 columns per block, 144 columns (workload 2) left 112 threads of every
+// block idle (35 us; 28 us now); C columns per thread use each value read from LDS C times and load the C index
+// bytes of a row of b_idx as one word.
 constexpr int kDirectMaxN = 32;
-constexpr int kDirectRows = 64;
+constexpr int direct_rows(int nn) { return 2048 / nn; }     // rows of g per block: 16 KiB of LDS as doubles
 
-template <int NN>
+template <int NN, int C>
 __global__ __launch_bounds__(256)
 void da_direct_kernel(const float *__restrict__ g, const int8_t *__restrict__ b_idx, int M, int N, int K,
-                      double delta_b, double b_offset, float *__restrict__ out)
+                      double delta_b, double b_offset, float *__restrict__ out, int vec_store)
 {
-    __shared__ double gs[kDirectRows][NN];
-    const int row0 = blockIdx.x * kDirectRows;
-    const int k = blockIdx.y * 256 + threadIdx.x;
-    const int rows = min(kDirectRows, M - row0);
-    for (int i = threadIdx.x; i < kDirectRows * NN; i += 256) {
+    constexpr int kRows = direct_rows(NN);
+    __shared__ double gs[kRows][NN];
+    const int row0 = blockIdx.x * kRows;
+    const int rows = min(kRows, M - row0);
+    const int groups_total = (K + C - 1) / C;              // groups of C columns
+    const int gpb = min(groups_total, 256);                // of them per block
+    const int row_groups = 256 / gpb;
+    const int cg = blockIdx.y * gpb + (int)threadIdx.x % gpb, rg = (int)threadIdx.x / gpb;
+    for (int i = threadIdx.x; i < kRows * NN; i += 256) {
         const int r = i / NN, n = i - r * NN;
         gs[r][n] = (r < rows && n < N) ? (double)g[(int64_t)(row0 + r) * N + n] : 0.0;
     }
-    double b[NN];
+    const bool active = cg < groups_total && rg < row_groups;
+    double b[C][NN];
+    if (C == 4 && vec_store) {
+        // (K % 4 == 0: the four index bytes of a row of b_idx in one load)
 #pragma unroll
-    for (int n = 0; n < NN; ++n) b[n] = (n < N && k < K) ? (double)b_idx[(int64_t)n * K + k] + b_offset : 0.0;   // (the level index itself)
+        for (int n = 0; n < NN; ++n) {
+            const uint32_t w4 = (active && n < N) ? *reinterpret_cast<const uint32_t *>(b_idx + (int64_t)n * K + cg * C) : 0u;
+#pragma unroll
+            for (int c = 0; c < C; ++c) b[c][n] = (active && n < N) ? (double)(int8_t)(w4 >> (8 * c)) + b_offset : 0.0;
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const int k = cg * C + c;
+#pragma unroll
+            for (int n = 0; n < NN; ++n) b[c][n] = (active && n < N && k < K) ? (double)b_idx[(int64_t)n * K + k] + b_offset : 0.0;   // (the level index itself)
+        }
+    }
     __syncthreads();
-    if (k >= K) return;
-    for (int r = 0; r < rows; ++r) {
-        double acc = 0.0;
+    if (!active) return;
+    const int k0 = cg * C;
+    for (int r = rg; r < rows; r += row_groups) {
+        double acc[C];
 #pragma unroll
-        for (int n = 0; n < NN; ++n) acc = fma(gs[r][n], b[n], acc);
-        out[(int64_t)(row0 + r) * K + k] = (float)(acc * delta_b);
+        for (int c = 0; c < C; ++c) acc[c] = 0.0;
+#pragma unroll
+        for (int n = 0; n < NN; ++n) {
+            const double gv = gs[r][n];
+#pragma unroll
+            for (int c = 0; c < C; ++c) acc[c] = fma(gv, b[c][n], acc[c]);
+        }
+        float *o = out + (int64_t)(row0 + r) * K + k0;
+        if (C == 4 && vec_store) {
+            *reinterpret_cast<float4 *>(o) = make_float4((float)(acc[0] * delta_b), (float)(acc[1] * delta_b), (float)(acc[2] * delta_b), (float)(acc[3] * delta_b));
+        } else {
+#pragma unroll
+            for (int c = 0; c < C; ++c)
+                if (k0 + c < K) o[c] = (float)(acc[c] * delta_b);
+        }
     }
 }
 
@@ -2352,9 +2386,14 @@ int launch_qgemm_bwd(const float *gr, const int8_t *a_idx, const int8_t *b_idx,
     if ((int64_t)M * N * K == 0) return check_launch();
 
     if (d_a_hat && N <= kDirectMaxN) {
-        const dim3 grid((M + kDirectRows - 1) / kDirectRows, (K + 255) / 256);
-        if (N <= 16) CDL_LAUNCH("da_direct_kernel", stream, da_direct_kernel<16>, grid, dim3(256), 0, gr, b_idx, M, N, K, (double)delta_b, (double)b_offset, d_a_hat);
-        else CDL_LAUNCH("da_direct_kernel", stream, da_direct_kernel<32>, grid, dim3(256), 0, gr, b_idx, M, N, K, (double)delta_b, (double)b_offset, d_a_hat);
+        // four columns per thread (two where 32 index values per column would not leave registers for four)
+        const int c_per = N <= 16 ? 4 : 2;
+        const int col_groups = (K + c_per - 1) / c_per;
+        const int rows_per = direct_rows(N <= 16 ? 16 : 32);
+        const dim3 grid((M + rows_per - 1) / rows_per, (col_groups + 255) / 256);
+        const int vec_store = K % 4 == 0 && (reinterpret_cast<uintptr_t>(d_a_hat) & 15) == 0 && (reinterpret_cast<uintptr_t>(b_idx) & 3) == 0;
+        if (N <= 16) CDL_LAUNCH("da_direct_kernel", stream, (da_direct_kernel<16, 4>), grid, dim3(256), 0, gr, b_idx, M, N, K, (double)delta_b, (double)b_offset, d_a_hat, vec_store);
+        else CDL_LAUNCH("da_direct_kernel", stream, (da_direct_kernel<32, 2>), grid, dim3(256), 0, gr, b_idx, M, N, K, (double)delta_b, (double)b_offset, d_a_hat, vec_store);
         d_a_hat = nullptr;           // done; what follows is for the other product only
         if (!want_db) return check_launch();
     }

@@ -90,7 +90,10 @@ def test_qgemm_fwd_outputs_are_optional(oracle):
 
 
 BWD_SHAPES = [(32, 128, 256), (300, 200, 144), (257, 129, 80), (1000, 16, 144), (70, 50, 100), (5, 3, 7),
-              (2048, 96, 320)]
+              (2048, 96, 320),
+              # contractions of at most 32 entries (the direct kernel) with more output columns than one block of it
+              # covers: 4 columns per thread (N <= 16) and 2 (N <= 32), whole and ragged groups of columns
+              (200, 16, 1100), (130, 24, 1030), (64, 8, 2051), (70, 32, 513)]
 
 
 @pytest.mark.parametrize("M,N,K", BWD_SHAPES)
