@@ -397,7 +397,7 @@ size_t cdl_qconv_bwd_activations_workspace_bytes(int32_t B, int32_t H, int32_t W
 {
     int64_t M_out = 0;
     if (conv_dx_geometry(B, H, W, C, N, R, S, stride, pad, &M_out) != CDL_OK) return 0;
-    return qconv_bwd_activations_workspace_bytes(M_out, N, C, R, S);
+    return qconv_bwd_activations_workspace_bytes(M_out, N, C, R, S, stride);
 }
 
 int cdl_qconv_bwd_activations(const float *g, const int8_t *w_idx, int32_t B, int32_t H, int32_t W, int32_t C, int32_t N,
@@ -410,7 +410,7 @@ int cdl_qconv_bwd_activations(const float *g, const int8_t *w_idx, int32_t B, in
     if (!(std::isfinite(delta_w) && delta_w > 0.0f)) return CDL_ERR_PARAM;
     if (!g || !w_idx || !d_x_hat) return CDL_ERR_NULL;
     if (!aligned(g, 16) || !aligned(w_idx, 16) || !aligned(d_x_hat, 16)) return CDL_ERR_ALIGN;
-    rc = check_ws(ws, ws_bytes, qconv_bwd_activations_workspace_bytes(M_out, N, C, R, S));
+    rc = check_ws(ws, ws_bytes, qconv_bwd_activations_workspace_bytes(M_out, N, C, R, S, stride));
     if (rc != CDL_OK) return rc;
     return launch_qconv_bwd_activations(g, w_idx, B, H, W, C, N, R, S, stride, pad, delta_w, d_x_hat, ws, (hipStream_t)hip_stream);
 }

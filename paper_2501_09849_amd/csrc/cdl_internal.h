@@ -140,7 +140,7 @@ int launch_qconv_fwd(const int8_t *x_idx, const int8_t *w_idx, int32_t B, int32_
                      int32_t *acc, float *y, void *ws, hipStream_t stream);
 
 // Activation gradient of a convolutional layer (N % 128 == 0, stride 1 or 2): d_x_hat [B][H][W][C].
-size_t qconv_bwd_activations_workspace_bytes(int64_t M_out, int32_t N, int32_t C, int32_t R, int32_t S);
+size_t qconv_bwd_activations_workspace_bytes(int64_t M_out, int32_t N, int32_t C, int32_t R, int32_t S, int32_t stride);
 int launch_qconv_bwd_activations(const float *g, const int8_t *w_idx, int32_t B, int32_t H, int32_t W, int32_t C, int32_t N,
                                  int32_t R, int32_t S, int32_t stride, int32_t pad, float delta_w, float *d_x_hat, void *ws,
                                  hipStream_t stream);

@@ -234,12 +234,18 @@ struct LimbArgs {
     QConst fq_k;
     int fq_wsel;              // band_template(fq_k)
     float fq_scale;           // forward product with the quantizer in its prologue: delta_a * delta_b
-    // activation gradient of a convolution (CONVG): the rows of the fp32 operand are gathered.  Output row m is the input
-    // pixel (b, h, w); contraction entry k = (tap (r, s), output channel n) is read from G[b, p, q, n] with
-    // p = (h + pad - r) / stride, q = (w + pad - s) / stride where those are whole and inside the output image, else 0.
-    // A thread's four consecutive entries share a tap (N % 4 == 0).
-    int cg_H, cg_W, cg_P, cg_Q, cg_stride, cg_S, cg_pad;
+    // activation gradient of a convolution (CONVG): the rows of the fp32 operand are gathered.  Output row m is pixel
+    // (b, i, j) of a grid of cg_H x cg_W pixels per image; contraction entry k = (tap (r, s) of cg_R' x cg_S taps, output
+    // channel n) is read from G[b, p, q, n] with p = i + pad_h - r, q = j + pad_w - s where those are inside the output
+    // image, else 0.  A thread's four consecutive entries share a tap (N % 4 == 0).  Stride 1: the grid is the input
+    // image.  Stride 2: one launch per parity class (a, c) of the input pixels, whose grid holds the pixels
+    // (2 i + a, 2 j + c) and whose taps are those of the same parity as (a + pad, c + pad) - the only ones that reach
+    // such a pixel -, renumbered; the output rows then lie scattered in the tensor (cg_ostep = 2).
+    int cg_H, cg_W, cg_P, cg_Q, cg_S, cg_pad_h, cg_pad_w;
     float cg_inv_n, cg_inv_s;     // 1 / N, 1 / S
+    int cg_ostep, cg_oa, cg_oc, cg_oH, cg_oW;   // output pixel of grid pixel (b, i, j): (b, ostep i + oa, ostep j + oc) of oH x oW
+    uint32_t cg_mul_hw, cg_mul_w;               // m / (cg_H cg_W) and m / cg_W as multiplications (div_by)
+    int cg_sh_hw, cg_sh_w;
     int tn;                       // 32-column tiles per wave (1..3; with six limbs at most 2)
     const double *row_corr;   // [rows] or null: added to every entry of an output row (the index operand is stored with an offset:
                               // the missing part of the product is offset * step * sum of g over the contraction); splits == 1 only
@@ -746,6 +752,23 @@ void conv_prep_kernel(int8_t *page, int off, const int8_t *w, int N, int Kc, int
 // without an offset, so that such calls need no workspace
 static __device__ __align__(256) int8_t conv_zero_page[256];
 
+// n / d for 0 <= n < 2^31 by one multiplication: with s = ceil(log2 d) and mul = ceil(2^(31 + s) / d) (below 2^32) the
+// quotient is (n * mul) >> (31 + s), exactly (the excess mul * d - 2^(31 + s) is below d <= 2^s, so it adds less than
+// one unit of the quotient over the whole range of n); sh = s - 1, or -1 for d = 1.
+struct DivBy { uint32_t mul; int sh; };
+inline DivBy make_div_by(uint32_t d)
+{
+    if (d <= 1) return DivBy{0u, -1};
+    int s = 0;
+    while ((1ull << s) < d) ++s;
+    const unsigned long long mul = ((1ull << (31 + s)) + d - 1) / d;
+    return DivBy{(uint32_t)mul, s - 1};
+}
+__device__ __forceinline__ int div_by(int n, uint32_t mul, int sh)
+{
+    return sh < 0 ? n : (int)(__umulhi((uint32_t)n, mul) >> sh);
+}
+
 // Digits of four values: out[l] holds digit l (a signed byte, l = 0 least significant) of g[0..3] in
 // its bytes 0..3.  x = g * gscale is exact (gscale is a power of two) and |x| < 0.99 * 2^(8L-1);
 // q = rint(x) = sum_l d_l 256^l with d_l in [-128, 127]: the bytes of (q + 0x80..80) ^ 0x80..80.
@@ -882,8 +905,8 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int m = min(tile_r0 * kLRows + ar + 8 * q, a.rows - 1), hw = a.cg_H * a.cg_W;
-            const int b = m / hw, rem = m - b * hw;
-            cg_h[q] = rem / a.cg_W;
+            const int b = div_by(m, a.cg_mul_hw, a.cg_sh_hw), rem = m - b * hw;
+            cg_h[q] = div_by(rem, a.cg_mul_w, a.cg_sh_w);
             cg_w[q] = rem - cg_h[q] * a.cg_W;
             cg_base[q] = b * a.cg_P * a.cg_Q;
         }
@@ -896,13 +919,11 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
             // from a whole number on either side and truncates to the quotient; likewise tap / S)
             const int tap = (int)(((float)k0 + 0.5f) * a.cg_inv_n), n0 = k0 - tap * a.N;
             const int tr = (int)(((float)tap + 0.5f) * a.cg_inv_s), ts = tap - tr * a.cg_S;
-            const int dh = a.cg_pad - tr, dw = a.cg_pad - ts;
+            const int dh = a.cg_pad_h - tr, dw = a.cg_pad_w - ts;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                int hh = cg_h[q] + dh, ww = cg_w[q] + dw;
-                bool ok = true;
-                if (a.cg_stride == 2) { ok = ((hh | ww) & 1) == 0; hh >>= 1; ww >>= 1; }
-                ok = ok && (unsigned)hh < (unsigned)a.cg_P && (unsigned)ww < (unsigned)a.cg_Q;
+                const int hh = cg_h[q] + dh, ww = cg_w[q] + dw;
+                const bool ok = (unsigned)hh < (unsigned)a.cg_P && (unsigned)ww < (unsigned)a.cg_Q;
                 const int64_t o = ok ? (int64_t)(cg_base[q] + hh * a.cg_Q + ww) * a.N + n0 : 0;
                 const float4 v = *reinterpret_cast<const float4 *>(a.G + o);
                 g[4 * q] = ok ? v.x : 0.0f; g[4 * q + 1] = ok ? v.y : 0.0f; g[4 * q + 2] = ok ? v.z : 0.0f; g[4 * q + 3] = ok ? v.w : 0.0f;
@@ -1093,6 +1114,22 @@ __device__ __forceinline__ void limb_gemm_body(const LimbArgs &a, int8_t *lds, f
                 }
             }
         };
+        if (CONVG && a.cg_ostep != 1) {
+            // the rows of a parity class lie scattered in the tensor: one address per row (no loads between the stores)
+#pragma unroll
+            for (int rr = 0; rr < 16; ++rr) {
+                const int m = erow + 8 * (rr >> 2) + (rr & 3);
+                if (m >= a.rows) continue;
+                const int b = div_by(m, a.cg_mul_hw, a.cg_sh_hw), rem = m - b * (a.cg_H * a.cg_W);
+                const int i = div_by(rem, a.cg_mul_w, a.cg_sh_w), jj = rem - i * a.cg_W;
+                const int64_t pix = ((int64_t)b * a.cg_oH + a.cg_ostep * i + a.cg_oa) * a.cg_oW + a.cg_ostep * jj + a.cg_oc;
+                float *p = a.out + pix * a.cols + ecol;
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    if (ecol + j * 32 < a.cols) p[j * 32] = (float)__builtin_fma(combined(j, rr), out_scale, 0.0);
+            }
+            return;
+        }
         if (direct) {
             if (corr) {
                 if (full) emit(std::true_type{}, std::true_type{}, a.out + first);
@@ -1439,28 +1476,37 @@ void conv_dx_direct_kernel(const float *__restrict__ g, const int8_t *__restrict
     }
 }
 
-// For that product: the weights [N][R][S][C] rearranged as its index operand Wr[c][(r, s, n)] (contraction index
-// contiguous, rows ld bytes apart, zero beyond R*S*N) and the sum of |w| over the contraction per channel c (the limb
-// rule's column sums).
+// For that product: the weights [N][R][S][C] rearranged as its index operand Wr[c][(r', s', n)] (contraction index
+// contiguous, rows ld bytes apart, zero beyond the contraction length) and the sum of |w| over the contraction per
+// channel c (the limb rule's column sums).  One rearrangement per class of taps (blockIdx.y): the taps
+// (r0 + tstep r', s0 + tstep s') with r' < Rc, s' < Sc - all of them for stride 1 (one class, tstep = 1), those of one
+// parity for stride 2.
+struct ConvDxClass { int r0, s0, Rc, Sc; };
+struct ConvDxClasses { ConvDxClass c[4]; int tstep; };
+
 __global__ __launch_bounds__(256)
-void conv_dx_prep_kernel(const int8_t *__restrict__ w, int N, int R, int S, int C, int8_t *__restrict__ wr, int64_t ld,
+void conv_dx_prep_kernel(const int8_t *__restrict__ w, int N, int R, int S, int C, ConvDxClasses cls, int8_t *__restrict__ wr, int64_t ld,
                          unsigned int *__restrict__ col_abs)
 {
-    // one block per input channel c; four entries per thread and trip (one 4-byte store): the byte loads are a stride of C
-    // apart and nothing but latency, so as many of them as possible are in flight
+    // one block per input channel c and class; four entries per thread and trip (one 4-byte store): the byte loads are a
+    // stride of C apart and nothing but latency, so as many of them as possible are in flight
     __shared__ unsigned int red[4];
-    const int kc = R * S * N;
+    const ConvDxClass k_ = cls.c[blockIdx.y];
+    const int kc = k_.Rc * k_.Sc * N;
     const int c = blockIdx.x;
+    int8_t *dst = wr + ((int64_t)blockIdx.y * C + c) * ld;
     unsigned int s_abs = 0u;
     for (int k4 = threadIdx.x * 4; k4 < (int)ld; k4 += 1024) {
         int v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int k = k4 + e, kk = min(k, kc - 1), tap = kk / N, n = kk - tap * N;
-            const int x = (int)w[((int64_t)n * R * S + tap) * C + c];
+            const int tr = tap / k_.Sc, ts = tap - tr * k_.Sc;
+            const int r = k_.r0 + cls.tstep * tr, sx = k_.s0 + cls.tstep * ts;
+            const int x = (int)w[(((int64_t)n * R + r) * S + sx) * C + c];
             v[e] = k < kc ? x : 0;
         }
-        *reinterpret_cast<uint32_t *>(wr + (int64_t)c * ld + k4) =
+        *reinterpret_cast<uint32_t *>(dst + k4) =
             (uint32_t)(v[0] & 0xff) | ((uint32_t)(v[1] & 0xff) << 8) | ((uint32_t)(v[2] & 0xff) << 16) | ((uint32_t)(v[3] & 0xff) << 24);
 #pragma unroll
         for (int e = 0; e < 4; ++e) s_abs += (unsigned int)(v[e] < 0 ? -v[e] : v[e]);
@@ -1469,7 +1515,7 @@ void conv_dx_prep_kernel(const int8_t *__restrict__ w, int N, int R, int S, int 
     for (int o = 32; o > 0; o >>= 1) s_abs += (unsigned int)__shfl_down((int)s_abs, o, 64);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s_abs;
     __syncthreads();
-    if (threadIdx.x == 0) col_abs[c] = (red[0] + red[1]) + (red[2] + red[3]);
+    if (threadIdx.x == 0) col_abs[blockIdx.y * C + c] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
 // The forward product with the quantizer of the activations in its prologue: y = delta_a delta_b (Q_idx(X) . Wi^T)
@@ -2204,29 +2250,31 @@ bool conv_dx_is_direct(int32_t N, int32_t C, int32_t R, int32_t S)
 // workspace of the activation gradient of a convolution: [plan][per-block max|g|][col sums][Wr]
 struct ConvDxLayout {
     size_t plan, block_max, ss_b, wr, total;
-    int n_max, nk;
+    int n_max, nk, classes;
     int64_t ld;
 };
 
-ConvDxLayout conv_dx_layout(int64_t M_out, int32_t N, int32_t C, int32_t R, int32_t S)
+ConvDxLayout conv_dx_layout(int64_t M_out, int32_t N, int32_t C, int32_t R, int32_t S, int32_t stride)
 {
     ConvDxLayout L;
-    const int64_t kc = (int64_t)R * S * N;
+    // stride 2: four classes of taps, each with at most ceil(R / 2) x ceil(S / 2) of them
+    L.classes = stride == 2 ? 4 : 1;
+    const int64_t kc = stride == 2 ? (int64_t)((R + 1) / 2) * ((S + 1) / 2) * N : (int64_t)R * S * N;
     L.nk = (int)((kc + kLBK - 1) / kLBK);
     L.ld = (int64_t)(L.nk | 1) * kLBK;
     L.n_max = (int)blocks_for((M_out * N) >> 2, 2048, 2048);
     size_t off = 0;
     L.plan = off;      off += align_up(sizeof(BwdPlan), 256);
     L.block_max = off; off += align_up((size_t)L.n_max * sizeof(unsigned int), 256);
-    L.ss_b = off;      off += align_up((size_t)C * sizeof(unsigned int), 256);
-    L.wr = off;        off += align_up((size_t)C * (size_t)L.ld, 256);
+    L.ss_b = off;      off += align_up((size_t)L.classes * C * sizeof(unsigned int), 256);
+    L.wr = off;        off += align_up((size_t)L.classes * C * (size_t)L.ld, 256);
     L.total = off;
     return L;
 }
 
-size_t qconv_bwd_activations_workspace_bytes(int64_t M_out, int32_t N, int32_t C, int32_t R, int32_t S)
+size_t qconv_bwd_activations_workspace_bytes(int64_t M_out, int32_t N, int32_t C, int32_t R, int32_t S, int32_t stride)
 {
-    return conv_dx_layout(M_out, N, C, R, S).total;
+    return conv_dx_layout(M_out, N, C, R, S, stride).total;
 }
 
 int launch_qconv_bwd_activations(const float *g, const int8_t *w_idx, int32_t B, int32_t H, int32_t W, int32_t C, int32_t N,
@@ -2243,49 +2291,93 @@ int launch_qconv_bwd_activations(const float *g, const int8_t *w_idx, int32_t B,
         else CDL_LAUNCH("conv_dx_direct_kernel", stream, conv_dx_direct_kernel<32>, dim3(grid), dim3(256), lds, g, w_idx, B, H, W, C, N, R, S, stride, pad, P, Q, (double)delta_w, d_x_hat);
         return check_launch();
     }
-    const ConvDxLayout L = conv_dx_layout(M_out, N, C, R, S);
+    const ConvDxLayout L = conv_dx_layout(M_out, N, C, R, S, stride);
     char *base = reinterpret_cast<char *>(ws);
     BwdPlan *plan = reinterpret_cast<BwdPlan *>(base + L.plan);
     unsigned int *block_max = reinterpret_cast<unsigned int *>(base + L.block_max);
     unsigned int *ss_b = reinterpret_cast<unsigned int *>(base + L.ss_b);
     int8_t *wr = reinterpret_cast<int8_t *>(base + L.wr);
+
+    // The classes of input pixels.  Stride 1: all of them, every tap.  Stride 2: input pixel (h, w) is reached only by the
+    // taps r = h + pad, s = w + pad (mod 2) - with all R x S taps three products in four would multiply zeros -, so the
+    // pixels (2 i + a, 2 j + c) of each parity (a, c) form a product of their own over the taps r = r0 + 2 r',
+    // s = s0 + 2 s' (r0 = (a + pad) mod 2, likewise s0), in which g is read at p = i + (a + pad - r0) / 2 - r'.
+    struct Cls { int oa, oc, Hc, Wc, pad_h, pad_w, Rc, Sc; };
+    Cls cl[4];
+    ConvDxClasses taps{};
+    taps.tstep = stride;
+    int n_cls = 0;
+    bool zero_first = false;
+    if (stride == 1) {
+        cl[n_cls] = Cls{0, 0, H, W, pad, pad, R, S};
+        taps.c[n_cls++] = ConvDxClass{0, 0, R, S};
+    } else {
+        for (int pa = 0; pa < 2; ++pa)
+            for (int pc = 0; pc < 2; ++pc) {
+                const int Hc = (H - pa + 1) / 2, Wc = (W - pc + 1) / 2;
+                if (Hc <= 0 || Wc <= 0) continue;
+                const int r0 = (pa + pad) & 1, s0 = (pc + pad) & 1;
+                const int Rc = r0 < R ? (R - r0 + 1) / 2 : 0, Sc = s0 < S ? (S - s0 + 1) / 2 : 0;
+                if (Rc == 0 || Sc == 0) { zero_first = true; continue; }     // no tap reaches these pixels
+                cl[n_cls] = Cls{pa, pc, Hc, Wc, (pa + pad - r0) / 2, (pc + pad - s0) / 2, Rc, Sc};
+                taps.c[n_cls++] = ConvDxClass{r0, s0, Rc, Sc};
+            }
+    }
+    if (zero_first)
+        CDL_LAUNCH("zero_f32_kernel", stream, zero_f32_kernel, dim3(blocks_for((int64_t)B * H * W * C, 256, 4096)), dim3(256), 0, d_x_hat, (int64_t)B * H * W * C);
+    if (n_cls == 0) return check_launch();
     CDL_LAUNCH("absmax_kernel", stream, absmax_kernel, dim3(L.n_max), dim3(256), 0, g, M_out * N, block_max, ss_b, 0);
-    CDL_LAUNCH("conv_dx_prep_kernel", stream, conv_dx_prep_kernel, dim3((unsigned)C), dim3(256), 0,
-               w_idx, N, R, S, C, wr, L.ld, ss_b);
+    CDL_LAUNCH("conv_dx_prep_kernel", stream, conv_dx_prep_kernel, dim3((unsigned)C, (unsigned)n_cls), dim3(256), 0,
+               w_idx, N, R, S, C, taps, wr, L.ld, ss_b);
+    // (one limb count for all classes: the largest column sum of any of them)
     CDL_LAUNCH("plan_kernel", stream, plan_kernel, dim3(1), dim3(1024), 0, plan, block_max, L.n_max,
-               (const unsigned int *)nullptr, 0, ss_b, C, 1.0f, delta_w);
+               (const unsigned int *)nullptr, 0, ss_b, n_cls * C, 1.0f, delta_w);
     int rc = check_launch();
     if (rc != CDL_OK) return rc;
     LimbArgs a{};
     a.G = g; a.M = (int)M_out; a.N = N;
-    a.Bt = wr; a.ldb = L.ld;
-    a.rows = B * H * W; a.cols = C; a.kc = R * S * N;
-    a.nk = L.nk;
-    a.tiles_r = (a.rows + kLRows - 1) / kLRows; a.splits = 1; a.kt_per_split = L.nk;
+    a.ldb = L.ld;
+    a.cols = C;
+    a.splits = 1;
     a.units_per_block = 1;
     a.plan = plan; a.which = 0;
     a.out = d_x_hat;
-    a.cg_H = H; a.cg_W = W; a.cg_P = P; a.cg_Q = Q; a.cg_stride = stride; a.cg_S = S; a.cg_pad = pad;
-    a.cg_inv_n = 1.0f / (float)N; a.cg_inv_s = 1.0f / (float)S;
+    a.cg_P = P; a.cg_Q = Q;
+    a.cg_inv_n = 1.0f / (float)N;
+    a.cg_ostep = stride; a.cg_oH = H; a.cg_oW = W;
     // the tile width (128, 256 or 384 columns) that pads the channels least; the widest of those that pad equally
     a.tn = 3;
     for (int tn = 2; tn >= 1; --tn) {
         const int w = 128 * tn, wbest = 128 * a.tn;
         if ((C + w - 1) / w * w < (C + wbest - 1) / wbest * wbest) a.tn = tn;
     }
-    // (the grid is sized before the limb count is known: six limbs take tiles of at most 256 columns)
-    const int narrow = 128 * (a.tn < 2 ? a.tn : 2);
-    const int64_t items = (int64_t)a.tiles_r * ((a.cols + narrow - 1) / narrow);
-    if (items > 2147483640LL) return CDL_ERR_PARAM;
     if ((int64_t)limb_cols(3) * a.ldb > 0xffffffffLL) return CDL_ERR_RANGE;
-    const unsigned grid = (unsigned)((items + 7) / 8 * 8);
     const void *fn = a.tn == 1 ? (const void *)limb_conv_dx_kernel<1> : a.tn == 2 ? (const void *)limb_conv_dx_kernel<2> : (const void *)limb_conv_dx_kernel<3>;
     const int lds_bytes = conv_dx_lds_bytes(a.tn);
     const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return hip_failed(e);
-    if (a.tn == 1) CDL_LAUNCH("limb_gemm_kernel(conv d_x_hat)", stream, limb_conv_dx_kernel<1>, dim3(grid), dim3(kLThreads), lds_bytes, a);
-    else if (a.tn == 2) CDL_LAUNCH("limb_gemm_kernel(conv d_x_hat)", stream, limb_conv_dx_kernel<2>, dim3(grid), dim3(kLThreads), lds_bytes, a);
-    else CDL_LAUNCH("limb_gemm_kernel(conv d_x_hat)", stream, limb_conv_dx_kernel<3>, dim3(grid), dim3(kLThreads), lds_bytes, a);
+    for (int ci = 0; ci < n_cls; ++ci) {
+        const Cls &k = cl[ci];
+        a.Bt = wr + (int64_t)ci * C * L.ld;
+        a.rows = B * k.Hc * k.Wc;
+        a.kc = k.Rc * k.Sc * N;
+        a.nk = (a.kc + kLBK - 1) / kLBK;
+        a.kt_per_split = a.nk;
+        a.tiles_r = (a.rows + kLRows - 1) / kLRows;
+        a.cg_H = k.Hc; a.cg_W = k.Wc; a.cg_S = k.Sc; a.cg_pad_h = k.pad_h; a.cg_pad_w = k.pad_w;
+        a.cg_inv_s = 1.0f / (float)k.Sc;
+        a.cg_oa = k.oa; a.cg_oc = k.oc;
+        const DivBy by_hw = make_div_by((uint32_t)k.Hc * (uint32_t)k.Wc), by_w = make_div_by((uint32_t)k.Wc);
+        a.cg_mul_hw = by_hw.mul; a.cg_sh_hw = by_hw.sh; a.cg_mul_w = by_w.mul; a.cg_sh_w = by_w.sh;
+        // (the grid is sized before the limb count is known: six limbs take tiles of at most 256 columns)
+        const int narrow = 128 * (a.tn < 2 ? a.tn : 2);
+        const int64_t items = (int64_t)a.tiles_r * ((a.cols + narrow - 1) / narrow);
+        if (items > 2147483640LL) return CDL_ERR_PARAM;
+        const unsigned grid = (unsigned)((items + 7) / 8 * 8);
+        if (a.tn == 1) CDL_LAUNCH("limb_gemm_kernel(conv d_x_hat)", stream, limb_conv_dx_kernel<1>, dim3(grid), dim3(kLThreads), lds_bytes, a);
+        else if (a.tn == 2) CDL_LAUNCH("limb_gemm_kernel(conv d_x_hat)", stream, limb_conv_dx_kernel<2>, dim3(grid), dim3(kLThreads), lds_bytes, a);
+        else CDL_LAUNCH("limb_gemm_kernel(conv d_x_hat)", stream, limb_conv_dx_kernel<3>, dim3(grid), dim3(kLThreads), lds_bytes, a);
+    }
     return check_launch();
 }
 
