@@ -189,6 +189,8 @@ XGRAD = [(2, 7, 9, 16, 128, 3, 3, 1, 1), (1, 8, 8, 20, 128, 3, 3, 2, 1), (3, 6, 
          # more than 256 row tiles with a short contraction: blocks that work through runs of two and three row tiles (the last
          # run shorter; one and two column tiles per row tile; both strides)
          (16, 28, 28, 64, 64, 3, 3, 1, 1), (17, 23, 21, 40, 36, 3, 3, 1, 1), (25, 28, 28, 48, 32, 3, 3, 2, 1), (10, 30, 30, 512, 16, 3, 3, 1, 1),
+         # the first stride-2 transition of a ResNet-18 on 32 images: a hundred thousand input pixels in four parity classes
+         (32, 56, 56, 64, 128, 3, 3, 2, 1),
          # output channels that are not whole K-tiles of 128: K-tiles then run across taps (the first stages of a ResNet)
          (4, 16, 16, 16, 16, 3, 3, 1, 1), (2, 16, 16, 32, 64, 3, 3, 2, 1), (3, 9, 9, 16, 48, 3, 3, 1, 1), (1, 7, 7, 8, 20, 5, 5, 1, 2),
          (2, 12, 12, 64, 32, 1, 1, 1, 0),
